@@ -1,0 +1,184 @@
+/*
+ * libhag -- GNN neighbourhood set-aggregation over a Hierarchically Aggregated
+ * computation Graph (HAG) on AMD MI355X (gfx950).  C ABI.
+ *
+ * Vocabulary (paper, Section 3.1): V are the nodes of the input graph, N(v) the
+ * in-neighbour set of v, V_A the aggregation nodes a HAG adds, Nhat_v the
+ * in-neighbours of v in the HAG (a mix of original and aggregation nodes).
+ *
+ * Graph layout.  CSR with rows = destinations and columns = in-neighbours
+ * (Section 3.1: an edge (u,v) means computing v needs u):
+ *     rowptr  int64 [n+1], col  int32 [rowptr[n]], 0 <= col < n.
+ * A neighbourhood is a set: a duplicate inside one row is an error unless
+ * HAG_SEARCH_DEDUP is given.  Self-loops and isolated nodes are legal.  The
+ * graph need not be symmetric; the backward pass uses the true transpose.
+ *
+ * Unified ids.  Original nodes are 0..n-1.  Aggregation nodes are n..n+a-1.
+ * Two numberings exist: "creation order" (the order Algorithm 3 created them,
+ * used by hag_from_merges / hag_get_merges) and "level order" (sorted by depth,
+ * stable; used by hag_get_forward and on the device).
+ *
+ * Feature layout.  Row-major [n, d] matrices, row stride d elements, base
+ * pointer 16-byte aligned, d a positive multiple of 4 (other d: HAG_EINVAL).
+ * dtype f32 or i32.  int32 sums wrap modulo 2^32.
+ *
+ * Semantics taken where the paper is silent:
+ *   empty N(v): sum 0, mean 0, max 0 with argmax -1 (and no gradient);
+ *   mean = sum / |N(v)| with the degree of the INPUT graph (not of the HAG);
+ *   max ties go to the smallest original node id; argmax holds original ids.
+ *
+ * Ownership.  The library owns hag_t and every array returned by a getter (valid
+ * until hag_free).  The caller owns all arrays it passes in; host arrays are
+ * copied during the call.  Device arrays (x, y, gy, gx, argmax, workspace) are
+ * caller-owned device memory and must not alias each other.
+ *
+ * Execution.  Device entry points enqueue kernels on `stream` (a hipStream_t
+ * passed as void*, NULL = the default stream) and return without synchronising;
+ * they allocate nothing.  All functions return a status (0 = HAG_OK); the
+ * message of the last failure on the calling thread is hag_last_error().
+ */
+#ifndef HAG_H
+#define HAG_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct hag_handle hag_t; /* opaque; immutable after construction except hag_upload */
+
+typedef enum { HAG_SUM = 0, HAG_MEAN = 1, HAG_MAX = 2 } hag_op_t;   /* Table 1, set Aggregate */
+typedef enum { HAG_F32 = 0, HAG_I32 = 1 } hag_dtype_t;
+
+enum {
+    HAG_OK = 0,
+    HAG_EINVAL = -1,  /* bad argument (message says which) */
+    HAG_ENOMEM = -2,  /* host or device allocation failed */
+    HAG_EHIP = -3,    /* a HIP runtime call failed (message holds the HIP error string) */
+    HAG_ESTATE = -4   /* device entry point called before hag_upload */
+};
+
+enum {
+    HAG_SEARCH_CANONICAL = 1, /* among pairs of maximal redundancy take the lexicographically
+                                 smallest (smaller id, larger id); result is then unique */
+    HAG_SEARCH_DEDUP = 2      /* drop duplicate neighbours instead of rejecting them */
+};
+
+typedef struct hag_stats {
+    int64_t n;            /* |V| */
+    int64_t e;            /* |E|, directed edges of the input graph */
+    int64_t a;            /* |V_A| */
+    int64_t levels;       /* depth of the deepest aggregation node (0 if a == 0) */
+    int64_t h;            /* sum over v in V of |Nhat_v| (edges of the final gather) */
+    int64_t e_hag;        /* |E^| = h + 2a */
+    int64_t aggr_naive;   /* binary aggregations on the GNN-graph: sum max(|N(v)|-1, 0)   (Section 4.1) */
+    int64_t aggr_hag;     /* the same count on the HAG: sum over V and V_A of max(|Nhat|-1, 0) */
+    int64_t xfer_naive;   /* neighbour-row transfers on the GNN-graph = |E|              (Section 5.4) */
+    int64_t xfer_hag;     /* neighbour-row transfers on the HAG = |E^| */
+    int64_t max_degree;   /* largest |N(v)| */
+    int64_t max_hag_degree; /* largest |Nhat_v| */
+} hag_stats_t;
+
+/* ---------------------------------------------------------------- host ---- */
+
+/* Algorithm 3 for a set Aggregate: starting from the GNN-graph, repeatedly take
+ * the pair (v1, v2) of HAG nodes that the largest number of original nodes
+ * aggregate together (Redundancy), create an aggregation node w = v1 (+) v2 and
+ * replace the pair by w in every list holding both; stop at `capacity`
+ * aggregation nodes or when the best redundancy is <= 1 (such a merge saves
+ * nothing; the listing's loop would not terminate there).
+ * max_depth > 0 forbids aggregation nodes deeper than that (0 = no limit; the
+ * paper has no such limit).  All pointers are host memory.  *out receives a new
+ * handle (free with hag_free).  Errors: HAG_EINVAL for n < 0, capacity < 0,
+ * non-monotone rowptr, col out of range, duplicates without HAG_SEARCH_DEDUP,
+ * n + capacity >= 2^31; HAG_ENOMEM. */
+int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity,
+               uint32_t flags, int32_t max_depth, hag_t **out);
+
+/* The same search run independently on each of n_graphs disjoint graphs that
+ * share one block-diagonal CSR (graph g owns nodes graph_ptr[g]..graph_ptr[g+1]-1
+ * and no edge crosses graphs), each with its own capacity
+ * floor(capacity_fraction * nodes of the graph); the results are concatenated in
+ * graph order.  Used for batches of small graphs (graph classification). */
+int hag_search_batched(int64_t n, const int64_t *rowptr, const int32_t *col,
+                       int64_t n_graphs, const int64_t *graph_ptr, double capacity_fraction,
+                       uint32_t flags, int32_t max_depth, hag_t **out);
+
+/* Build a handle from an explicit merge list in creation order: aggregation node
+ * n+i aggregates left[i] and right[i] (unified creation-order ids < n+i), and
+ * replaces that pair in every Nhat_u that holds both at that point -- the rewrite
+ * loop of Algorithm 3.  HAG_EINVAL if an id is out of range, left[i] == right[i],
+ * or a merge is used by no list. */
+int hag_from_merges(int64_t n, const int64_t *rowptr, const int32_t *col,
+                    int64_t n_merges, const int32_t *left, const int32_t *right,
+                    uint32_t flags, hag_t **out);
+
+/* New handle holding only the first n_merges merges of h (greedy with a fixed
+ * tie-break is prefix-stable, so this is the HAG of a smaller capacity). */
+int hag_prefix(const hag_t *h, int64_t n_merges, hag_t **out);
+
+void hag_free(hag_t *h);
+
+int hag_stats(const hag_t *h, hag_stats_t *out);
+
+/* Merge list in creation order; redundancy[i] = number of lists rewritten by merge i. */
+int hag_get_merges(const hag_t *h, int64_t *n_merges, const int32_t **left, const int32_t **right,
+                   const int32_t **redundancy);
+
+/* Level-ordered forward form (what the device executes):
+ *   agg_left/right [a]: inputs of aggregation node n+i, level-order ids;
+ *   level_ptr [levels+1]: nodes n+level_ptr[l-1] .. n+level_ptr[l]-1 have depth l;
+ *   hrowptr [n+1], hcol [h]: Nhat_v for v in V, level-order ids, ascending per row.
+ * Any out pointer may be NULL. */
+int hag_get_forward(const hag_t *h, const int32_t **agg_left, const int32_t **agg_right,
+                    const int32_t **level_ptr, int32_t *n_levels,
+                    const int64_t **hrowptr, const int32_t **hcol);
+
+/* ------------------------------------------------------------- device ---- */
+
+/* Copy the index arrays and launch schedules of h to the current device (once per
+ * handle; allocates device memory that hag_free releases; synchronises). */
+int hag_upload(hag_t *h, void *stream);
+
+/* Bytes of caller-provided scratch that hag_forward / hag_backward need for this
+ * op, dtype and d (aggregation-node rows, partial sums of split rows).  The
+ * contents need not survive between calls: nothing is memorised for the backward
+ * pass except argmax (Algorithm 2's caption). */
+size_t hag_workspace_bytes(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d);
+
+/* Algorithm 2 without the Update line: aggregation nodes level by level, then
+ * y[v] = Aggregate over Nhat_v for every v in V.  x, y: device [n, d].
+ * argmax: device int32 [n, d], required for HAG_MAX, ignored otherwise.
+ * HAG_MEAN requires HAG_F32. */
+int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                const void *x, void *y, int32_t *argmax, void *workspace, void *stream);
+
+/* Transposed pass (the hag_aggregate_grad operation of Section 5.1; by the
+ * definition of equivalence in Section 3.2 it must return the gradient of the
+ * naive aggregation): gx[u] = sum over consumers of u.  sum/mean run over the
+ * transposed HAG, deepest level first; max uses only argmax
+ * (gx[argmax[v,f], f] += gy[v,f], hardware atomics: fp32 order not fixed).
+ * gx is overwritten. */
+int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                 const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream);
+
+/* The GNN-graph baseline (Algorithm 1's Aggregate line; a HAG with V_A empty):
+ * same arguments, same kernels, run on the input CSR and its transpose. */
+int hag_naive_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                      const void *x, void *y, int32_t *argmax, void *workspace, void *stream);
+int hag_naive_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                       const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream);
+
+/* Algorithmic bytes one call moves (every HAG edge one row read, every produced
+ * row one write, plus index reads), for roofline accounting.  which: 0 hag_forward,
+ * 1 hag_backward, 2 hag_naive_forward, 3 hag_naive_backward. */
+int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d);
+
+const char *hag_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HAG_H */

@@ -1,0 +1,239 @@
+"""ctypes front end of libhag: argument marshalling only.
+
+Function names follow include/hag.h.  Host arrays are numpy; device arrays are
+torch tensors used purely as device memory (data_ptr) and for the current
+stream.  Every step of the aggregation path runs in the library's HIP kernels;
+there is no fallback: if libhag.so is missing or fails to load, importing a
+symbol from it raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libhag.so")
+
+HAG_SUM, HAG_MEAN, HAG_MAX = 0, 1, 2
+HAG_F32, HAG_I32 = 0, 1
+HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE = 0, -1, -2, -3, -4
+HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP = 1, 2
+OPS = {"sum": HAG_SUM, "mean": HAG_MEAN, "max": HAG_MAX}
+
+EXPORTS = [
+    "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
+    "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
+    "hag_backward", "hag_naive_forward", "hag_naive_backward", "hag_algorithmic_bytes", "hag_last_error",
+]
+
+
+class HagError(RuntimeError):
+    def __init__(self, code, msg):
+        super().__init__(f"libhag error {code}: {msg}")
+        self.code = code
+
+
+class hag_stats_t(ctypes.Structure):
+    _fields_ = [(k, ctypes.c_int64) for k in (
+        "n", "e", "a", "levels", "h", "e_hag", "aggr_naive", "aggr_hag", "xfer_naive", "xfer_hag",
+        "max_degree", "max_hag_degree")]
+
+
+_lib = None
+
+
+def lib():
+    """Load libhag.so (built by paper_1906_03707_amd.build); fails loudly if absent."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} not found: run `python -m paper_1906_03707_amd.build` "
+                              "(there is no CPU fallback)")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i64, i32, u32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int32, ctypes.c_uint32
+        L.hag_search.argtypes = [i64, vp, vp, i64, u32, i32, ctypes.POINTER(vp)]
+        L.hag_search_batched.argtypes = [i64, vp, vp, i64, vp, ctypes.c_double, u32, i32, ctypes.POINTER(vp)]
+        L.hag_from_merges.argtypes = [i64, vp, vp, i64, vp, vp, u32, ctypes.POINTER(vp)]
+        L.hag_prefix.argtypes = [vp, i64, ctypes.POINTER(vp)]
+        L.hag_free.argtypes = [vp]
+        L.hag_free.restype = None
+        L.hag_stats.argtypes = [vp, ctypes.POINTER(hag_stats_t)]
+        L.hag_get_merges.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+        L.hag_get_forward.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(vp), ctypes.POINTER(vp),
+                                      ctypes.POINTER(i32), ctypes.POINTER(vp), ctypes.POINTER(vp)]
+        L.hag_upload.argtypes = [vp, vp]
+        L.hag_workspace_bytes.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64]
+        L.hag_workspace_bytes.restype = ctypes.c_size_t
+        for name in ("hag_forward", "hag_naive_forward"):
+            getattr(L, name).argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp, vp]
+        for name in ("hag_backward", "hag_naive_backward"):
+            getattr(L, name).argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp, vp]
+        L.hag_algorithmic_bytes.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64]
+        L.hag_algorithmic_bytes.restype = i64
+        L.hag_last_error.restype = ctypes.c_char_p
+        _lib = L
+    return _lib
+
+
+def _check(rc):
+    if rc != 0:
+        raise HagError(rc, lib().hag_last_error().decode())
+
+
+def _np(a, dtype):
+    return np.ascontiguousarray(a, dtype=dtype)
+
+
+def _view(ptr, count, dtype):
+    if count == 0 or not ptr:
+        return np.zeros(0, dtype=dtype)
+    ct = {np.int32: ctypes.c_int32, np.int64: ctypes.c_int64}[dtype]
+    return np.ctypeslib.as_array(ctypes.cast(ptr, ctypes.POINTER(ct)), shape=(count,)).copy()
+
+
+def _dtype_code(t):
+    import torch
+    if t.dtype == torch.float32:
+        return HAG_F32
+    if t.dtype == torch.int32:
+        return HAG_I32
+    raise TypeError(f"unsupported dtype {t.dtype}")
+
+
+def _stream_ptr():
+    import torch
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev_ptr(t):
+    if t is None:
+        return None
+    if not t.is_cuda or not t.is_contiguous():
+        raise ValueError("device tensors must be contiguous and on the GPU")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+class Hag:
+    """Owner of one hag_t handle."""
+
+    def __init__(self, handle):
+        self._h = ctypes.c_void_p(handle)
+        self._ws = {}
+
+    def __del__(self):
+        try:
+            if self._h:
+                lib().hag_free(self._h)
+                self._h = None
+        except Exception:
+            pass
+
+    # ---- host side ---------------------------------------------------------------------------
+    def stats(self) -> dict:
+        s = hag_stats_t()
+        _check(lib().hag_stats(self._h, ctypes.byref(s)))
+        return {k: getattr(s, k) for k, _ in s._fields_}
+
+    def get_merges(self):
+        n = ctypes.c_int64()
+        l, r, red = ctypes.c_void_p(), ctypes.c_void_p(), ctypes.c_void_p()
+        _check(lib().hag_get_merges(self._h, ctypes.byref(n), ctypes.byref(l), ctypes.byref(r), ctypes.byref(red)))
+        return _view(l.value, n.value, np.int32), _view(r.value, n.value, np.int32), _view(red.value, n.value, np.int32)
+
+    def get_forward(self):
+        st = self.stats()
+        l, r, lp, hp, hc = (ctypes.c_void_p() for _ in range(5))
+        nl = ctypes.c_int32()
+        _check(lib().hag_get_forward(self._h, ctypes.byref(l), ctypes.byref(r), ctypes.byref(lp), ctypes.byref(nl),
+                                     ctypes.byref(hp), ctypes.byref(hc)))
+        return dict(agg_left=_view(l.value, st["a"], np.int32), agg_right=_view(r.value, st["a"], np.int32),
+                    level_ptr=_view(lp.value, nl.value + 1, np.int32), n_levels=nl.value,
+                    hrowptr=_view(hp.value, st["n"] + 1, np.int64), hcol=_view(hc.value, st["h"], np.int32))
+
+    def prefix(self, n_merges) -> "Hag":
+        out = ctypes.c_void_p()
+        _check(lib().hag_prefix(self._h, int(n_merges), ctypes.byref(out)))
+        return Hag(out.value)
+
+    def algorithmic_bytes(self, which, op, d) -> int:
+        return int(lib().hag_algorithmic_bytes(self._h, which, OPS[op], int(d)))
+
+    # ---- device side -------------------------------------------------------------------------
+    def upload(self):
+        _check(lib().hag_upload(self._h, _stream_ptr()))
+        return self
+
+    def workspace_bytes(self, op, dtype_code, d) -> int:
+        return int(lib().hag_workspace_bytes(self._h, OPS[op], dtype_code, int(d)))
+
+    def _workspace(self, op, t):
+        import torch
+        nbytes = self.workspace_bytes(op, _dtype_code(t), t.shape[1])
+        key = (t.device.index,)
+        ws = self._ws.get(key)
+        if ws is None or ws.numel() < nbytes:
+            ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=t.device)
+            self._ws[key] = ws
+        return ws
+
+    def _fwd(self, fn, x, op, y, argmax, workspace):
+        import torch
+        n, d = x.shape
+        if y is None:
+            y = torch.empty_like(x)
+        if op == "max" and argmax is None:
+            argmax = torch.empty((n, d), dtype=torch.int32, device=x.device)
+        ws = workspace if workspace is not None else self._workspace(op, x)
+        _check(fn(self._h, OPS[op], _dtype_code(x), d, _dev_ptr(x), _dev_ptr(y), _dev_ptr(argmax), _dev_ptr(ws),
+                  _stream_ptr()))
+        return (y, argmax) if op == "max" else y
+
+    def _bwd(self, fn, gy, op, argmax, gx, workspace):
+        import torch
+        n, d = gy.shape
+        if gx is None:
+            gx = torch.empty_like(gy)
+        ws = workspace if workspace is not None else self._workspace(op, gy)
+        _check(fn(self._h, OPS[op], _dtype_code(gy), d, _dev_ptr(gy), _dev_ptr(argmax), _dev_ptr(gx), _dev_ptr(ws),
+                  _stream_ptr()))
+        return gx
+
+    def forward(self, x, op="sum", y=None, argmax=None, workspace=None):
+        return self._fwd(lib().hag_forward, x, op, y, argmax, workspace)
+
+    def backward(self, gy, op="sum", argmax=None, gx=None, workspace=None):
+        return self._bwd(lib().hag_backward, gy, op, argmax, gx, workspace)
+
+    def naive_forward(self, x, op="sum", y=None, argmax=None, workspace=None):
+        return self._fwd(lib().hag_naive_forward, x, op, y, argmax, workspace)
+
+    def naive_backward(self, gy, op="sum", argmax=None, gx=None, workspace=None):
+        return self._bwd(lib().hag_naive_backward, gy, op, argmax, gx, workspace)
+
+
+def hag_search(rowptr, col, capacity, flags=HAG_SEARCH_CANONICAL, max_depth=0) -> Hag:
+    rowptr, col = _np(rowptr, np.int64), _np(col, np.int32)
+    out = ctypes.c_void_p()
+    _check(lib().hag_search(rowptr.size - 1, rowptr.ctypes.data, col.ctypes.data, int(capacity), flags, max_depth,
+                            ctypes.byref(out)))
+    return Hag(out.value)
+
+
+def hag_search_batched(rowptr, col, graph_ptr, capacity_fraction, flags=HAG_SEARCH_CANONICAL, max_depth=0) -> Hag:
+    rowptr, col, graph_ptr = _np(rowptr, np.int64), _np(col, np.int32), _np(graph_ptr, np.int64)
+    out = ctypes.c_void_p()
+    _check(lib().hag_search_batched(rowptr.size - 1, rowptr.ctypes.data, col.ctypes.data, graph_ptr.size - 1,
+                                    graph_ptr.ctypes.data, float(capacity_fraction), flags, max_depth,
+                                    ctypes.byref(out)))
+    return Hag(out.value)
+
+
+def hag_from_merges(rowptr, col, left, right, flags=0) -> Hag:
+    rowptr, col = _np(rowptr, np.int64), _np(col, np.int32)
+    left, right = _np(left, np.int32), _np(right, np.int32)
+    out = ctypes.c_void_p()
+    _check(lib().hag_from_merges(rowptr.size - 1, rowptr.ctypes.data, col.ctypes.data, left.size,
+                                 left.ctypes.data, right.ctypes.data, flags, ctypes.byref(out)))
+    return Hag(out.value)

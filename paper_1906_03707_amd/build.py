@@ -1,0 +1,34 @@
+"""Build libhag.so (host C++ + HIP kernels for gfx950) in-tree with hipcc."""
+from __future__ import annotations
+
+import os
+import subprocess
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+ROOT = os.path.dirname(HERE)
+LIB = os.path.join(HERE, "libhag.so")
+SOURCES = [os.path.join(HERE, "csrc", "hag_host.cpp"), os.path.join(HERE, "csrc", "hag_device.hip")]
+HEADERS = [os.path.join(HERE, "csrc", "hag_internal.hpp"), os.path.join(ROOT, "include", "hag.h")]
+
+
+def build_library(force: bool = True, verbose: bool = False) -> str:
+    if not force and os.path.exists(LIB):
+        newest = max(os.path.getmtime(p) for p in SOURCES + HEADERS)
+        if os.path.getmtime(LIB) >= newest:
+            return LIB
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    cmd = [
+        hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
+        "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
+        "-Wall", "-Wno-unused-function",
+        "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
+        *SOURCES, "-o", LIB, "-lpthread",
+    ]
+    if verbose:
+        print(" ".join(cmd))
+    subprocess.check_call(cmd)
+    return LIB
+
+
+if __name__ == "__main__":
+    print(build_library(force=True, verbose=True))

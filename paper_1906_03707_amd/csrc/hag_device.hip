@@ -1,0 +1,514 @@
+// Device side of libhag for gfx950 (MI355X): the kernels of Algorithm 2 and of its
+// transposed pass, and the C entry points that enqueue them.
+//
+// The path is a sparse gather-reduce (about one add or compare per four bytes
+// loaded), so it is bound by memory traffic, not by arithmetic: there is no MFMA
+// here.  What matters is that every neighbour row is fetched with full-width
+// coalesced 16-byte loads, that enough independent loads are in flight per wave,
+// and that work is balanced across 256 compute units although row lengths are
+// heavy-tailed.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <string>
+
+#include "hag_internal.hpp"
+
+namespace hag {
+
+constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes
+constexpr int kWave = 64;
+
+enum { R_SUM = 0, R_MAX = 1 };
+
+template <typename T> struct V4;
+template <> struct V4<float> { using type = float4; };
+template <> struct V4<int32_t> { using type = int4; };
+
+template <typename T>
+struct GatherArgs {
+    const Item *items;
+    int64_t n_items;
+    const int32_t *col;
+    const T *src_lo;          // rows of ids < split
+    const T *src_hi;          // rows of ids >= split, row (id - split)
+    const int32_t *id_hi;     // R_MAX: winning original ids stored beside src_hi rows
+    int32_t split;
+    T *out;                   // final rows, row (item.row - out_off)
+    int32_t *out_id;          // R_MAX
+    int32_t out_off;
+    T *part;                  // partial slots of split rows
+    int32_t *part_id;         // R_MAX
+    const float *in_scale;    // optional: multiplies rows of ids < split (mean, transposed pass)
+    const float *out_scale;   // optional: multiplies final rows (mean, forward), indexed by item.row
+    int32_t d;
+};
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ int4 ld4(const int32_t *p) { return *reinterpret_cast<const int4 *>(p); }
+__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ void st4(int32_t *p, int4 v) { *reinterpret_cast<int4 *>(p) = v; }
+
+__device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+// int32 sums wrap modulo 2^32: add as unsigned
+__device__ __forceinline__ void add4(int4 &a, const int4 &b) {
+    a.x = (int)((unsigned)a.x + (unsigned)b.x); a.y = (int)((unsigned)a.y + (unsigned)b.y);
+    a.z = (int)((unsigned)a.z + (unsigned)b.z); a.w = (int)((unsigned)a.w + (unsigned)b.w);
+}
+__device__ __forceinline__ void scale4(float4 &a, float s) { a.x *= s; a.y *= s; a.z *= s; a.w *= s; }
+__device__ __forceinline__ void scale4(int4 &, float) {}
+
+// (value, id) max with ties to the smaller id; id < 0 means "nothing yet"
+template <typename S>
+__device__ __forceinline__ void max1(S &v, int &vi, S w, int wi) {
+    bool take = (wi >= 0) && (vi < 0 || w > v || (w == v && wi < vi));
+    v = take ? w : v;
+    vi = take ? wi : vi;
+}
+template <typename V>
+__device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi) {
+    max1(v.x, vi.x, w.x, wi.x); max1(v.y, vi.y, w.y, wi.y);
+    max1(v.z, vi.z, w.z, wi.z); max1(v.w, vi.w, w.w, wi.w);
+}
+
+// Gather-reduce.  A sub-group of LPR lanes owns one item; lane sl of the sub-group owns
+// the four consecutive features starting at (blockIdx.y * LPR + sl) * 4, so one neighbour
+// row is fetched by LPR adjacent lanes as one contiguous run of 16-byte loads.  Column
+// indices are read LPR at a time (coalesced) and handed round inside the sub-group with
+// cross-lane reads; four neighbour rows are requested before the first is consumed.
+template <typename T, int RED, int LPR>
+__global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
+    using V = typename V4<T>::type;
+    constexpr int SG = kWave / LPR;
+    const int lane = threadIdx.x & (kWave - 1);
+    const int wave = threadIdx.x / kWave;
+    const int sg = lane / LPR, sl = lane % LPR;
+    const int64_t item_idx = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * SG + sg;
+    const bool has_item = item_idx < A.n_items;
+    Item it{0, 0, 0};
+    if (has_item) {
+        const int4 raw = *reinterpret_cast<const int4 *>(A.items + item_idx);
+        it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)raw.y << 32);
+        it.cnt = raw.z;
+        it.row = raw.w;
+    }
+    const int cbase = (blockIdx.y * LPR + sl) * 4;
+    const bool col_ok = cbase < A.d;
+    int maxcnt = it.cnt;
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
+
+    V acc{};  // zero
+    int4 acc_id = make_int4(-1, -1, -1, -1);
+    const size_t d = (size_t)A.d;
+
+    for (int base = 0; base < maxcnt; base += LPR) {
+        const int mine = (base + sl < it.cnt) ? A.col[it.beg + base + sl] : -1;
+        const int lim = min(LPR, maxcnt - base);
+        for (int j = 0; j < lim; j += 4) {
+            int idx[4];
+            V val[4];
+            int4 vid[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) idx[k] = __shfl(mine, j + k, LPR);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                val[k] = V{};
+                vid[k] = make_int4(-1, -1, -1, -1);
+                if (idx[k] >= 0 && col_ok) {
+                    if (idx[k] < A.split) {
+                        val[k] = ld4(A.src_lo + (size_t)idx[k] * d + cbase);
+                        if (A.in_scale) scale4(val[k], A.in_scale[idx[k]]);
+                        if (RED == R_MAX) vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);
+                    } else {
+                        const size_t o = (size_t)(idx[k] - A.split) * d + cbase;
+                        val[k] = ld4(A.src_hi + o);
+                        if (RED == R_MAX) vid[k] = ld4(A.id_hi + o);
+                    }
+                }
+            }
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                if (RED == R_MAX) max4(acc, acc_id, val[k], vid[k]);
+                else add4(acc, val[k]);
+            }
+        }
+    }
+    if (has_item && col_ok) {
+        if (it.row >= 0) {
+            if (A.out_scale) scale4(acc, A.out_scale[it.row]);
+            const size_t o = (size_t)(it.row - A.out_off) * d + cbase;
+            st4(A.out + o, acc);
+            if (RED == R_MAX) st4(A.out_id + o, acc_id);
+        } else {
+            const size_t o = (size_t)(~it.row) * d + cbase;
+            st4(A.part + o, acc);
+            if (RED == R_MAX) st4(A.part_id + o, acc_id);
+        }
+    }
+}
+
+// One level of aggregation nodes (Algorithm 2, the loop over V_A): every node has exactly
+// two inputs, so the work is uniform: one thread per four features of one node.
+template <typename T, int RED>
+__global__ __launch_bounds__(kBlock) void level_kernel(const int32_t *__restrict__ left,
+                                                       const int32_t *__restrict__ right, int32_t first,
+                                                       int32_t last, int32_t n, int32_t d, const T *__restrict__ x,
+                                                       T *w, int32_t *wid) {
+    using V = typename V4<T>::type;
+    const int q = d / 4;
+    const int64_t t = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    const int64_t node = first + t / q;
+    if (node >= last) return;
+    const int c = (int)(t % q) * 4;
+    const int l = left[node], r = right[node];
+    V a, b;
+    int4 ai, bi;
+    if (l < n) {
+        a = ld4(x + (size_t)l * d + c);
+        ai = make_int4(l, l, l, l);
+    } else {
+        a = ld4(w + (size_t)(l - n) * d + c);
+        if (RED == R_MAX) ai = ld4(wid + (size_t)(l - n) * d + c);
+    }
+    if (r < n) {
+        b = ld4(x + (size_t)r * d + c);
+        bi = make_int4(r, r, r, r);
+    } else {
+        b = ld4(w + (size_t)(r - n) * d + c);
+        if (RED == R_MAX) bi = ld4(wid + (size_t)(r - n) * d + c);
+    }
+    if (RED == R_MAX) {
+        max4(a, ai, b, bi);
+        st4(wid + (size_t)node * d + c, ai);
+    } else {
+        add4(a, b);
+    }
+    st4(w + (size_t)node * d + c, a);
+}
+
+template <typename T>
+__global__ __launch_bounds__(kBlock) void fill_zero_kernel(T *p, int64_t n4) {
+    using V = typename V4<T>::type;
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i < n4) st4(p + i * 4, V{});
+}
+
+__device__ __forceinline__ void atomic_accumulate(float *p, float v) { unsafeAtomicAdd(p, v); }
+__device__ __forceinline__ void atomic_accumulate(int32_t *p, int32_t v) { atomicAdd(p, v); }
+
+// Transposed pass of max: each output element sends its gradient to the one source that won.
+template <typename T>
+__global__ __launch_bounds__(kBlock) void max_backward_kernel(const T *__restrict__ gy,
+                                                              const int32_t *__restrict__ argmax, T *gx,
+                                                              int64_t total, int32_t d) {
+    int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x;
+    if (i >= total) return;
+    int u = argmax[i];
+    if (u >= 0) atomic_accumulate(gx + (size_t)u * d + (i % d), gy[i]);
+}
+
+// ------------------------------------------------------------------------------------------
+// launch helpers
+// ------------------------------------------------------------------------------------------
+static int hip_fail(hipError_t e, const char *what) {
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return HAG_EHIP;
+}
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) return hip_fail(_e, #expr); \
+    } while (0)
+
+static int pick_lpr(int64_t d) {
+    int64_t q = d / 4;
+    int l = 4;
+    while (l < 64 && l < q) l <<= 1;
+    return l;
+}
+
+template <typename T, int RED, int LPR>
+static int launch_gather_lpr(const GatherArgs<T> &a, hipStream_t s) {
+    constexpr int SG = kWave / LPR;
+    const int64_t per_block = (kBlock / kWave) * SG;
+    const int64_t gx = (a.n_items + per_block - 1) / per_block;
+    const int64_t gy = (a.d / 4 + LPR - 1) / LPR;
+    if (gx <= 0) return HAG_OK;
+    if (gx > 0x7fffffffLL || gy > 65535) { set_error("launch too large"); return HAG_EINVAL; }
+    hipLaunchKernelGGL((gather_kernel<T, RED, LPR>), dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, a);
+    HIP_TRY(hipGetLastError());
+    return HAG_OK;
+}
+
+template <typename T, int RED>
+static int launch_gather(const GatherArgs<T> &a, hipStream_t s) {
+    switch (pick_lpr(a.d)) {
+        case 4: return launch_gather_lpr<T, RED, 4>(a, s);
+        case 8: return launch_gather_lpr<T, RED, 8>(a, s);
+        case 16: return launch_gather_lpr<T, RED, 16>(a, s);
+        case 32: return launch_gather_lpr<T, RED, 32>(a, s);
+        default: return launch_gather_lpr<T, RED, 64>(a, s);
+    }
+}
+
+struct Workspace {
+    char *agg = nullptr;      // [a, d] aggregation-node rows (forward) or their gradients (transposed pass)
+    char *part = nullptr;     // [max_slots, d]
+    char *agg_id = nullptr;   // max only
+    char *part_id = nullptr;  // max only
+    size_t total = 0;
+};
+
+static size_t align_up(size_t x) { return (x + 255) & ~(size_t)255; }
+
+static Workspace carve(const hag_handle *h, hag_op_t op, int64_t d, void *base) {
+    Workspace w;
+    size_t row = (size_t)d * 4;
+    size_t s_agg = align_up((size_t)h->a * row), s_part = align_up((size_t)h->max_slots * row);
+    char *p = (char *)base;
+    w.agg = p; p += s_agg;
+    w.part = p; p += s_part;
+    if (op == HAG_MAX) {
+        w.agg_id = p; p += s_agg;
+        w.part_id = p; p += s_part;
+    }
+    w.total = (size_t)(p - (char *)base);
+    return w;
+}
+
+// run one schedule: the gather itself, then the fold of split rows
+template <typename T, int RED>
+static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, GatherArgs<T> a, const Workspace &w,
+                    hipStream_t s) {
+    a.items = p.d_items;
+    a.n_items = (int64_t)p.items.size();
+    a.col = d_col;
+    a.part = (T *)w.part;
+    a.part_id = (int32_t *)w.part_id;
+    int rc = launch_gather<T, RED>(a, s);
+    if (rc) return rc;
+    if (!p.combine.empty()) {
+        GatherArgs<T> c = a;
+        c.items = p.d_combine;
+        c.n_items = (int64_t)p.combine.size();
+        c.col = h->d_slot_ids;
+        c.split = 0;               // every id refers to a partial slot
+        c.src_lo = nullptr;
+        c.src_hi = (const T *)w.part;
+        c.id_hi = (const int32_t *)w.part_id;
+        c.in_scale = nullptr;
+        rc = launch_gather<T, RED>(c, s);
+    }
+    return rc;
+}
+
+static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *in, const void *out,
+                        const void *ws, bool needs_ws) {
+    if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
+    if (!h->uploaded) { set_error("hag_upload has not been called on this handle"); return HAG_ESTATE; }
+    if (op != HAG_SUM && op != HAG_MEAN && op != HAG_MAX) { set_error("unknown op"); return HAG_EINVAL; }
+    if (dt != HAG_F32 && dt != HAG_I32) { set_error("unknown dtype"); return HAG_EINVAL; }
+    if (op == HAG_MEAN && dt != HAG_F32) { set_error("mean is defined for f32 only"); return HAG_EINVAL; }
+    if (d <= 0 || (d % 4) != 0) { set_error("d must be a positive multiple of 4"); return HAG_EINVAL; }
+    if (d > (1 << 20)) { set_error("d too large"); return HAG_EINVAL; }
+    if (h->n > 0 && (!in || !out)) { set_error("NULL feature pointer"); return HAG_EINVAL; }
+    if (((uintptr_t)in | (uintptr_t)out | (uintptr_t)ws) & 15) { set_error("pointers must be 16-byte aligned"); return HAG_EINVAL; }
+    if (needs_ws && !ws) { set_error("workspace is NULL but hag_workspace_bytes() > 0"); return HAG_EINVAL; }
+    return HAG_OK;
+}
+
+template <typename T, int RED>
+static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *x, T *y, int32_t *argmax,
+                        void *ws, hipStream_t s) {
+    Workspace w = carve(h, op, d, ws);
+    const int32_t n = (int32_t)h->n;
+    if (!naive) {
+        for (int32_t l = 1; l <= h->levels; ++l) {
+            int32_t first = h->level_ptr[l - 1], last = h->level_ptr[l];
+            int64_t threads = (int64_t)(last - first) * (d / 4);
+            if (threads <= 0) continue;
+            int64_t blocks = (threads + kBlock - 1) / kBlock;
+            hipLaunchKernelGGL((level_kernel<T, RED>), dim3((unsigned)blocks), dim3(kBlock), 0, s, h->d_left, h->d_right,
+                               first, last, n, (int32_t)d, x, (T *)w.agg, (int32_t *)w.agg_id);
+            HIP_TRY(hipGetLastError());
+        }
+    }
+    GatherArgs<T> a{};
+    a.src_lo = x;
+    a.src_hi = (const T *)w.agg;
+    a.id_hi = (const int32_t *)w.agg_id;
+    a.split = n;
+    a.out = y;
+    a.out_id = argmax;
+    a.out_off = 0;
+    a.in_scale = nullptr;
+    a.out_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.d = (int32_t)d;
+    return run_plan<T, RED>(h, naive ? h->p_naive_fwd : h->p_fwd, naive ? h->d_gcol : h->d_hcol, a, w, s);
+}
+
+template <typename T>
+static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *gy, const int32_t *argmax,
+                         T *gx, void *ws, hipStream_t s) {
+    const int32_t n = (int32_t)h->n;
+    if (op == HAG_MAX) {
+        int64_t total = h->n * d;
+        if (total == 0) return HAG_OK;
+        hipLaunchKernelGGL((fill_zero_kernel<T>), dim3((unsigned)((total / 4 + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                           s, gx, total / 4);
+        HIP_TRY(hipGetLastError());
+        hipLaunchKernelGGL((max_backward_kernel<T>), dim3((unsigned)((total + kBlock - 1) / kBlock)), dim3(kBlock), 0,
+                           s, gy, argmax, gx, total, (int32_t)d);
+        HIP_TRY(hipGetLastError());
+        return HAG_OK;
+    }
+    Workspace w = carve(h, op, d, ws);
+    GatherArgs<T> a{};
+    a.src_lo = gy;
+    a.src_hi = (const T *)w.agg;
+    a.id_hi = nullptr;
+    a.split = n;
+    a.in_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.out_scale = nullptr;
+    a.d = (int32_t)d;
+    if (naive) {
+        a.out = gx;
+        a.out_off = 0;
+        return run_plan<T, R_SUM>(h, h->p_naive_bwd, h->d_gtcol, a, w, s);
+    }
+    // deepest level first: its consumers are destinations only; level l may also be consumed
+    // by aggregation nodes of deeper levels, whose gradient rows are complete by then
+    for (int32_t l = h->levels; l >= 1; --l) {
+        a.out = (T *)w.agg;
+        a.out_off = n;
+        int rc = run_plan<T, R_SUM>(h, h->p_bwd_level[l - 1], h->d_tcol, a, w, s);
+        if (rc) return rc;
+    }
+    a.out = gx;
+    a.out_off = 0;
+    return run_plan<T, R_SUM>(h, h->p_bwd_src, h->d_tcol, a, w, s);
+}
+
+template <typename T>
+static int upload_array(hag_handle *h, const std::vector<T> &v, T **dst, hipStream_t s) {
+    *dst = nullptr;
+    if (v.empty()) return HAG_OK;
+    void *p = nullptr;
+    hipError_t e = hipMalloc(&p, v.size() * sizeof(T));
+    if (e != hipSuccess) { set_error(std::string("hipMalloc: ") + hipGetErrorString(e)); return HAG_ENOMEM; }
+    h->d_allocs.push_back(p);
+    HIP_TRY(hipMemcpyAsync(p, v.data(), v.size() * sizeof(T), hipMemcpyHostToDevice, s));
+    *dst = (T *)p;
+    return HAG_OK;
+}
+
+static int upload_plan(hag_handle *h, Plan &p, hipStream_t s) {
+    int rc = upload_array(h, p.items, &p.d_items, s);
+    if (rc) return rc;
+    return upload_array(h, p.combine, &p.d_combine, s);
+}
+
+void free_device(hag_handle *h) {
+    if (!h->d_allocs.empty()) {
+        int cur = -1;
+        bool sw = hipGetDevice(&cur) == hipSuccess && h->device >= 0 && cur != h->device;
+        if (sw) (void)hipSetDevice(h->device);
+        for (void *p : h->d_allocs) (void)hipFree(p);
+        if (sw) (void)hipSetDevice(cur);
+    }
+    h->d_allocs.clear();
+    h->uploaded = false;
+}
+
+}  // namespace hag
+
+using namespace hag;
+
+extern "C" {
+
+int hag_upload(hag_t *h, void *stream) {
+    if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
+    if (h->uploaded) return HAG_OK;
+    hipStream_t s = (hipStream_t)stream;
+    HIP_TRY(hipGetDevice(&h->device));
+    int rc = HAG_OK;
+    std::vector<int32_t> slots((size_t)h->max_slots);
+    for (size_t i = 0; i < slots.size(); ++i) slots[i] = (int32_t)i;
+    if ((rc = upload_array(h, h->left, &h->d_left, s))) goto bad;
+    if ((rc = upload_array(h, h->right, &h->d_right, s))) goto bad;
+    if ((rc = upload_array(h, h->hf.col, &h->d_hcol, s))) goto bad;
+    if ((rc = upload_array(h, h->ht.col, &h->d_tcol, s))) goto bad;
+    if ((rc = upload_array(h, h->g.col, &h->d_gcol, s))) goto bad;
+    if ((rc = upload_array(h, h->gt.col, &h->d_gtcol, s))) goto bad;
+    if ((rc = upload_array(h, slots, &h->d_slot_ids, s))) goto bad;
+    if ((rc = upload_array(h, h->inv_deg, &h->d_inv_deg, s))) goto bad;
+    if ((rc = upload_plan(h, h->p_fwd, s))) goto bad;
+    for (auto &p : h->p_bwd_level)
+        if ((rc = upload_plan(h, p, s))) goto bad;
+    if ((rc = upload_plan(h, h->p_bwd_src, s))) goto bad;
+    if ((rc = upload_plan(h, h->p_naive_fwd, s))) goto bad;
+    if ((rc = upload_plan(h, h->p_naive_bwd, s))) goto bad;
+    {
+        hipError_t e = hipStreamSynchronize(s);  // host vectors (slots) must outlive the copies
+        if (e != hipSuccess) { rc = hip_fail(e, "hipStreamSynchronize"); goto bad; }
+    }
+    h->uploaded = true;
+    return HAG_OK;
+bad:
+    (void)hipStreamSynchronize(s);
+    free_device(h);
+    return rc;
+}
+
+size_t hag_workspace_bytes(const hag_t *h, hag_op_t op, hag_dtype_t, int64_t d) {
+    if (!h || d <= 0) return 0;
+    return carve(h, op, d, nullptr).total;
+}
+
+static int forward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
+                         int32_t *argmax, void *ws, void *stream) {
+    int rc = check_common(h, op, dt, d, x, y, ws, hag_workspace_bytes(h, op, dt, d) > 0);
+    if (rc) return rc;
+    if (op == HAG_MAX && !argmax && h->n > 0) { set_error("argmax is required for max"); return HAG_EINVAL; }
+    if ((uintptr_t)argmax & 15) { set_error("argmax must be 16-byte aligned"); return HAG_EINVAL; }
+    if (x == y) { set_error("x and y must not alias"); return HAG_EINVAL; }
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == HAG_F32) {
+        if (op == HAG_MAX) return forward_impl<float, R_MAX>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s);
+        return forward_impl<float, R_SUM>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s);
+    }
+    if (op == HAG_MAX) return forward_impl<int32_t, R_MAX>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s);
+    return forward_impl<int32_t, R_SUM>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s);
+}
+
+static int backward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy,
+                          const int32_t *argmax, void *gx, void *ws, void *stream) {
+    int rc = check_common(h, op, dt, d, gy, gx, ws, op != HAG_MAX && hag_workspace_bytes(h, op, dt, d) > 0);
+    if (rc) return rc;
+    if (op == HAG_MAX && !argmax && h->n > 0) { set_error("argmax is required for max"); return HAG_EINVAL; }
+    if (gy == gx) { set_error("gy and gx must not alias"); return HAG_EINVAL; }
+    hipStream_t s = (hipStream_t)stream;
+    if (dt == HAG_F32) return backward_impl<float>(h, naive, op, d, (const float *)gy, argmax, (float *)gx, ws, s);
+    return backward_impl<int32_t>(h, naive, op, d, (const int32_t *)gy, argmax, (int32_t *)gx, ws, s);
+}
+
+int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y, int32_t *argmax,
+                void *ws, void *stream) {
+    return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream);
+}
+int hag_naive_forward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y, int32_t *argmax,
+                      void *ws, void *stream) {
+    return forward_entry(h, true, op, dt, d, x, y, argmax, ws, stream);
+}
+int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy, const int32_t *argmax,
+                 void *gx, void *ws, void *stream) {
+    return backward_entry(h, false, op, dt, d, gy, argmax, gx, ws, stream);
+}
+int hag_naive_backward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy, const int32_t *argmax,
+                       void *gx, void *ws, void *stream) {
+    return backward_entry(h, true, op, dt, d, gy, argmax, gx, ws, stream);
+}
+
+}  // extern "C"

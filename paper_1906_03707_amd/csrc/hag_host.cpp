@@ -1,0 +1,624 @@
+// Host side of libhag: input validation, the greedy HAG search (Algorithm 3, set
+// Aggregate), replay of a merge list, level ordering, transposes, launch
+// schedules and statistics.  No device code here.
+#include <algorithm>
+#include <atomic>
+#include <cmath>
+#include <cstdlib>
+#include <cstring>
+#include <memory>
+#include <new>
+#include <numeric>
+#include <queue>
+#include <thread>
+#include <tuple>
+
+#include "hag_internal.hpp"
+
+namespace hag {
+
+static thread_local std::string g_err;
+void set_error(const std::string &msg) { g_err = msg; }
+
+static int fail(int code, const std::string &msg) {
+    set_error(msg);
+    return code;
+}
+
+static unsigned host_threads() {
+    unsigned t = std::thread::hardware_concurrency();
+    if (const char *s = std::getenv("HAG_NUM_THREADS")) t = (unsigned)std::max(1, std::atoi(s));
+    if (const char *s = std::getenv("OMP_NUM_THREADS")) t = std::min(t, (unsigned)std::max(1, std::atoi(s)));
+    return std::max(1u, std::min(t, 64u));
+}
+
+template <class F>
+static void parallel_for(int64_t n, unsigned threads, F f) {
+    threads = (unsigned)std::min<int64_t>(threads, std::max<int64_t>(n, 1));
+    if (threads <= 1) {
+        for (int64_t i = 0; i < n; ++i) f(i, 0u);
+        return;
+    }
+    std::atomic<int64_t> next{0};
+    std::vector<std::thread> pool;
+    for (unsigned t = 0; t < threads; ++t)
+        pool.emplace_back([&, t] {
+            for (;;) {
+                int64_t i = next.fetch_add(1);
+                if (i >= n) break;
+                f(i, t);
+            }
+        });
+    for (auto &th : pool) th.join();
+}
+
+// ------------------------------------------------------------------------------------------
+// validation + copy of the input graph
+// ------------------------------------------------------------------------------------------
+static int load_graph(int64_t n, const int64_t *rowptr, const int32_t *col, uint32_t flags, Csr &g) {
+    if (n < 0) return fail(HAG_EINVAL, "n < 0");
+    if (!rowptr) return fail(HAG_EINVAL, "rowptr is NULL");
+    if (rowptr[0] != 0) return fail(HAG_EINVAL, "rowptr[0] != 0");
+    for (int64_t v = 0; v < n; ++v)
+        if (rowptr[v + 1] < rowptr[v]) return fail(HAG_EINVAL, "rowptr is not monotone at row " + std::to_string(v));
+    int64_t e = rowptr[n];
+    if (e > 0 && !col) return fail(HAG_EINVAL, "col is NULL");
+    for (int64_t i = 0; i < e; ++i)
+        if (col[i] < 0 || col[i] >= n) return fail(HAG_EINVAL, "col out of range at entry " + std::to_string(i));
+    g.ptr.assign(n + 1, 0);
+    g.col.clear();
+    g.col.reserve((size_t)e);
+    std::vector<int32_t> tmp;
+    for (int64_t v = 0; v < n; ++v) {
+        tmp.assign(col + rowptr[v], col + rowptr[v + 1]);
+        std::sort(tmp.begin(), tmp.end());
+        auto last = std::unique(tmp.begin(), tmp.end());
+        if (last != tmp.end()) {
+            if (!(flags & HAG_SEARCH_DEDUP))
+                return fail(HAG_EINVAL, "duplicate neighbour in row " + std::to_string(v) + " (a neighbourhood is a set; pass HAG_SEARCH_DEDUP to drop duplicates)");
+            tmp.erase(last, tmp.end());
+        }
+        g.col.insert(g.col.end(), tmp.begin(), tmp.end());
+        g.ptr[v + 1] = (int64_t)g.col.size();
+    }
+    return HAG_OK;
+}
+
+// rows of `t` = columns of `c`; `rows_out` = number of rows of t
+static void transpose(const Csr &c, int64_t rows_out, Csr &t) {
+    int64_t rows_in = (int64_t)c.ptr.size() - 1;
+    t.ptr.assign(rows_out + 1, 0);
+    for (int32_t x : c.col) t.ptr[x + 1]++;
+    for (int64_t i = 0; i < rows_out; ++i) t.ptr[i + 1] += t.ptr[i];
+    t.col.resize(c.col.size());
+    std::vector<int64_t> fill(t.ptr.begin(), t.ptr.end() - 1);
+    for (int64_t r = 0; r < rows_in; ++r)
+        for (int64_t i = c.ptr[r]; i < c.ptr[r + 1]; ++i) t.col[fill[c.col[i]]++] = (int32_t)r;
+}
+
+// ------------------------------------------------------------------------------------------
+// Working state of Algorithm 3: the current lists Nhat_u (u in V) and, for every HAG node x,
+// the sorted list out[x] of the u whose list holds x.
+// ------------------------------------------------------------------------------------------
+struct Builder {
+    int64_t n = 0;
+    const Csr *g = nullptr;
+    std::vector<int32_t> nb;        // lists, in place of g->col (a list never grows)
+    std::vector<int32_t> len;       // current length of each list
+    Csr gt;                         // out-lists of original nodes, shrunk in place
+    std::vector<int32_t> olen;
+    std::vector<std::vector<int32_t>> out_agg;
+    std::vector<int32_t> m_left, m_right, m_red, depth;
+    std::vector<int32_t> scratch;
+
+    void init(const Csr &graph) {
+        g = &graph;
+        n = (int64_t)graph.ptr.size() - 1;
+        nb = graph.col;
+        len.resize(n);
+        for (int64_t u = 0; u < n; ++u) len[u] = (int32_t)(graph.ptr[u + 1] - graph.ptr[u]);
+        transpose(graph, n, gt);
+        olen.resize(n);
+        for (int64_t x = 0; x < n; ++x) olen[x] = (int32_t)(gt.ptr[x + 1] - gt.ptr[x]);
+    }
+    int64_t a() const { return (int64_t)m_left.size(); }
+    const int32_t *out_ptr(int32_t x) const { return x < n ? gt.col.data() + gt.ptr[x] : out_agg[x - n].data(); }
+    int32_t out_len(int32_t x) const { return x < n ? olen[x] : (int32_t)out_agg[x - n].size(); }
+    int32_t depth_of(int32_t x) const { return x < n ? 0 : depth[x - n]; }
+
+    int32_t intersect(int32_t p, int32_t q, std::vector<int32_t> *dst) const {
+        const int32_t *a_ = out_ptr(p), *b_ = out_ptr(q);
+        int32_t la = out_len(p), lb = out_len(q), i = 0, j = 0, c = 0;
+        while (i < la && j < lb) {
+            if (a_[i] < b_[j]) ++i;
+            else if (a_[i] > b_[j]) ++j;
+            else { if (dst) dst->push_back(a_[i]); ++c; ++i; ++j; }
+        }
+        return c;
+    }
+    void remove_from_out(int32_t x, const std::vector<int32_t> &rm) {
+        int32_t *o = x < n ? gt.col.data() + gt.ptr[x] : out_agg[x - n].data();
+        int32_t l = out_len(x), k = 0;
+        size_t j = 0;
+        for (int32_t i = 0; i < l; ++i) {
+            while (j < rm.size() && rm[j] < o[i]) ++j;
+            if (j < rm.size() && rm[j] == o[i]) continue;
+            o[k++] = o[i];
+        }
+        if (x < n) olen[x] = k; else out_agg[x - n].resize(k);
+    }
+    // the rewrite loop of Algorithm 3 for the pair (p, q); returns the redundancy
+    int32_t apply_merge(int32_t p, int32_t q) {
+        scratch.clear();
+        int32_t r = intersect(p, q, &scratch);
+        int32_t w = (int32_t)(n + a());
+        for (int32_t u : scratch) {
+            int32_t *l = nb.data() + g->ptr[u];
+            int32_t k = 0, L = len[u];
+            for (int32_t i = 0; i < L; ++i)
+                if (l[i] != p && l[i] != q) l[k++] = l[i];
+            l[k++] = w;
+            len[u] = k;
+        }
+        remove_from_out(p, scratch);
+        remove_from_out(q, scratch);
+        out_agg.emplace_back(scratch);
+        m_left.push_back(std::min(p, q));
+        m_right.push_back(std::max(p, q));
+        m_red.push_back(r);
+        depth.push_back(1 + std::max(depth_of(p), depth_of(q)));
+        return r;
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// Algorithm 3 with lazily evaluated upper bounds.
+//
+// The listing asks for the pair of maximal Redundancy in every iteration.  A heap over all
+// co-occurring pairs is infeasible for dense graphs (sum over u of |N(u)|^2 / 2 entries), so
+// the heap here is over NODES: key[x] is an upper bound on max_y Redundancy(x, y).  Pair
+// redundancies of existing pairs never grow (a rewrite only removes members from lists) and
+// a new node w = (p, q) satisfies Redundancy(x, w) <= Redundancy(x, p), so a bound stays
+// valid until it is re-evaluated, and an exact value (partner y, count c) stays exact until
+// x or y takes part in a merge that changes Redundancy(x, y).  The heap is ordered by
+// (key descending, id ascending) and the partner tie-break is the smallest id, which makes
+// the chosen pair the lexicographically smallest one of maximal redundancy.
+// ------------------------------------------------------------------------------------------
+struct Searcher {
+    Builder b;
+    int64_t capacity = 0;
+    int32_t max_depth = 0;
+    std::vector<int32_t> key, partner, version;
+    std::vector<int64_t> eval_stamp, mod_stamp;   // iteration numbers
+    std::vector<uint8_t> exact;
+    int64_t iter = 1;
+    using Entry = std::tuple<int32_t, int32_t, int32_t>;  // key, -id, version
+    std::priority_queue<Entry> heap;
+    unsigned threads = 1;
+    bool single_thread = false;
+    std::vector<std::vector<int32_t>> cnt, touched;
+
+    void push(int32_t x) {
+        version[x]++;
+        if (key[x] >= 2) heap.emplace(key[x], -x, version[x]);
+    }
+    bool mergeable(int32_t x) const { return max_depth <= 0 || b.depth_of(x) < max_depth; }
+
+    // exact best partner of x: one counting sweep over the lists that hold x
+    void evaluate(int32_t x, unsigned t) {
+        auto &c = cnt[t];
+        auto &tl = touched[t];
+        tl.clear();
+        const int32_t *o = b.out_ptr(x);
+        int32_t ol = b.out_len(x);
+        for (int32_t i = 0; i < ol; ++i) {
+            int32_t u = o[i];
+            const int32_t *l = b.nb.data() + b.g->ptr[u];
+            int32_t L = b.len[u];
+            for (int32_t j = 0; j < L; ++j) {
+                int32_t y = l[j];
+                if (c[y]++ == 0) tl.push_back(y);
+            }
+        }
+        int32_t best = 0, by = -1;
+        for (int32_t y : tl) {
+            int32_t v = c[y];
+            c[y] = 0;
+            if (y == x || !mergeable(y)) continue;
+            if (v > best || (v == best && y < by)) { best = v; by = y; }
+        }
+        key[x] = best;
+        partner[x] = by;
+        exact[x] = 1;
+        eval_stamp[x] = iter;
+    }
+
+    bool still_valid(int32_t x) {
+        if (!exact[x]) return false;
+        if (mod_stamp[x] >= eval_stamp[x]) return false;
+        int32_t y = partner[x];
+        if (y < 0) return true;
+        if (mod_stamp[y] >= eval_stamp[x]) {
+            // the partner changed; the value survives only if the shared lists did not
+            if (b.intersect(x, y, nullptr) != key[x]) return false;
+            eval_stamp[x] = iter;
+        }
+        return true;
+    }
+
+    void run() {
+        int64_t n = b.n, m = n + capacity;
+        key.assign(m, 0); partner.assign(m, -1); version.assign(m, 0);
+        eval_stamp.assign(m, 0); mod_stamp.assign(m, 0); exact.assign(m, 0);
+        threads = single_thread ? 1u : host_threads();
+        cnt.assign(threads, std::vector<int32_t>(m, 0));
+        touched.assign(threads, {});
+        for (int64_t x = 0; x < n; ++x) { key[x] = b.olen[x]; push((int32_t)x); }
+        std::vector<int32_t> batch, dirty;
+        while (b.a() < capacity) {
+            int32_t chosen = -1;
+            while (!heap.empty()) {
+                batch.clear();
+                dirty.clear();
+                // take the top entries: the first decides, the rest are evaluated speculatively
+                while (!heap.empty() && batch.size() < threads) {
+                    auto [k, negx, ver] = heap.top();
+                    int32_t x = -negx;
+                    if (ver != version[x]) { heap.pop(); continue; }
+                    if (!batch.empty() && k < key[batch[0]] / 2) break;
+                    heap.pop();
+                    batch.push_back(x);
+                }
+                if (batch.empty()) break;
+                bool top_valid = still_valid(batch[0]);
+                if (top_valid) {
+                    chosen = batch[0];
+                    for (size_t i = 1; i < batch.size(); ++i) heap.emplace(key[batch[i]], -batch[i], version[batch[i]]);
+                    break;
+                }
+                for (int32_t x : batch) {
+                    if (still_valid(x)) heap.emplace(key[x], -x, version[x]);
+                    else dirty.push_back(x);
+                }
+                parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { evaluate(dirty[i], t); });
+                for (int32_t x : dirty) push(x);
+            }
+            if (chosen < 0 || key[chosen] < 2) break;
+            int32_t p = chosen, q = partner[chosen];
+            b.apply_merge(p, q);
+            int32_t w = (int32_t)(b.n + b.a() - 1);
+            mod_stamp[p] = mod_stamp[q] = iter;
+            ++iter;
+            for (int32_t x : {p, q}) {
+                exact[x] = 0;
+                key[x] = std::min(key[x], b.out_len(x));
+                push(x);
+            }
+            exact[w] = 0;
+            key[w] = mergeable(w) ? b.out_len(w) : 0;
+            push(w);
+        }
+    }
+};
+
+// ------------------------------------------------------------------------------------------
+// schedules
+// ------------------------------------------------------------------------------------------
+static int64_t env_i64(const char *name, int64_t dflt) {
+    const char *s = std::getenv(name);
+    return s ? std::atoll(s) : dflt;
+}
+
+static int length_class(int32_t cnt) {
+    if (cnt <= 16) return cnt;
+    int lg = 31 - __builtin_clz((unsigned)cnt);         // >= 4
+    return 16 + (lg - 4) * 4 + ((cnt >> (lg - 2)) & 3);  // quarter-octave classes
+}
+
+void build_plan(const Csr &c, int64_t row_begin, int64_t row_end, Plan &p) {
+    const int64_t chunk = env_i64("HAG_CHUNK", 1024);
+    const int64_t split_above = env_i64("HAG_SPLIT_ABOVE", 1536);
+    p.items.clear();
+    p.combine.clear();
+    p.n_slots = 0;
+    for (int64_t r = row_begin; r < row_end; ++r) {
+        int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
+        if (cnt <= split_above) {
+            p.items.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
+        } else {
+            int64_t pieces = (cnt + chunk - 1) / chunk;
+            int64_t per = (cnt + pieces - 1) / pieces;
+            p.combine.push_back(Item{p.n_slots, (int32_t)pieces, (int32_t)r});
+            for (int64_t k = 0; k < pieces; ++k) {
+                int64_t b0 = beg + k * per, b1 = std::min(beg + cnt, b0 + per);
+                p.items.push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots + k)});
+            }
+            p.n_slots += pieces;
+        }
+    }
+    std::stable_sort(p.items.begin(), p.items.end(),
+                     [](const Item &x, const Item &y) { return length_class(x.cnt) > length_class(y.cnt); });
+}
+
+// ------------------------------------------------------------------------------------------
+// finalisation: levels, level-ordered forward form, transposes, schedules, statistics
+// ------------------------------------------------------------------------------------------
+static int finalize_from_builder(hag_handle *h, Builder &b) {
+    const int64_t n = b.n, a = b.a();
+    h->n = n;
+    h->a = a;
+    h->e = (int64_t)h->g.col.size();
+    h->m_left = b.m_left;
+    h->m_right = b.m_right;
+    h->m_red = b.m_red;
+    // depth(original) = 0, depth(w) = 1 + max over its inputs; creation order is topological
+    std::vector<int32_t> order(a);
+    std::iota(order.begin(), order.end(), 0);
+    std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) { return b.depth[x] < b.depth[y]; });
+    std::vector<int32_t> newid(a);
+    for (int64_t i = 0; i < a; ++i) newid[order[i]] = (int32_t)(n + i);
+    auto remap = [&](int32_t x) { return x < n ? x : newid[x - n]; };
+    h->levels = a ? b.depth[order[a - 1]] : 0;
+    h->left.resize(a);
+    h->right.resize(a);
+    h->level_ptr.assign(h->levels + 1, 0);
+    for (int64_t i = 0; i < a; ++i) {
+        int32_t c = order[i];
+        int32_t l = remap(b.m_left[c]), r = remap(b.m_right[c]);
+        h->left[i] = std::min(l, r);
+        h->right[i] = std::max(l, r);
+        h->level_ptr[b.depth[c]] = (int32_t)(i + 1);
+    }
+    for (int32_t l = 1; l <= h->levels; ++l) h->level_ptr[l] = std::max(h->level_ptr[l], h->level_ptr[l - 1]);
+    // Nhat_v, level-order ids, ascending
+    h->hf.ptr.assign(n + 1, 0);
+    for (int64_t v = 0; v < n; ++v) h->hf.ptr[v + 1] = h->hf.ptr[v] + b.len[v];
+    h->hf.col.resize((size_t)h->hf.ptr[n]);
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t *dst = h->hf.col.data() + h->hf.ptr[v];
+        const int32_t *src = b.nb.data() + h->g.ptr[v];
+        for (int32_t i = 0; i < b.len[v]; ++i) dst[i] = remap(src[i]);
+        std::sort(dst, dst + b.len[v]);
+    }
+    // transposed HAG: consumers of every source
+    {
+        Csr all;  // rows: destinations 0..n-1 then aggregation nodes; cols: their in-neighbours
+        all.ptr.resize(n + a + 1);
+        all.col.reserve(h->hf.col.size() + 2 * (size_t)a);
+        all.col = h->hf.col;
+        for (int64_t v = 0; v <= n; ++v) all.ptr[v] = h->hf.ptr[v];
+        for (int64_t i = 0; i < a; ++i) {
+            all.col.push_back(h->left[i]);
+            all.col.push_back(h->right[i]);
+            all.ptr[n + i + 1] = (int64_t)all.col.size();
+        }
+        transpose(all, n + a, h->ht);
+    }
+    transpose(h->g, n, h->gt);
+    h->inv_deg.resize(n);
+    for (int64_t v = 0; v < n; ++v) {
+        int64_t d = h->g.ptr[v + 1] - h->g.ptr[v];
+        h->inv_deg[v] = 1.0f / (float)std::max<int64_t>(d, 1);
+    }
+    // schedules
+    build_plan(h->hf, 0, n, h->p_fwd);
+    h->p_bwd_level.assign(h->levels, Plan{});
+    for (int32_t l = 1; l <= h->levels; ++l)
+        build_plan(h->ht, n + h->level_ptr[l - 1], n + h->level_ptr[l], h->p_bwd_level[l - 1]);
+    build_plan(h->ht, 0, n, h->p_bwd_src);
+    build_plan(h->g, 0, n, h->p_naive_fwd);
+    build_plan(h->gt, 0, n, h->p_naive_bwd);
+    h->max_slots = std::max({h->p_fwd.n_slots, h->p_bwd_src.n_slots, h->p_naive_fwd.n_slots, h->p_naive_bwd.n_slots});
+    for (auto &p : h->p_bwd_level) h->max_slots = std::max(h->max_slots, p.n_slots);
+    // statistics (Section 4.1: k in-neighbours cost k-1 binary aggregations; Section 5.4: one
+    // row transfer per aggregated neighbour)
+    hag_stats_t &s = h->st;
+    s = hag_stats_t{};
+    s.n = n; s.e = h->e; s.a = a; s.levels = h->levels;
+    s.h = (int64_t)h->hf.col.size();
+    s.e_hag = s.h + 2 * a;
+    for (int64_t v = 0; v < n; ++v) {
+        int64_t d = h->g.ptr[v + 1] - h->g.ptr[v], dh = h->hf.ptr[v + 1] - h->hf.ptr[v];
+        s.aggr_naive += std::max<int64_t>(d - 1, 0);
+        s.aggr_hag += std::max<int64_t>(dh - 1, 0);
+        s.max_degree = std::max(s.max_degree, d);
+        s.max_hag_degree = std::max(s.max_hag_degree, dh);
+    }
+    s.aggr_hag += a;
+    s.xfer_naive = s.e;
+    s.xfer_hag = s.e_hag;
+    return HAG_OK;
+}
+
+static int replay(hag_handle *h, int64_t n_merges, const int32_t *left, const int32_t *right) {
+    Builder b;
+    b.init(h->g);
+    for (int64_t i = 0; i < n_merges; ++i) {
+        int64_t lim = b.n + i;
+        if (left[i] < 0 || right[i] < 0 || left[i] >= lim || right[i] >= lim)
+            return fail(HAG_EINVAL, "merge " + std::to_string(i) + " refers to a node that does not exist yet");
+        if (left[i] == right[i]) return fail(HAG_EINVAL, "merge " + std::to_string(i) + " has equal inputs");
+        if (b.apply_merge(left[i], right[i]) < 1)
+            return fail(HAG_EINVAL, "merge " + std::to_string(i) + " is used by no list");
+    }
+    return finalize_from_builder(h, b);
+}
+
+}  // namespace hag
+
+using namespace hag;
+
+extern "C" {
+
+const char *hag_last_error(void) { return g_err.c_str(); }
+
+int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, uint32_t flags,
+               int32_t max_depth, hag_t **out) {
+    if (!out) return fail(HAG_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (capacity < 0) return fail(HAG_EINVAL, "capacity < 0");
+    if (max_depth < 0) return fail(HAG_EINVAL, "max_depth < 0");
+    if (n + capacity >= (int64_t)INT32_MAX) return fail(HAG_EINVAL, "n + capacity must be below 2^31");
+    try {
+        std::unique_ptr<hag_handle> h(new hag_handle);
+        int rc = load_graph(n, rowptr, col, flags, h->g);
+        if (rc) return rc;
+        Searcher s;
+        s.capacity = capacity;
+        s.max_depth = max_depth;
+        s.b.init(h->g);
+        if (capacity > 0) s.run();
+        rc = finalize_from_builder(h.get(), s.b);
+        if (rc) return rc;
+        *out = h.release();
+        return HAG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(HAG_ENOMEM, "out of host memory");
+    }
+}
+
+int hag_search_batched(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_graphs,
+                       const int64_t *graph_ptr, double capacity_fraction, uint32_t flags, int32_t max_depth,
+                       hag_t **out) {
+    if (!out) return fail(HAG_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (n_graphs < 0 || !graph_ptr) return fail(HAG_EINVAL, "bad graph_ptr");
+    if (capacity_fraction < 0) return fail(HAG_EINVAL, "capacity_fraction < 0");
+    if (max_depth < 0) return fail(HAG_EINVAL, "max_depth < 0");
+    if (graph_ptr[0] != 0 || graph_ptr[n_graphs] != n) return fail(HAG_EINVAL, "graph_ptr must span 0..n");
+    for (int64_t gi = 0; gi < n_graphs; ++gi)
+        if (graph_ptr[gi + 1] < graph_ptr[gi]) return fail(HAG_EINVAL, "graph_ptr is not monotone");
+    try {
+        std::unique_ptr<hag_handle> h(new hag_handle);
+        int rc = load_graph(n, rowptr, col, flags, h->g);
+        if (rc) return rc;
+        for (int64_t gi = 0; gi < n_graphs; ++gi)
+            for (int64_t v = graph_ptr[gi]; v < graph_ptr[gi + 1]; ++v)
+                for (int64_t i = h->g.ptr[v]; i < h->g.ptr[v + 1]; ++i)
+                    if (h->g.col[i] < graph_ptr[gi] || h->g.col[i] >= graph_ptr[gi + 1])
+                        return fail(HAG_EINVAL, "edge crosses graphs at row " + std::to_string(v));
+        // search every graph on its own (local ids), in parallel
+        struct Local { std::vector<int32_t> l, r; };
+        std::vector<Local> res(n_graphs);
+        parallel_for(n_graphs, host_threads(), [&](int64_t gi, unsigned) {
+            int64_t v0 = graph_ptr[gi], nv = graph_ptr[gi + 1] - v0;
+            Csr sub;
+            sub.ptr.resize(nv + 1);
+            for (int64_t v = 0; v <= nv; ++v) sub.ptr[v] = h->g.ptr[v0 + v] - h->g.ptr[v0];
+            sub.col.resize((size_t)sub.ptr[nv]);
+            for (size_t i = 0; i < sub.col.size(); ++i) sub.col[i] = (int32_t)(h->g.col[h->g.ptr[v0] + i] - v0);
+            Searcher s;
+            s.capacity = (int64_t)std::floor(capacity_fraction * (double)nv);
+            s.max_depth = max_depth;
+            s.b.init(sub);
+            s.single_thread = true;
+            if (s.capacity > 0) s.run();
+            res[gi].l = s.b.m_left;
+            res[gi].r = s.b.m_right;
+        });
+        // concatenate: local aggregation node j of graph gi becomes n + offset[gi] + j
+        std::vector<int32_t> left, right;
+        int64_t off = 0;
+        for (int64_t gi = 0; gi < n_graphs; ++gi) {
+            int64_t v0 = graph_ptr[gi], nv = graph_ptr[gi + 1] - v0;
+            auto map = [&](int32_t x) { return (int32_t)(x < nv ? v0 + x : n + off + (x - nv)); };
+            for (size_t j = 0; j < res[gi].l.size(); ++j) {
+                left.push_back(map(res[gi].l[j]));
+                right.push_back(map(res[gi].r[j]));
+            }
+            off += (int64_t)res[gi].l.size();
+        }
+        rc = replay(h.get(), (int64_t)left.size(), left.data(), right.data());
+        if (rc) return rc;
+        *out = h.release();
+        return HAG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(HAG_ENOMEM, "out of host memory");
+    }
+}
+
+int hag_from_merges(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t n_merges, const int32_t *left,
+                    const int32_t *right, uint32_t flags, hag_t **out) {
+    if (!out) return fail(HAG_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (n_merges < 0 || (n_merges > 0 && (!left || !right))) return fail(HAG_EINVAL, "bad merge list");
+    if (n + n_merges >= (int64_t)INT32_MAX) return fail(HAG_EINVAL, "n + n_merges must be below 2^31");
+    try {
+        std::unique_ptr<hag_handle> h(new hag_handle);
+        int rc = load_graph(n, rowptr, col, flags, h->g);
+        if (rc) return rc;
+        rc = replay(h.get(), n_merges, left, right);
+        if (rc) return rc;
+        *out = h.release();
+        return HAG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(HAG_ENOMEM, "out of host memory");
+    }
+}
+
+int hag_prefix(const hag_t *src, int64_t n_merges, hag_t **out) {
+    if (!out) return fail(HAG_EINVAL, "out is NULL");
+    *out = nullptr;
+    if (!src) return fail(HAG_EINVAL, "handle is NULL");
+    if (n_merges < 0 || n_merges > src->a) return fail(HAG_EINVAL, "n_merges out of range");
+    try {
+        std::unique_ptr<hag_handle> h(new hag_handle);
+        h->g = src->g;
+        int rc = replay(h.get(), n_merges, src->m_left.data(), src->m_right.data());
+        if (rc) return rc;
+        *out = h.release();
+        return HAG_OK;
+    } catch (const std::bad_alloc &) {
+        return fail(HAG_ENOMEM, "out of host memory");
+    }
+}
+
+void hag_free(hag_t *h) {
+    if (!h) return;
+    free_device(h);
+    delete h;
+}
+
+int hag_stats(const hag_t *h, hag_stats_t *out) {
+    if (!h || !out) return fail(HAG_EINVAL, "NULL argument");
+    *out = h->st;
+    return HAG_OK;
+}
+
+int hag_get_merges(const hag_t *h, int64_t *n_merges, const int32_t **left, const int32_t **right,
+                   const int32_t **redundancy) {
+    if (!h) return fail(HAG_EINVAL, "handle is NULL");
+    if (n_merges) *n_merges = h->a;
+    if (left) *left = h->m_left.data();
+    if (right) *right = h->m_right.data();
+    if (redundancy) *redundancy = h->m_red.data();
+    return HAG_OK;
+}
+
+int hag_get_forward(const hag_t *h, const int32_t **agg_left, const int32_t **agg_right, const int32_t **level_ptr,
+                    int32_t *n_levels, const int64_t **hrowptr, const int32_t **hcol) {
+    if (!h) return fail(HAG_EINVAL, "handle is NULL");
+    if (agg_left) *agg_left = h->left.data();
+    if (agg_right) *agg_right = h->right.data();
+    if (level_ptr) *level_ptr = h->level_ptr.data();
+    if (n_levels) *n_levels = h->levels;
+    if (hrowptr) *hrowptr = h->hf.ptr.data();
+    if (hcol) *hcol = h->hf.col.data();
+    return HAG_OK;
+}
+
+int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d) {
+    if (!h || d <= 0) return -1;
+    const int64_t n = h->n, a = h->a, row = 4 * d;
+    bool naive = which >= 2, bwd = which & 1;
+    int64_t edges = naive ? h->e : h->st.e_hag;   // one row read per edge
+    int64_t rows_out = naive ? n : n + a;         // one row write per produced node
+    int64_t ptrs = bwd && !naive ? n + a + 1 : n + 1;
+    if (op == HAG_MAX && bwd)                     // argmax read, gy read, gx cleared, gx updated
+        return 4 * row * n;
+    int64_t bytes = row * edges + row * rows_out + 4 * edges + 8 * ptrs;
+    if (op == HAG_MAX) bytes += row * rows_out;   // winning ids written beside the values
+    return bytes;
+}
+
+}  // extern "C"

@@ -1,0 +1,178 @@
+"""GPU parity: the HIP path (through the C ABI) against the CPU oracle, element by element.
+
+Bars: int32 and max (values and argmax) bit-exact; fp32 sum / mean within
+|gpu - oracle| <= 1e-5 * sum|terms| per output element (the oracle accumulates in fp64).
+"""
+import numpy as np
+import pytest
+
+import oracle
+from paper_1906_03707_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1906_03707_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def assert_close(gpu, ref, s, what):
+    gpu = gpu.cpu().numpy().astype(np.float64)
+    err = np.abs(gpu - ref)
+    bad = err > TOL * s
+    assert not bad.any(), f"{what}: {bad.sum()} elements beyond 1e-5*sum|x|; worst ratio {np.max(err / np.maximum(s, 1e-300)):.3e}"
+
+
+def assert_equal(gpu, ref, what):
+    gpu = gpu.cpu().numpy()
+    assert gpu.dtype == ref.dtype or gpu.dtype.kind == ref.dtype.kind, what
+    assert np.array_equal(gpu, ref.astype(gpu.dtype)), f"{what}: {np.count_nonzero(gpu != ref.astype(gpu.dtype))} mismatches"
+
+
+def run_all_ops(B, h, rowptr, col, d, seed, ops=("sum", "mean", "max"), dtypes=("f32", "i32")):
+    """Forward + backward of the HAG path and of the naive-CSR GPU baseline vs the oracle."""
+    n = rowptr.size - 1
+    h.upload()
+    for dt in dtypes:
+        if dt == "f32":
+            x, gy = synth.features_f32(n, d, seed), synth.features_f32(n, d, seed + 1)
+        else:
+            x, gy = synth.features_i32(n, d, seed), synth.features_i32(n, d, seed + 1)
+        xd, gyd = dev(x), dev(gy)
+        for op in ops:
+            if op == "mean" and dt == "i32":
+                continue
+            tag = f"n={n} d={d} {dt} {op}"
+            y_ref, s, am_ref = oracle.naive_forward(rowptr, col, x, op)
+            for name, fwd, bwd in (("hag", h.forward, h.backward), ("naive", h.naive_forward, h.naive_backward)):
+                out = fwd(xd, op)
+                torch.cuda.synchronize()
+                if op == "max":
+                    y, am = out
+                    assert_equal(y, y_ref, f"{name} fwd values {tag}")
+                    assert_equal(am, am_ref, f"{name} fwd argmax {tag}")
+                    gx_ref, gs = oracle.naive_backward(rowptr, col, gy, op, am_ref)
+                    gx = bwd(gyd, op, argmax=am)
+                else:
+                    if dt == "f32":
+                        assert_close(out, y_ref, s, f"{name} fwd {tag}")
+                    else:
+                        assert_equal(out, y_ref, f"{name} fwd {tag}")
+                    gx_ref, gs = oracle.naive_backward(rowptr, col, gy, op)
+                    gx = bwd(gyd, op)
+                torch.cuda.synchronize()
+                if dt == "f32":
+                    assert_close(gx, gx_ref, gs, f"{name} bwd {tag}")
+                else:
+                    assert_equal(gx, gx_ref, f"{name} bwd {tag}")
+
+
+@pytest.mark.parametrize("n,p,d,directed", [
+    (37, 0.3, 4, False), (200, 0.1, 8, True), (333, 0.15, 16, False), (500, 0.08, 32, True),
+    (777, 0.05, 64, False), (1000, 0.04, 128, True), (301, 0.2, 100, False), (150, 0.3, 260, True),
+    (260, 0.2, 512, False), (129, 0.25, 1028, False),
+])
+def test_random_graphs_all_ops(B, n, p, d, directed):
+    rowptr, col = synth.random_graph(n, p, seed=n + d, directed=directed)
+    h = B.hag_search(rowptr, col, n // 2)
+    assert h.stats()["a"] > 0
+    run_all_ops(B, h, rowptr, col, d, seed=7 * n + d)
+
+
+def test_capacity_zero_is_the_gnn_graph(B):
+    # Section 3.1: the GNN-graph is the HAG with V_A empty -> identical kernels, identical bits
+    rowptr, col = synth.random_graph(400, 0.1, seed=3)
+    h = B.hag_search(rowptr, col, 0).upload()
+    x = dev(synth.features_f32(400, 64, 4))
+    assert torch.equal(h.forward(x, "sum"), h.naive_forward(x, "sum"))
+    assert torch.equal(h.backward(x, "sum"), h.naive_backward(x, "sum"))
+
+
+def test_split_rows_hubs_and_isolated_nodes(B):
+    # a few hubs with thousands of neighbours (rows split across items and folded in a second
+    # launch), many leaves, some isolated nodes; unsymmetric
+    n, d = 6000, 64
+    rng = np.random.default_rng(11)
+    rows, cols = [], []
+    for hub, deg in ((0, 5000), (1, 3100), (2, 1537), (3, 1536), (4, 2049)):
+        nb = rng.choice(np.arange(10, n - 50), size=deg, replace=False)
+        rows += [hub] * deg
+        cols += nb.tolist()
+        rows += nb[: deg // 2].tolist()          # half of them point back
+        cols += [hub] * (deg // 2)
+    extra_r = rng.integers(10, n - 50, 20000)
+    extra_c = rng.integers(0, n - 50, 20000)
+    keys = np.unique(np.concatenate([np.asarray(rows) * n + np.asarray(cols), extra_r * n + extra_c]))
+    r, c = keys // n, keys % n
+    keep = r != c
+    r, c = r[keep], c[keep]
+    rowptr = np.concatenate([[0], np.cumsum(np.bincount(r, minlength=n))]).astype(np.int64)
+    col = c.astype(np.int32)
+    assert np.diff(rowptr)[-50:].max() == 0 and np.diff(rowptr).max() == 5000
+    h = B.hag_search(rowptr, col, n // 4)
+    run_all_ops(B, h, rowptr, col, d, seed=12)
+    run_all_ops(B, h, rowptr, col, 16, seed=13, ops=("sum", "max"), dtypes=("f32",))
+
+
+def test_max_ties_bit_exact(B):
+    # few distinct values -> many exact ties; argmax must be the smallest original id
+    n, d = 600, 32
+    rowptr, col = synth.random_graph(n, 0.1, seed=21)
+    h = B.hag_search(rowptr, col, n // 2).upload()
+    x = np.random.default_rng(22).integers(0, 3, size=(n, d)).astype(np.float32)
+    y_ref, _, am_ref = oracle.naive_forward(rowptr, col, x, "max")
+    for fwd in (h.forward, h.naive_forward):
+        y, am = fwd(dev(x), "max")
+        assert_equal(y, y_ref, "tied max values")
+        assert_equal(am, am_ref, "tied max argmax")
+
+
+def test_empty_graph_and_edgeless_graph(B):
+    h = B.hag_search(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4).upload()
+    y = h.forward(torch.empty((0, 8), device="cuda"), "sum")
+    assert y.shape == (0, 8)
+    n = 70
+    h = B.hag_search(np.zeros(n + 1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4).upload()
+    x = dev(synth.features_f32(n, 8, 1))
+    assert torch.count_nonzero(h.forward(x, "sum")) == 0
+    y, am = h.forward(x, "max")
+    assert torch.count_nonzero(y) == 0 and bool((am == -1).all())
+    assert torch.count_nonzero(h.backward(x, "max", argmax=am)) == 0
+    assert torch.count_nonzero(h.backward(x, "mean")) == 0
+
+
+def test_device_argument_errors(B):
+    rowptr, col = synth.random_graph(20, 0.3, seed=1)
+    h = B.hag_search(rowptr, col, 4).upload()
+    x = torch.zeros((20, 6), device="cuda")
+    with pytest.raises(B.HagError) as e:
+        h.forward(x, "sum")                      # d not a multiple of 4
+    assert e.value.code == B.HAG_EINVAL
+    xi = torch.zeros((20, 8), dtype=torch.int32, device="cuda")
+    with pytest.raises(B.HagError):
+        h.forward(xi, "mean")                    # integer mean is undefined
+    x8 = torch.zeros((20, 8), device="cuda")
+    with pytest.raises(B.HagError):
+        h.forward(x8, "sum", y=x8)               # aliasing
+
+
+def test_config1_sbm_sum_f32_and_i32(B):
+    rowptr, col = synth.sbm()
+    n = rowptr.size - 1
+    h = B.hag_search(rowptr, col, n // 4)
+    ref = oracle.search(rowptr, col, n // 4)     # canonical search parity at full config-1 size
+    l, r, red = h.get_merges()
+    assert np.array_equal(l, ref.left) and np.array_equal(r, ref.right) and np.array_equal(red, ref.red)
+    run_all_ops(B, h, rowptr, col, 64, seed=synth.SEED_BASE + 1001, ops=("sum",))
