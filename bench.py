@@ -1,0 +1,226 @@
+#!/usr/bin/env python3
+"""Benchmark of the HAG aggregation hot path on one MI355X.
+
+A step = one hag_forward + one hag_backward (all phases: aggregation-node levels,
+final gather; transposed levels, source gather) over one synthetic graph whose
+feature matrices already live in HBM.  The default workload is BASELINE config 2
+(Holme-Kim power-law cluster graph, 56,944 nodes, D=128, capacity |V|/4, sum).
+
+Prints ONE JSON line (stdout); a human-readable breakdown goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
+
+# HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# (scaled by a copy kernel of known size); the summaries are in profiles/.  None = not measured.
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def build_workload(cfg: int, binding, synth):
+    t0 = time.time()
+    rowptr, col, graph_ptr = synth.graph_for_config(cfg)
+    n = rowptr.size - 1
+    t1 = time.time()
+    if cfg == 4:
+        h = binding.hag_search_batched(rowptr, col, graph_ptr, 0.25)
+    else:
+        h = binding.hag_search(rowptr, col, n // 4)
+    t2 = time.time()
+    log(f"[bench] config {cfg}: graph {t1 - t0:.1f}s, hag_search {t2 - t1:.1f}s")
+    d = {1: 64, 2: 128, 3: 128, 4: 64, 5: 128}[cfg]
+    return rowptr, col, h, d
+
+
+def time_steps(torch, fn, steps, warmup):
+    for _ in range(warmup):
+        fn()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        fn()
+    torch.cuda.synchronize()
+    return (time.perf_counter() - t0) / steps * 1e3
+
+
+def time_kernel(torch, pre, fn, post, steps, warmup):
+    """Average duration (ms) of `fn` inside the full step, bracketed by events on the launch stream."""
+    for _ in range(warmup):
+        pre(); fn(); post()
+    ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(steps)]
+    torch.cuda.synchronize()
+    for a, b in ev:
+        pre()
+        a.record()
+        fn()
+        b.record()
+        post()
+    torch.cuda.synchronize()
+    return sum(a.elapsed_time(b) for a, b in ev) / steps
+
+
+def cpu_baseline(oracle, synth, rowptr, col, h, d, seed, budget_s=20.0):
+    """The oracle's HAG forward + backward (fp64 accumulation) on the host, on a bounded sample."""
+    import numpy as np
+
+    st = h.stats()
+    n = st["n"]
+    f = h.get_forward()
+    oh = oracle.Hag(n, f["agg_left"], f["agg_right"], f["hrowptr"], f["hcol"])
+    deg = np.diff(rowptr)
+    # bounded sample: a slice of the feature columns, all rows (same graph, same HAG)
+    d_s = d
+    est = 2.0 * st["e_hag"] * d / 2.0e8          # ~2e8 aggregated elements/s/core, rough
+    while d_s > 4 and est * d_s / d > budget_s:
+        d_s //= 2
+    x = synth.features_f32(n, d_s, seed)
+    gy = synth.features_f32(n, d_s, seed + 1)
+    t0 = time.perf_counter()
+    reps = 0
+    while True:
+        oracle.hag_forward(oh, deg, x, "sum")
+        oracle.hag_backward(oh, deg, gy, "sum")
+        reps += 1
+        if time.perf_counter() - t0 > budget_s / 2 or reps >= 3:
+            break
+    dt = (time.perf_counter() - t0) / reps
+    threads = int(os.environ.get("OMP_NUM_THREADS", os.cpu_count() or 1))
+    return {
+        "value": 2.0 * st["e"] * d_s / dt,
+        "unit": "feature-elems/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": f"whole graph and HAG, {d_s} of {d} feature columns, {reps} reps of forward+backward; "
+                  f"fp64 accumulation; OpenMP on the final forward loop only ({threads} threads), the rest serial",
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload")
+    ap.add_argument("--op", default="sum", choices=["sum", "mean", "max"])
+    ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
+
+    import numpy as np
+    import torch
+
+    from paper_1906_03707_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible (the HIP path has no CPU fallback)")
+    binding.lib()
+    torch.cuda.set_device(0)
+    cfg = args.config
+    rowptr, col, h, d = build_workload(cfg, binding, synth)
+    if args.d:
+        d = args.d
+    op = args.op
+    st = h.stats()
+    n, e = st["n"], st["e"]
+    h.upload()
+    seed = synth.SEED_BASE + cfg
+    x = torch.from_numpy(synth.features_f32(n, d, seed + 1000)).cuda()
+    gy = torch.from_numpy(synth.features_f32(n, d, seed + 2000)).cuda()
+    y = torch.empty_like(x)
+    gx = torch.empty_like(x)
+    am = torch.empty((n, d), dtype=torch.int32, device="cuda") if op == "max" else None
+
+    def step_hag():
+        h.forward(x, op, y=y, argmax=am)
+        h.backward(gy, op, argmax=am, gx=gx)
+
+    def step_naive():
+        h.naive_forward(x, op, y=y, argmax=am)
+        h.naive_backward(gy, op, argmax=am, gx=gx)
+
+    ms_hag = time_steps(torch, step_hag, args.steps, args.warmup)
+    ms_naive = time_steps(torch, step_naive, args.steps, args.warmup)
+    ms_fwd = time_steps(torch, lambda: h.forward(x, op, y=y, argmax=am), args.steps, args.warmup)
+    ms_nfwd = time_steps(torch, lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
+
+    # dominant kernel: the final gather of hag_forward (one launch per step), timed inside the step
+    P = binding
+    ms_gather = time_kernel(
+        torch,
+        lambda: h.forward_phases(x, P.HAG_PHASE_LEVELS, op, y=y, argmax=am),
+        lambda: h.forward_phases(x, P.HAG_PHASE_GATHER, op, y=y, argmax=am),
+        lambda: h.backward(gy, op, argmax=am, gx=gx),
+        args.steps, args.warmup)
+    row = 4 * d
+    gather_bytes = (row + 4) * st["h"] + (row + 16) * n       # row reads + index reads, row writes + schedule
+    if op == "max":
+        gather_bytes += row * n                               # argmax rows written beside the values
+    kernel_name = f"gather_kernel<float, {1 if op == 'max' else 0}, {min(64, max(4, 1 << (max(d // 4, 1) - 1).bit_length()))}, 0>"
+    achieved = gather_bytes / (ms_gather * 1e-3) / 1e9
+    workload = f"config{cfg}:{synth.CONFIGS[cfg]['name']}"
+    traffic = MEASURED_TRAFFIC_BYTES.get((workload, d, op))
+
+    alg_hag = h.algorithmic_bytes(0, op, d) + h.algorithmic_bytes(1, op, d)
+    alg_naive = h.algorithmic_bytes(2, op, d) + h.algorithmic_bytes(3, op, d)
+    value = 2.0 * e * d / (ms_hag * 1e-3)
+    out = {
+        "metric": "HAG agg fwd+bwd: feature-elems/s, HBM GB/s (% peak), speedup vs naive CSR",
+        "value": value,
+        "unit": "feature-elems/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_hag,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "f32",
+        "data": "synthetic",
+        "config": {"workload": workload, "nodes": n, "edges": e, "feature_dim": d, "op": op,
+                   "capacity": st["a"], "levels": st["levels"], "hag_edges": st["e_hag"]},
+        "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                     "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+                     "kernel": kernel_name, "kernel_ms": ms_gather, "algorithmic_bytes": gather_bytes},
+        "effective_GBps_fwd_bwd": alg_hag / (ms_hag * 1e-3) / 1e9,
+        "effective_frac_of_peak": alg_hag / (ms_hag * 1e-3) / 1e9 / HBM_PEAK_GBS,
+        "naive_csr": {"ms_per_step": ms_naive, "feature_elems_per_s": 2.0 * e * d / (ms_naive * 1e-3),
+                      "effective_GBps": alg_naive / (ms_naive * 1e-3) / 1e9},
+        "speedup_vs_naive": ms_naive / ms_hag,
+        "aggregation_reduction": st["aggr_naive"] / max(st["aggr_hag"], 1),
+        "transfer_reduction": st["xfer_naive"] / max(st["xfer_hag"], 1),
+        "forward_ms": {"hag": ms_fwd, "naive": ms_nfwd},
+    }
+    log(f"[bench] {workload} D={d} op={op}: N={n} E={e} A={st['a']} levels={st['levels']} E^={st['e_hag']}")
+    log(f"[bench] fwd+bwd  hag {ms_hag:.4f} ms  naive {ms_naive:.4f} ms  speedup {ms_naive / ms_hag:.3f}x "
+        f"(aggregations {out['aggregation_reduction']:.3f}x, transfers {out['transfer_reduction']:.3f}x fewer)")
+    log(f"[bench] fwd only hag {ms_fwd:.4f} ms  naive {ms_nfwd:.4f} ms")
+    log(f"[bench] effective (algorithmic) GB/s fwd+bwd: hag {out['effective_GBps_fwd_bwd']:.0f}  "
+        f"naive {out['naive_csr']['effective_GBps']:.0f}  (peak {HBM_PEAK_GBS:.0f})")
+    log(f"[bench] dominant kernel {kernel_name}: {ms_gather * 1e3:.1f} us, {gather_bytes / 1e6:.1f} MB -> {achieved:.0f} GB/s "
+        f"= {100 * achieved / HBM_PEAK_GBS:.1f}% of HBM peak")
+    if not args.no_cpu_baseline:
+        import oracle
+
+        out["cpu_baseline"] = cpu_baseline(oracle, synth, rowptr, col, h, d, seed + 3000)
+        log(f"[bench] cpu oracle: {out['cpu_baseline']['value']:.3e} feature-elems/s on {out['cpu_baseline']['cores']} threads")
+    print(json.dumps(out), flush=True)
+
+
+if __name__ == "__main__":
+    main()

@@ -164,6 +164,18 @@ int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
 int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
                  const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream);
 
+/* The same two calls restricted to some of their phases, for per-kernel timing: a later
+ * phase reads what an earlier call left in `workspace`.  HAG_PHASE_LEVELS = the
+ * aggregation-node levels (forward: Algorithm 2's loop over V_A; backward: their
+ * gradient rows); HAG_PHASE_GATHER = the per-node gather over V. */
+enum { HAG_PHASE_LEVELS = 1, HAG_PHASE_GATHER = 2, HAG_PHASE_ALL = 3 };
+int hag_forward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                       const void *x, void *y, int32_t *argmax, void *workspace, void *stream,
+                       uint32_t phases);
+int hag_backward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                        const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream,
+                        uint32_t phases);
+
 /* The GNN-graph baseline (Algorithm 1's Aggregate line; a HAG with V_A empty):
  * same arguments, same kernels, run on the input CSR and its transpose. */
 int hag_naive_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,

@@ -20,12 +20,14 @@ HAG_SUM, HAG_MEAN, HAG_MAX = 0, 1, 2
 HAG_F32, HAG_I32 = 0, 1
 HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE = 0, -1, -2, -3, -4
 HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP = 1, 2
+HAG_PHASE_LEVELS, HAG_PHASE_GATHER, HAG_PHASE_ALL = 1, 2, 3
 OPS = {"sum": HAG_SUM, "mean": HAG_MEAN, "max": HAG_MAX}
 
 EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
-    "hag_backward", "hag_naive_forward", "hag_naive_backward", "hag_algorithmic_bytes", "hag_last_error",
+    "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
+    "hag_algorithmic_bytes", "hag_last_error",
 ]
 
 
@@ -70,6 +72,8 @@ def lib():
             getattr(L, name).argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp, vp]
         for name in ("hag_backward", "hag_naive_backward"):
             getattr(L, name).argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp, vp]
+        for name in ("hag_forward_phases", "hag_backward_phases"):
+            getattr(L, name).argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp, vp, u32]
         L.hag_algorithmic_bytes.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64]
         L.hag_algorithmic_bytes.restype = i64
         L.hag_last_error.restype = ctypes.c_char_p
@@ -178,7 +182,7 @@ class Hag:
             self._ws[key] = ws
         return ws
 
-    def _fwd(self, fn, x, op, y, argmax, workspace):
+    def _fwd(self, fn, x, op, y, argmax, workspace, *extra):
         import torch
         n, d = x.shape
         if y is None:
@@ -187,17 +191,17 @@ class Hag:
             argmax = torch.empty((n, d), dtype=torch.int32, device=x.device)
         ws = workspace if workspace is not None else self._workspace(op, x)
         _check(fn(self._h, OPS[op], _dtype_code(x), d, _dev_ptr(x), _dev_ptr(y), _dev_ptr(argmax), _dev_ptr(ws),
-                  _stream_ptr()))
+                  _stream_ptr(), *extra))
         return (y, argmax) if op == "max" else y
 
-    def _bwd(self, fn, gy, op, argmax, gx, workspace):
+    def _bwd(self, fn, gy, op, argmax, gx, workspace, *extra):
         import torch
         n, d = gy.shape
         if gx is None:
             gx = torch.empty_like(gy)
         ws = workspace if workspace is not None else self._workspace(op, gy)
         _check(fn(self._h, OPS[op], _dtype_code(gy), d, _dev_ptr(gy), _dev_ptr(argmax), _dev_ptr(gx), _dev_ptr(ws),
-                  _stream_ptr()))
+                  _stream_ptr(), *extra))
         return gx
 
     def forward(self, x, op="sum", y=None, argmax=None, workspace=None):
@@ -205,6 +209,12 @@ class Hag:
 
     def backward(self, gy, op="sum", argmax=None, gx=None, workspace=None):
         return self._bwd(lib().hag_backward, gy, op, argmax, gx, workspace)
+
+    def forward_phases(self, x, phases, op="sum", y=None, argmax=None, workspace=None):
+        return self._fwd(lib().hag_forward_phases, x, op, y, argmax, workspace, int(phases))
+
+    def backward_phases(self, gy, phases, op="sum", argmax=None, gx=None, workspace=None):
+        return self._bwd(lib().hag_backward_phases, gy, op, argmax, gx, workspace, int(phases))
 
     def naive_forward(self, x, op="sum", y=None, argmax=None, workspace=None):
         return self._fwd(lib().hag_naive_forward, x, op, y, argmax, workspace)

@@ -21,6 +21,9 @@ constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes
 constexpr int kWave = 64;
 
 enum { R_SUM = 0, R_MAX = 1 };
+// which phase a gather launch belongs to: only a tag, so that every phase has a kernel symbol
+// of its own in profiler output
+enum { G_HAG_FWD = 0, G_HAG_BWD_LEVEL = 1, G_HAG_BWD_SRC = 2, G_NAIVE_FWD = 3, G_NAIVE_BWD = 4, G_FOLD = 5 };
 
 template <typename T> struct V4;
 template <> struct V4<float> { using type = float4; };
@@ -29,7 +32,8 @@ template <> struct V4<int32_t> { using type = int4; };
 template <typename T>
 struct GatherArgs {
     const Item *items;
-    int64_t n_items;
+    int64_t n_items;          // all items
+    int64_t n_block;          // the first n_block of them take one workgroup each
     const int32_t *col;
     const T *src_lo;          // rows of ids < split
     const T *src_hi;          // rows of ids >= split, row (id - split)
@@ -72,81 +76,152 @@ __device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi)
     max1(v.z, vi.z, w.z, wi.z); max1(v.w, vi.w, w.w, wi.w);
 }
 
-// Gather-reduce.  A sub-group of LPR lanes owns one item; lane sl of the sub-group owns
-// the four consecutive features starting at (blockIdx.y * LPR + sl) * 4, so one neighbour
-// row is fetched by LPR adjacent lanes as one contiguous run of 16-byte loads.  Column
-// indices are read LPR at a time (coalesced) and handed round inside the sub-group with
-// cross-lane reads; four neighbour rows are requested before the first is consumed.
-template <typename T, int RED, int LPR>
-__global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
+__device__ __forceinline__ Item load_item(const Item *p) {
+    const int4 raw = *reinterpret_cast<const int4 *>(p);
+    Item it;
+    it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)raw.y << 32);
+    it.cnt = raw.z;
+    it.row = raw.w;
+    return it;
+}
+
+// Reduce `cnt` neighbour rows whose ids start at col[beg] into (acc, acc_id), for the four
+// features starting at cbase.  Called by all LPR lanes of a sub-group together; `maxcnt` is
+// the largest cnt among the sub-groups of the wavefront, so that every lane of the wavefront
+// executes the same number of cross-lane reads.  Column ids are read LPR at a time
+// (coalesced) and handed round inside the sub-group; UNR neighbour rows are requested
+// before the first is consumed.
+template <typename T, int RED, int LPR, int UNR>
+__device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg, int cnt, int maxcnt, int sl,
+                                            int cbase, bool col_ok, typename V4<T>::type &acc, int4 &acc_id) {
     using V = typename V4<T>::type;
-    constexpr int SG = kWave / LPR;
-    const int lane = threadIdx.x & (kWave - 1);
-    const int wave = threadIdx.x / kWave;
-    const int sg = lane / LPR, sl = lane % LPR;
-    const int64_t item_idx = ((int64_t)blockIdx.x * (kBlock / kWave) + wave) * SG + sg;
-    const bool has_item = item_idx < A.n_items;
-    Item it{0, 0, 0};
-    if (has_item) {
-        const int4 raw = *reinterpret_cast<const int4 *>(A.items + item_idx);
-        it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)raw.y << 32);
-        it.cnt = raw.z;
-        it.row = raw.w;
-    }
-    const int cbase = (blockIdx.y * LPR + sl) * 4;
-    const bool col_ok = cbase < A.d;
-    int maxcnt = it.cnt;
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
-
-    V acc{};  // zero
-    int4 acc_id = make_int4(-1, -1, -1, -1);
     const size_t d = (size_t)A.d;
-
     for (int base = 0; base < maxcnt; base += LPR) {
-        const int mine = (base + sl < it.cnt) ? A.col[it.beg + base + sl] : -1;
+        const int mine = (base + sl < cnt) ? A.col[beg + base + sl] : -1;
         const int lim = min(LPR, maxcnt - base);
-        for (int j = 0; j < lim; j += 4) {
-            int idx[4];
-            V val[4];
-            int4 vid[4];
+        for (int j = 0; j < lim; j += UNR) {
+            int idx[UNR];
+            V val[UNR];
+            int4 vid[UNR];
 #pragma unroll
-            for (int k = 0; k < 4; ++k) idx[k] = __shfl(mine, j + k, LPR);
+            for (int k = 0; k < UNR; ++k) idx[k] = __shfl(mine, j + k, LPR);
+            // Lists are sorted, so ids >= split (rows of the second matrix) come last: most
+            // iterations see none in the whole wavefront and take the single-matrix path.
+            int hi_any = 0;
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
-                val[k] = V{};
-                vid[k] = make_int4(-1, -1, -1, -1);
-                if (idx[k] >= 0 && col_ok) {
-                    if (idx[k] < A.split) {
-                        val[k] = ld4(A.src_lo + (size_t)idx[k] * d + cbase);
-                        if (A.in_scale) scale4(val[k], A.in_scale[idx[k]]);
-                        if (RED == R_MAX) vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);
-                    } else {
-                        const size_t o = (size_t)(idx[k] - A.split) * d + cbase;
-                        val[k] = ld4(A.src_hi + o);
-                        if (RED == R_MAX) vid[k] = ld4(A.id_hi + o);
-                    }
+            for (int k = 0; k < UNR; ++k) hi_any |= (idx[k] >= A.split);
+            if (!__any(hi_any)) {
+#pragma unroll
+                for (int k = 0; k < UNR; ++k) {
+                    val[k] = V{};
+                    if (idx[k] >= 0 && col_ok) val[k] = ld4(A.src_lo + (size_t)idx[k] * d + cbase);
+                }
+            } else {
+                // mixed: select the address, not the path, so the loads still issue together
+                const T *ptr[UNR];
+#pragma unroll
+                for (int k = 0; k < UNR; ++k) {
+                    const int id = max(idx[k], 0);
+                    const bool lo = id < A.split;
+                    const T *base_ptr = lo ? A.src_lo : A.src_hi;
+                    ptr[k] = base_ptr + (size_t)(lo ? id : id - A.split) * d + cbase;
+                }
+#pragma unroll
+                for (int k = 0; k < UNR; ++k) {
+                    val[k] = V{};
+                    if (idx[k] >= 0 && col_ok) val[k] = ld4(ptr[k]);
+                }
+            }
+            if (A.in_scale) {
+#pragma unroll
+                for (int k = 0; k < UNR; ++k)
+                    if (idx[k] >= 0 && idx[k] < A.split) scale4(val[k], A.in_scale[idx[k]]);
+            }
+            if (RED == R_MAX) {
+#pragma unroll
+                for (int k = 0; k < UNR; ++k) {
+                    vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);   // -1 stays "nothing"
+                    if (idx[k] >= A.split && col_ok) vid[k] = ld4(A.id_hi + (size_t)(idx[k] - A.split) * d + cbase);
+                    if (!col_ok) vid[k] = make_int4(-1, -1, -1, -1);
                 }
             }
 #pragma unroll
-            for (int k = 0; k < 4; ++k) {
+            for (int k = 0; k < UNR; ++k) {
                 if (RED == R_MAX) max4(acc, acc_id, val[k], vid[k]);
                 else add4(acc, val[k]);
             }
         }
     }
-    if (has_item && col_ok) {
-        if (it.row >= 0) {
-            if (A.out_scale) scale4(acc, A.out_scale[it.row]);
-            const size_t o = (size_t)(it.row - A.out_off) * d + cbase;
-            st4(A.out + o, acc);
-            if (RED == R_MAX) st4(A.out_id + o, acc_id);
-        } else {
-            const size_t o = (size_t)(~it.row) * d + cbase;
-            st4(A.part + o, acc);
-            if (RED == R_MAX) st4(A.part_id + o, acc_id);
-        }
+}
+
+template <typename T, int RED>
+__device__ __forceinline__ void store_result(const GatherArgs<T> &A, int row, int cbase, typename V4<T>::type acc,
+                                             int4 acc_id) {
+    const size_t d = (size_t)A.d;
+    if (row >= 0) {
+        if (A.out_scale) scale4(acc, A.out_scale[row]);
+        const size_t o = (size_t)(row - A.out_off) * d + cbase;
+        st4(A.out + o, acc);
+        if (RED == R_MAX) st4(A.out_id + o, acc_id);
+    } else {
+        const size_t o = (size_t)(~row) * d + cbase;
+        st4(A.part + o, acc);
+        if (RED == R_MAX) st4(A.part_id + o, acc_id);
     }
+}
+
+// Gather-reduce.  Lane sl of a sub-group of LPR lanes owns the four consecutive features
+// starting at (blockIdx.y * LPR + sl) * 4, so a neighbour row is fetched by LPR adjacent
+// lanes as one contiguous run of 16-byte loads.
+//   workgroups [0, n_block): one long item each; its 256/LPR sub-groups take equal slices
+//     of the neighbour list and fold their partial rows through LDS in a fixed order;
+//   later workgroups: one short item per sub-group.
+template <typename T, int RED, int LPR, int ROLE>
+__global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
+    using V = typename V4<T>::type;
+    constexpr int SG = kWave / LPR;       // sub-groups per wavefront
+    constexpr int NSG = kBlock / LPR;     // sub-groups per workgroup
+    constexpr int UNR = 4;
+    __shared__ V red_val[kBlock];
+    __shared__ int4 red_id[RED == R_MAX ? kBlock : 1];
+    const int lane = threadIdx.x & (kWave - 1);
+    const int sl = lane % LPR;
+    const int cbase = (blockIdx.y * LPR + sl) * 4;
+    const bool col_ok = cbase < A.d;
+    V acc{};
+    int4 acc_id = make_int4(-1, -1, -1, -1);
+
+    if ((int64_t)blockIdx.x < A.n_block) {
+        const Item it = load_item(A.items + blockIdx.x);
+        const int sg = threadIdx.x / LPR;
+        int per = (it.cnt + NSG - 1) / NSG;
+        per = (per + UNR - 1) / UNR * UNR;
+        const int lo = min(it.cnt, sg * per), hi = min(it.cnt, lo + per);
+        reduce_rows<T, RED, LPR, UNR>(A, it.beg + lo, hi - lo, min(it.cnt, per), sl, cbase, col_ok, acc, acc_id);
+        red_val[threadIdx.x] = acc;
+        if (RED == R_MAX) red_id[threadIdx.x] = acc_id;
+        __syncthreads();
+        if (threadIdx.x < LPR && col_ok) {
+#pragma unroll
+            for (int s = 1; s < NSG; ++s) {
+                if (RED == R_MAX) max4(acc, acc_id, red_val[s * LPR + sl], red_id[s * LPR + sl]);
+                else add4(acc, red_val[s * LPR + sl]);
+            }
+            store_result<T, RED>(A, it.row, cbase, acc, acc_id);
+        }
+        return;
+    }
+    const int wave = threadIdx.x / kWave;
+    const int sg = lane / LPR;
+    const int64_t item_idx = A.n_block + (((int64_t)blockIdx.x - A.n_block) * (kBlock / kWave) + wave) * SG + sg;
+    const bool has_item = item_idx < A.n_items;
+    Item it{0, 0, 0};
+    if (has_item) it = load_item(A.items + item_idx);
+    int maxcnt = it.cnt;
+#pragma unroll
+    for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
+    reduce_rows<T, RED, LPR, UNR>(A, it.beg, it.cnt, maxcnt, sl, cbase, col_ok, acc, acc_id);
+    if (has_item && col_ok) store_result<T, RED>(A, it.row, cbase, acc, acc_id);
 }
 
 // One level of aggregation nodes (Algorithm 2, the loop over V_A): every node has exactly
@@ -229,27 +304,27 @@ static int pick_lpr(int64_t d) {
     return l;
 }
 
-template <typename T, int RED, int LPR>
+template <typename T, int RED, int LPR, int ROLE>
 static int launch_gather_lpr(const GatherArgs<T> &a, hipStream_t s) {
     constexpr int SG = kWave / LPR;
     const int64_t per_block = (kBlock / kWave) * SG;
-    const int64_t gx = (a.n_items + per_block - 1) / per_block;
+    const int64_t gx = a.n_block + (a.n_items - a.n_block + per_block - 1) / per_block;
     const int64_t gy = (a.d / 4 + LPR - 1) / LPR;
     if (gx <= 0) return HAG_OK;
     if (gx > 0x7fffffffLL || gy > 65535) { set_error("launch too large"); return HAG_EINVAL; }
-    hipLaunchKernelGGL((gather_kernel<T, RED, LPR>), dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, a);
+    hipLaunchKernelGGL((gather_kernel<T, RED, LPR, ROLE>), dim3((unsigned)gx, (unsigned)gy), dim3(kBlock), 0, s, a);
     HIP_TRY(hipGetLastError());
     return HAG_OK;
 }
 
-template <typename T, int RED>
+template <typename T, int RED, int ROLE>
 static int launch_gather(const GatherArgs<T> &a, hipStream_t s) {
     switch (pick_lpr(a.d)) {
-        case 4: return launch_gather_lpr<T, RED, 4>(a, s);
-        case 8: return launch_gather_lpr<T, RED, 8>(a, s);
-        case 16: return launch_gather_lpr<T, RED, 16>(a, s);
-        case 32: return launch_gather_lpr<T, RED, 32>(a, s);
-        default: return launch_gather_lpr<T, RED, 64>(a, s);
+        case 4: return launch_gather_lpr<T, RED, 4, ROLE>(a, s);
+        case 8: return launch_gather_lpr<T, RED, 8, ROLE>(a, s);
+        case 16: return launch_gather_lpr<T, RED, 16, ROLE>(a, s);
+        case 32: return launch_gather_lpr<T, RED, 32, ROLE>(a, s);
+        default: return launch_gather_lpr<T, RED, 64, ROLE>(a, s);
     }
 }
 
@@ -279,27 +354,29 @@ static Workspace carve(const hag_handle *h, hag_op_t op, int64_t d, void *base) 
 }
 
 // run one schedule: the gather itself, then the fold of split rows
-template <typename T, int RED>
+template <typename T, int RED, int ROLE>
 static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, GatherArgs<T> a, const Workspace &w,
                     hipStream_t s) {
     a.items = p.d_items;
     a.n_items = (int64_t)p.items.size();
+    a.n_block = p.n_block;
     a.col = d_col;
     a.part = (T *)w.part;
     a.part_id = (int32_t *)w.part_id;
-    int rc = launch_gather<T, RED>(a, s);
+    int rc = launch_gather<T, RED, ROLE>(a, s);
     if (rc) return rc;
     if (!p.combine.empty()) {
         GatherArgs<T> c = a;
         c.items = p.d_combine;
         c.n_items = (int64_t)p.combine.size();
+        c.n_block = 0;
         c.col = h->d_slot_ids;
         c.split = 0;               // every id refers to a partial slot
         c.src_lo = nullptr;
         c.src_hi = (const T *)w.part;
         c.id_hi = (const int32_t *)w.part_id;
         c.in_scale = nullptr;
-        rc = launch_gather<T, RED>(c, s);
+        rc = launch_gather<T, RED, G_FOLD>(c, s);
     }
     return rc;
 }
@@ -321,10 +398,10 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
 
 template <typename T, int RED>
 static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *x, T *y, int32_t *argmax,
-                        void *ws, hipStream_t s) {
+                        void *ws, hipStream_t s, uint32_t phases) {
     Workspace w = carve(h, op, d, ws);
     const int32_t n = (int32_t)h->n;
-    if (!naive) {
+    if (!naive && (phases & HAG_PHASE_LEVELS)) {
         for (int32_t l = 1; l <= h->levels; ++l) {
             int32_t first = h->level_ptr[l - 1], last = h->level_ptr[l];
             int64_t threads = (int64_t)(last - first) * (d / 4);
@@ -346,16 +423,18 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
     a.in_scale = nullptr;
     a.out_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
     a.d = (int32_t)d;
-    return run_plan<T, RED>(h, naive ? h->p_naive_fwd : h->p_fwd, naive ? h->d_gcol : h->d_hcol, a, w, s);
+    if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
+    if (naive) return run_plan<T, RED, G_NAIVE_FWD>(h, h->p_naive_fwd, h->d_gcol, a, w, s);
+    return run_plan<T, RED, G_HAG_FWD>(h, h->p_fwd, h->d_hcol, a, w, s);
 }
 
 template <typename T>
 static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *gy, const int32_t *argmax,
-                         T *gx, void *ws, hipStream_t s) {
+                         T *gx, void *ws, hipStream_t s, uint32_t phases) {
     const int32_t n = (int32_t)h->n;
     if (op == HAG_MAX) {
         int64_t total = h->n * d;
-        if (total == 0) return HAG_OK;
+        if (total == 0 || !(phases & HAG_PHASE_GATHER)) return HAG_OK;
         hipLaunchKernelGGL((fill_zero_kernel<T>), dim3((unsigned)((total / 4 + kBlock - 1) / kBlock)), dim3(kBlock), 0,
                            s, gx, total / 4);
         HIP_TRY(hipGetLastError());
@@ -376,19 +455,21 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
     if (naive) {
         a.out = gx;
         a.out_off = 0;
-        return run_plan<T, R_SUM>(h, h->p_naive_bwd, h->d_gtcol, a, w, s);
+        if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
+        return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s);
     }
     // deepest level first: its consumers are destinations only; level l may also be consumed
     // by aggregation nodes of deeper levels, whose gradient rows are complete by then
-    for (int32_t l = h->levels; l >= 1; --l) {
+    for (int32_t l = h->levels; l >= 1 && (phases & HAG_PHASE_LEVELS); --l) {
         a.out = (T *)w.agg;
         a.out_off = n;
-        int rc = run_plan<T, R_SUM>(h, h->p_bwd_level[l - 1], h->d_tcol, a, w, s);
+        int rc = run_plan<T, R_SUM, G_HAG_BWD_LEVEL>(h, h->p_bwd_level[l - 1], h->d_tcol, a, w, s);
         if (rc) return rc;
     }
     a.out = gx;
     a.out_off = 0;
-    return run_plan<T, R_SUM>(h, h->p_bwd_src, h->d_tcol, a, w, s);
+    if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
+    return run_plan<T, R_SUM, G_HAG_BWD_SRC>(h, h->p_bwd_src, h->d_tcol, a, w, s);
 }
 
 template <typename T>
@@ -468,47 +549,55 @@ size_t hag_workspace_bytes(const hag_t *h, hag_op_t op, hag_dtype_t, int64_t d) 
 }
 
 static int forward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
-                         int32_t *argmax, void *ws, void *stream) {
+                         int32_t *argmax, void *ws, void *stream, uint32_t phases) {
     int rc = check_common(h, op, dt, d, x, y, ws, hag_workspace_bytes(h, op, dt, d) > 0);
     if (rc) return rc;
     if (op == HAG_MAX && !argmax && h->n > 0) { set_error("argmax is required for max"); return HAG_EINVAL; }
     if ((uintptr_t)argmax & 15) { set_error("argmax must be 16-byte aligned"); return HAG_EINVAL; }
-    if (x == y) { set_error("x and y must not alias"); return HAG_EINVAL; }
+    if (x == y && h->n > 0) { set_error("x and y must not alias"); return HAG_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
     if (dt == HAG_F32) {
-        if (op == HAG_MAX) return forward_impl<float, R_MAX>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s);
-        return forward_impl<float, R_SUM>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s);
+        if (op == HAG_MAX) return forward_impl<float, R_MAX>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s, phases);
+        return forward_impl<float, R_SUM>(h, naive, op, d, (const float *)x, (float *)y, argmax, ws, s, phases);
     }
-    if (op == HAG_MAX) return forward_impl<int32_t, R_MAX>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s);
-    return forward_impl<int32_t, R_SUM>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s);
+    if (op == HAG_MAX) return forward_impl<int32_t, R_MAX>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s, phases);
+    return forward_impl<int32_t, R_SUM>(h, naive, op, d, (const int32_t *)x, (int32_t *)y, argmax, ws, s, phases);
 }
 
 static int backward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy,
-                          const int32_t *argmax, void *gx, void *ws, void *stream) {
+                          const int32_t *argmax, void *gx, void *ws, void *stream, uint32_t phases) {
     int rc = check_common(h, op, dt, d, gy, gx, ws, op != HAG_MAX && hag_workspace_bytes(h, op, dt, d) > 0);
     if (rc) return rc;
     if (op == HAG_MAX && !argmax && h->n > 0) { set_error("argmax is required for max"); return HAG_EINVAL; }
-    if (gy == gx) { set_error("gy and gx must not alias"); return HAG_EINVAL; }
+    if (gy == gx && h->n > 0) { set_error("gy and gx must not alias"); return HAG_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
-    if (dt == HAG_F32) return backward_impl<float>(h, naive, op, d, (const float *)gy, argmax, (float *)gx, ws, s);
-    return backward_impl<int32_t>(h, naive, op, d, (const int32_t *)gy, argmax, (int32_t *)gx, ws, s);
+    if (dt == HAG_F32) return backward_impl<float>(h, naive, op, d, (const float *)gy, argmax, (float *)gx, ws, s, phases);
+    return backward_impl<int32_t>(h, naive, op, d, (const int32_t *)gy, argmax, (int32_t *)gx, ws, s, phases);
 }
 
 int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y, int32_t *argmax,
                 void *ws, void *stream) {
-    return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream);
+    return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, HAG_PHASE_ALL);
+}
+int hag_forward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
+                       int32_t *argmax, void *ws, void *stream, uint32_t phases) {
+    return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, phases);
 }
 int hag_naive_forward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y, int32_t *argmax,
                       void *ws, void *stream) {
-    return forward_entry(h, true, op, dt, d, x, y, argmax, ws, stream);
+    return forward_entry(h, true, op, dt, d, x, y, argmax, ws, stream, HAG_PHASE_ALL);
 }
 int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy, const int32_t *argmax,
                  void *gx, void *ws, void *stream) {
-    return backward_entry(h, false, op, dt, d, gy, argmax, gx, ws, stream);
+    return backward_entry(h, false, op, dt, d, gy, argmax, gx, ws, stream, HAG_PHASE_ALL);
+}
+int hag_backward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy, const int32_t *argmax,
+                        void *gx, void *ws, void *stream, uint32_t phases) {
+    return backward_entry(h, false, op, dt, d, gy, argmax, gx, ws, stream, phases);
 }
 int hag_naive_backward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy, const int32_t *argmax,
                        void *gx, void *ws, void *stream) {
-    return backward_entry(h, true, op, dt, d, gy, argmax, gx, ws, stream);
+    return backward_entry(h, true, op, dt, d, gy, argmax, gx, ws, stream, HAG_PHASE_ALL);
 }
 
 }  // extern "C"

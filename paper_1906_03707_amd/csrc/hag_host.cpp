@@ -3,6 +3,8 @@
 // schedules and statistics.  No device code here.
 #include <algorithm>
 #include <atomic>
+#include <chrono>
+#include <cstdio>
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
@@ -23,6 +25,11 @@ void set_error(const std::string &msg) { g_err = msg; }
 static int fail(int code, const std::string &msg) {
     set_error(msg);
     return code;
+}
+
+static int64_t env_i64(const char *name, int64_t dflt) {
+    const char *s = std::getenv(name);
+    return s ? std::atoll(s) : dflt;
 }
 
 static unsigned host_threads() {
@@ -110,16 +117,31 @@ struct Builder {
     std::vector<std::vector<int32_t>> out_agg;
     std::vector<int32_t> m_left, m_right, m_red, depth;
     std::vector<int32_t> scratch;
+    // Every list keeps its original members first, ordered by descending prio (their initial
+    // out-degree, an upper bound on any redundancy they can ever reach), then its aggregation
+    // members in creation order (whose creation redundancies are non-increasing).  A sweep
+    // that only cares about partners able to reach a threshold can then stop early.
+    std::vector<int32_t> prio, norig;
 
-    void init(const Csr &graph) {
+    void init(const Csr &graph, bool order_by_priority = false, unsigned threads = 1) {
         g = &graph;
         n = (int64_t)graph.ptr.size() - 1;
         nb = graph.col;
         len.resize(n);
         for (int64_t u = 0; u < n; ++u) len[u] = (int32_t)(graph.ptr[u + 1] - graph.ptr[u]);
+        norig = len;
         transpose(graph, n, gt);
         olen.resize(n);
         for (int64_t x = 0; x < n; ++x) olen[x] = (int32_t)(gt.ptr[x + 1] - gt.ptr[x]);
+        if (order_by_priority) {
+            prio = olen;
+            parallel_for((n + 255) / 256, threads, [&](int64_t blk, unsigned) {
+                for (int64_t u = blk * 256; u < std::min<int64_t>(n, blk * 256 + 256); ++u)
+                    std::sort(nb.begin() + graph.ptr[u], nb.begin() + graph.ptr[u + 1], [&](int32_t x, int32_t y) {
+                        return prio[x] != prio[y] ? prio[x] > prio[y] : x < y;
+                    });
+            });
+        }
     }
     int64_t a() const { return (int64_t)m_left.size(); }
     const int32_t *out_ptr(int32_t x) const { return x < n ? gt.col.data() + gt.ptr[x] : out_agg[x - n].data(); }
@@ -159,6 +181,7 @@ struct Builder {
                 if (l[i] != p && l[i] != q) l[k++] = l[i];
             l[k++] = w;
             len[u] = k;
+            norig[u] -= (p < n) + (q < n);
         }
         remove_from_out(p, scratch);
         remove_from_out(q, scratch);
@@ -196,6 +219,28 @@ struct Searcher {
     std::priority_queue<Entry> heap;
     unsigned threads = 1;
     bool single_thread = false;
+    // optional progress log / checkpoint of the merge list (environment: HAG_SEARCH_PROGRESS=<every>,
+    // HAG_SEARCH_CHECKPOINT=<file>); long searches can then be resumed with hag_from_merges
+    int64_t progress_every = 0;
+    std::chrono::steady_clock::time_point t_start;
+    int64_t n_eval = 0, n_eval_exact = 0;
+
+    void report_progress() {
+        double el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
+        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps (%lld exact)\n",
+                     (long long)b.a(), b.m_red.back(), el, (long long)n_eval, (long long)n_eval_exact);
+        if (const char *path = std::getenv("HAG_SEARCH_CHECKPOINT")) {
+            std::string tmp = std::string(path) + ".tmp";
+            if (FILE *f = std::fopen(tmp.c_str(), "wb")) {
+                int64_t a = b.a();
+                std::fwrite(&a, sizeof a, 1, f);
+                std::fwrite(b.m_left.data(), sizeof(int32_t), (size_t)a, f);
+                std::fwrite(b.m_right.data(), sizeof(int32_t), (size_t)a, f);
+                std::fclose(f);
+                std::rename(tmp.c_str(), path);
+            }
+        }
+    }
     std::vector<std::vector<int32_t>> cnt, touched;
 
     void push(int32_t x) {
@@ -204,19 +249,35 @@ struct Searcher {
     }
     bool mergeable(int32_t x) const { return max_depth <= 0 || b.depth_of(x) < max_depth; }
 
-    // exact best partner of x: one counting sweep over the lists that hold x
+    // Best partner of x by one counting sweep over the lists that hold x, restricted to
+    // partners whose static bound reaches theta = half of x's current key.  If the best
+    // count found reaches theta it is exact (every uncounted partner is below theta);
+    // otherwise theta-1 becomes x's new, smaller upper bound and x is looked at again
+    // later with a lower threshold.
     void evaluate(int32_t x, unsigned t) {
         auto &c = cnt[t];
         auto &tl = touched[t];
         tl.clear();
+        const int32_t theta = std::max(2, (key[x] + 1) / 2);
         const int32_t *o = b.out_ptr(x);
-        int32_t ol = b.out_len(x);
+        const int32_t ol = b.out_len(x);
+        const int32_t n = (int32_t)b.n;
         for (int32_t i = 0; i < ol; ++i) {
-            int32_t u = o[i];
+            const int32_t u = o[i];
             const int32_t *l = b.nb.data() + b.g->ptr[u];
-            int32_t L = b.len[u];
-            for (int32_t j = 0; j < L; ++j) {
+            const int32_t no = b.norig[u], L = b.len[u];
+            int32_t lo = 0, hi = no;          // first original member with prio < theta
+            while (lo < hi) {
+                int32_t mid = (lo + hi) >> 1;
+                if (b.prio[l[mid]] >= theta) lo = mid + 1; else hi = mid;
+            }
+            for (int32_t j = 0; j < lo; ++j) {
                 int32_t y = l[j];
+                if (c[y]++ == 0) tl.push_back(y);
+            }
+            for (int32_t j = no; j < L; ++j) {
+                int32_t y = l[j];
+                if (b.m_red[y - n] < theta) break;
                 if (c[y]++ == 0) tl.push_back(y);
             }
         }
@@ -227,9 +288,15 @@ struct Searcher {
             if (y == x || !mergeable(y)) continue;
             if (v > best || (v == best && y < by)) { best = v; by = y; }
         }
-        key[x] = best;
-        partner[x] = by;
-        exact[x] = 1;
+        if (best >= theta || theta <= 2) {
+            key[x] = best;
+            partner[x] = by;
+            exact[x] = 1;
+        } else {
+            key[x] = theta - 1;
+            partner[x] = -1;
+            exact[x] = 0;
+        }
         eval_stamp[x] = iter;
     }
 
@@ -251,6 +318,8 @@ struct Searcher {
         key.assign(m, 0); partner.assign(m, -1); version.assign(m, 0);
         eval_stamp.assign(m, 0); mod_stamp.assign(m, 0); exact.assign(m, 0);
         threads = single_thread ? 1u : host_threads();
+        progress_every = single_thread ? 0 : env_i64("HAG_SEARCH_PROGRESS", 0);
+        t_start = std::chrono::steady_clock::now();
         cnt.assign(threads, std::vector<int32_t>(m, 0));
         touched.assign(threads, {});
         for (int64_t x = 0; x < n; ++x) { key[x] = b.olen[x]; push((int32_t)x); }
@@ -281,11 +350,14 @@ struct Searcher {
                     else dirty.push_back(x);
                 }
                 parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { evaluate(dirty[i], t); });
+                n_eval += (int64_t)dirty.size();
+                for (int32_t x : dirty) n_eval_exact += exact[x];
                 for (int32_t x : dirty) push(x);
             }
             if (chosen < 0 || key[chosen] < 2) break;
             int32_t p = chosen, q = partner[chosen];
             b.apply_merge(p, q);
+            if (progress_every > 0 && b.a() % progress_every == 0) report_progress();
             int32_t w = (int32_t)(b.n + b.a() - 1);
             mod_stamp[p] = mod_stamp[q] = iter;
             ++iter;
@@ -304,40 +376,45 @@ struct Searcher {
 // ------------------------------------------------------------------------------------------
 // schedules
 // ------------------------------------------------------------------------------------------
-static int64_t env_i64(const char *name, int64_t dflt) {
-    const char *s = std::getenv(name);
-    return s ? std::atoll(s) : dflt;
-}
-
 static int length_class(int32_t cnt) {
     if (cnt <= 16) return cnt;
     int lg = 31 - __builtin_clz((unsigned)cnt);         // >= 4
     return 16 + (lg - 4) * 4 + ((cnt >> (lg - 2)) & 3);  // quarter-octave classes
 }
 
+// Rows of at most `sub_max` entries go to one sub-group of lanes; longer rows get a whole
+// workgroup whose sub-groups share the row and fold through LDS; rows beyond `block_max`
+// are cut into pieces of one workgroup each that write partial rows, folded by a second
+// launch.  Long work is ordered first so that the tail of a launch consists of short items.
 void build_plan(const Csr &c, int64_t row_begin, int64_t row_end, Plan &p) {
-    const int64_t chunk = env_i64("HAG_CHUNK", 1024);
-    const int64_t split_above = env_i64("HAG_SPLIT_ABOVE", 1536);
-    p.items.clear();
+    const int64_t sub_max = env_i64("HAG_SUB_MAX", 64);
+    const int64_t block_max = env_i64("HAG_BLOCK_MAX", 1024);
+    std::vector<Item> blk, sub;
     p.combine.clear();
     p.n_slots = 0;
     for (int64_t r = row_begin; r < row_end; ++r) {
         int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
-        if (cnt <= split_above) {
-            p.items.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
+        if (cnt <= sub_max) {
+            sub.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
+        } else if (cnt <= block_max) {
+            blk.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
         } else {
-            int64_t pieces = (cnt + chunk - 1) / chunk;
+            int64_t pieces = (cnt + block_max - 1) / block_max;
             int64_t per = (cnt + pieces - 1) / pieces;
             p.combine.push_back(Item{p.n_slots, (int32_t)pieces, (int32_t)r});
             for (int64_t k = 0; k < pieces; ++k) {
                 int64_t b0 = beg + k * per, b1 = std::min(beg + cnt, b0 + per);
-                p.items.push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots + k)});
+                blk.push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots + k)});
             }
             p.n_slots += pieces;
         }
     }
-    std::stable_sort(p.items.begin(), p.items.end(),
-                     [](const Item &x, const Item &y) { return length_class(x.cnt) > length_class(y.cnt); });
+    auto longer = [](const Item &x, const Item &y) { return length_class(x.cnt) > length_class(y.cnt); };
+    std::stable_sort(blk.begin(), blk.end(), longer);
+    std::stable_sort(sub.begin(), sub.end(), longer);
+    p.n_block = (int64_t)blk.size();
+    p.items = std::move(blk);
+    p.items.insert(p.items.end(), sub.begin(), sub.end());
 }
 
 // ------------------------------------------------------------------------------------------
@@ -466,7 +543,7 @@ int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t cap
         Searcher s;
         s.capacity = capacity;
         s.max_depth = max_depth;
-        s.b.init(h->g);
+        s.b.init(h->g, true, host_threads());
         if (capacity > 0) s.run();
         rc = finalize_from_builder(h.get(), s.b);
         if (rc) return rc;
@@ -510,8 +587,8 @@ int hag_search_batched(int64_t n, const int64_t *rowptr, const int32_t *col, int
             Searcher s;
             s.capacity = (int64_t)std::floor(capacity_fraction * (double)nv);
             s.max_depth = max_depth;
-            s.b.init(sub);
             s.single_thread = true;
+            s.b.init(sub, true);
             if (s.capacity > 0) s.run();
             res[gi].l = s.b.m_left;
             res[gi].r = s.b.m_right;

@@ -26,7 +26,10 @@ static_assert(sizeof(Item) == 16, "Item is loaded as one 16-byte vector");
 // Schedule of one gather launch (plus the optional second launch that folds the
 // partial slots of split rows).
 struct Plan {
-    std::vector<Item> items;     // ordered long -> short so that long items start first
+    // items[0 .. n_block): one whole workgroup each (long rows, longest first);
+    // items[n_block ..): one sub-group of lanes each (short rows, longest first)
+    std::vector<Item> items;
+    int64_t n_block = 0;
     std::vector<Item> combine;   // per split row: beg = first slot, cnt = #slots, row = output row
     int64_t n_slots = 0;
     // device copies
