@@ -199,21 +199,34 @@ struct Builder {
 //
 // The listing asks for the pair of maximal Redundancy in every iteration.  A heap over all
 // co-occurring pairs is infeasible for dense graphs (sum over u of |N(u)|^2 / 2 entries), so
-// the heap here is over NODES: key[x] is an upper bound on max_y Redundancy(x, y).  Pair
-// redundancies of existing pairs never grow (a rewrite only removes members from lists) and
-// a new node w = (p, q) satisfies Redundancy(x, w) <= Redundancy(x, p), so a bound stays
-// valid until it is re-evaluated, and an exact value (partner y, count c) stays exact until
-// x or y takes part in a merge that changes Redundancy(x, y).  The heap is ordered by
-// (key descending, id ascending) and the partner tie-break is the smallest id, which makes
-// the chosen pair the lexicographically smallest one of maximal redundancy.
+// the heap here is over NODES: key[x] is an upper bound on max_y Redundancy(x, y).
+//
+// Facts used (all follow from the rewrite loop, which only removes p and q from lists and
+// adds the new node w):
+//   (1) Redundancy(x, y) of an existing pair never grows, and changes only in an iteration
+//       that merges x or y;
+//   (2) a new node w = (p, q) has Redundancy(x, w) <= Redundancy(x, p) and <= Redundancy(x, q).
+// Per node x the search keeps a short list of candidate partners (y, c) with c an upper bound
+// on Redundancy(x, y) (exact at the iteration `stamp`), and `tail`, an upper bound for every
+// partner that existed at x's last sweep and is not listed.  By (2) a partner created later is
+// bounded by its parents, so key[x] = max(best c, tail) bounds all of x's pairs.  When x is on
+// top of the heap its best entry is made exact by intersecting the two out-lists (cheap), the
+// children of a changed partner are looked up the same way, and only when the list is
+// exhausted (best c <= tail) is x swept again: one counting pass over the lists that hold x.
+// The heap is ordered by (key descending, id ascending), entries by (c descending, id
+// ascending); this makes the accepted pair the lexicographically smallest (smaller id, larger
+// id) among the pairs of maximal redundancy, i.e. the result does not depend on the laziness.
 // ------------------------------------------------------------------------------------------
 struct Searcher {
     Builder b;
     int64_t capacity = 0;
     int32_t max_depth = 0;
-    std::vector<int32_t> key, partner, version;
-    std::vector<int64_t> eval_stamp, mod_stamp;   // iteration numbers
-    std::vector<uint8_t> exact;
+    static constexpr int kKeep = 12;              // candidates kept per sweep (more if tied)
+    struct Cand { int32_t y, c; int64_t stamp; };
+    std::vector<std::vector<Cand>> cand;           // sorted by (c desc, y asc)
+    std::vector<int32_t> key, tail, version;
+    std::vector<int64_t> mod_stamp, born;          // last iteration a node was merged / its creation
+    std::vector<std::vector<int32_t>> children;    // aggregation nodes built from a node
     int64_t iter = 1;
     using Entry = std::tuple<int32_t, int32_t, int32_t>;  // key, -id, version
     std::priority_queue<Entry> heap;
@@ -223,12 +236,13 @@ struct Searcher {
     // HAG_SEARCH_CHECKPOINT=<file>); long searches can then be resumed with hag_from_merges
     int64_t progress_every = 0;
     std::chrono::steady_clock::time_point t_start;
-    int64_t n_eval = 0, n_eval_exact = 0;
+    int64_t n_sweep = 0, n_refresh = 0;
+    std::vector<std::vector<int32_t>> cnt, touched;
 
     void report_progress() {
         double el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
-        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps (%lld exact)\n",
-                     (long long)b.a(), b.m_red.back(), el, (long long)n_eval, (long long)n_eval_exact);
+        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps, %lld refreshes\n",
+                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, (long long)n_refresh);
         if (const char *path = std::getenv("HAG_SEARCH_CHECKPOINT")) {
             std::string tmp = std::string(path) + ".tmp";
             if (FILE *f = std::fopen(tmp.c_str(), "wb")) {
@@ -241,20 +255,21 @@ struct Searcher {
             }
         }
     }
-    std::vector<std::vector<int32_t>> cnt, touched;
 
+    static bool better(const Cand &p, const Cand &q) { return p.c != q.c ? p.c > q.c : p.y < q.y; }
+    int32_t best_c(int32_t x) const { return cand[x].empty() ? 0 : cand[x][0].c; }
+    void rekey(int32_t x) { key[x] = std::max(best_c(x), tail[x]); }
     void push(int32_t x) {
         version[x]++;
         if (key[x] >= 2) heap.emplace(key[x], -x, version[x]);
     }
     bool mergeable(int32_t x) const { return max_depth <= 0 || b.depth_of(x) < max_depth; }
 
-    // Best partner of x by one counting sweep over the lists that hold x, restricted to
-    // partners whose static bound reaches theta = half of x's current key.  If the best
-    // count found reaches theta it is exact (every uncounted partner is below theta);
-    // otherwise theta-1 becomes x's new, smaller upper bound and x is looked at again
-    // later with a lower threshold.
-    void evaluate(int32_t x, unsigned t) {
+    // One counting pass over the lists that hold x, restricted to partners whose static bound
+    // reaches theta = half of x's key.  Counts >= theta are exact and complete; if none
+    // reaches theta, theta-1 becomes the bound for everything and x is swept again later with
+    // a lower threshold.
+    void sweep(int32_t x, unsigned t) {
         auto &c = cnt[t];
         auto &tl = touched[t];
         tl.clear();
@@ -281,93 +296,135 @@ struct Searcher {
                 if (c[y]++ == 0) tl.push_back(y);
             }
         }
-        int32_t best = 0, by = -1;
+        auto &lst = cand[x];
+        lst.clear();
+        int32_t below = theta - 1;   // bound for everything not listed
         for (int32_t y : tl) {
             int32_t v = c[y];
             c[y] = 0;
             if (y == x || !mergeable(y)) continue;
-            if (v > best || (v == best && y < by)) { best = v; by = y; }
+            if (v >= theta) lst.push_back(Cand{y, v, iter});
         }
-        if (best >= theta || theta <= 2) {
-            key[x] = best;
-            partner[x] = by;
-            exact[x] = 1;
-        } else {
-            key[x] = theta - 1;
-            partner[x] = -1;
-            exact[x] = 0;
+        std::sort(lst.begin(), lst.end(), better);
+        if ((int)lst.size() > kKeep) {
+            int32_t cut = lst[kKeep].c;            // first dropped count; keep only strictly larger
+            size_t keep = kKeep;
+            while (keep > 0 && lst[keep - 1].c == cut) --keep;
+            if (keep == 0) {                        // more than kKeep partners tied at the top
+                keep = kKeep;
+                while (keep < lst.size() && lst[keep].c == cut) ++keep;
+                cut = keep < lst.size() ? lst[keep].c : below;
+            }
+            lst.resize(keep);
+            below = std::max(below, cut);
         }
-        eval_stamp[x] = iter;
+        tail[x] = below;
+        rekey(x);
+        dump("swept", x);
     }
 
-    bool still_valid(int32_t x) {
-        if (!exact[x]) return false;
-        if (mod_stamp[x] >= eval_stamp[x]) return false;
-        int32_t y = partner[x];
-        if (y < 0) return true;
-        if (mod_stamp[y] >= eval_stamp[x]) {
-            // the partner changed; the value survives only if the shared lists did not
-            if (b.intersect(x, y, nullptr) != key[x]) return false;
-            eval_stamp[x] = iter;
+    // Make x's best entry exact, or report that x needs a sweep.  Returns 1 if the best entry
+    // is exact and beats the tail (x may be accepted), 0 if the key changed (push x back),
+    // -1 if the list is exhausted.
+    void dump(const char *what, int32_t x) {
+        if (!std::getenv("HAG_SEARCH_DEBUG")) return;
+        std::fprintf(stderr, "  [%s] iter %lld x=%d key=%d tail=%d mod=%lld outlen=%d:", what, (long long)iter, x, key[x], tail[x], (long long)mod_stamp[x], b.out_len(x));
+        for (auto &q : cand[x]) std::fprintf(stderr, " (%d,%d,@%lld)", q.y, q.c, (long long)q.stamp);
+        std::fprintf(stderr, "\n");
+    }
+    int refresh(int32_t x) {
+        auto &lst = cand[x];
+        dump("refresh", x);
+        if (lst.empty() || lst[0].c <= tail[x]) return tail[x] >= 2 || !lst.empty() ? -1 : 0;
+        Cand &e = lst[0];
+        if (mod_stamp[x] < e.stamp && mod_stamp[e.y] < e.stamp) return 1;
+        ++n_refresh;
+        const int64_t since = e.stamp;
+        const int32_t y = e.y;
+        e.c = b.intersect(x, y, nullptr);
+        e.stamp = iter;
+        // partners born from y since the entry was exact (fact 2: bounded by the old entry)
+        std::vector<int32_t> stack;
+        for (int32_t w : children[y]) if (born[w] >= since) stack.push_back(w);
+        while (!stack.empty()) {
+            int32_t w = stack.back();
+            stack.pop_back();
+            if (w == x || !mergeable(w)) continue;
+            bool listed = false;
+            for (const Cand &q : lst) listed |= (q.y == w);
+            if (listed) continue;
+            int32_t cw = b.intersect(x, w, nullptr);
+            if (cw <= tail[x]) continue;       // and so are its descendants
+            lst.push_back(Cand{w, cw, iter});
+            for (int32_t w2 : children[w]) stack.push_back(w2);
         }
-        return true;
+        std::sort(lst.begin(), lst.end(), better);
+        while (!lst.empty() && lst.back().c <= tail[x]) lst.pop_back();   // covered by the tail bound
+        rekey(x);
+        return 0;
     }
 
     void run() {
         int64_t n = b.n, m = n + capacity;
-        key.assign(m, 0); partner.assign(m, -1); version.assign(m, 0);
-        eval_stamp.assign(m, 0); mod_stamp.assign(m, 0); exact.assign(m, 0);
+        key.assign(m, 0); tail.assign(m, 0); version.assign(m, 0);
+        mod_stamp.assign(m, 0); born.assign(m, 0);
+        cand.assign(m, {}); children.assign(m, {});
         threads = single_thread ? 1u : host_threads();
         progress_every = single_thread ? 0 : env_i64("HAG_SEARCH_PROGRESS", 0);
         t_start = std::chrono::steady_clock::now();
         cnt.assign(threads, std::vector<int32_t>(m, 0));
         touched.assign(threads, {});
-        for (int64_t x = 0; x < n; ++x) { key[x] = b.olen[x]; push((int32_t)x); }
+        for (int64_t x = 0; x < n; ++x) { tail[x] = b.olen[x]; key[x] = tail[x]; push((int32_t)x); }
         std::vector<int32_t> batch, dirty;
         while (b.a() < capacity) {
             int32_t chosen = -1;
             while (!heap.empty()) {
-                batch.clear();
+                auto [k, negx, ver] = heap.top();
+                int32_t x = -negx;
+                heap.pop();
+                if (ver != version[x]) continue;
+                int rc = refresh(x);
+                if (rc == 1) { chosen = x; break; }
+                if (rc == 0) { push(x); continue; }
+                // x needs a sweep; sweep it together with the next few exhausted nodes
+                batch.assign(1, x);
                 dirty.clear();
-                // take the top entries: the first decides, the rest are evaluated speculatively
                 while (!heap.empty() && batch.size() < threads) {
-                    auto [k, negx, ver] = heap.top();
-                    int32_t x = -negx;
-                    if (ver != version[x]) { heap.pop(); continue; }
-                    if (!batch.empty() && k < key[batch[0]] / 2) break;
+                    auto [k2, negx2, ver2] = heap.top();
+                    int32_t x2 = -negx2;
+                    if (ver2 != version[x2]) { heap.pop(); continue; }
+                    if (k2 < key[x] / 2) break;
                     heap.pop();
-                    batch.push_back(x);
+                    batch.push_back(x2);
                 }
-                if (batch.empty()) break;
-                bool top_valid = still_valid(batch[0]);
-                if (top_valid) {
-                    chosen = batch[0];
-                    for (size_t i = 1; i < batch.size(); ++i) heap.emplace(key[batch[i]], -batch[i], version[batch[i]]);
-                    break;
+                for (int32_t z : batch) {
+                    bool exhausted = cand[z].empty() || cand[z][0].c <= tail[z];
+                    if (exhausted && key[z] >= 2) dirty.push_back(z);
+                    else heap.emplace(key[z], -z, version[z]);
                 }
-                for (int32_t x : batch) {
-                    if (still_valid(x)) heap.emplace(key[x], -x, version[x]);
-                    else dirty.push_back(x);
-                }
-                parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { evaluate(dirty[i], t); });
-                n_eval += (int64_t)dirty.size();
-                for (int32_t x : dirty) n_eval_exact += exact[x];
-                for (int32_t x : dirty) push(x);
+                parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { sweep(dirty[i], t); });
+                n_sweep += (int64_t)dirty.size();
+                for (int32_t z : dirty) push(z);
             }
             if (chosen < 0 || key[chosen] < 2) break;
-            int32_t p = chosen, q = partner[chosen];
+            int32_t p = chosen, q = cand[chosen][0].y;
+            if (std::getenv("HAG_SEARCH_DEBUG")) std::fprintf(stderr, "MERGE %d %d\n", p, q);
             b.apply_merge(p, q);
             if (progress_every > 0 && b.a() % progress_every == 0) report_progress();
             int32_t w = (int32_t)(b.n + b.a() - 1);
             mod_stamp[p] = mod_stamp[q] = iter;
+            born[w] = iter;
+            children[p].push_back(w);
+            children[q].push_back(w);
             ++iter;
             for (int32_t x : {p, q}) {
-                exact[x] = 0;
-                key[x] = std::min(key[x], b.out_len(x));
+                tail[x] = std::min(tail[x], b.out_len(x));
+                for (Cand &e : cand[x]) e.c = std::min(e.c, b.out_len(x));
+                rekey(x);
                 push(x);
             }
-            exact[w] = 0;
-            key[w] = mergeable(w) ? b.out_len(w) : 0;
+            tail[w] = mergeable(w) ? b.out_len(w) : 0;
+            rekey(w);
             push(w);
         }
     }
