@@ -31,19 +31,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_workload(cfg: int, binding, synth):
+def build_workload(cfg: int, capacity, workloads, synth):
     t0 = time.time()
     rowptr, col, graph_ptr = synth.graph_for_config(cfg)
-    n = rowptr.size - 1
-    t1 = time.time()
-    if cfg == 4:
-        h = binding.hag_search_batched(rowptr, col, graph_ptr, 0.25)
-    else:
-        h = binding.hag_search(rowptr, col, n // 4)
-    t2 = time.time()
-    log(f"[bench] config {cfg}: graph {t1 - t0:.1f}s, hag_search {t2 - t1:.1f}s")
-    d = {1: 64, 2: 128, 3: 128, 4: 64, 5: 128}[cfg]
-    return rowptr, col, h, d
+    log(f"[bench] config {cfg}: graph generated in {time.time() - t0:.1f}s")
+    h = workloads.build_hag(cfg, rowptr, col, graph_ptr, capacity, log=lambda m: log("[bench] " + m))
+    return rowptr, col, h, workloads.FEATURE_DIM[cfg]
 
 
 def time_steps(torch, fn, steps, warmup):
@@ -117,7 +110,11 @@ def main():
     ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload")
     ap.add_argument("--op", default="sum", choices=["sum", "mean", "max"])
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
+    ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
+                         "WRITE_SIZE readings of the same run can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on ONE GPU only (no collectives, no sharding); use --gpus 1")
@@ -125,14 +122,14 @@ def main():
     import numpy as np
     import torch
 
-    from paper_1906_03707_amd import binding, synth
+    from paper_1906_03707_amd import binding, synth, workloads
 
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible (the HIP path has no CPU fallback)")
     binding.lib()
     torch.cuda.set_device(0)
     cfg = args.config
-    rowptr, col, h, d = build_workload(cfg, binding, synth)
+    rowptr, col, h, d = build_workload(cfg, None if args.capacity < 0 else args.capacity, workloads, synth)
     if args.d:
         d = args.d
     op = args.op
@@ -145,6 +142,14 @@ def main():
     y = torch.empty_like(x)
     gx = torch.empty_like(x)
     am = torch.empty((n, d), dtype=torch.int32, device="cuda") if op == "max" else None
+
+    if args.copy_calibration:
+        a = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        b = torch.empty_like(a)
+        for _ in range(3):
+            b.copy_(a)                       # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del a, b
 
     def step_hag():
         h.forward(x, op, y=y, argmax=am)

@@ -79,6 +79,7 @@ typedef struct hag_stats {
     int64_t xfer_hag;     /* neighbour-row transfers on the HAG = |E^| */
     int64_t max_degree;   /* largest |N(v)| */
     int64_t max_hag_degree; /* largest |Nhat_v| */
+    int64_t stages;       /* kernel launches the aggregation nodes take (runs of fused levels) */
 } hag_stats_t;
 
 /* ---------------------------------------------------------------- host ---- */

@@ -11,6 +11,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <string>
 
 #include "hag_internal.hpp"
@@ -23,7 +24,7 @@ constexpr int kWave = 64;
 enum { R_SUM = 0, R_MAX = 1 };
 // which phase a gather launch belongs to: only a tag, so that every phase has a kernel symbol
 // of its own in profiler output
-enum { G_HAG_FWD = 0, G_HAG_BWD_LEVEL = 1, G_HAG_BWD_SRC = 2, G_NAIVE_FWD = 3, G_NAIVE_BWD = 4, G_FOLD = 5 };
+enum { G_HAG_FWD = 0, G_HAG_BWD_LEVEL = 1, G_HAG_BWD_SRC = 2, G_NAIVE_FWD = 3, G_NAIVE_BWD = 4, G_FOLD = 5, G_HAG_FWD_STAGE = 6 };
 
 template <typename T> struct V4;
 template <> struct V4<float> { using type = float4; };
@@ -32,8 +33,12 @@ template <> struct V4<int32_t> { using type = int4; };
 template <typename T>
 struct GatherArgs {
     const Item *items;
-    int64_t n_items;          // all items
-    int64_t n_block;          // the first n_block of them take one workgroup each
+    int np;                   // 1 or kPartitions: workgroup b works on partition b mod np
+    struct {
+        int64_t begin;        // first item of the partition
+        int64_t n_block;      // its first n_block items take one workgroup each
+        int64_t n_items;      // all its items
+    } seg[kPartitions];
     const int32_t *col;
     const T *src_lo;          // rows of ids < split
     const T *src_hi;          // rows of ids >= split, row (id - split)
@@ -191,8 +196,11 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     V acc{};
     int4 acc_id = make_int4(-1, -1, -1, -1);
 
-    if ((int64_t)blockIdx.x < A.n_block) {
-        const Item it = load_item(A.items + blockIdx.x);
+    const int part = blockIdx.x % A.np;
+    const int64_t vb = blockIdx.x / A.np;            // index of this workgroup inside its partition
+    const int64_t p_begin = A.seg[part].begin, p_block = A.seg[part].n_block, p_items = A.seg[part].n_items;
+    if (vb < p_block) {
+        const Item it = load_item(A.items + p_begin + vb);
         const int sg = threadIdx.x / LPR;
         int per = (it.cnt + NSG - 1) / NSG;
         per = (per + UNR - 1) / UNR * UNR;
@@ -213,10 +221,10 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     }
     const int wave = threadIdx.x / kWave;
     const int sg = lane / LPR;
-    const int64_t item_idx = A.n_block + (((int64_t)blockIdx.x - A.n_block) * (kBlock / kWave) + wave) * SG + sg;
-    const bool has_item = item_idx < A.n_items;
+    const int64_t local = p_block + ((vb - p_block) * (kBlock / kWave) + wave) * SG + sg;
+    const bool has_item = local < p_items;
     Item it{0, 0, 0};
-    if (has_item) it = load_item(A.items + item_idx);
+    if (has_item) it = load_item(A.items + p_begin + local);
     int maxcnt = it.cnt;
 #pragma unroll
     for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
@@ -308,7 +316,10 @@ template <typename T, int RED, int LPR, int ROLE>
 static int launch_gather_lpr(const GatherArgs<T> &a, hipStream_t s) {
     constexpr int SG = kWave / LPR;
     const int64_t per_block = (kBlock / kWave) * SG;
-    const int64_t gx = a.n_block + (a.n_items - a.n_block + per_block - 1) / per_block;
+    int64_t most = 0;   // workgroups of the busiest partition; the grid gives every partition that many
+    for (int k = 0; k < a.np; ++k)
+        most = std::max(most, a.seg[k].n_block + (a.seg[k].n_items - a.seg[k].n_block + per_block - 1) / per_block);
+    const int64_t gx = most * a.np;
     const int64_t gy = (a.d / 4 + LPR - 1) / LPR;
     if (gx <= 0) return HAG_OK;
     if (gx > 0x7fffffffLL || gy > 65535) { set_error("launch too large"); return HAG_EINVAL; }
@@ -358,8 +369,19 @@ template <typename T, int RED, int ROLE>
 static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, GatherArgs<T> a, const Workspace &w,
                     hipStream_t s) {
     a.items = p.d_items;
-    a.n_items = (int64_t)p.items.size();
-    a.n_block = p.n_block;
+    a.np = p.np;
+    // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
+    // eight neighbours, and needs one when a single sub-group would walk it for too long.
+    {
+        static const int64_t sub_max = [] { const char *e = std::getenv("HAG_SUB_MAX"); return e ? std::atoll(e) : 0LL; }();
+        const int64_t nsg = kBlock / pick_lpr(a.d);
+        const int64_t threshold = sub_max > 0 ? sub_max : std::max<int64_t>(64, 8 * nsg);
+        for (int k = 0; k < p.np; ++k) {
+            a.seg[k].begin = p.part_begin[k];
+            a.seg[k].n_items = p.part_begin[k + 1] - p.part_begin[k];
+            a.seg[k].n_block = long_items(p, k, threshold);
+        }
+    }
     a.col = d_col;
     a.part = (T *)w.part;
     a.part_id = (int32_t *)w.part_id;
@@ -368,8 +390,10 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     if (!p.combine.empty()) {
         GatherArgs<T> c = a;
         c.items = p.d_combine;
-        c.n_items = (int64_t)p.combine.size();
-        c.n_block = 0;
+        c.np = 1;
+        c.seg[0].begin = 0;
+        c.seg[0].n_block = 0;
+        c.seg[0].n_items = (int64_t)p.combine.size();
         c.col = h->d_slot_ids;
         c.split = 0;               // every id refers to a partial slot
         c.src_lo = nullptr;
@@ -402,14 +426,30 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
     Workspace w = carve(h, op, d, ws);
     const int32_t n = (int32_t)h->n;
     if (!naive && (phases & HAG_PHASE_LEVELS)) {
-        for (int32_t l = 1; l <= h->levels; ++l) {
-            int32_t first = h->level_ptr[l - 1], last = h->level_ptr[l];
-            int64_t threads = (int64_t)(last - first) * (d / 4);
-            if (threads <= 0) continue;
-            int64_t blocks = (threads + kBlock - 1) / kBlock;
-            hipLaunchKernelGGL((level_kernel<T, RED>), dim3((unsigned)blocks), dim3(kBlock), 0, s, h->d_left, h->d_right,
-                               first, last, n, (int32_t)d, x, (T *)w.agg, (int32_t *)w.agg_id);
-            HIP_TRY(hipGetLastError());
+        for (int32_t st = 0; st < h->stages; ++st) {
+            const int32_t first = h->stage_ptr[st], last = h->stage_ptr[st + 1];
+            if (h->stage_single_level[st]) {
+                int64_t threads = (int64_t)(last - first) * (d / 4);
+                if (threads <= 0) continue;
+                int64_t blocks = (threads + kBlock - 1) / kBlock;
+                hipLaunchKernelGGL((level_kernel<T, RED>), dim3((unsigned)blocks), dim3(kBlock), 0, s, h->d_left,
+                                   h->d_right, first, last, n, (int32_t)d, x, (T *)w.agg, (int32_t *)w.agg_id);
+                HIP_TRY(hipGetLastError());
+            } else {
+                // several levels in one launch: every node gathers its inputs expanded down to
+                // earlier stages
+                GatherArgs<T> e{};
+                e.src_lo = x;
+                e.src_hi = (const T *)w.agg;
+                e.id_hi = (const int32_t *)w.agg_id;
+                e.split = n;
+                e.out = (T *)w.agg;
+                e.out_id = (int32_t *)w.agg_id;
+                e.out_off = n;
+                e.d = (int32_t)d;
+                int rc = run_plan<T, RED, G_HAG_FWD_STAGE>(h, h->p_fwd_stage[st], h->d_ecol, e, w, s);
+                if (rc) return rc;
+            }
         }
     }
     GatherArgs<T> a{};
@@ -458,12 +498,12 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
         if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
         return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s);
     }
-    // deepest level first: its consumers are destinations only; level l may also be consumed
-    // by aggregation nodes of deeper levels, whose gradient rows are complete by then
-    for (int32_t l = h->levels; l >= 1 && (phases & HAG_PHASE_LEVELS); --l) {
+    // deepest stage first: its consumers are destinations only; an earlier stage may also be
+    // consumed by aggregation nodes of later stages, whose gradient rows are complete by then
+    for (int32_t st = h->stages - 1; st >= 0 && (phases & HAG_PHASE_LEVELS); --st) {
         a.out = (T *)w.agg;
         a.out_off = n;
-        int rc = run_plan<T, R_SUM, G_HAG_BWD_LEVEL>(h, h->p_bwd_level[l - 1], h->d_tcol, a, w, s);
+        int rc = run_plan<T, R_SUM, G_HAG_BWD_LEVEL>(h, h->p_bwd_stage[st], h->d_tcol, a, w, s);
         if (rc) return rc;
     }
     a.out = gx;
@@ -519,14 +559,17 @@ int hag_upload(hag_t *h, void *stream) {
     for (size_t i = 0; i < slots.size(); ++i) slots[i] = (int32_t)i;
     if ((rc = upload_array(h, h->left, &h->d_left, s))) goto bad;
     if ((rc = upload_array(h, h->right, &h->d_right, s))) goto bad;
-    if ((rc = upload_array(h, h->hf.col, &h->d_hcol, s))) goto bad;
-    if ((rc = upload_array(h, h->ht.col, &h->d_tcol, s))) goto bad;
-    if ((rc = upload_array(h, h->g.col, &h->d_gcol, s))) goto bad;
-    if ((rc = upload_array(h, h->gt.col, &h->d_gtcol, s))) goto bad;
+    if ((rc = upload_array(h, h->hf_dcol, &h->d_hcol, s))) goto bad;
+    if ((rc = upload_array(h, h->ht_dcol, &h->d_tcol, s))) goto bad;
+    if ((rc = upload_array(h, h->he.col, &h->d_ecol, s))) goto bad;
+    if ((rc = upload_array(h, h->g_dcol, &h->d_gcol, s))) goto bad;
+    if ((rc = upload_array(h, h->gt_dcol, &h->d_gtcol, s))) goto bad;
     if ((rc = upload_array(h, slots, &h->d_slot_ids, s))) goto bad;
     if ((rc = upload_array(h, h->inv_deg, &h->d_inv_deg, s))) goto bad;
     if ((rc = upload_plan(h, h->p_fwd, s))) goto bad;
-    for (auto &p : h->p_bwd_level)
+    for (auto &p : h->p_bwd_stage)
+        if ((rc = upload_plan(h, p, s))) goto bad;
+    for (auto &p : h->p_fwd_stage)
         if ((rc = upload_plan(h, p, s))) goto bad;
     if ((rc = upload_plan(h, h->p_bwd_src, s))) goto bad;
     if ((rc = upload_plan(h, h->p_naive_fwd, s))) goto bad;
@@ -536,6 +579,7 @@ int hag_upload(hag_t *h, void *stream) {
         if (e != hipSuccess) { rc = hip_fail(e, "hipStreamSynchronize"); goto bad; }
     }
     h->uploaded = true;
+    for (auto *v : {&h->hf_dcol, &h->ht_dcol, &h->g_dcol, &h->gt_dcol}) std::vector<int32_t>().swap(*v);
     return HAG_OK;
 bad:
     (void)hipStreamSynchronize(s);

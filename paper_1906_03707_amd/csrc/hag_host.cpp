@@ -221,7 +221,7 @@ struct Searcher {
     Builder b;
     int64_t capacity = 0;
     int32_t max_depth = 0;
-    static constexpr int kKeep = 12;              // candidates kept per sweep (more if tied)
+    int kKeep = 12;                               // candidates kept per sweep (more if tied)
     struct Cand { int32_t y, c; int64_t stamp; };
     std::vector<std::vector<Cand>> cand;           // sorted by (c desc, y asc)
     std::vector<int32_t> key, tail, version;
@@ -237,12 +237,14 @@ struct Searcher {
     int64_t progress_every = 0;
     std::chrono::steady_clock::time_point t_start;
     int64_t n_sweep = 0, n_refresh = 0;
+    double t_sweep = 0, t_refresh = 0, t_merge = 0;
+    int64_t sweep_work = 0;
     std::vector<std::vector<int32_t>> cnt, touched;
 
     void report_progress() {
         double el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
-        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps, %lld refreshes\n",
-                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, (long long)n_refresh);
+        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps (%.1f s), %lld refreshes (%.1f s), merges %.1f s\n",
+                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, t_sweep, (long long)n_refresh, t_refresh, t_merge);
         if (const char *path = std::getenv("HAG_SEARCH_CHECKPOINT")) {
             std::string tmp = std::string(path) + ".tmp";
             if (FILE *f = std::fopen(tmp.c_str(), "wb")) {
@@ -308,10 +310,10 @@ struct Searcher {
         std::sort(lst.begin(), lst.end(), better);
         if ((int)lst.size() > kKeep) {
             int32_t cut = lst[kKeep].c;            // first dropped count; keep only strictly larger
-            size_t keep = kKeep;
+            size_t keep = (size_t)kKeep;
             while (keep > 0 && lst[keep - 1].c == cut) --keep;
             if (keep == 0) {                        // more than kKeep partners tied at the top
-                keep = kKeep;
+                keep = (size_t)kKeep;
                 while (keep < lst.size() && lst[keep].c == cut) ++keep;
                 cut = keep < lst.size() ? lst[keep].c : below;
             }
@@ -320,21 +322,13 @@ struct Searcher {
         }
         tail[x] = below;
         rekey(x);
-        dump("swept", x);
     }
 
     // Make x's best entry exact, or report that x needs a sweep.  Returns 1 if the best entry
     // is exact and beats the tail (x may be accepted), 0 if the key changed (push x back),
     // -1 if the list is exhausted.
-    void dump(const char *what, int32_t x) {
-        if (!std::getenv("HAG_SEARCH_DEBUG")) return;
-        std::fprintf(stderr, "  [%s] iter %lld x=%d key=%d tail=%d mod=%lld outlen=%d:", what, (long long)iter, x, key[x], tail[x], (long long)mod_stamp[x], b.out_len(x));
-        for (auto &q : cand[x]) std::fprintf(stderr, " (%d,%d,@%lld)", q.y, q.c, (long long)q.stamp);
-        std::fprintf(stderr, "\n");
-    }
     int refresh(int32_t x) {
         auto &lst = cand[x];
-        dump("refresh", x);
         if (lst.empty() || lst[0].c <= tail[x]) return tail[x] >= 2 || !lst.empty() ? -1 : 0;
         Cand &e = lst[0];
         if (mod_stamp[x] < e.stamp && mod_stamp[e.y] < e.stamp) return 1;
@@ -371,6 +365,7 @@ struct Searcher {
         cand.assign(m, {}); children.assign(m, {});
         threads = single_thread ? 1u : host_threads();
         progress_every = single_thread ? 0 : env_i64("HAG_SEARCH_PROGRESS", 0);
+        kKeep = (int)std::max<int64_t>(1, env_i64("HAG_SEARCH_KEEP", 12));
         t_start = std::chrono::steady_clock::now();
         cnt.assign(threads, std::vector<int32_t>(m, 0));
         touched.assign(threads, {});
@@ -383,7 +378,9 @@ struct Searcher {
                 int32_t x = -negx;
                 heap.pop();
                 if (ver != version[x]) continue;
+                auto t0 = std::chrono::steady_clock::now();
                 int rc = refresh(x);
+                t_refresh += std::chrono::duration<double>(std::chrono::steady_clock::now() - t0).count();
                 if (rc == 1) { chosen = x; break; }
                 if (rc == 0) { push(x); continue; }
                 // x needs a sweep; sweep it together with the next few exhausted nodes
@@ -402,14 +399,17 @@ struct Searcher {
                     if (exhausted && key[z] >= 2) dirty.push_back(z);
                     else heap.emplace(key[z], -z, version[z]);
                 }
+                auto t1 = std::chrono::steady_clock::now();
                 parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { sweep(dirty[i], t); });
+                t_sweep += std::chrono::duration<double>(std::chrono::steady_clock::now() - t1).count();
                 n_sweep += (int64_t)dirty.size();
                 for (int32_t z : dirty) push(z);
             }
             if (chosen < 0 || key[chosen] < 2) break;
             int32_t p = chosen, q = cand[chosen][0].y;
-            if (std::getenv("HAG_SEARCH_DEBUG")) std::fprintf(stderr, "MERGE %d %d\n", p, q);
+            auto t2 = std::chrono::steady_clock::now();
             b.apply_merge(p, q);
+            t_merge += std::chrono::duration<double>(std::chrono::steady_clock::now() - t2).count();
             if (progress_every > 0 && b.a() % progress_every == 0) report_progress();
             int32_t w = (int32_t)(b.n + b.a() - 1);
             mod_stamp[p] = mod_stamp[q] = iter;
@@ -439,39 +439,117 @@ static int length_class(int32_t cnt) {
     return 16 + (lg - 4) * 4 + ((cnt >> (lg - 2)) & 3);  // quarter-octave classes
 }
 
-// Rows of at most `sub_max` entries go to one sub-group of lanes; longer rows get a whole
-// workgroup whose sub-groups share the row and fold through LDS; rows beyond `block_max`
-// are cut into pieces of one workgroup each that write partial rows, folded by a second
-// launch.  Long work is ordered first so that the tail of a launch consists of short items.
-void build_plan(const Csr &c, int64_t row_begin, int64_t row_end, Plan &p) {
-    const int64_t sub_max = env_i64("HAG_SUB_MAX", 64);
+// Schedule of one gather launch over rows [row_begin, row_end) of `c`.
+//
+// One item per row; rows beyond `block_max` entries are cut into pieces that write partial
+// rows, folded by a second launch.  Which items get a whole workgroup and which a single
+// sub-group of lanes is decided at launch time (see long_items()).
+//
+// Source partitioning.  MI355X has 8 XCDs with a private 4 MB L2 each, and workgroups are
+// handed to XCDs round-robin, so workgroup b runs on XCD b mod 8.  When the gathered matrix
+// is much larger than one L2, every row of at least `part_min` entries is cut by SOURCE id
+// (id mod 8) into 8 segments and segment k is scheduled on workgroups with b mod 8 == k:
+// each L2 then only ever sees one eighth of the source rows, which raises its hit rate.
+// `dcol` (a copy of c.col) is reordered inside such rows so that a segment is contiguous.
+// The segments write partial rows that the fold launch adds up.  Items of unpartitioned rows
+// are dealt round-robin to the 8 lists.
+void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p,
+                bool partition) {
     const int64_t block_max = env_i64("HAG_BLOCK_MAX", 1024);
-    std::vector<Item> blk, sub;
+    const int64_t part_min = env_i64("HAG_PART_MIN", 128);
+    // cutting by source only pays when the rows long enough to be cut hold most of the entries;
+    // otherwise keep one list, which also keeps neighbouring rows on neighbouring workgroups
+    if (partition) {
+        int64_t total = c.ptr[row_end] - c.ptr[row_begin], in_long = 0;
+        for (int64_t r = row_begin; r < row_end; ++r) {
+            int64_t cnt = c.ptr[r + 1] - c.ptr[r];
+            if (cnt >= part_min) in_long += cnt;
+        }
+        partition = total > 0 && in_long * 100 >= total * env_i64("HAG_PART_SHARE_PCT", 30);
+    }
+    const int np = partition ? kPartitions : 1;
+    std::vector<std::vector<Item>> lists(np);
+    p.items.clear();
     p.combine.clear();
     p.n_slots = 0;
+    p.np = np;
+    auto cut = [&](int part, int64_t beg, int64_t cnt, bool partial, int64_t row) {
+        // appends the items of one contiguous run of entries; returns nothing, bumps n_slots
+        if (!partial && cnt <= block_max) {
+            lists[part].push_back(Item{beg, (int32_t)cnt, (int32_t)row});
+            return;
+        }
+        int64_t pieces = std::max<int64_t>(1, (cnt + block_max - 1) / block_max);
+        int64_t per = (cnt + pieces - 1) / pieces;
+        for (int64_t k = 0; k < pieces; ++k) {
+            int64_t b0 = beg + k * per, b1 = std::min(beg + cnt, b0 + per);
+            lists[part].push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots++)});
+        }
+    };
+    int rr = 0, rr_run = 0;     // whole rows go to the lists in runs of 64, which keeps neighbours together
+    auto next_list = [&] { if (++rr_run == 64) { rr_run = 0; rr = (rr + 1) % np; } };
     for (int64_t r = row_begin; r < row_end; ++r) {
         int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
-        if (cnt <= sub_max) {
-            sub.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
-        } else if (cnt <= block_max) {
-            blk.push_back(Item{beg, (int32_t)cnt, (int32_t)r});
-        } else {
-            int64_t pieces = (cnt + block_max - 1) / block_max;
-            int64_t per = (cnt + pieces - 1) / pieces;
-            p.combine.push_back(Item{p.n_slots, (int32_t)pieces, (int32_t)r});
-            for (int64_t k = 0; k < pieces; ++k) {
-                int64_t b0 = beg + k * per, b1 = std::min(beg + cnt, b0 + per);
-                blk.push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots + k)});
+        if (np > 1 && cnt >= part_min) {
+            int32_t *row = dcol.data() + beg;
+            std::sort(row, row + cnt, [](int32_t x, int32_t y) {
+                int px = x & (kPartitions - 1), py = y & (kPartitions - 1);
+                return px != py ? px < py : x < y;
+            });
+            int64_t first_slot = p.n_slots, i = 0;
+            while (i < cnt) {
+                int part = row[i] & (kPartitions - 1);
+                int64_t j = i;
+                while (j < cnt && (row[j] & (kPartitions - 1)) == part) ++j;
+                cut(part, beg + i, j - i, true, r);
+                i = j;
             }
-            p.n_slots += pieces;
+            p.combine.push_back(Item{first_slot, (int32_t)(p.n_slots - first_slot), (int32_t)r});
+        } else if (cnt > block_max) {
+            int64_t first_slot = p.n_slots;
+            cut(rr, beg, cnt, true, r);
+            next_list();
+            p.combine.push_back(Item{first_slot, (int32_t)(p.n_slots - first_slot), (int32_t)r});
+        } else {
+            cut(rr, beg, cnt, false, r);
+            next_list();
+        }
+    }
+    if (np > 1) {
+        // even out the lists: move whole-row items from long lists to short ones (their source
+        // ids are mixed anyway), so that every XCD gets about the same number of entries
+        std::vector<int64_t> load(np, 0);
+        int64_t total = 0;
+        for (int k = 0; k < np; ++k) for (const Item &it : lists[k]) load[k] += it.cnt + 8;
+        for (int k = 0; k < np; ++k) total += load[k];
+        int64_t target = total / np;
+        std::vector<Item> pool;
+        for (int k = 0; k < np; ++k) {
+            auto &l = lists[k];
+            for (size_t i = l.size(); i-- > 0 && load[k] > target;)
+                if (l[i].row >= 0) { load[k] -= l[i].cnt + 8; pool.push_back(l[i]); l.erase(l.begin() + i); }
+        }
+        for (const Item &it : pool) {
+            int k = (int)(std::min_element(load.begin(), load.end()) - load.begin());
+            lists[k].push_back(it);
+            load[k] += it.cnt + 8;
         }
     }
     auto longer = [](const Item &x, const Item &y) { return length_class(x.cnt) > length_class(y.cnt); };
-    std::stable_sort(blk.begin(), blk.end(), longer);
-    std::stable_sort(sub.begin(), sub.end(), longer);
-    p.n_block = (int64_t)blk.size();
-    p.items = std::move(blk);
-    p.items.insert(p.items.end(), sub.begin(), sub.end());
+    p.part_begin.assign(np + 1, 0);
+    for (int k = 0; k < np; ++k) {
+        std::stable_sort(lists[k].begin(), lists[k].end(), longer);
+        p.items.insert(p.items.end(), lists[k].begin(), lists[k].end());
+        p.part_begin[k + 1] = (int64_t)p.items.size();
+    }
+}
+
+// Number of leading items of partition k whose length class exceeds that of `threshold` entries.
+int64_t long_items(const Plan &p, int k, int64_t threshold) {
+    const int cls = length_class((int32_t)std::min<int64_t>(threshold, INT32_MAX));
+    auto b = p.items.begin() + p.part_begin[k], e = p.items.begin() + p.part_begin[k + 1];
+    auto it = std::partition_point(b, e, [cls](const Item &x) { return length_class(x.cnt) > cls; });
+    return (int64_t)(it - b);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -514,18 +592,78 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
         for (int32_t i = 0; i < b.len[v]; ++i) dst[i] = remap(src[i]);
         std::sort(dst, dst + b.len[v]);
     }
-    // transposed HAG: consumers of every source
+    // Stages: consecutive levels executed by one launch.  A node of a stage is expressed over
+    // nodes of earlier stages (and originals) by expanding its inputs that lie in the same
+    // stage, which by cover()'s definition (Section 3.1) leaves aggr(w) unchanged.  A level
+    // joins the running stage while the extra row reads this causes stay small against the
+    // cost of one more launch; a stage of a single level keeps the two-input form.
     {
-        Csr all;  // rows: destinations 0..n-1 then aggregation nodes; cols: their in-neighbours
+        const int64_t extra_rows = env_i64("HAG_STAGE_EXTRA_ROWS", 32768);
+        const double extra_frac = 0.25;
+        const int64_t max_expand = 256;
+        Csr &he = h->he;
+        he.ptr.assign(1, 0);
+        he.col.clear();
+        h->stage_ptr.assign(1, 0);
+        std::vector<int32_t> node_level(a);
+        for (int32_t l = 1; l <= h->levels; ++l)
+            for (int32_t i = h->level_ptr[l - 1]; i < h->level_ptr[l]; ++i) node_level[i] = l;
+        int32_t base_level = 0;              // levels <= base_level belong to closed stages
+        int64_t stage_reads = 0, stage_nodes = 0;
+        std::vector<int32_t> tmp;
+        auto expand_level = [&](int32_t l, std::vector<int64_t> &ptr_out, std::vector<int32_t> &col_out) {
+            int64_t worst = 0;
+            ptr_out.clear();
+            col_out.clear();
+            for (int32_t i = h->level_ptr[l - 1]; i < h->level_ptr[l]; ++i) {
+                size_t before = col_out.size();
+                for (int32_t u : {h->left[i], h->right[i]}) {
+                    if (u >= n && node_level[u - n] > base_level)
+                        col_out.insert(col_out.end(), he.col.begin() + he.ptr[u - n], he.col.begin() + he.ptr[u - n + 1]);
+                    else
+                        col_out.push_back(u);
+                }
+                std::sort(col_out.begin() + before, col_out.end());
+                worst = std::max<int64_t>(worst, (int64_t)(col_out.size() - before));
+                ptr_out.push_back((int64_t)col_out.size());
+            }
+            return worst;
+        };
+        std::vector<int64_t> lp;
+        std::vector<int32_t> lc;
+        for (int32_t l = 1; l <= h->levels; ++l) {
+            int64_t nodes = h->level_ptr[l] - h->level_ptr[l - 1];
+            int64_t worst = expand_level(l, lp, lc);
+            bool first = (l == base_level + 1);
+            int64_t reads = stage_reads + (int64_t)lc.size(), cnt = stage_nodes + nodes;
+            bool ok = first || (worst <= max_expand && reads <= 2 * cnt + extra_rows + (int64_t)(extra_frac * 2 * cnt));
+            if (!ok) {                       // close the stage before this level and start a new one
+                h->stage_ptr.push_back(h->level_ptr[l - 1]);
+                base_level = l - 1;
+                stage_reads = stage_nodes = 0;
+                expand_level(l, lp, lc);
+            }
+            int64_t off = (int64_t)he.col.size();
+            he.col.insert(he.col.end(), lc.begin(), lc.end());
+            for (int64_t q : lp) he.ptr.push_back(off + q);
+            stage_reads += (int64_t)lc.size();
+            stage_nodes += nodes;
+        }
+        if (a > 0) h->stage_ptr.push_back((int32_t)a);
+        h->stages = (int32_t)h->stage_ptr.size() - 1;
+        h->stage_single_level.assign(h->stages, 0);
+        for (int32_t st = 0; st < h->stages; ++st)
+            h->stage_single_level[st] = node_level[h->stage_ptr[st]] == node_level[h->stage_ptr[st + 1] - 1];
+    }
+    // transposed HAG (in its staged form): consumers of every source
+    {
+        Csr all;  // rows: destinations 0..n-1 then aggregation nodes; cols: their (expanded) in-neighbours
         all.ptr.resize(n + a + 1);
-        all.col.reserve(h->hf.col.size() + 2 * (size_t)a);
+        all.col.reserve(h->hf.col.size() + h->he.col.size());
         all.col = h->hf.col;
         for (int64_t v = 0; v <= n; ++v) all.ptr[v] = h->hf.ptr[v];
-        for (int64_t i = 0; i < a; ++i) {
-            all.col.push_back(h->left[i]);
-            all.col.push_back(h->right[i]);
-            all.ptr[n + i + 1] = (int64_t)all.col.size();
-        }
+        all.col.insert(all.col.end(), h->he.col.begin(), h->he.col.end());
+        for (int64_t i = 0; i < a; ++i) all.ptr[n + i + 1] = h->hf.ptr[n] + h->he.ptr[i + 1];
         transpose(all, n + a, h->ht);
     }
     transpose(h->g, n, h->gt);
@@ -535,20 +673,34 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
         h->inv_deg[v] = 1.0f / (float)std::max<int64_t>(d, 1);
     }
     // schedules
-    build_plan(h->hf, 0, n, h->p_fwd);
-    h->p_bwd_level.assign(h->levels, Plan{});
-    for (int32_t l = 1; l <= h->levels; ++l)
-        build_plan(h->ht, n + h->level_ptr[l - 1], n + h->level_ptr[l], h->p_bwd_level[l - 1]);
-    build_plan(h->ht, 0, n, h->p_bwd_src);
-    build_plan(h->g, 0, n, h->p_naive_fwd);
-    build_plan(h->gt, 0, n, h->p_naive_bwd);
+    const bool part = env_i64("HAG_PARTITION", 1) != 0 && (n + a) >= env_i64("HAG_PARTITION_MIN_ROWS", 16384);
+    h->hf_dcol = h->hf.col;
+    h->ht_dcol = h->ht.col;
+    h->g_dcol = h->g.col;
+    h->gt_dcol = h->gt.col;
+    std::vector<int32_t> he_dcol = h->he.col;   // never partitioned: stays as it is
+    build_plan(h->hf, h->hf_dcol, 0, n, h->p_fwd, part);
+    h->p_fwd_stage.assign(h->stages, Plan{});
+    h->p_bwd_stage.assign(h->stages, Plan{});
+    for (int32_t st = 0; st < h->stages; ++st) {
+        if (!h->stage_single_level[st]) {
+            build_plan(h->he, he_dcol, h->stage_ptr[st], h->stage_ptr[st + 1], h->p_fwd_stage[st], false);
+            for (Item &it : h->p_fwd_stage[st].items) if (it.row >= 0) it.row += (int32_t)n;   // unified ids
+            for (Item &it : h->p_fwd_stage[st].combine) it.row += (int32_t)n;
+        }
+        build_plan(h->ht, h->ht_dcol, n + h->stage_ptr[st], n + h->stage_ptr[st + 1], h->p_bwd_stage[st], part);
+    }
+    build_plan(h->ht, h->ht_dcol, 0, n, h->p_bwd_src, part);
+    build_plan(h->g, h->g_dcol, 0, n, h->p_naive_fwd, part);
+    build_plan(h->gt, h->gt_dcol, 0, n, h->p_naive_bwd, part);
     h->max_slots = std::max({h->p_fwd.n_slots, h->p_bwd_src.n_slots, h->p_naive_fwd.n_slots, h->p_naive_bwd.n_slots});
-    for (auto &p : h->p_bwd_level) h->max_slots = std::max(h->max_slots, p.n_slots);
+    for (auto &p : h->p_bwd_stage) h->max_slots = std::max(h->max_slots, p.n_slots);
+    for (auto &p : h->p_fwd_stage) h->max_slots = std::max(h->max_slots, p.n_slots);
     // statistics (Section 4.1: k in-neighbours cost k-1 binary aggregations; Section 5.4: one
     // row transfer per aggregated neighbour)
     hag_stats_t &s = h->st;
     s = hag_stats_t{};
-    s.n = n; s.e = h->e; s.a = a; s.levels = h->levels;
+    s.n = n; s.e = h->e; s.a = a; s.levels = h->levels; s.stages = h->stages;
     s.h = (int64_t)h->hf.col.size();
     s.e_hag = s.h + 2 * a;
     for (int64_t v = 0; v < n; ++v) {

@@ -25,11 +25,14 @@ static_assert(sizeof(Item) == 16, "Item is loaded as one 16-byte vector");
 
 // Schedule of one gather launch (plus the optional second launch that folds the
 // partial slots of split rows).
+constexpr int kPartitions = 8;   // XCDs of the device; workgroup b runs on XCD b mod 8
+
 struct Plan {
-    // items[0 .. n_block): one whole workgroup each (long rows, longest first);
-    // items[n_block ..): one sub-group of lanes each (short rows, longest first)
+    // items of partition k are items[part_begin[k] .. part_begin[k+1]), each partition sorted by
+    // length class, longest first; partition k is executed by workgroups with index mod np == k
     std::vector<Item> items;
-    int64_t n_block = 0;
+    int np = 1;
+    std::vector<int64_t> part_begin;
     std::vector<Item> combine;   // per split row: beg = first slot, cnt = #slots, row = output row
     int64_t n_slots = 0;
     // device copies
@@ -55,14 +58,22 @@ struct hag_handle {
     std::vector<int32_t> left, right;     // [a]
     std::vector<int32_t> level_ptr;       // [levels+1]
     hag::Csr hf;                          // Nhat_v, v in V
+    // stages: runs of consecutive levels executed by one launch
+    int32_t stages = 0;
+    std::vector<int32_t> stage_ptr;       // [stages+1], in aggregation-node index space
+    std::vector<uint8_t> stage_single_level;
+    hag::Csr he;                          // row i: inputs of aggregation node n+i expanded to earlier stages
     // transposed HAG: row s in [0, n+a) lists the consumers of s; a consumer id < n is a
     // destination (reads gY), an id >= n is aggregation node id (reads its gradient row)
     hag::Csr ht;
+    // column arrays in device order (rows cut by source partition are reordered); released after upload
+    std::vector<int32_t> hf_dcol, ht_dcol, g_dcol, gt_dcol;
     hag_stats_t st{};
 
     // schedules
     hag::Plan p_fwd;                       // final gather over hf
-    std::vector<hag::Plan> p_bwd_level;    // [levels]; index l-1 covers rows of depth l in ht
+    std::vector<hag::Plan> p_fwd_stage;    // [stages]; rows of he (unused for single-level stages)
+    std::vector<hag::Plan> p_bwd_stage;    // [stages]; rows of ht that belong to the stage
     hag::Plan p_bwd_src;                   // rows 0..n-1 of ht
     hag::Plan p_naive_fwd, p_naive_bwd;
     int64_t max_slots = 0;
@@ -71,7 +82,7 @@ struct hag_handle {
     bool uploaded = false;
     int device = -1;
     int32_t *d_left = nullptr, *d_right = nullptr;
-    int32_t *d_hcol = nullptr, *d_tcol = nullptr, *d_gcol = nullptr, *d_gtcol = nullptr;
+    int32_t *d_hcol = nullptr, *d_tcol = nullptr, *d_gcol = nullptr, *d_gtcol = nullptr, *d_ecol = nullptr;
     int32_t *d_slot_ids = nullptr;
     float *d_inv_deg = nullptr;
     std::vector<void *> d_allocs;
@@ -80,7 +91,8 @@ struct hag_handle {
 namespace hag {
 // hag_host.cpp
 int finalize(hag_handle *h, uint32_t flags);  // levels, forward form, transposes, schedules, stats
-void build_plan(const Csr &c, int64_t row_begin, int64_t row_end, Plan &p);
+void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p, bool partition);
+int64_t long_items(const Plan &p, int k, int64_t threshold);
 // hag_device.hip
 void free_device(hag_handle *h);
 }  // namespace hag

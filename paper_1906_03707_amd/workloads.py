@@ -1,0 +1,73 @@
+"""BASELINE workloads: graph + HAG for each config, with an on-disk cache of merge lists.
+
+A HAG depends only on the graph, the capacity and the aggregate type, so it is searched once and
+reused (the paper's own remark on reusability).  For the 114M-edge graph of configs 3 and 5 the
+search takes about an hour of CPU time, so its merge list (canonical greedy, capacity |V|/2; every
+smaller capacity is a prefix) is stored under data/ by `python -m paper_1906_03707_amd.workloads
+--make-cache 3` and replayed with hag_from_merges.  A cached list is only trusted after the replay
+has validated it (every merge must rewrite at least one list) and the tests re-check Theorem 2.
+"""
+from __future__ import annotations
+
+import os
+import sys
+import time
+
+import numpy as np
+
+from . import binding, synth
+
+DATA = os.path.join(os.path.dirname(os.path.abspath(__file__)), "data")
+FEATURE_DIM = {1: 64, 2: 128, 3: 128, 4: 64, 5: 128}
+
+
+def cache_path(cfg: int) -> str:
+    name = synth.CONFIGS[3 if cfg == 5 else cfg]["name"]
+    return os.path.join(DATA, f"{name}_merges.npz")
+
+
+def load_cached_merges(cfg: int):
+    p = cache_path(cfg)
+    if not os.path.exists(p):
+        return None
+    z = np.load(p)
+    return z["left"], z["right"]
+
+
+def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None):
+    """HAG of BASELINE config `cfg` (capacity |V|/4 unless given), from the cache when one exists."""
+    n = rowptr.size - 1
+    cap = n // 4 if capacity is None else int(capacity)
+    t0 = time.time()
+    if cfg == 4 and capacity is None:
+        h = binding.hag_search_batched(rowptr, col, graph_ptr, 0.25)
+        how = "hag_search_batched"
+    else:
+        cached = load_cached_merges(cfg) if cap > 0 else None
+        if cached is not None and cached[0].size >= cap:
+            h = binding.hag_from_merges(rowptr, col, cached[0][:cap], cached[1][:cap])
+            how = "hag_from_merges (cached canonical merge list)"
+        else:
+            h = binding.hag_search(rowptr, col, cap)
+            how = "hag_search"
+    if log:
+        log(f"config {cfg}: {how} capacity {cap} -> |V_A|={h.stats()['a']} in {time.time() - t0:.1f}s")
+    return h
+
+
+def make_cache(cfg: int, capacity=None):
+    rowptr, col, _ = synth.graph_for_config(cfg)
+    n = rowptr.size - 1
+    cap = n // 2 if capacity is None else capacity
+    h = binding.hag_search(rowptr, col, cap)
+    left, right, red = h.get_merges()
+    os.makedirs(DATA, exist_ok=True)
+    np.savez_compressed(cache_path(cfg), left=left, right=right, red=red)
+    print(f"wrote {cache_path(cfg)}: {left.size} merges, redundancy {red[0]}..{red[-1]}")
+
+
+if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "--make-cache":
+        make_cache(int(sys.argv[2]), int(sys.argv[3]) if len(sys.argv) > 3 else None)
+    else:
+        sys.exit("usage: python -m paper_1906_03707_amd.workloads --make-cache <config> [capacity]")

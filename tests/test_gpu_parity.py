@@ -91,6 +91,37 @@ def test_random_graphs_all_ops(B, n, p, d, directed):
     run_all_ops(B, h, rowptr, col, d, seed=7 * n + d)
 
 
+def test_fused_and_unfused_stages(B, monkeypatch):
+    # levels are fused into stages (one launch each) when that costs few extra row reads; both the
+    # fused form and the one-launch-per-level form must match the oracle
+    rowptr, col = synth.sbm(n_blocks=3, block=60, p_in=0.5, p_out=0.02, seed=31)
+    n = rowptr.size - 1
+    fused = B.hag_search(rowptr, col, n)
+    assert fused.stats()["levels"] >= 3 and fused.stats()["stages"] < fused.stats()["levels"]
+    run_all_ops(B, fused, rowptr, col, 32, seed=32)
+    monkeypatch.setenv("HAG_STAGE_EXTRA_ROWS", "-1000000")
+    unfused = B.hag_search(rowptr, col, n)
+    assert unfused.stats()["stages"] == unfused.stats()["levels"]
+    run_all_ops(B, unfused, rowptr, col, 32, seed=32)
+
+
+def test_source_partitioned_schedule(B, monkeypatch):
+    # rows cut by source id into per-XCD segments with partial rows folded afterwards: forced on
+    # for a small graph (by default only large graphs use it), incl. hubs that are also split
+    monkeypatch.setenv("HAG_PARTITION_MIN_ROWS", "0")
+    monkeypatch.setenv("HAG_PART_MIN", "8")
+    monkeypatch.setenv("HAG_BLOCK_MAX", "40")
+    rowptr, col = synth.holme_kim(1500, 9, 0.5, seed=41)
+    n = rowptr.size - 1
+    assert np.diff(rowptr).max() > 100
+    h = B.hag_search(rowptr, col, n // 4)
+    run_all_ops(B, h, rowptr, col, 64, seed=42)
+    run_all_ops(B, h, rowptr, col, 16, seed=43, ops=("sum", "max"), dtypes=("f32",))
+    rowptr, col = synth.random_graph(300, 0.2, seed=44, directed=True)
+    h = B.hag_search(rowptr, col, 150)
+    run_all_ops(B, h, rowptr, col, 128, seed=45)
+
+
 def test_capacity_zero_is_the_gnn_graph(B):
     # Section 3.1: the GNN-graph is the HAG with V_A empty -> identical kernels, identical bits
     rowptr, col = synth.random_graph(400, 0.1, seed=3)
