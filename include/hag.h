@@ -168,8 +168,9 @@ int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
 /* The same two calls restricted to some of their phases, for per-kernel timing: a later
  * phase reads what an earlier call left in `workspace`.  HAG_PHASE_LEVELS = the
  * aggregation-node levels (forward: Algorithm 2's loop over V_A; backward: their
- * gradient rows); HAG_PHASE_GATHER = the per-node gather over V. */
-enum { HAG_PHASE_LEVELS = 1, HAG_PHASE_GATHER = 2, HAG_PHASE_ALL = 3 };
+ * gradient rows); HAG_PHASE_GATHER = the per-node gather over V; HAG_PHASE_FOLD = the small
+ * launches that add up the partial rows of rows that were cut into pieces. */
+enum { HAG_PHASE_LEVELS = 1, HAG_PHASE_GATHER = 2, HAG_PHASE_FOLD = 4, HAG_PHASE_ALL = 7 };
 int hag_forward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
                        const void *x, void *y, int32_t *argmax, void *workspace, void *stream,
                        uint32_t phases);

@@ -75,6 +75,18 @@ __device__ __forceinline__ void max1(S &v, int &vi, S w, int wi) {
     v = take ? w : v;
     vi = take ? wi : vi;
 }
+// the same when the candidate's id is known to exceed every id already folded in
+template <typename S>
+__device__ __forceinline__ void max_first1(S &v, int &vi, S w, int wi) {
+    bool take = (wi >= 0) && (vi < 0 || w > v);
+    v = take ? w : v;
+    vi = take ? wi : vi;
+}
+template <typename V>
+__device__ __forceinline__ void max_first4(V &v, int4 &vi, const V &w, int wi) {
+    max_first1(v.x, vi.x, w.x, wi); max_first1(v.y, vi.y, w.y, wi);
+    max_first1(v.z, vi.z, w.z, wi); max_first1(v.w, vi.w, w.w, wi);
+}
 template <typename V>
 __device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi) {
     max1(v.x, vi.x, w.x, wi.x); max1(v.y, vi.y, w.y, wi.y);
@@ -115,7 +127,8 @@ __device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg,
             int hi_any = 0;
 #pragma unroll
             for (int k = 0; k < UNR; ++k) hi_any |= (idx[k] >= A.split);
-            if (!__any(hi_any)) {
+            const bool single = !__any(hi_any);
+            if (single) {
 #pragma unroll
                 for (int k = 0; k < UNR; ++k) {
                     val[k] = V{};
@@ -143,17 +156,28 @@ __device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg,
                     if (idx[k] >= 0 && idx[k] < A.split) scale4(val[k], A.in_scale[idx[k]]);
             }
             if (RED == R_MAX) {
+                if (single) {
+                    // Only original rows here, and a list holds its original ids in ascending
+                    // order before any aggregation node: whatever the accumulator holds came
+                    // from a smaller id, so a tie keeps it and "greater than" is the whole test.
 #pragma unroll
-                for (int k = 0; k < UNR; ++k) {
-                    vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);   // -1 stays "nothing"
-                    if (idx[k] >= A.split && col_ok) vid[k] = ld4(A.id_hi + (size_t)(idx[k] - A.split) * d + cbase);
-                    if (!col_ok) vid[k] = make_int4(-1, -1, -1, -1);
+                    for (int k = 0; k < UNR; ++k) {
+                        const int wi = col_ok ? idx[k] : -1;
+                        max_first4(acc, acc_id, val[k], wi);
+                    }
+                } else {
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) {
+                        vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);   // -1 stays "nothing"
+                        if (idx[k] >= A.split && col_ok) vid[k] = ld4(A.id_hi + (size_t)(idx[k] - A.split) * d + cbase);
+                        if (!col_ok) vid[k] = make_int4(-1, -1, -1, -1);
+                    }
+#pragma unroll
+                    for (int k = 0; k < UNR; ++k) max4(acc, acc_id, val[k], vid[k]);
                 }
-            }
+            } else {
 #pragma unroll
-            for (int k = 0; k < UNR; ++k) {
-                if (RED == R_MAX) max4(acc, acc_id, val[k], vid[k]);
-                else add4(acc, val[k]);
+                for (int k = 0; k < UNR; ++k) add4(acc, val[k]);
             }
         }
     }
@@ -367,7 +391,7 @@ static Workspace carve(const hag_handle *h, hag_op_t op, int64_t d, void *base) 
 // run one schedule: the gather itself, then the fold of split rows
 template <typename T, int RED, int ROLE>
 static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, GatherArgs<T> a, const Workspace &w,
-                    hipStream_t s) {
+                    hipStream_t s, uint32_t phases = HAG_PHASE_ALL) {
     a.items = p.d_items;
     a.np = p.np;
     // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
@@ -385,9 +409,9 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     a.col = d_col;
     a.part = (T *)w.part;
     a.part_id = (int32_t *)w.part_id;
-    int rc = launch_gather<T, RED, ROLE>(a, s);
+    int rc = (phases & HAG_PHASE_GATHER) ? launch_gather<T, RED, ROLE>(a, s) : HAG_OK;
     if (rc) return rc;
-    if (!p.combine.empty()) {
+    if (!p.combine.empty() && (phases & HAG_PHASE_FOLD)) {
         GatherArgs<T> c = a;
         c.items = p.d_combine;
         c.np = 1;
@@ -463,9 +487,9 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
     a.in_scale = nullptr;
     a.out_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
     a.d = (int32_t)d;
-    if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
-    if (naive) return run_plan<T, RED, G_NAIVE_FWD>(h, h->p_naive_fwd, h->d_gcol, a, w, s);
-    return run_plan<T, RED, G_HAG_FWD>(h, h->p_fwd, h->d_hcol, a, w, s);
+    if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
+    if (naive) return run_plan<T, RED, G_NAIVE_FWD>(h, h->p_naive_fwd, h->d_gcol, a, w, s, phases);
+    return run_plan<T, RED, G_HAG_FWD>(h, h->p_fwd, h->d_hcol, a, w, s, phases);
 }
 
 template <typename T>
@@ -495,8 +519,8 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
     if (naive) {
         a.out = gx;
         a.out_off = 0;
-        if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
-        return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s);
+        if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
+        return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s, phases);
     }
     // deepest stage first: its consumers are destinations only; an earlier stage may also be
     // consumed by aggregation nodes of later stages, whose gradient rows are complete by then
@@ -508,8 +532,8 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
     }
     a.out = gx;
     a.out_off = 0;
-    if (!(phases & HAG_PHASE_GATHER)) return HAG_OK;
-    return run_plan<T, R_SUM, G_HAG_BWD_SRC>(h, h->p_bwd_src, h->d_tcol, a, w, s);
+    if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
+    return run_plan<T, R_SUM, G_HAG_BWD_SRC>(h, h->p_bwd_src, h->d_tcol, a, w, s, phases);
 }
 
 template <typename T>

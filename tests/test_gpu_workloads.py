@@ -1,0 +1,229 @@
+"""GPU parity at the full sizes of BASELINE configs 2-5, in the launch configuration bench.py times.
+
+Aggregation is element-wise in the feature index, so the oracle can compute any subset of
+output columns exactly by running on the same graph with only those columns of the input.
+Small configs are compared in full; the 114M-edge graph is compared on sampled columns
+(all rows), which still covers every row length, every split row and every aggregation node.
+"""
+import os
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_1906_03707_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+TOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1906_03707_amd import binding
+    binding.lib()
+    return binding
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).cuda()
+
+
+def oracle_view(h):
+    f = h.get_forward()
+    return oracle.Hag(h.stats()["n"], f["agg_left"], f["agg_right"], f["hrowptr"], f["hcol"])
+
+
+def check_columns(h, rowptr, col, d, op, cols, seed, check_naive=True):
+    """Forward + backward of the HAG path (and the naive-CSR GPU kernels) at feature width d,
+    compared with the oracle on the columns `cols`."""
+    n = rowptr.size - 1
+    x = synth.features_f32(n, d, seed)
+    gy = synth.features_f32(n, d, seed + 1)
+    xd, gyd = dev(x), dev(gy)
+    xs, gys = np.ascontiguousarray(x[:, cols]), np.ascontiguousarray(gy[:, cols])
+    y_ref, s, am_ref = oracle.naive_forward(rowptr, col, xs, op)
+    if op == "max":
+        gx_ref, gs = oracle.naive_backward(rowptr, col, gys, op, am_ref)
+    else:
+        gx_ref, gs = oracle.naive_backward(rowptr, col, gys, op)
+    paths = [("hag", h.forward, h.backward)]
+    if check_naive:
+        paths.append(("naive", h.naive_forward, h.naive_backward))
+    for name, fwd, bwd in paths:
+        tag = f"{name} d={d} {op}"
+        if op == "max":
+            y, am = fwd(xd, op)
+            gx = bwd(gyd, op, argmax=am)
+            torch.cuda.synchronize()
+            assert np.array_equal(y.cpu().numpy()[:, cols].astype(np.float64), y_ref), f"{tag}: max values differ"
+            assert np.array_equal(am.cpu().numpy()[:, cols], am_ref), f"{tag}: argmax differs"
+        else:
+            y = fwd(xd, op)
+            gx = bwd(gyd, op)
+            torch.cuda.synchronize()
+            err = np.abs(y.cpu().numpy()[:, cols].astype(np.float64) - y_ref)
+            assert np.all(err <= TOL * s), f"{tag}: forward worst {np.max(err / np.maximum(s, 1e-300)):.2e}"
+        err = np.abs(gx.cpu().numpy()[:, cols].astype(np.float64) - gx_ref)
+        assert np.all(err <= TOL * gs), f"{tag}: backward worst {np.max(err / np.maximum(gs, 1e-300)):.2e}"
+        del y, gx
+
+
+def test_config2_holme_kim_sum_and_mean(B):
+    rowptr, col = synth.holme_kim()
+    n = rowptr.size - 1
+    h = B.hag_search(rowptr, col, n // 4).upload()
+    st = h.stats()
+    assert st["a"] == n // 4 and st["aggr_hag"] < st["aggr_naive"]
+    assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0          # Theorem 2
+    cols = np.arange(128)
+    for op in ("sum", "mean"):
+        check_columns(h, rowptr, col, 128, op, cols, synth.SEED_BASE + 2 + 1000)
+
+
+def test_config4_graph_batch_sum(B):
+    rowptr, col, gp = synth.er_batch()
+    n = rowptr.size - 1
+    h = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+    st = h.stats()
+    assert st["a"] == 5000 * 18
+    assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0
+    f = h.get_forward()
+    # aggregation nodes never cross graphs: both inputs and every consumer lie in one block of 74
+    orig_of = np.full(n + st["a"], -1, dtype=np.int64)
+    orig_of[:n] = np.arange(n) // 74
+    for i in range(st["a"]):
+        gl, gr = orig_of[f["agg_left"][i]], orig_of[f["agg_right"][i]]
+        assert gl == gr
+        orig_of[n + i] = gl
+    rows = np.repeat(np.arange(n), np.diff(f["hrowptr"]))
+    assert np.array_equal(orig_of[f["hcol"]], rows // 74)
+    check_columns(h, rowptr, col, 64, "sum", np.arange(64), synth.SEED_BASE + 4 + 1000)
+
+
+# ------------------------------------------------------------------------------------------------
+# configs 3 and 5: the 232,965-node degree-corrected SBM (114M directed edges)
+#
+# These take minutes (graph generation, replay of the cached merge list, oracle passes over 114M
+# edges), so every step reports a line past pytest's capture: a silent run looks hung from outside.
+# ------------------------------------------------------------------------------------------------
+import time
+
+_T0 = time.time()
+
+
+def progress(request, msg):
+    cap = request.config.pluginmanager.getplugin("capturemanager")
+    with cap.global_and_fixture_disabled():
+        print(f"\n[{time.time() - _T0:6.0f}s] {msg}", flush=True)
+
+
+@pytest.fixture(scope="module")
+def big_graph(request):
+    progress(request, "generating the 232,965-node degree-corrected SBM ...")
+    rowptr, col = synth.dcsbm()
+    progress(request, f"graph ready: {col.size} directed edges")
+    return rowptr, col
+
+
+@pytest.fixture(scope="module")
+def big_hags(request, B, big_graph):
+    """HAGs of capacity 0, |V|/8, |V|/4, |V|/2: prefixes of one cached canonical merge list."""
+    from paper_1906_03707_amd import workloads
+    rowptr, col = big_graph
+    n = rowptr.size - 1
+    cached = workloads.load_cached_merges(3)
+    assert cached is not None and cached[0].size >= n // 2, \
+        "merge-list cache for the 114M-edge graph is missing or short: run " \
+        "`python -m paper_1906_03707_amd.workloads --make-cache 3` (about an hour of CPU time)"
+    hags = {}
+    for cap in (0, n // 8, n // 4, n // 2):
+        progress(request, f"replaying {cap} merges (hag_from_merges) ...")
+        hags[cap] = workloads.build_hag(3, rowptr, col, capacity=cap)
+        assert hags[cap].stats()["a"] == cap
+    progress(request, "HAGs built")
+    return hags
+
+
+_REF = {}
+
+
+def sampled_reference(request, rowptr, col, d, op, cols, seed):
+    key = (d, op)
+    if key not in _REF:
+        _REF.clear()                      # keep one reference at a time (host memory)
+        progress(request, f"oracle: naive {op} forward+backward on {cols.size} of {d} columns ...")
+        n = rowptr.size - 1
+        x = synth.features_f32(n, d, seed)
+        gy = synth.features_f32(n, d, seed + 1)
+        xs, gys = np.ascontiguousarray(x[:, cols]), np.ascontiguousarray(gy[:, cols])
+        y_ref, s, am_ref = oracle.naive_forward(rowptr, col, xs, op)
+        gx_ref, gs = oracle.naive_backward(rowptr, col, gys, op, am_ref) if op == "max" else \
+            oracle.naive_backward(rowptr, col, gys, op)
+        _REF[key] = dict(x=x, gy=gy, y=y_ref, s=s, am=am_ref, gx=gx_ref, gs=gs)
+    return _REF[key]
+
+
+def compare_with_reference(h, ref, d, op, cols, naive=False):
+    xd, gyd = dev(ref["x"]), dev(ref["gy"])
+    fwd, bwd = (h.naive_forward, h.naive_backward) if naive else (h.forward, h.backward)
+    if op == "max":
+        y, am = fwd(xd, op)
+        gx = bwd(gyd, op, argmax=am)
+        torch.cuda.synchronize()
+        assert np.array_equal(y.cpu().numpy()[:, cols].astype(np.float64), ref["y"])
+        assert np.array_equal(am.cpu().numpy()[:, cols], ref["am"])
+        del am
+    else:
+        y = fwd(xd, op)
+        gx = bwd(gyd, op)
+        torch.cuda.synchronize()
+        err = np.abs(y.cpu().numpy()[:, cols].astype(np.float64) - ref["y"])
+        assert np.all(err <= TOL * ref["s"]), f"forward worst {np.max(err / np.maximum(ref['s'], 1e-300)):.2e}"
+    err = np.abs(gx.cpu().numpy()[:, cols].astype(np.float64) - ref["gx"])
+    assert np.all(err <= TOL * ref["gs"]), f"backward worst {np.max(err / np.maximum(ref['gs'], 1e-300)):.2e}"
+    del y, gx, xd, gyd
+    torch.cuda.empty_cache()
+
+
+@pytest.mark.timeout(1800)
+def test_config3_structure(request, B, big_graph, big_hags):
+    rowptr, col = big_graph
+    n = rowptr.size - 1
+    aggr = [big_hags[c].stats()["aggr_hag"] for c in (0, n // 8, n // 4, n // 2)]
+    assert all(a > b for a, b in zip(aggr, aggr[1:]))                     # larger capacity, lower cost (Section 5.5)
+    h = big_hags[n // 4]
+    st = h.stats()
+    assert st["a"] == n // 4 and st["e"] == col.size
+    progress(request, "Theorem 2 (cover == neighbourhood) on the capacity-|V|/4 HAG ...")
+    assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0
+    _, _, red = h.get_merges()
+    assert np.all(np.diff(red) <= 0) and red.min() >= 2
+    assert st["aggr_naive"] - st["aggr_hag"] == int((red.astype(np.int64) - 1).sum())
+    progress(request, f"config 3 HAG: aggregations {st['aggr_naive']} -> {st['aggr_hag']}, levels {st['levels']}, "
+                      f"stages {st['stages']}, redundancy {red[0]}..{red[-1]}")
+
+
+@pytest.mark.timeout(900)
+def test_config3_dcsbm_sum(request, B, big_graph, big_hags):
+    rowptr, col = big_graph
+    n = rowptr.size - 1
+    h = big_hags[n // 4].upload()
+    cols = np.arange(0, 128, 8)                                           # 16 of 128 columns, all rows
+    ref = sampled_reference(request, rowptr, col, 128, "sum", cols, synth.SEED_BASE + 3 + 1000)
+    compare_with_reference(h, ref, 128, "sum", cols)
+    compare_with_reference(h, ref, 128, "sum", cols, naive=True)
+
+
+@pytest.mark.timeout(900)
+@pytest.mark.parametrize("d,op", [(16, "max"), (16, "sum"), (128, "max"), (128, "sum"), (512, "max"), (512, "sum")])
+def test_config5_capacity_and_width_sweep(request, B, big_graph, big_hags, d, op):
+    rowptr, col = big_graph
+    cols = np.arange(0, d, max(d // 8, 1))[:8]                            # 8 sampled columns, all rows
+    ref = sampled_reference(request, rowptr, col, d, op, cols, synth.SEED_BASE + 5 + 1000 + d)
+    for cap, h in big_hags.items():
+        progress(request, f"config 5: d={d} {op} capacity {cap}")
+        compare_with_reference(h.upload(), ref, d, op, cols)
