@@ -14,7 +14,7 @@ import os
 import numpy as np
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libhag.so")
+LIB_PATH = os.environ.get("HAG_LIB", os.path.join(_HERE, "libhag.so"))
 
 HAG_SUM, HAG_MEAN, HAG_MAX = 0, 1, 2
 HAG_F32, HAG_I32 = 0, 1

@@ -157,6 +157,27 @@ def test_split_rows_hubs_and_isolated_nodes(B):
     run_all_ops(B, h, rowptr, col, 16, seed=13, ops=("sum", "max"), dtypes=("f32",))
 
 
+def test_self_loops_and_dedup(B):
+    # a node may be its own neighbour (source and destination roles are distinct); duplicates are
+    # dropped on request
+    n = 200
+    rowptr, col = synth.random_graph(n, 0.08, seed=51, directed=True)
+    rows = np.repeat(np.arange(n), np.diff(rowptr))
+    rows = np.concatenate([rows, np.arange(0, n, 2), rows[:300]])          # self-loops on even nodes + duplicates
+    cols = np.concatenate([col, np.arange(0, n, 2), col[:300]])
+    order = np.argsort(rows, kind="stable")
+    rows, cols = rows[order], cols[order].astype(np.int32)
+    rp = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=n))]).astype(np.int64)
+    with pytest.raises(B.HagError):
+        B.hag_search(rp, cols, n // 2)
+    h = B.hag_search(rp, cols, n // 2, flags=B.HAG_SEARCH_DEDUP)
+    keys = np.unique(rows.astype(np.int64) * n + cols)
+    r2, c2 = keys // n, (keys % n).astype(np.int32)
+    rp2 = np.concatenate([[0], np.cumsum(np.bincount(r2, minlength=n))]).astype(np.int64)
+    assert h.stats()["e"] == c2.size and np.any(r2 == c2)
+    run_all_ops(B, h, rp2, c2, 32, seed=52)
+
+
 def test_max_ties_bit_exact(B):
     # few distinct values -> many exact ties; argmax must be the smallest original id
     n, d = 600, 32
