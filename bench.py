@@ -164,10 +164,39 @@ def main():
         h.naive_forward(x, op, y=y, argmax=am)
         h.naive_backward(gy, op, argmax=am, gx=gx)
 
+    def time_cold(fn, reps=5):
+        """One step right after a write sweep over 1 GiB (larger than L2 + the 256 MB Infinity Cache)."""
+        flush = torch.empty(1 << 28, dtype=torch.float32, device="cuda")
+        tot = 0.0
+        for i in range(reps):
+            flush.fill_(float(i))
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(); fn(); b.record()
+            torch.cuda.synchronize()
+            tot += a.elapsed_time(b)
+        return tot / reps
+
+    def copy_ceiling_GBps(reps=10):
+        """Plain device copy of 1 GiB (read + write counted), the practical streaming ceiling."""
+        src = torch.empty(1 << 28, dtype=torch.float32, device="cuda").normal_()
+        dst = torch.empty_like(src)
+        for _ in range(2):
+            dst.copy_(src)
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(reps):
+            dst.copy_(src)
+        b.record()
+        torch.cuda.synchronize()
+        return 2.0 * src.numel() * 4 * reps / (a.elapsed_time(b) * 1e-3) / 1e9
+
     ms_hag = time_steps(torch, step_hag, args.steps, args.warmup)
     ms_naive = time_steps(torch, step_naive, args.steps, args.warmup)
     ms_fwd = time_steps(torch, lambda: h.forward(x, op, y=y, argmax=am), args.steps, args.warmup)
     ms_nfwd = time_steps(torch, lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
+    ms_hag_cold = time_cold(step_hag)
+    ms_naive_cold = time_cold(step_naive)
+    copy_gbps = copy_ceiling_GBps()
 
     # dominant kernel: the final gather of hag_forward (one launch per step), timed inside the step
     P = binding
@@ -215,11 +244,16 @@ def main():
         "aggregation_reduction": st["aggr_naive"] / max(st["aggr_hag"], 1),
         "transfer_reduction": st["xfer_naive"] / max(st["xfer_hag"], 1),
         "forward_ms": {"hag": ms_fwd, "naive": ms_nfwd},
+        "cold_cache_ms_per_step": {"hag": ms_hag_cold, "naive": ms_naive_cold},
+        "device_copy_GBps": copy_gbps,
+        "effective_frac_of_copy": alg_hag / (ms_hag * 1e-3) / 1e9 / copy_gbps,
     }
     log(f"[bench] {workload} D={d} op={op}: N={n} E={e} A={st['a']} levels={st['levels']} E^={st['e_hag']}")
     log(f"[bench] fwd+bwd  hag {ms_hag:.4f} ms  naive {ms_naive:.4f} ms  speedup {ms_naive / ms_hag:.3f}x "
         f"(aggregations {out['aggregation_reduction']:.3f}x, transfers {out['transfer_reduction']:.3f}x fewer)")
     log(f"[bench] fwd only hag {ms_fwd:.4f} ms  naive {ms_nfwd:.4f} ms")
+    log(f"[bench] cold caches (after a 1 GiB write sweep): hag {ms_hag_cold:.4f} ms  naive {ms_naive_cold:.4f} ms; "
+        f"plain 1 GiB device copy {copy_gbps:.0f} GB/s")
     log(f"[bench] effective (algorithmic) GB/s fwd+bwd: hag {out['effective_GBps_fwd_bwd']:.0f}  "
         f"naive {out['naive_csr']['effective_GBps']:.0f}  (peak {HBM_PEAK_GBS:.0f})")
     log(f"[bench] dominant kernel {kernel_name}: {ms_gather * 1e3:.1f} us, {gather_bytes / 1e6:.1f} MB -> {achieved:.0f} GB/s "

@@ -455,7 +455,7 @@ static int length_class(int32_t cnt) {
 // are dealt round-robin to the 8 lists.
 void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p,
                 bool partition) {
-    const int64_t block_max = env_i64("HAG_BLOCK_MAX", 1024);
+    const int64_t block_max = env_i64("HAG_BLOCK_MAX", 2048);
     const int64_t part_min = env_i64("HAG_PART_MIN", 128);
     // cutting by source only pays when the rows long enough to be cut hold most of the entries;
     // otherwise keep one list, which also keeps neighbouring rows on neighbouring workgroups
