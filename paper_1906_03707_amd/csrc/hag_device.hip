@@ -295,6 +295,175 @@ __global__ __launch_bounds__(kBlock) void level_kernel(const int32_t *__restrict
     st4(w + (size_t)node * d + c, a);
 }
 
+// ------------------------------------------------------------------------------------------
+// Component-local pass: a batch of small graphs.  One workgroup per connected component.  Its
+// feature rows and its index lists are read from HBM once into LDS, its aggregation nodes are
+// evaluated in LDS stage by stage (Algorithm 2's loop over V_A, never touching global
+// memory), and every output row is then reduced out of LDS.  The transposed pass is the same
+// code with the transposed lists and the stages in reverse order.  Rows in LDS are padded by
+// four elements so that rows do not all start in the same bank.
+// ------------------------------------------------------------------------------------------
+template <typename T>
+struct CompArgs {
+    const int32_t *meta;         // per component: first node, #nodes, first aggregation slot, #agg | #stages << 16
+    const uint8_t *stage;        // stage of each aggregation slot
+    const int32_t *row_ptr;      // lists of the rows written to global memory (index: global node id)
+    const uint16_t *row_col;
+    const int32_t *agg_row_ptr;  // lists of the aggregation rows kept in LDS (component-major index)
+    const uint16_t *agg_row_col;
+    const T *in;
+    T *out;
+    int32_t *out_id;
+    const float *scale_in, *scale_out;
+    int32_t d, stride;           // feature width; padded row stride in LDS, in elements
+    int32_t id_rows_off;         // offset of the id rows (max), in 4-byte elements
+    int32_t lists_off;           // offset of the staged aggregation lists, in bytes
+    int32_t max_agg;             // most aggregation rows a component has
+    int32_t use_agg, reverse;
+};
+
+// Reduce the LDS rows listed in col[beg .. beg+cnt) for the four features at column 4*k into
+// (acc, acc_id).  Called by all lanes of a wavefront with a common maxcnt.  Entries past cnt
+// read row `zrow`, which holds zeros (and id -1), so the inner loop has no branches: at LDS
+// speed the loop is bound by instruction issue, not by data.
+template <typename T, int RED, int LPR>
+__device__ __forceinline__ void lds_reduce(const T *buf, const int32_t *ids, int nv, int v0, int stride, int zrow,
+                                           const uint16_t *col, int beg, int cnt, int maxcnt, int sl, int k,
+                                           typename V4<T>::type &acc, int4 &acc_id) {
+    using V = typename V4<T>::type;
+    const T *colbuf = buf + 4 * k;
+    const int32_t *colids = ids + 4 * k;
+    for (int base = 0; base < maxcnt; base += LPR) {
+        const int mine = (base + sl < cnt) ? (int)col[beg + base + sl] : zrow;
+        const int lim = min(LPR, maxcnt - base);
+        for (int j = 0; j < lim; j += 4) {
+            int u[4];
+#pragma unroll
+            for (int t = 0; t < 4; ++t) u[t] = __shfl(mine, j + t, LPR);
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+                const V x = *reinterpret_cast<const V *>(colbuf + u[t] * stride);
+                if (RED == R_MAX) {
+                    int4 xi;
+                    if (u[t] < nv) xi = make_int4(v0 + u[t], v0 + u[t], v0 + u[t], v0 + u[t]);
+                    else xi = *reinterpret_cast<const int4 *>(colids + (u[t] - nv) * stride);
+                    max4(acc, acc_id, x, xi);
+                } else {
+                    add4(acc, x);
+                }
+            }
+        }
+    }
+}
+
+template <typename T, int RED, int LPR>
+__global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
+    using V = typename V4<T>::type;
+    constexpr int NSG = kBlock / LPR;      // sub-groups per workgroup
+    constexpr int SG = kWave / LPR;        // sub-groups per wavefront
+    constexpr int NW = kBlock / kWave;
+    extern __shared__ __align__(16) unsigned char smem[];
+    T *buf = reinterpret_cast<T *>(smem);
+    int32_t *ids = reinterpret_cast<int32_t *>(smem) + A.id_rows_off;       // id rows of aggregation nodes (max)
+    int32_t *l_agg_ptr = reinterpret_cast<int32_t *>(smem + A.lists_off);   // [na+1], rebased
+    int32_t *l_agg_stage = l_agg_ptr + A.max_agg + 1;                        // [na]
+    uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_stage + A.max_agg + 1);
+    const int c = blockIdx.x;
+    const int4 meta = *reinterpret_cast<const int4 *>(A.meta + 4 * (size_t)c);   // v0, nv, a0, na | stages << 16
+    const int v0 = meta.x, nv = meta.y, a0 = meta.z;
+    const int na = A.use_agg ? (meta.w & 0xffff) : 0;
+    const int n_stages = A.use_agg ? (meta.w >> 16) : 0;
+    const int q = A.d / 4, stride = A.stride;
+    const int zrow = nv + na;              // a row of zeros / "nothing"
+    const int tid = threadIdx.x, sg = tid / LPR, sl = tid % LPR;
+    const int wave = tid / kWave, sgw = (tid & (kWave - 1)) / LPR;
+
+    // stage the component: rows (forward: activations; transposed pass: seeds), the zero row,
+    // and the short lists of its aggregation rows
+    for (int i = tid; i < nv * q; i += kBlock) {
+        const int r = i / q, k = i - r * q;
+        V x = ld4(A.in + (size_t)(v0 + r) * A.d + 4 * k);
+        if (A.scale_in) scale4(x, A.scale_in[v0 + r]);
+        *reinterpret_cast<V *>(buf + r * stride + 4 * k) = x;
+    }
+    for (int k = tid; k < q; k += kBlock) {
+        *reinterpret_cast<V *>(buf + zrow * stride + 4 * k) = V{};
+        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + na * stride + 4 * k) = make_int4(-1, -1, -1, -1);
+    }
+    if (na > 0) {
+        const int e0 = A.agg_row_ptr[a0], ne = A.agg_row_ptr[a0 + na] - e0;
+        for (int i = tid; i <= na; i += kBlock) l_agg_ptr[i] = A.agg_row_ptr[a0 + i] - e0;
+        for (int i = tid; i < na; i += kBlock) l_agg_stage[i] = A.stage[a0 + i];
+        for (int i = tid; i < ne; i += kBlock) l_agg_col[i] = A.agg_row_col[e0 + i];
+    }
+    __syncthreads();
+
+    // Aggregation rows, stage by stage (forward: first stage first; transposed pass: last
+    // first).  A component has few of them, so a whole wavefront takes one row: its sub-groups
+    // walk interleaved slices of the list and combine with cross-lane adds.
+    for (int step = 1; step <= n_stages; ++step) {
+        const int st = A.reverse ? n_stages + 1 - step : step;
+        for (int jb = 0; jb < na; jb += NW) {
+            const int j = jb + wave;
+            const bool has = j < na && l_agg_stage[min(j, na - 1)] == st;
+            const int beg = has ? l_agg_ptr[j] : 0;
+            const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
+            int per = (cnt + SG - 1) / SG;
+            per = (per + 3) & ~3;
+            const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
+            for (int kb = 0; kb < q; kb += LPR) {
+                const int k = min(kb + sl, q - 1);
+                V acc{};
+                int4 acc_id = make_int4(-1, -1, -1, -1);
+                lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k,
+                                        acc, acc_id);
+#pragma unroll
+                for (int off = LPR; off < kWave; off <<= 1) {
+                    V o;
+                    o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
+                    o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
+                    if (RED == R_MAX) {
+                        int4 oi;
+                        oi.x = __shfl_xor(acc_id.x, off); oi.y = __shfl_xor(acc_id.y, off);
+                        oi.z = __shfl_xor(acc_id.z, off); oi.w = __shfl_xor(acc_id.w, off);
+                        max4(acc, acc_id, o, oi);
+                    } else {
+                        add4(acc, o);
+                    }
+                }
+                if (has && kb + sl < q && sgw == 0) {
+                    *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+                    if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
+                }
+            }
+        }
+        __syncthreads();
+    }
+
+    // rows written to global memory: forward y[v] over Nhat_v, transposed pass gx[u] over u's consumers
+    for (int vb = 0; vb < nv; vb += NSG) {
+        const int v = vb + sg;
+        const bool has = v < nv;
+        const int beg = has ? A.row_ptr[v0 + v] : 0;
+        const int cnt = has ? A.row_ptr[v0 + v + 1] - beg : 0;
+        int maxcnt = cnt;
+#pragma unroll
+        for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
+        for (int kb = 0; kb < q; kb += LPR) {
+            const int k = min(kb + sl, q - 1);
+            V acc{};
+            int4 acc_id = make_int4(-1, -1, -1, -1);
+            lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, A.row_col, beg, cnt, maxcnt, sl, k, acc, acc_id);
+            if (has && kb + sl < q) {
+                if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
+                const size_t o = (size_t)(v0 + v) * A.d + 4 * k;
+                st4(A.out + o, acc);
+                if (RED == R_MAX) st4(A.out_id + o, acc_id);
+            }
+        }
+    }
+}
+
 template <typename T>
 __global__ __launch_bounds__(kBlock) void fill_zero_kernel(T *p, int64_t n4) {
     using V = typename V4<T>::type;
@@ -444,9 +613,78 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
     return HAG_OK;
 }
 
+// LDS layout of the component-local pass:
+//   [rows + zero row][id rows + "nothing" row (max)][agg ptr][agg stage][agg list ids]
+struct CompLayout {
+    size_t id_rows_off = 0, lists_off = 0, total = 0;   // id_rows_off in 4-byte elements, the rest in bytes
+};
+// layout.total == 0: the pass does not apply to this call
+static CompLayout component_layout(const hag_handle *h, bool naive, bool backward, hag_op_t op, int64_t d) {
+    CompLayout L;
+    const Components &c = h->comp;
+    if (!c.enabled || !h->comp_uploaded) return L;
+    // max stays on the generic kernels: their ordered comparison path is cheaper per element than
+    // the (value, id) comparison this kernel would need for every LDS row
+    if (op == HAG_MAX) return L;
+    const size_t stride = (size_t)d + 4;
+    const size_t rows = (size_t)c.max_nodes + (naive ? 0 : (size_t)c.max_agg) + 1;
+    L.id_rows_off = rows * stride;
+    size_t bytes = rows * stride * 4;
+    if (op == HAG_MAX && !backward) bytes += ((naive ? 0 : (size_t)c.max_agg) + 1) * stride * 4;
+    L.lists_off = bytes;
+    if (!naive) {
+        const size_t entries = backward ? c.max_entries_bwd : c.max_entries_fwd;   // aggregation lists only
+        bytes += 2 * ((size_t)c.max_agg + 1) * 4 + entries * 2;
+    }
+    bytes = (bytes + 15) & ~(size_t)15;
+    if (bytes <= 64 * 1024) L.total = bytes;
+    return L;
+}
+
+template <typename T, int RED, bool BACKWARD>
+static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *in, T *out,
+                            int32_t *out_id, hipStream_t s) {
+    const Components &c = h->comp;
+    const CompLayout L = component_layout(h, naive, BACKWARD, op, d);
+    CompArgs<T> a{};
+    a.meta = c.d_meta;
+    a.stage = c.d_stage;
+    const LocalLists &rows = BACKWARD ? (naive ? c.nbwd : c.bwd_orig) : (naive ? c.nfwd : c.fwd);
+    const LocalLists &aggs = BACKWARD ? c.bwd_agg : c.fwd_agg;
+    a.row_ptr = rows.d_ptr;
+    a.row_col = rows.d_col;
+    a.agg_row_ptr = aggs.d_ptr;
+    a.agg_row_col = aggs.d_col;
+    a.in = in;
+    a.out = out;
+    a.out_id = out_id;
+    a.scale_in = (BACKWARD && op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.scale_out = (!BACKWARD && op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.d = (int32_t)d;
+    a.stride = (int32_t)d + 4;
+    a.use_agg = naive ? 0 : 1;
+    a.reverse = BACKWARD ? 1 : 0;
+    a.id_rows_off = (int32_t)L.id_rows_off;
+    a.lists_off = (int32_t)L.lists_off;
+    a.max_agg = c.max_agg;
+    const dim3 grid((unsigned)c.count), block(kBlock);
+    switch (pick_lpr(d)) {
+        case 4: hipLaunchKernelGGL((component_kernel<T, RED, 4>), grid, block, L.total, s, a); break;
+        case 8: hipLaunchKernelGGL((component_kernel<T, RED, 8>), grid, block, L.total, s, a); break;
+        case 16: hipLaunchKernelGGL((component_kernel<T, RED, 16>), grid, block, L.total, s, a); break;
+        case 32: hipLaunchKernelGGL((component_kernel<T, RED, 32>), grid, block, L.total, s, a); break;
+        default: hipLaunchKernelGGL((component_kernel<T, RED, 64>), grid, block, L.total, s, a); break;
+    }
+    HIP_TRY(hipGetLastError());
+    return HAG_OK;
+}
+
 template <typename T, int RED>
 static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *x, T *y, int32_t *argmax,
                         void *ws, hipStream_t s, uint32_t phases) {
+    // a batch of small graphs: the whole pass is one launch out of LDS
+    if (phases == HAG_PHASE_ALL && component_layout(h, naive, false, op, d).total > 0)
+        return launch_component<T, RED, false>(h, naive, op, d, x, y, argmax, s);
     Workspace w = carve(h, op, d, ws);
     const int32_t n = (int32_t)h->n;
     if (!naive && (phases & HAG_PHASE_LEVELS)) {
@@ -507,6 +745,8 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
         HIP_TRY(hipGetLastError());
         return HAG_OK;
     }
+    if (phases == HAG_PHASE_ALL && component_layout(h, naive, true, op, d).total > 0)
+        return launch_component<T, R_SUM, true>(h, naive, op, d, gy, gx, nullptr, s);
     Workspace w = carve(h, op, d, ws);
     GatherArgs<T> a{};
     a.src_lo = gy;
@@ -565,6 +805,7 @@ void free_device(hag_handle *h) {
     }
     h->d_allocs.clear();
     h->uploaded = false;
+    h->comp_uploaded = false;
 }
 
 }  // namespace hag
@@ -598,6 +839,16 @@ int hag_upload(hag_t *h, void *stream) {
     if ((rc = upload_plan(h, h->p_bwd_src, s))) goto bad;
     if ((rc = upload_plan(h, h->p_naive_fwd, s))) goto bad;
     if ((rc = upload_plan(h, h->p_naive_bwd, s))) goto bad;
+    if (h->comp.enabled) {
+        Components &c = h->comp;
+        if ((rc = upload_array(h, c.meta, &c.d_meta, s))) goto bad;
+        if ((rc = upload_array(h, c.stage, &c.d_stage, s))) goto bad;
+        for (LocalLists *l : {&c.fwd, &c.fwd_agg, &c.bwd_orig, &c.bwd_agg, &c.nfwd, &c.nbwd}) {
+            if ((rc = upload_array(h, l->ptr, &l->d_ptr, s))) goto bad;
+            if ((rc = upload_array(h, l->col, &l->d_col, s))) goto bad;
+        }
+        h->comp_uploaded = true;
+    }
     {
         hipError_t e = hipStreamSynchronize(s);  // host vectors (slots) must outlive the copies
         if (e != hipSuccess) { rc = hip_fail(e, "hipStreamSynchronize"); goto bad; }

@@ -555,6 +555,107 @@ int64_t long_items(const Plan &p, int k, int64_t threshold) {
 // ------------------------------------------------------------------------------------------
 // finalisation: levels, level-ordered forward form, transposes, schedules, statistics
 // ------------------------------------------------------------------------------------------
+// Detect a batch of small graphs: every connected component of the input graph occupies a
+// contiguous id range and is small.  Aggregation nodes never cross components (their inputs
+// co-occur in some list, hence lie in one component).  Fills h->comp or leaves it disabled.
+static void build_components(hag_handle *h) {
+    Components &c = h->comp;
+    c = Components{};
+    const int64_t n = h->n, a = h->a;
+    if (env_i64("HAG_COMPONENT", 1) == 0 || n < 1024) return;
+    std::vector<int32_t> parent(n);
+    std::iota(parent.begin(), parent.end(), 0);
+    auto find = [&](int32_t x) {
+        while (parent[x] != x) { parent[x] = parent[parent[x]]; x = parent[x]; }
+        return x;
+    };
+    for (int64_t v = 0; v < n; ++v)
+        for (int64_t i = h->g.ptr[v]; i < h->g.ptr[v + 1]; ++i) {
+            int32_t ra = find((int32_t)v), rb = find(h->g.col[i]);
+            if (ra != rb) parent[std::max(ra, rb)] = std::min(ra, rb);   // root = smallest id
+        }
+    // contiguity: walking ids upwards, the root may only change to the current id
+    std::vector<int32_t> comp_of(n + a);
+    c.node_ptr.clear();
+    int32_t cur = -1;
+    for (int64_t v = 0; v < n; ++v) {
+        int32_t r = find((int32_t)v);
+        if (r != cur) {
+            if (r != v) return;                 // an older component resumes: ids not contiguous
+            cur = r;
+            c.node_ptr.push_back((int32_t)v);
+        }
+        comp_of[v] = (int32_t)c.node_ptr.size() - 1;
+    }
+    c.node_ptr.push_back((int32_t)n);
+    c.count = (int32_t)c.node_ptr.size() - 1;
+    if (c.count < 64) return;                   // too few workgroups to fill the device
+    // aggregation nodes per component, sorted by level (level order is already by level)
+    std::vector<int32_t> agg_count(c.count, 0);
+    for (int64_t i = 0; i < a; ++i) {
+        comp_of[n + i] = comp_of[h->left[i]];
+        if (comp_of[h->right[i]] != comp_of[n + i]) return;   // cannot happen for a valid HAG
+        agg_count[comp_of[n + i]]++;
+    }
+    c.agg_ptr.assign(c.count + 1, 0);
+    for (int32_t k = 0; k < c.count; ++k) {
+        c.agg_ptr[k + 1] = c.agg_ptr[k] + agg_count[k];
+        c.max_nodes = std::max(c.max_nodes, c.node_ptr[k + 1] - c.node_ptr[k]);
+        c.max_agg = std::max(c.max_agg, agg_count[k]);
+    }
+    if (c.max_nodes + c.max_agg > 4096) return;  // local ids are 16 bit and must fit LDS anyway
+    // local id of every unified id
+    std::vector<int32_t> local(n + a), fill(c.agg_ptr.begin(), c.agg_ptr.end() - 1);
+    c.stage.resize(a);
+    c.n_stages.assign(c.count, 0);
+    if (h->stages > 255) return;
+    std::vector<int32_t> slot_of(a);             // component-major index of aggregation node i
+    for (int64_t v = 0; v < n; ++v) local[v] = (int32_t)v - c.node_ptr[comp_of[v]];
+    for (int32_t st = 0; st < h->stages; ++st)
+        for (int32_t i = h->stage_ptr[st]; i < h->stage_ptr[st + 1]; ++i) {   // level order: stages ascending
+            int32_t k = comp_of[n + i];
+            int32_t slot = fill[k]++;
+            slot_of[i] = slot;
+            local[n + i] = (c.node_ptr[k + 1] - c.node_ptr[k]) + (slot - c.agg_ptr[k]);
+            c.stage[slot] = (uint8_t)(st + 1);
+            c.n_stages[k] = std::max(c.n_stages[k], (uint8_t)(st + 1));
+        }
+    if (h->hf.col.size() >= (size_t)INT32_MAX || h->ht.col.size() >= (size_t)INT32_MAX) return;
+    // rows [row_begin, row_end) of src in the given order of rows, ids made local
+    auto localise = [&](const Csr &src, const std::vector<int64_t> &rows, LocalLists &dst) {
+        dst.ptr.assign(1, 0);
+        dst.col.clear();
+        for (int64_t r : rows) {
+            for (int64_t i = src.ptr[r]; i < src.ptr[r + 1]; ++i) dst.col.push_back((uint16_t)local[src.col[i]]);
+            dst.ptr.push_back((int32_t)dst.col.size());
+        }
+    };
+    std::vector<int64_t> orig_rows(n), agg_rows_he(a), agg_rows_ht(a);
+    std::iota(orig_rows.begin(), orig_rows.end(), 0);
+    for (int64_t i = 0; i < a; ++i) { agg_rows_he[slot_of[i]] = i; agg_rows_ht[slot_of[i]] = n + i; }
+    localise(h->hf, orig_rows, c.fwd);
+    localise(h->he, agg_rows_he, c.fwd_agg);
+    localise(h->ht, orig_rows, c.bwd_orig);
+    localise(h->ht, agg_rows_ht, c.bwd_agg);
+    localise(h->g, orig_rows, c.nfwd);
+    localise(h->gt, orig_rows, c.nbwd);
+    for (int32_t k = 0; k < c.count; ++k) {
+        int32_t v0 = c.node_ptr[k], v1 = c.node_ptr[k + 1], a0 = c.agg_ptr[k], a1 = c.agg_ptr[k + 1];
+        auto span = [&](const LocalLists &l, int32_t lo, int32_t hi) { return l.ptr[hi] - l.ptr[lo]; };
+        (void)v0; (void)v1;
+        c.max_entries_fwd = std::max(c.max_entries_fwd, span(c.fwd_agg, a0, a1));
+        c.max_entries_bwd = std::max(c.max_entries_bwd, span(c.bwd_agg, a0, a1));
+    }
+    c.meta.resize(4 * (size_t)c.count);
+    for (int32_t k = 0; k < c.count; ++k) {
+        c.meta[4 * k + 0] = c.node_ptr[k];
+        c.meta[4 * k + 1] = c.node_ptr[k + 1] - c.node_ptr[k];
+        c.meta[4 * k + 2] = c.agg_ptr[k];
+        c.meta[4 * k + 3] = (c.agg_ptr[k + 1] - c.agg_ptr[k]) | ((int32_t)c.n_stages[k] << 16);
+    }
+    c.enabled = true;
+}
+
 static int finalize_from_builder(hag_handle *h, Builder &b) {
     const int64_t n = b.n, a = b.a();
     h->n = n;
@@ -696,6 +797,7 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
     h->max_slots = std::max({h->p_fwd.n_slots, h->p_bwd_src.n_slots, h->p_naive_fwd.n_slots, h->p_naive_bwd.n_slots});
     for (auto &p : h->p_bwd_stage) h->max_slots = std::max(h->max_slots, p.n_slots);
     for (auto &p : h->p_fwd_stage) h->max_slots = std::max(h->max_slots, p.n_slots);
+    build_components(h);
     // statistics (Section 4.1: k in-neighbours cost k-1 binary aggregations; Section 5.4: one
     // row transfer per aggregated neighbour)
     hag_stats_t &s = h->st;

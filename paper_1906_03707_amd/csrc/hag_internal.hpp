@@ -40,6 +40,35 @@ struct Plan {
     Item *d_combine = nullptr;
 };
 
+// Component-local form of a graph made of many small connected components with contiguous
+// node ids (a batch of small graphs): everything one component needs fits in the LDS of one
+// workgroup, so a whole pass (aggregation nodes and final gather) is a single launch that
+// reads every feature row from HBM once.  Ids are LOCAL to the component: originals
+// 0..nv-1, then its aggregation nodes sorted by level.
+struct LocalLists {
+    std::vector<int32_t> ptr;    // [rows+1] offsets into col
+    std::vector<uint16_t> col;   // local ids
+    int32_t *d_ptr = nullptr;
+    uint16_t *d_col = nullptr;
+};
+struct Components {
+    bool enabled = false;
+    int32_t count = 0;
+    int32_t max_nodes = 0, max_agg = 0;      // largest nv and na over the components
+    // most aggregation-list entries one component has, per pass (sizes their LDS staging area)
+    int32_t max_entries_fwd = 0, max_entries_bwd = 0;
+    std::vector<int32_t> node_ptr;           // [count+1] first original node of each component
+    std::vector<int32_t> agg_ptr;            // [count+1] into the component-major aggregation arrays
+    std::vector<uint8_t> stage;              // [a] stage of the node (1-based), component-major
+    std::vector<uint8_t> n_stages;           // [count] last stage the component takes part in
+    LocalLists fwd, fwd_agg;                 // Nhat_v of original nodes; staged inputs of aggregation nodes
+    LocalLists bwd_orig, bwd_agg;            // consumers of original nodes / of aggregation nodes (staged form)
+    LocalLists nfwd, nbwd;                   // the input graph and its transpose (naive baseline)
+    std::vector<int32_t> meta;               // [4*count] first node, #nodes, first slot, #agg | #stages << 16
+    int32_t *d_meta = nullptr;
+    uint8_t *d_stage = nullptr;
+};
+
 void set_error(const std::string &msg);
 
 }  // namespace hag
@@ -77,9 +106,10 @@ struct hag_handle {
     hag::Plan p_bwd_src;                   // rows 0..n-1 of ht
     hag::Plan p_naive_fwd, p_naive_bwd;
     int64_t max_slots = 0;
+    hag::Components comp;
 
     // device copies
-    bool uploaded = false;
+    bool uploaded = false, comp_uploaded = false;
     int device = -1;
     int32_t *d_left = nullptr, *d_right = nullptr;
     int32_t *d_hcol = nullptr, *d_tcol = nullptr, *d_gcol = nullptr, *d_gtcol = nullptr, *d_ecol = nullptr;

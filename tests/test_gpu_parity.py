@@ -122,6 +122,43 @@ def test_source_partitioned_schedule(B, monkeypatch):
     run_all_ops(B, h, rowptr, col, 128, seed=45)
 
 
+def ragged_batch(sizes, p, seed):
+    """Disjoint G(size, p) graphs of the given sizes (size 1 = an isolated node), block-diagonal CSR."""
+    rng = np.random.default_rng(seed)
+    rows, cols, off = [], [], 0
+    for sz in sizes:
+        m = np.triu(rng.random((sz, sz)) < p, 1)
+        m = m | m.T
+        r, c = np.nonzero(m)
+        rows.append(r + off)
+        cols.append(c + off)
+        off += sz
+    rows, cols = np.concatenate(rows), np.concatenate(cols)
+    rowptr = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=off))]).astype(np.int64)
+    return rowptr, cols.astype(np.int32), np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
+
+
+@pytest.mark.parametrize("d", [16, 64, 260])
+def test_component_local_pass_on_graph_batches(B, d, monkeypatch):
+    # a batch of small graphs runs as one launch per pass out of LDS (one workgroup per graph):
+    # ragged sizes incl. isolated nodes and graphs without aggregation nodes, all ops and dtypes
+    sizes = np.random.default_rng(61).integers(1, 41, size=150)
+    rowptr, col, gp = ragged_batch(sizes, 0.6, seed=62)
+    assert rowptr.size - 1 >= 1024
+    h = B.hag_search_batched(rowptr, col, gp, 0.25)
+    assert h.stats()["a"] > 100 and h.stats()["levels"] >= 2
+    run_all_ops(B, h, rowptr, col, d, seed=63 + d)
+    # the same handle through the generic kernels must agree bit for bit on int32
+    monkeypatch.setenv("HAG_COMPONENT", "0")
+    g = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+    x = dev(synth.features_i32(rowptr.size - 1, d, 5))
+    assert torch.equal(h.forward(x, "sum"), g.forward(x, "sum"))
+    assert torch.equal(h.backward(x, "sum"), g.backward(x, "sum"))
+    ya, aa = h.forward(x, "max")
+    yb, ab = g.forward(x, "max")
+    assert torch.equal(ya, yb) and torch.equal(aa, ab)
+
+
 def test_capacity_zero_is_the_gnn_graph(B):
     # Section 3.1: the GNN-graph is the HAG with V_A empty -> identical kernels, identical bits
     rowptr, col = synth.random_graph(400, 0.1, seed=3)
