@@ -52,6 +52,7 @@ struct GatherArgs {
     const float *in_scale;    // optional: multiplies rows of ids < split (mean, transposed pass)
     const float *out_scale;   // optional: multiplies final rows (mean, forward), indexed by item.row
     int32_t d;
+    int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
 };
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -102,83 +103,101 @@ __device__ __forceinline__ Item load_item(const Item *p) {
     return it;
 }
 
-// Reduce `cnt` neighbour rows whose ids start at col[beg] into (acc, acc_id), for the four
-// features starting at cbase.  Called by all LPR lanes of a sub-group together; `maxcnt` is
-// the largest cnt among the sub-groups of the wavefront, so that every lane of the wavefront
-// executes the same number of cross-lane reads.  Column ids are read LPR at a time
-// (coalesced) and handed round inside the sub-group; UNR neighbour rows are requested
-// before the first is consumed.
-template <typename T, int RED, int LPR, int UNR>
-__device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg, int cnt, int maxcnt, int sl,
-                                            int cbase, bool col_ok, typename V4<T>::type &acc, int4 &acc_id) {
+// One step of the reduction: UNR neighbour rows with ids idx[0..UNR) (all valid when !TAIL;
+// idx < 0 = nothing when TAIL) for the four features at element offset cb of a row.
+// The gathered matrices are addressed as base + 32-bit byte offset when OFF32 (both matrices
+// below 4 GiB), which costs one multiply-add per row instead of 64-bit pointer arithmetic;
+// at cache-hit rates this loop is bound by instruction issue, so every instruction counts.
+template <typename T, int RED, int UNR, bool OFF32, bool TAIL>
+__device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&idx)[UNR], int cb,
+                                            typename V4<T>::type &acc, int4 &acc_id) {
     using V = typename V4<T>::type;
+    const uint32_t row_bytes = (uint32_t)A.d * 4u, cb_bytes = (uint32_t)cb * 4u;
     const size_t d = (size_t)A.d;
-    for (int base = 0; base < maxcnt; base += LPR) {
-        const int mine = (base + sl < cnt) ? A.col[beg + base + sl] : -1;
-        const int lim = min(LPR, maxcnt - base);
-        for (int j = 0; j < lim; j += UNR) {
+    V val[UNR];
+    // Lists are sorted, so ids >= split (rows of the second matrix) come last: most steps see
+    // none in the whole wavefront and take the single-matrix path.
+    int hi_any = 0;
+#pragma unroll
+    for (int k = 0; k < UNR; ++k) hi_any |= (idx[k] >= A.split);
+    const bool single = !__any(hi_any);
+    if (single) {
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) {
+            val[k] = V{};
+            if (!TAIL || idx[k] >= 0) {
+                if (OFF32) val[k] = ld4(reinterpret_cast<const T *>(reinterpret_cast<const char *>(A.src_lo) +
+                                                                     ((uint32_t)idx[k] * row_bytes + cb_bytes)));
+                else val[k] = ld4(A.src_lo + (size_t)idx[k] * d + cb);
+            }
+        }
+    } else {
+        // mixed: select the address, not the path, so the loads still issue together
+        const T *ptr[UNR];
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) {
+            const int id = TAIL ? max(idx[k], 0) : idx[k];
+            const bool lo = id < A.split;
+            const T *base_ptr = lo ? A.src_lo : A.src_hi;
+            ptr[k] = base_ptr + (size_t)(lo ? id : id - A.split) * d + cb;
+        }
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) {
+            val[k] = V{};
+            if (!TAIL || idx[k] >= 0) val[k] = ld4(ptr[k]);
+        }
+    }
+    if (A.in_scale) {
+#pragma unroll
+        for (int k = 0; k < UNR; ++k)
+            if (idx[k] >= 0 && idx[k] < A.split) scale4(val[k], A.in_scale[idx[k]]);
+    }
+    if (RED == R_MAX) {
+        if (single) {
+            // Only original rows here, and a list holds its original ids in ascending order
+            // before any aggregation node: whatever the accumulator holds came from a smaller
+            // id, so a tie keeps it and "greater than" is the whole test.
+#pragma unroll
+            for (int k = 0; k < UNR; ++k) max_first4(acc, acc_id, val[k], idx[k]);
+        } else {
+#pragma unroll
+            for (int k = 0; k < UNR; ++k) {
+                int4 vid = make_int4(idx[k], idx[k], idx[k], idx[k]);   // -1 stays "nothing"
+                if (idx[k] >= A.split) vid = ld4(A.id_hi + (size_t)(idx[k] - A.split) * d + cb);
+                max4(acc, acc_id, val[k], vid);
+            }
+        }
+    } else {
+#pragma unroll
+        for (int k = 0; k < UNR; ++k) add4(acc, val[k]);
+    }
+}
+
+// Reduce `cnt` neighbour rows whose ids start at col[beg] into (acc, acc_id), for the four
+// features starting at element cb of a row.  Called by all LPR lanes of a sub-group together
+// (sub-groups of one wavefront may have different cnt: the loop then simply runs with part of
+// the wavefront masked off).  Column ids are read LPR at a time (coalesced) and handed round
+// inside the sub-group; UNR neighbour rows are requested before the first is consumed; full
+// groups of UNR ids take a path without any per-row predicate.
+template <typename T, int RED, int LPR, int UNR, bool OFF32>
+__device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg, int cnt, int sl, int cb,
+                                            typename V4<T>::type &acc, int4 &acc_id) {
+    for (int base = 0; base < cnt; base += LPR) {
+        const int here = min(LPR, cnt - base);
+        const int mine = (sl < here) ? A.col[beg + base + sl] : -1;
+        const int full = here & ~(UNR - 1);
+        int j = 0;
+        for (; j < full; j += UNR) {
             int idx[UNR];
-            V val[UNR];
-            int4 vid[UNR];
 #pragma unroll
             for (int k = 0; k < UNR; ++k) idx[k] = __shfl(mine, j + k, LPR);
-            // Lists are sorted, so ids >= split (rows of the second matrix) come last: most
-            // iterations see none in the whole wavefront and take the single-matrix path.
-            int hi_any = 0;
+            reduce_step<T, RED, UNR, OFF32, false>(A, idx, cb, acc, acc_id);
+        }
+        if (j < here) {
+            int idx[UNR];
 #pragma unroll
-            for (int k = 0; k < UNR; ++k) hi_any |= (idx[k] >= A.split);
-            const bool single = !__any(hi_any);
-            if (single) {
-#pragma unroll
-                for (int k = 0; k < UNR; ++k) {
-                    val[k] = V{};
-                    if (idx[k] >= 0 && col_ok) val[k] = ld4(A.src_lo + (size_t)idx[k] * d + cbase);
-                }
-            } else {
-                // mixed: select the address, not the path, so the loads still issue together
-                const T *ptr[UNR];
-#pragma unroll
-                for (int k = 0; k < UNR; ++k) {
-                    const int id = max(idx[k], 0);
-                    const bool lo = id < A.split;
-                    const T *base_ptr = lo ? A.src_lo : A.src_hi;
-                    ptr[k] = base_ptr + (size_t)(lo ? id : id - A.split) * d + cbase;
-                }
-#pragma unroll
-                for (int k = 0; k < UNR; ++k) {
-                    val[k] = V{};
-                    if (idx[k] >= 0 && col_ok) val[k] = ld4(ptr[k]);
-                }
-            }
-            if (A.in_scale) {
-#pragma unroll
-                for (int k = 0; k < UNR; ++k)
-                    if (idx[k] >= 0 && idx[k] < A.split) scale4(val[k], A.in_scale[idx[k]]);
-            }
-            if (RED == R_MAX) {
-                if (single) {
-                    // Only original rows here, and a list holds its original ids in ascending
-                    // order before any aggregation node: whatever the accumulator holds came
-                    // from a smaller id, so a tie keeps it and "greater than" is the whole test.
-#pragma unroll
-                    for (int k = 0; k < UNR; ++k) {
-                        const int wi = col_ok ? idx[k] : -1;
-                        max_first4(acc, acc_id, val[k], wi);
-                    }
-                } else {
-#pragma unroll
-                    for (int k = 0; k < UNR; ++k) {
-                        vid[k] = make_int4(idx[k], idx[k], idx[k], idx[k]);   // -1 stays "nothing"
-                        if (idx[k] >= A.split && col_ok) vid[k] = ld4(A.id_hi + (size_t)(idx[k] - A.split) * d + cbase);
-                        if (!col_ok) vid[k] = make_int4(-1, -1, -1, -1);
-                    }
-#pragma unroll
-                    for (int k = 0; k < UNR; ++k) max4(acc, acc_id, val[k], vid[k]);
-                }
-            } else {
-#pragma unroll
-                for (int k = 0; k < UNR; ++k) add4(acc, val[k]);
-            }
+            for (int k = 0; k < UNR; ++k) idx[k] = __shfl(mine, j + k, LPR);
+            reduce_step<T, RED, UNR, OFF32, true>(A, idx, cb, acc, acc_id);
         }
     }
 }
@@ -217,6 +236,7 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     const int sl = lane % LPR;
     const int cbase = (blockIdx.y * LPR + sl) * 4;
     const bool col_ok = cbase < A.d;
+    const int cb = col_ok ? cbase : 0;      // lanes past the last feature read column 0 and store nothing
     V acc{};
     int4 acc_id = make_int4(-1, -1, -1, -1);
 
@@ -229,7 +249,8 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
         int per = (it.cnt + NSG - 1) / NSG;
         per = (per + UNR - 1) / UNR * UNR;
         const int lo = min(it.cnt, sg * per), hi = min(it.cnt, lo + per);
-        reduce_rows<T, RED, LPR, UNR>(A, it.beg + lo, hi - lo, min(it.cnt, per), sl, cbase, col_ok, acc, acc_id);
+        if (A.off32) reduce_rows<T, RED, LPR, UNR, true>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
+        else reduce_rows<T, RED, LPR, UNR, false>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
         red_val[threadIdx.x] = acc;
         if (RED == R_MAX) red_id[threadIdx.x] = acc_id;
         __syncthreads();
@@ -249,10 +270,8 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     const bool has_item = local < p_items;
     Item it{0, 0, 0};
     if (has_item) it = load_item(A.items + p_begin + local);
-    int maxcnt = it.cnt;
-#pragma unroll
-    for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
-    reduce_rows<T, RED, LPR, UNR>(A, it.beg, it.cnt, maxcnt, sl, cbase, col_ok, acc, acc_id);
+    if (A.off32) reduce_rows<T, RED, LPR, UNR, true>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
+    else reduce_rows<T, RED, LPR, UNR, false>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
     if (has_item && col_ok) store_result<T, RED>(A, it.row, cbase, acc, acc_id);
 }
 
@@ -563,6 +582,13 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
                     hipStream_t s, uint32_t phases = HAG_PHASE_ALL) {
     a.items = p.d_items;
     a.np = p.np;
+    // rows of ids < split live in a matrix of `split` rows, the others in one of at most
+    // n + a (aggregation rows) or max_slots (partial rows) rows
+    {
+        const uint64_t row_bytes = (uint64_t)a.d * 4;
+        const uint64_t lo_rows = (uint64_t)std::max<int64_t>(a.split, 1);
+        a.off32 = lo_rows * row_bytes < (1ull << 32) ? 1 : 0;
+    }
     // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
     // eight neighbours, and needs one when a single sub-group would walk it for too long.
     {
