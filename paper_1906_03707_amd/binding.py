@@ -40,7 +40,7 @@ class HagError(RuntimeError):
 class hag_stats_t(ctypes.Structure):
     _fields_ = [(k, ctypes.c_int64) for k in (
         "n", "e", "a", "levels", "h", "e_hag", "aggr_naive", "aggr_hag", "xfer_naive", "xfer_hag",
-        "max_degree", "max_hag_degree", "stages")]
+        "max_degree", "max_hag_degree", "stages", "components")]
 
 
 _lib = None

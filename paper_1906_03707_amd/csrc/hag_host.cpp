@@ -815,6 +815,7 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
     s.aggr_hag += a;
     s.xfer_naive = s.e;
     s.xfer_hag = s.e_hag;
+    s.components = h->comp.enabled ? h->comp.count : 0;
     return HAG_OK;
 }
 

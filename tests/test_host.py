@@ -176,3 +176,34 @@ def test_config1_search_invariants():
     assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0
     assert st["aggr_naive"] - st["aggr_hag"] == int((red - 1).sum())
     assert st["e"] - st["e_hag"] == int((red - 2).sum())
+
+
+def test_stage_fusion_and_component_detection(monkeypatch):
+    # levels are fused into stages when that is cheap; a batch of small graphs with contiguous ids is
+    # recognised as such (one workgroup per component on the device), anything else is not
+    rowptr, col, gp = synth.er_batch(100, 16, 0.7, seed=12)
+    h = B.hag_search_batched(rowptr, col, gp, 0.25)
+    st = h.stats()
+    assert 1 <= st["stages"] <= st["levels"] and st["components"] == 100
+    assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0
+    monkeypatch.setenv("HAG_STAGE_EXTRA_ROWS", "-1000000")
+    assert B.hag_search_batched(rowptr, col, gp, 0.25).stats()["stages"] == st["levels"]
+    monkeypatch.delenv("HAG_STAGE_EXTRA_ROWS")
+    # the same graphs with node ids shuffled: components are no longer contiguous ranges
+    n = rowptr.size - 1
+    perm = np.random.default_rng(13).permutation(n)
+    rows = perm[np.repeat(np.arange(n), np.diff(rowptr))]
+    cols = perm[col]
+    order = np.lexsort((cols, rows))
+    rp2 = np.concatenate([[0], np.cumsum(np.bincount(rows, minlength=n))]).astype(np.int64)
+    h2 = B.hag_search(rp2, cols[order].astype(np.int32), n // 4)
+    assert h2.stats()["components"] == 0
+    # one connected graph: no components either
+    rowptr, col = synth.sbm(n_blocks=8, block=160, p_in=0.1, p_out=0.01, seed=14)
+    assert B.hag_search(rowptr, col, 64).stats()["components"] == 0
+    # workspace grows with d and covers the aggregation rows
+    h3 = B.hag_search(rowptr, col, 64)
+    a = h3.stats()["a"]
+    assert h3.workspace_bytes("sum", B.HAG_F32, 64) >= a * 64 * 4
+    assert h3.workspace_bytes("max", B.HAG_F32, 64) >= 2 * a * 64 * 4
+    assert h3.workspace_bytes("sum", B.HAG_F32, 128) > h3.workspace_bytes("sum", B.HAG_F32, 64)
