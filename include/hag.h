@@ -62,7 +62,8 @@ enum {
 
 enum {
     HAG_SEARCH_CANONICAL = 1, /* among pairs of maximal redundancy take the lexicographically
-                                 smallest (smaller id, larger id); result is then unique */
+                                 smallest (smaller id, larger id), which makes the result unique.
+                                 The search always does this; the flag is accepted and ignored. */
     HAG_SEARCH_DEDUP = 2      /* drop duplicate neighbours instead of rejecting them */
 };
 

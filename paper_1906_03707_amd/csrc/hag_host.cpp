@@ -640,9 +640,8 @@ static void build_components(hag_handle *h) {
     localise(h->g, orig_rows, c.nfwd);
     localise(h->gt, orig_rows, c.nbwd);
     for (int32_t k = 0; k < c.count; ++k) {
-        int32_t v0 = c.node_ptr[k], v1 = c.node_ptr[k + 1], a0 = c.agg_ptr[k], a1 = c.agg_ptr[k + 1];
+        int32_t a0 = c.agg_ptr[k], a1 = c.agg_ptr[k + 1];
         auto span = [&](const LocalLists &l, int32_t lo, int32_t hi) { return l.ptr[hi] - l.ptr[lo]; };
-        (void)v0; (void)v1;
         c.max_entries_fwd = std::max(c.max_entries_fwd, span(c.fwd_agg, a0, a1));
         c.max_entries_bwd = std::max(c.max_entries_bwd, span(c.bwd_agg, a0, a1));
     }
