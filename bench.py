@@ -194,6 +194,20 @@ def main():
     ms_naive = time_steps(torch, step_naive, args.steps, args.warmup)
     ms_fwd = time_steps(torch, lambda: h.forward(x, op, y=y, argmax=am), args.steps, args.warmup)
     ms_nfwd = time_steps(torch, lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
+    def time_graph_replay(fn):
+        """The same step captured once into a HIP graph and replayed (no per-launch host work)."""
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        return time_steps(torch, g.replay, args.steps, args.warmup)
+
+    ms_hag_graph = time_graph_replay(step_hag)
+    ms_naive_graph = time_graph_replay(step_naive)
     ms_hag_cold = time_cold(step_hag)
     ms_naive_cold = time_cold(step_naive)
     copy_gbps = copy_ceiling_GBps()
@@ -245,6 +259,7 @@ def main():
         "transfer_reduction": st["xfer_naive"] / max(st["xfer_hag"], 1),
         "forward_ms": {"hag": ms_fwd, "naive": ms_nfwd},
         "cold_cache_ms_per_step": {"hag": ms_hag_cold, "naive": ms_naive_cold},
+        "hip_graph_replay_ms_per_step": {"hag": ms_hag_graph, "naive": ms_naive_graph},
         "device_copy_GBps": copy_gbps,
         "effective_frac_of_copy": alg_hag / (ms_hag * 1e-3) / 1e9 / copy_gbps,
     }
@@ -252,6 +267,7 @@ def main():
     log(f"[bench] fwd+bwd  hag {ms_hag:.4f} ms  naive {ms_naive:.4f} ms  speedup {ms_naive / ms_hag:.3f}x "
         f"(aggregations {out['aggregation_reduction']:.3f}x, transfers {out['transfer_reduction']:.3f}x fewer)")
     log(f"[bench] fwd only hag {ms_fwd:.4f} ms  naive {ms_nfwd:.4f} ms")
+    log(f"[bench] replayed from a HIP graph: hag {ms_hag_graph:.4f} ms  naive {ms_naive_graph:.4f} ms")
     log(f"[bench] cold caches (after a 1 GiB write sweep): hag {ms_hag_cold:.4f} ms  naive {ms_naive_cold:.4f} ms; "
         f"plain 1 GiB device copy {copy_gbps:.0f} GB/s")
     log(f"[bench] effective (algorithmic) GB/s fwd+bwd: hag {out['effective_GBps_fwd_bwd']:.0f}  "

@@ -215,6 +215,49 @@ def test_self_loops_and_dedup(B):
     run_all_ops(B, h, rp2, c2, 32, seed=52)
 
 
+def test_forward_backward_inside_a_hip_graph(B):
+    # the device entry points allocate nothing, never synchronise and clear memory with kernels, so a
+    # whole step can be captured once and replayed; every replay must reproduce the eager result
+    rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=71)
+    n, d = rowptr.size - 1, 64
+    h = B.hag_search(rowptr, col, n // 4).upload()
+    assert h.stats()["levels"] >= 2
+    x = dev(synth.features_f32(n, d, 72))
+    gy = dev(synth.features_f32(n, d, 73))
+    y, gx = torch.empty_like(x), torch.empty_like(x)
+    ym, am, gm = torch.empty_like(x), torch.empty((n, d), dtype=torch.int32, device="cuda"), torch.empty_like(x)
+    ws = torch.empty(h.workspace_bytes("max", B.HAG_F32, d), dtype=torch.uint8, device="cuda")
+
+    def step():
+        h.forward(x, "sum", y=y, workspace=ws)
+        h.backward(gy, "mean", gx=gx, workspace=ws)
+        h.forward(x, "max", y=ym, argmax=am, workspace=ws)
+        h.backward(gy, "max", argmax=am, gx=gm, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    want = [t.clone() for t in (y, gx, ym, am)]
+    want_gm = gm.clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        step()                                   # warm-up on the capture stream
+    torch.cuda.current_stream().wait_stream(side)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        step()
+    for rep in range(3):
+        for t in (y, gx, ym, gm):
+            t.zero_()                            # eager work between replays
+        am.fill_(-7)
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for got, ref in zip((y, gx, ym, am), want):
+            assert torch.equal(got, ref), f"replay {rep} differs from the eager run"
+        assert torch.allclose(gm, want_gm, rtol=1e-5, atol=1e-5)   # atomics: order not fixed
+
+
 def test_max_ties_bit_exact(B):
     # few distinct values -> many exact ties; argmax must be the smallest original id
     n, d = 600, 32
