@@ -113,7 +113,7 @@ def main():
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload")
-    ap.add_argument("--op", default="sum", choices=["sum", "mean", "max"])
+    ap.add_argument("--op", default="sum", choices=["sum", "mean", "max", "gcn"])
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")

@@ -49,7 +49,9 @@ extern "C" {
 
 typedef struct hag_handle hag_t; /* opaque; immutable after construction except hag_upload */
 
-typedef enum { HAG_SUM = 0, HAG_MEAN = 1, HAG_MAX = 2 } hag_op_t;   /* Table 1, set Aggregate */
+/* Table 1, set Aggregate.  HAG_GCN is the GCN row's Update up to the weight matrix, fused
+ * into the aggregation: y[v] = (sum over N(v) of x[u] + x[v]) / (|N(v)| + 1); f32 only. */
+typedef enum { HAG_SUM = 0, HAG_MEAN = 1, HAG_MAX = 2, HAG_GCN = 3 } hag_op_t;
 typedef enum { HAG_F32 = 0, HAG_I32 = 1 } hag_dtype_t;
 
 enum {
@@ -155,7 +157,7 @@ size_t hag_workspace_bytes(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64
 /* Algorithm 2 without the Update line: aggregation nodes level by level, then
  * y[v] = Aggregate over Nhat_v for every v in V.  x, y: device [n, d].
  * argmax: device int32 [n, d], required for HAG_MAX, ignored otherwise.
- * HAG_MEAN requires HAG_F32. */
+ * HAG_MEAN and HAG_GCN require HAG_F32. */
 int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
                 const void *x, void *y, int32_t *argmax, void *workspace, void *stream);
 

@@ -19,8 +19,8 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "hag_oracle.c")
 _LIB = os.path.join(_HERE, "libhag_oracle.so")
 
-OP_SUM, OP_MEAN, OP_MAX = 0, 1, 2
-_OPS = {"sum": OP_SUM, "mean": OP_MEAN, "max": OP_MAX}
+OP_SUM, OP_MEAN, OP_MAX, OP_GCN = 0, 1, 2, 3
+_OPS = {"sum": OP_SUM, "mean": OP_MEAN, "max": OP_MAX, "gcn": OP_GCN}
 
 _lib = None
 
@@ -60,7 +60,8 @@ def _csr(rowptr, col):
 
 
 def naive_forward(rowptr, col, x, op="sum"):
-    """Algorithm 1, Aggregate line, with the set aggregates of Table 1 (+ mean).
+    """Algorithm 1, Aggregate line, with the set aggregates of Table 1 (+ mean); op "gcn" is
+    Table 1's GCN row up to the weight matrix: (sum over N(v) of h_u + h_v) / (|N(v)| + 1).
 
     fp32 ``x`` -> (y float64, s_abs float64, argmax int32 or None);
     int32 ``x`` -> (y int32, None, argmax or None)."""
@@ -77,8 +78,8 @@ def naive_forward(rowptr, col, x, op="sum"):
         lib.oracle_naive_forward_f32(_i64(n), _p(rowptr), _p(col), _i64(d), o, _p(x), _p(y), _p(s), _p(am))
         return y, s, am
     if x.dtype == np.int32:
-        if o == OP_MEAN:
-            raise ValueError("mean is not defined for int32")
+        if o in (OP_MEAN, OP_GCN):
+            raise ValueError("mean / gcn are not defined for int32")
         y = np.zeros((n, d), dtype=np.int32)
         lib.oracle_naive_forward_i32(_i64(n), _p(rowptr), _p(col), _i64(d), o, _p(x), _p(y), _p(am))
         return y, None, am

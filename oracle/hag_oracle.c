@@ -47,7 +47,8 @@
 #include <string.h>
 #include <math.h>
 
-enum { OP_SUM = 0, OP_MEAN = 1, OP_MAX = 2 };
+enum { OP_SUM = 0, OP_MEAN = 1, OP_MAX = 2, OP_GCN = 3 };
+/* OP_GCN: GCN's Update before the weight matrix (Table 1): (sum over N(v) of h_u + h_v) / (|N(v)| + 1) */
 
 /* ------------------------------------------------------------------ */
 /* Algorithm 1, Aggregate line: a_v = Aggregate({h_u : u in N(v)})     */
@@ -73,6 +74,11 @@ void oracle_naive_forward_f32(int64_t n, const int64_t *rowptr, const int32_t *c
                 sa += fabs(xv);
             }
             if (op == OP_MEAN && deg > 0) { acc /= (double)deg; sa /= (double)deg; }
+            if (op == OP_GCN) {
+                double xs = (double)x[v * d + f];
+                acc = (acc + xs) / (double)(deg + 1);
+                sa = (sa + fabs(xs)) / (double)(deg + 1);
+            }
             y[v * d + f] = acc;
             if (s_abs) s_abs[v * d + f] = sa;
             if (op == OP_MAX && argmax) argmax[v * d + f] = am;
@@ -95,6 +101,11 @@ void oracle_naive_backward_f32(int64_t n, const int64_t *rowptr, const int32_t *
             int64_t deg = rowptr[v + 1] - rowptr[v];
             double g = (double)gy[v * d + f];
             if (op == OP_MEAN && deg > 0) g /= (double)deg;
+            if (op == OP_GCN) {               /* v also aggregates itself */
+                g /= (double)(deg + 1);
+                gx[v * d + f] += g;
+                if (s_abs) s_abs[v * d + f] += fabs(g);
+            }
             if (op == OP_MAX) {
                 int32_t u = argmax[v * d + f];
                 if (u >= 0) { gx[(int64_t)u * d + f] += g; if (s_abs) s_abs[(int64_t)u * d + f] += fabs(g); }
@@ -191,6 +202,7 @@ void oracle_hag_forward_f32(int64_t n, int64_t a, const int32_t *left, const int
                 } else acc += xv;
             }
             if (op == OP_MEAN && deg[v] > 0) acc /= (double)deg[v];
+            if (op == OP_GCN) acc = (acc + ahat[v * d + f]) / (double)(deg[v] + 1);
             y[v * d + f] = acc;
             if (op == OP_MAX && argmax) argmax[v * d + f] = am;
         }
@@ -210,6 +222,7 @@ void oracle_hag_backward_f32(int64_t n, int64_t a, const int32_t *left, const in
         for (int64_t f = 0; f < d; ++f) {
             double g = (double)gy[v * d + f];
             if (op == OP_MEAN && deg[v] > 0) g /= (double)deg[v];
+            if (op == OP_GCN) { g /= (double)(deg[v] + 1); ghat[v * d + f] += g; }
             for (int64_t e = hrowptr[v]; e < hrowptr[v + 1]; ++e)
                 ghat[(int64_t)hcol[e] * d + f] += g;
         }

@@ -51,6 +51,8 @@ struct GatherArgs {
     int32_t *part_id;         // R_MAX
     const float *in_scale;    // optional: multiplies rows of ids < split (mean, transposed pass)
     const float *out_scale;   // optional: multiplies final rows (mean, forward), indexed by item.row
+    const T *self;            // optional: row item.row of this matrix is added to a final row (gcn) ...
+    const float *self_scale;  // ... after being multiplied by self_scale[item.row], if given
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
 };
@@ -207,6 +209,11 @@ __device__ __forceinline__ void store_result(const GatherArgs<T> &A, int row, in
                                              int4 acc_id) {
     const size_t d = (size_t)A.d;
     if (row >= 0) {
+        if (A.self) {
+            auto own = ld4(A.self + (size_t)row * d + cbase);
+            if (A.self_scale) scale4(own, A.self_scale[row]);
+            add4(acc, own);
+        }
         if (A.out_scale) scale4(acc, A.out_scale[row]);
         const size_t o = (size_t)(row - A.out_off) * d + cbase;
         st4(A.out + o, acc);
@@ -334,6 +341,8 @@ struct CompArgs {
     T *out;
     int32_t *out_id;
     const float *scale_in, *scale_out;
+    const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
+    int32_t add_self;
     int32_t d, stride;           // feature width; padded row stride in LDS, in elements
     int32_t id_rows_off;         // offset of the id rows (max), in 4-byte elements
     int32_t lists_off;           // offset of the staged aggregation lists, in bytes
@@ -474,6 +483,10 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
             int4 acc_id = make_int4(-1, -1, -1, -1);
             lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, A.row_col, beg, cnt, maxcnt, sl, k, acc, acc_id);
             if (has && kb + sl < q) {
+                if (A.add_self) {
+                    // the staged row already carries scale_in, which is the factor the own row needs
+                    add4(acc, *reinterpret_cast<const V *>(buf + v * stride + 4 * k));
+                }
                 if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
                 const size_t o = (size_t)(v0 + v) * A.d + 4 * k;
                 st4(A.out + o, acc);
@@ -628,9 +641,9 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
                         const void *ws, bool needs_ws) {
     if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
     if (!h->uploaded) { set_error("hag_upload has not been called on this handle"); return HAG_ESTATE; }
-    if (op != HAG_SUM && op != HAG_MEAN && op != HAG_MAX) { set_error("unknown op"); return HAG_EINVAL; }
+    if (op != HAG_SUM && op != HAG_MEAN && op != HAG_MAX && op != HAG_GCN) { set_error("unknown op"); return HAG_EINVAL; }
     if (dt != HAG_F32 && dt != HAG_I32) { set_error("unknown dtype"); return HAG_EINVAL; }
-    if (op == HAG_MEAN && dt != HAG_F32) { set_error("mean is defined for f32 only"); return HAG_EINVAL; }
+    if ((op == HAG_MEAN || op == HAG_GCN) && dt != HAG_F32) { set_error("mean and gcn are defined for f32 only"); return HAG_EINVAL; }
     if (d <= 0 || (d % 4) != 0) { set_error("d must be a positive multiple of 4"); return HAG_EINVAL; }
     if (d > (1 << 20)) { set_error("d too large"); return HAG_EINVAL; }
     if (h->n > 0 && (!in || !out)) { set_error("NULL feature pointer"); return HAG_EINVAL; }
@@ -684,8 +697,11 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.in = in;
     a.out = out;
     a.out_id = out_id;
-    a.scale_in = (BACKWARD && op == HAG_MEAN) ? h->d_inv_deg : nullptr;
-    a.scale_out = (!BACKWARD && op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    const float *norm = op == HAG_MEAN ? h->d_inv_deg : op == HAG_GCN ? h->d_inv_deg1 : nullptr;
+    a.scale_in = BACKWARD ? norm : nullptr;
+    a.scale_out = BACKWARD ? nullptr : norm;
+    a.add_self = op == HAG_GCN ? 1 : 0;
+    a.self_scale = nullptr;
     a.d = (int32_t)d;
     a.stride = (int32_t)d + 4;
     a.use_agg = naive ? 0 : 1;
@@ -749,7 +765,8 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
     a.out_id = argmax;
     a.out_off = 0;
     a.in_scale = nullptr;
-    a.out_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.out_scale = op == HAG_MEAN ? h->d_inv_deg : op == HAG_GCN ? h->d_inv_deg1 : nullptr;
+    a.self = op == HAG_GCN ? x : nullptr;
     a.d = (int32_t)d;
     if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
     if (naive) return run_plan<T, RED, G_NAIVE_FWD>(h, h->p_naive_fwd, h->d_gcol, a, w, s, phases);
@@ -779,12 +796,13 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
     a.src_hi = (const T *)w.agg;
     a.id_hi = nullptr;
     a.split = n;
-    a.in_scale = (op == HAG_MEAN) ? h->d_inv_deg : nullptr;
+    a.in_scale = op == HAG_MEAN ? h->d_inv_deg : op == HAG_GCN ? h->d_inv_deg1 : nullptr;
     a.out_scale = nullptr;
     a.d = (int32_t)d;
     if (naive) {
         a.out = gx;
         a.out_off = 0;
+        if (op == HAG_GCN) { a.self = gy; a.self_scale = h->d_inv_deg1; }
         if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
         return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s, phases);
     }
@@ -798,6 +816,7 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
     }
     a.out = gx;
     a.out_off = 0;
+    if (op == HAG_GCN) { a.self = gy; a.self_scale = h->d_inv_deg1; }
     if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
     return run_plan<T, R_SUM, G_HAG_BWD_SRC>(h, h->p_bwd_src, h->d_tcol, a, w, s, phases);
 }
@@ -857,6 +876,7 @@ int hag_upload(hag_t *h, void *stream) {
     if ((rc = upload_array(h, h->gt_dcol, &h->d_gtcol, s))) goto bad;
     if ((rc = upload_array(h, slots, &h->d_slot_ids, s))) goto bad;
     if ((rc = upload_array(h, h->inv_deg, &h->d_inv_deg, s))) goto bad;
+    if ((rc = upload_array(h, h->inv_deg1, &h->d_inv_deg1, s))) goto bad;
     if ((rc = upload_plan(h, h->p_fwd, s))) goto bad;
     for (auto &p : h->p_bwd_stage)
         if ((rc = upload_plan(h, p, s))) goto bad;

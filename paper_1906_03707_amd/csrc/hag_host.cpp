@@ -768,9 +768,11 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
     }
     transpose(h->g, n, h->gt);
     h->inv_deg.resize(n);
+    h->inv_deg1.resize(n);
     for (int64_t v = 0; v < n; ++v) {
         int64_t d = h->g.ptr[v + 1] - h->g.ptr[v];
         h->inv_deg[v] = 1.0f / (float)std::max<int64_t>(d, 1);
+        h->inv_deg1[v] = 1.0f / (float)(d + 1);
     }
     // schedules
     const bool part = env_i64("HAG_PARTITION", 1) != 0 && (n + a) >= env_i64("HAG_PARTITION_MIN_ROWS", 16384);
@@ -1006,6 +1008,7 @@ int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d)
         return 4 * row * n;
     int64_t bytes = row * edges + row * rows_out + 4 * edges + 8 * ptrs;
     if (op == HAG_MAX) bytes += row * rows_out;   // winning ids written beside the values
+    if (op == HAG_GCN) bytes += row * n;          // the node's own row
     return bytes;
 }
 

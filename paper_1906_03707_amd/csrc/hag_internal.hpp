@@ -79,6 +79,7 @@ struct hag_handle {
     hag::Csr g;    // input graph: rows = destinations
     hag::Csr gt;   // its transpose: rows = sources, cols = destinations
     std::vector<float> inv_deg;  // 1 / max(|N(v)|, 1)
+    std::vector<float> inv_deg1; // 1 / (|N(v)| + 1)
 
     // merge list, creation order, unified creation-order ids
     std::vector<int32_t> m_left, m_right, m_red;
@@ -114,7 +115,7 @@ struct hag_handle {
     int32_t *d_left = nullptr, *d_right = nullptr;
     int32_t *d_hcol = nullptr, *d_tcol = nullptr, *d_gcol = nullptr, *d_gtcol = nullptr, *d_ecol = nullptr;
     int32_t *d_slot_ids = nullptr;
-    float *d_inv_deg = nullptr;
+    float *d_inv_deg = nullptr, *d_inv_deg1 = nullptr;
     std::vector<void *> d_allocs;
 };
 

@@ -80,7 +80,7 @@ def test_config2_holme_kim_sum_and_mean(B):
     assert st["a"] == n // 4 and st["aggr_hag"] < st["aggr_naive"]
     assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0          # Theorem 2
     cols = np.arange(128)
-    for op in ("sum", "mean"):
+    for op in ("sum", "mean", "gcn"):
         check_columns(h, rowptr, col, 128, op, cols, synth.SEED_BASE + 2 + 1000)
 
 
@@ -102,6 +102,7 @@ def test_config4_graph_batch_sum(B):
     rows = np.repeat(np.arange(n), np.diff(f["hrowptr"]))
     assert np.array_equal(orig_of[f["hcol"]], rows // 74)
     check_columns(h, rowptr, col, 64, "sum", np.arange(64), synth.SEED_BASE + 4 + 1000)
+    check_columns(h, rowptr, col, 64, "gcn", np.arange(64), synth.SEED_BASE + 4 + 1000)
 
 
 # ------------------------------------------------------------------------------------------------

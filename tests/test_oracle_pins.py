@@ -79,6 +79,31 @@ def test_naive_sum_mean_vs_scipy(directed):
         assert np.abs(A @ x - A.T @ x).max() > 1e-3
 
 
+@pytest.mark.parametrize("directed", [False, True])
+def test_gcn_normalised_aggregation_vs_scipy(directed):
+    # Table 1, GCN row up to the weight matrix: (sum over N(v) of h_u + h_v) / (|N(v)| + 1)
+    # = D^-1 (A + I) h with D = diag(|N(v)| + 1); its transpose for the gradient
+    n, d = 70, 5
+    rowptr, col = synth.random_graph(n, 0.12, seed=3, directed=directed)
+    A = csr_matrix(rowptr, col, n)
+    deg = np.diff(rowptr)
+    M = sp.diags(1.0 / (deg + 1)) @ (A + sp.identity(n))
+    x = synth.features_f32(n, d, 1)
+    gy = synth.features_f32(n, d, 2)
+    y, s, _ = oracle.naive_forward(rowptr, col, x, "gcn")
+    np.testing.assert_allclose(y, M @ x.astype(np.float64), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(s, M @ np.abs(x.astype(np.float64)), rtol=0, atol=1e-12)
+    gx, gs = oracle.naive_backward(rowptr, col, gy, "gcn")
+    np.testing.assert_allclose(gx, M.T @ gy.astype(np.float64), rtol=0, atol=1e-12)
+    np.testing.assert_allclose(gs, M.T @ np.abs(gy.astype(np.float64)), rtol=0, atol=1e-12)
+    h = oracle.search(rowptr, col, 20)
+    assert h.a > 0
+    np.testing.assert_allclose(oracle.hag_forward(h, deg, x, "gcn")[0], y, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(oracle.hag_backward(h, deg, gy, "gcn"), gx, rtol=0, atol=1e-12)
+    if directed:
+        assert np.abs(M @ x - M.T @ x).max() > 1e-3
+
+
 def test_naive_max_vs_reduceat_and_bruteforce():
     n, d = 50, 5
     rowptr, col = synth.random_graph(n, 0.2, seed=21)
