@@ -107,6 +107,40 @@ def cpu_baseline(oracle, synth, rowptr, col, h, d, seed, budget_s=20.0):
     }
 
 
+def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
+    """Per-epoch time (forward + backward) of a 2-layer GCN with `hidden` hidden dims and a SoftMax
+    loss, the model of the paper's end-to-end measurement (Section 5.3), on the synthetic graph.
+    Each layer is h' = relu(gcn_agg(h W)): W is linear, so the layer transforms first and aggregates
+    at the narrow width.  Dense parts (h W, SoftMax) are torch; the aggregation is hag_forward /
+    hag_backward with op "gcn" (or the naive-CSR baseline)."""
+    fwd = h.naive_forward if naive else h.forward
+    bwd = h.naive_backward if naive else h.backward
+
+    class Agg(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, z):
+            return fwd(z.contiguous(), "gcn")
+
+        @staticmethod
+        def backward(ctx, g):
+            return bwd(g.contiguous(), "gcn")
+
+    n, d = x.shape
+    gen = torch.Generator(device="cuda").manual_seed(1)
+    w1 = (torch.randn(d, hidden, device="cuda", generator=gen) / d ** 0.5).requires_grad_()
+    w2 = (torch.randn(hidden, classes, device="cuda", generator=gen) / hidden ** 0.5).requires_grad_()
+    labels = torch.randint(0, classes, (n,), device="cuda", generator=gen)
+
+    def epoch():
+        h1 = torch.relu(Agg.apply(x @ w1))
+        logits = Agg.apply(h1 @ w2)
+        loss = torch.nn.functional.cross_entropy(logits, labels)
+        w1.grad = w2.grad = None
+        loss.backward()
+
+    return time_steps(torch, epoch, steps, warmup)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -117,6 +151,8 @@ def main():
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gcn-epoch", action="store_true",
+                    help="also time a 2-layer GCN epoch (16 hidden dims, SoftMax) around the aggregation")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain 1 GiB device copy (known traffic) so that rocprofv3 --pmc FETCH_SIZE / "
                          "WRITE_SIZE readings of the same run can be scaled")
@@ -274,6 +310,12 @@ def main():
         f"naive {out['naive_csr']['effective_GBps']:.0f}  (peak {HBM_PEAK_GBS:.0f})")
     log(f"[bench] dominant kernel {kernel_name}: {ms_gather * 1e3:.1f} us, {gather_bytes / 1e6:.1f} MB -> {achieved:.0f} GB/s "
         f"= {100 * achieved / HBM_PEAK_GBS:.1f}% of HBM peak")
+    if args.gcn_epoch:
+        e_hag = gcn_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=False)
+        e_naive = gcn_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=True)
+        out["gcn_epoch_ms"] = {"hag": e_hag, "naive": e_naive, "hidden": 16, "classes": 16, "layers": 2}
+        log(f"[bench] 2-layer GCN epoch (16 hidden dims, SoftMax, fwd+bwd): hag {e_hag:.4f} ms  naive {e_naive:.4f} ms  "
+            f"speedup {e_naive / e_hag:.3f}x")
     if not args.no_cpu_baseline:
         import oracle
 
