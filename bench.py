@@ -141,12 +141,53 @@ def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     return time_steps(torch, epoch, steps, warmup)
 
 
+def sweep_config5(torch, synth, workloads, steps, warmup):
+    """BASELINE config 5: the 232,965-node graph over capacity {0, |V|/8, |V|/4, |V|/2} x feature
+    dim {16, 128, 512} x {max, sum}, forward + backward.  One JSON line per point on stdout."""
+    rowptr, col, _ = synth.graph_for_config(5)
+    n = rowptr.size - 1
+    log(f"[bench] config 5 sweep: graph ready ({col.size} directed edges)")
+    hags = {}
+    for cap in (0, n // 8, n // 4, n // 2):
+        hags[cap] = workloads.build_hag(5, rowptr, col, None, cap, log=lambda m: log("[bench] " + m)).upload()
+    log("[bench] capacity      d  op    hag ms   naive ms  speedup  aggregations fewer")
+    for d in (16, 128, 512):
+        x = torch.from_numpy(synth.features_f32(n, d, synth.SEED_BASE + 5 + 1000 + d)).cuda()
+        gy = torch.from_numpy(synth.features_f32(n, d, synth.SEED_BASE + 5 + 2000 + d)).cuda()
+        y, gx = torch.empty_like(x), torch.empty_like(x)
+        am = torch.empty((n, d), dtype=torch.int32, device="cuda")
+        for op in ("max", "sum"):
+            for cap, h in hags.items():
+                st = h.stats()
+                a = am if op == "max" else None
+
+                def step_hag():
+                    h.forward(x, op, y=y, argmax=a)
+                    h.backward(gy, op, argmax=a, gx=gx)
+
+                def step_naive():
+                    h.naive_forward(x, op, y=y, argmax=a)
+                    h.naive_backward(gy, op, argmax=a, gx=gx)
+
+                ms_h = time_steps(torch, step_hag, steps, warmup)
+                ms_n = time_steps(torch, step_naive, steps, warmup)
+                red = st["aggr_naive"] / max(st["aggr_hag"], 1)
+                log(f"[bench] {cap:8d} {d:6d}  {op:4s} {ms_h:8.3f}  {ms_n:8.3f}  {ms_n / ms_h:6.3f}x  {red:6.3f}x")
+                print(json.dumps({"workload": "config5:dcsbm232965_sweep", "capacity": cap, "feature_dim": d, "op": op,
+                                  "ms_per_step": ms_h, "naive_ms_per_step": ms_n, "speedup_vs_naive": ms_n / ms_h,
+                                  "value": 2.0 * st["e"] * d / (ms_h * 1e-3), "unit": "feature-elems/s",
+                                  "aggregation_reduction": red, "levels": st["levels"], "stages": st["stages"]}),
+                      flush=True)
+        del x, gy, y, gx, am
+        torch.cuda.empty_cache()
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload")
+    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload; 5 runs the capacity x width x op sweep")
     ap.add_argument("--op", default="sum", choices=["sum", "mean", "max", "gcn"])
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
@@ -170,6 +211,9 @@ def main():
     binding.lib()
     torch.cuda.set_device(0)
     cfg = args.config
+    if cfg == 5:
+        sweep_config5(torch, synth, workloads, max(min(args.steps, 10), 3), 2)
+        return
     rowptr, col, h, d = build_workload(cfg, None if args.capacity < 0 else args.capacity, workloads, synth)
     if args.d:
         d = args.d
