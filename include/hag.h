@@ -83,8 +83,8 @@ typedef struct hag_stats {
     int64_t max_degree;   /* largest |N(v)| */
     int64_t max_hag_degree; /* largest |Nhat_v| */
     int64_t stages;       /* kernel launches the aggregation nodes take (runs of fused levels) */
-    int64_t components;   /* connected components, if the graph is a batch of small graphs with contiguous
-                             ids that the one-launch component-local pass can serve; else 0 */
+    int64_t components;   /* number of contiguous id ranges that no edge crosses, if the graph is a batch of
+                             small graphs that the one-launch component-local pass can serve; else 0 */
 } hag_stats_t;
 
 /* ---------------------------------------------------------------- host ---- */

@@ -108,8 +108,7 @@ __device__ __forceinline__ Item load_item(const Item *p) {
 // One step of the reduction: UNR neighbour rows with ids idx[0..UNR) (all valid when !TAIL;
 // idx < 0 = nothing when TAIL) for the four features at element offset cb of a row.
 // The gathered matrices are addressed as base + 32-bit byte offset when OFF32 (both matrices
-// below 4 GiB), which costs one multiply-add per row instead of 64-bit pointer arithmetic;
-// at cache-hit rates this loop is bound by instruction issue, so every instruction counts.
+// below 4 GiB), which costs one multiply-add per row instead of 64-bit pointer arithmetic.
 template <typename T, int RED, int UNR, bool OFF32, bool TAIL>
 __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&idx)[UNR], int cb,
                                             typename V4<T>::type &acc, int4 &acc_id) {

@@ -555,8 +555,8 @@ int64_t long_items(const Plan &p, int k, int64_t threshold) {
 // ------------------------------------------------------------------------------------------
 // finalisation: levels, level-ordered forward form, transposes, schedules, statistics
 // ------------------------------------------------------------------------------------------
-// Detect a batch of small graphs: every connected component of the input graph occupies a
-// contiguous id range and is small.  Aggregation nodes never cross components (their inputs
+// Detect a batch of small graphs: the node ids split into many small contiguous ranges that no
+// edge crosses.  Aggregation nodes never cross components (their inputs
 // co-occur in some list, hence lie in one component).  Fills h->comp or leaves it disabled.
 static void build_components(hag_handle *h) {
     Components &c = h->comp;
@@ -574,17 +574,16 @@ static void build_components(hag_handle *h) {
             int32_t ra = find((int32_t)v), rb = find(h->g.col[i]);
             if (ra != rb) parent[std::max(ra, rb)] = std::min(ra, rb);   // root = smallest id
         }
-    // contiguity: walking ids upwards, the root may only change to the current id
+    // blocks: the finest cut of 0..n-1 into contiguous ranges that no edge crosses (a block is one
+    // connected component or several interleaved ones)
+    std::vector<int32_t> last_of(n, -1);        // largest id of the component rooted at r
+    for (int64_t v = 0; v < n; ++v) last_of[find((int32_t)v)] = (int32_t)v;
     std::vector<int32_t> comp_of(n + a);
     c.node_ptr.clear();
-    int32_t cur = -1;
+    int32_t block_end = -1;
     for (int64_t v = 0; v < n; ++v) {
-        int32_t r = find((int32_t)v);
-        if (r != cur) {
-            if (r != v) return;                 // an older component resumes: ids not contiguous
-            cur = r;
-            c.node_ptr.push_back((int32_t)v);
-        }
+        if (v > block_end) c.node_ptr.push_back((int32_t)v);
+        block_end = std::max(block_end, last_of[find((int32_t)v)]);
         comp_of[v] = (int32_t)c.node_ptr.size() - 1;
     }
     c.node_ptr.push_back((int32_t)n);

@@ -147,6 +147,7 @@ def test_component_local_pass_on_graph_batches(B, d, monkeypatch):
     assert rowptr.size - 1 >= 1024
     h = B.hag_search_batched(rowptr, col, gp, 0.25)
     assert h.stats()["a"] > 100 and h.stats()["levels"] >= 2
+    assert h.stats()["components"] >= 64            # the component-local pass is the one that runs
     run_all_ops(B, h, rowptr, col, d, seed=63 + d)
     # the same handle through the generic kernels must agree bit for bit on int32
     monkeypatch.setenv("HAG_COMPONENT", "0")

@@ -186,6 +186,10 @@ def test_stage_fusion_and_component_detection(monkeypatch):
     st = h.stats()
     assert 1 <= st["stages"] <= st["levels"] and st["components"] == 100
     assert oracle.cover_check(rowptr, col, oracle_view(h)) == 0
+    # graphs that are not connected still give contiguous ranges: at most one range per component
+    rp, cl, gq = synth.er_batch(200, 9, 0.25, seed=15)
+    hb = B.hag_search_batched(rp, cl, gq, 0.25)
+    assert 200 <= hb.stats()["components"] < rp.size - 1
     monkeypatch.setenv("HAG_STAGE_EXTRA_ROWS", "-1000000")
     assert B.hag_search_batched(rowptr, col, gp, 0.25).stats()["stages"] == st["levels"]
     monkeypatch.delenv("HAG_STAGE_EXTRA_ROWS")
