@@ -36,11 +36,12 @@ def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def build_workload(cfg: int, capacity, workloads, synth):
+def build_workload(cfg: int, capacity, workloads, synth, device_search=False):
     t0 = time.time()
     rowptr, col, graph_ptr = synth.graph_for_config(cfg)
     log(f"[bench] config {cfg}: graph generated in {time.time() - t0:.1f}s")
-    h = workloads.build_hag(cfg, rowptr, col, graph_ptr, capacity, log=lambda m: log("[bench] " + m))
+    h = workloads.build_hag(cfg, rowptr, col, graph_ptr, capacity, log=lambda m: log("[bench] " + m),
+                            device_search=device_search)
     return rowptr, col, h, workloads.FEATURE_DIM[cfg]
 
 
@@ -192,6 +193,9 @@ def main():
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--device-search", action="store_true",
+                    help="build the HAG with hag_search + HAG_SEARCH_DEVICE (pair counting on the GPU) instead of "
+                         "the host search / the cached merge list; the search time is logged to stderr")
     ap.add_argument("--gcn-epoch", action="store_true",
                     help="also time a 2-layer GCN epoch (16 hidden dims, SoftMax) around the aggregation")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -214,7 +218,8 @@ def main():
     if cfg == 5:
         sweep_config5(torch, synth, workloads, max(min(args.steps, 10), 3), 2)
         return
-    rowptr, col, h, d = build_workload(cfg, None if args.capacity < 0 else args.capacity, workloads, synth)
+    rowptr, col, h, d = build_workload(cfg, None if args.capacity < 0 else args.capacity, workloads, synth,
+                                       device_search=args.device_search)
     if args.d:
         d = args.d
     op = args.op

@@ -66,7 +66,13 @@ enum {
     HAG_SEARCH_CANONICAL = 1, /* among pairs of maximal redundancy take the lexicographically
                                  smallest (smaller id, larger id), which makes the result unique.
                                  The search always does this; the flag is accepted and ignored. */
-    HAG_SEARCH_DEDUP = 2      /* drop duplicate neighbours instead of rejecting them */
+    HAG_SEARCH_DEDUP = 2,     /* drop duplicate neighbours instead of rejecting them */
+    HAG_SEARCH_DEVICE = 4     /* hag_search only: count co-occurrences (Redundancy of Algorithm 3) on the
+                                 current HIP device instead of on the host threads.  The result is the
+                                 same HAG, merge for merge.  The call allocates device memory of about
+                                 12 bytes per edge + 128 bytes per (node + capacity) and pinned host
+                                 memory of 4 bytes per edge for its duration, uses a stream of its own and
+                                 returns when the search is done; HAG_EHIP if there is no device. */
 };
 
 typedef struct hag_stats {

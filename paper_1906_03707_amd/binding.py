@@ -19,7 +19,7 @@ LIB_PATH = os.environ.get("HAG_LIB", os.path.join(_HERE, "libhag.so"))
 HAG_SUM, HAG_MEAN, HAG_MAX, HAG_GCN = 0, 1, 2, 3
 HAG_F32, HAG_I32 = 0, 1
 HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE = 0, -1, -2, -3, -4
-HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP = 1, 2
+HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP, HAG_SEARCH_DEVICE = 1, 2, 4
 HAG_PHASE_LEVELS, HAG_PHASE_GATHER, HAG_PHASE_FOLD, HAG_PHASE_ALL = 1, 2, 4, 7
 OPS = {"sum": HAG_SUM, "mean": HAG_MEAN, "max": HAG_MAX, "gcn": HAG_GCN}
 

@@ -7,7 +7,7 @@ import subprocess
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libhag.so")
-SOURCES = [os.path.join(HERE, "csrc", "hag_host.cpp"), os.path.join(HERE, "csrc", "hag_device.hip")]
+SOURCES = [os.path.join(HERE, "csrc", f) for f in ("hag_host.cpp", "hag_device.hip", "hag_search_device.hip")]
 HEADERS = [os.path.join(HERE, "csrc", "hag_internal.hpp"), os.path.join(ROOT, "include", "hag.h")]
 
 

@@ -122,8 +122,10 @@ struct Builder {
     // members in creation order (whose creation redundancies are non-increasing).  A sweep
     // that only cares about partners able to reach a threshold can then stop early.
     std::vector<int32_t> prio, norig;
+    unsigned threads = 1;
 
-    void init(const Csr &graph, bool order_by_priority = false, unsigned threads = 1) {
+    void init(const Csr &graph, bool order_by_priority = false, unsigned threads_ = 1) {
+        threads = threads_;
         g = &graph;
         n = (int64_t)graph.ptr.size() - 1;
         nb = graph.col;
@@ -174,7 +176,7 @@ struct Builder {
         scratch.clear();
         int32_t r = intersect(p, q, &scratch);
         int32_t w = (int32_t)(n + a());
-        for (int32_t u : scratch) {
+        auto rewrite = [&](int32_t u) {
             int32_t *l = nb.data() + g->ptr[u];
             int32_t k = 0, L = len[u];
             for (int32_t i = 0; i < L; ++i)
@@ -182,6 +184,15 @@ struct Builder {
             l[k++] = w;
             len[u] = k;
             norig[u] -= (p < n) + (q < n);
+        };
+        if (threads > 1 && r >= 1024) {
+            // the lists are independent; worth the threads only for the large merges of a big graph
+            const int64_t chunk = 64, chunks = (r + chunk - 1) / chunk;
+            parallel_for(chunks, threads, [&](int64_t c, unsigned) {
+                for (int64_t i = c * chunk; i < std::min<int64_t>(r, (c + 1) * chunk); ++i) rewrite(scratch[i]);
+            });
+        } else {
+            for (int32_t u : scratch) rewrite(u);
         }
         remove_from_out(p, scratch);
         remove_from_out(q, scratch);
@@ -236,15 +247,21 @@ struct Searcher {
     // HAG_SEARCH_CHECKPOINT=<file>); long searches can then be resumed with hag_from_merges
     int64_t progress_every = 0;
     std::chrono::steady_clock::time_point t_start;
-    int64_t n_sweep = 0, n_refresh = 0;
+    int64_t n_sweep = 0, n_batch = 0, n_refresh = 0;
     double t_sweep = 0, t_refresh = 0, t_merge = 0;
     int64_t sweep_work = 0;
     std::vector<std::vector<int32_t>> cnt, touched;
+    std::vector<std::vector<Found>> found_host;
+    // optional: counting on the GPU (HAG_SEARCH_DEVICE); the host lists stay authoritative
+    DeviceCounter *dev = nullptr;
+    std::string dev_err;
+    std::vector<std::vector<Found>> found_dev;
+    std::vector<char> overflow_dev;
 
     void report_progress() {
         double el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
-        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps (%.1f s), %lld refreshes (%.1f s), merges %.1f s\n",
-                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, t_sweep, (long long)n_refresh, t_refresh, t_merge);
+        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps in %lld batches (%.1f s), %lld refreshes (%.1f s), merges %.1f s\n",
+                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, (long long)n_batch, t_sweep, (long long)n_refresh, t_refresh, t_merge);
         if (const char *path = std::getenv("HAG_SEARCH_CHECKPOINT")) {
             std::string tmp = std::string(path) + ".tmp";
             if (FILE *f = std::fopen(tmp.c_str(), "wb")) {
@@ -271,11 +288,13 @@ struct Searcher {
     // reaches theta = half of x's key.  Counts >= theta are exact and complete; if none
     // reaches theta, theta-1 becomes the bound for everything and x is swept again later with
     // a lower threshold.
+    int32_t theta_of(int32_t x) const { return std::max(2, (key[x] + 1) / 2); }
+
     void sweep(int32_t x, unsigned t) {
         auto &c = cnt[t];
         auto &tl = touched[t];
         tl.clear();
-        const int32_t theta = std::max(2, (key[x] + 1) / 2);
+        const int32_t theta = theta_of(x);
         const int32_t *o = b.out_ptr(x);
         const int32_t ol = b.out_len(x);
         const int32_t n = (int32_t)b.n;
@@ -298,14 +317,23 @@ struct Searcher {
                 if (c[y]++ == 0) tl.push_back(y);
             }
         }
+        auto &fd = found_host[t];
+        fd.clear();
+        for (int32_t y : tl) {
+            if (c[y] >= theta) fd.push_back(Found{y, c[y]});
+            c[y] = 0;
+        }
+        finish_sweep(x, theta, fd);
+    }
+
+    // `found` = every (y, count) with count >= theta: rebuild x's candidate list and tail from it
+    void finish_sweep(int32_t x, int32_t theta, const std::vector<Found> &found) {
         auto &lst = cand[x];
         lst.clear();
         int32_t below = theta - 1;   // bound for everything not listed
-        for (int32_t y : tl) {
-            int32_t v = c[y];
-            c[y] = 0;
-            if (y == x || !mergeable(y)) continue;
-            if (v >= theta) lst.push_back(Cand{y, v, iter});
+        for (const Found &f : found) {
+            if (f.y == x || !mergeable(f.y)) continue;
+            if (f.c >= theta) lst.push_back(Cand{f.y, f.c, iter});
         }
         std::sort(lst.begin(), lst.end(), better);
         if ((int)lst.size() > kKeep) {
@@ -322,6 +350,18 @@ struct Searcher {
         }
         tail[x] = below;
         rekey(x);
+    }
+
+    // the same for a batch of nodes, counted on the device
+    bool sweep_on_device(const std::vector<int32_t> &xs) {
+        std::vector<int32_t> theta(xs.size());
+        for (size_t i = 0; i < xs.size(); ++i) theta[i] = theta_of(xs[i]);
+        if (!counter_sweep(dev, (int)xs.size(), xs.data(), theta.data(), found_dev, overflow_dev, dev_err)) return false;
+        for (size_t i = 0; i < xs.size(); ++i) {
+            if (overflow_dev[i]) sweep(xs[i], 0);
+            else finish_sweep(xs[i], theta[i], found_dev[i]);
+        }
+        return true;
     }
 
     // Make x's best entry exact, or report that x needs a sweep.  Returns 1 if the best entry
@@ -358,7 +398,8 @@ struct Searcher {
         return 0;
     }
 
-    void run() {
+    // false only if the device mirror failed (dev_err says why)
+    bool run() {
         int64_t n = b.n, m = n + capacity;
         key.assign(m, 0); tail.assign(m, 0); version.assign(m, 0);
         mod_stamp.assign(m, 0); born.assign(m, 0);
@@ -369,6 +410,8 @@ struct Searcher {
         t_start = std::chrono::steady_clock::now();
         cnt.assign(threads, std::vector<int32_t>(m, 0));
         touched.assign(threads, {});
+        found_host.assign(threads, {});
+        const size_t batch_max = dev ? (size_t)counter_max_batch(dev) : (size_t)threads;
         for (int64_t x = 0; x < n; ++x) { tail[x] = b.olen[x]; key[x] = tail[x]; push((int32_t)x); }
         std::vector<int32_t> batch, dirty;
         while (b.a() < capacity) {
@@ -386,7 +429,7 @@ struct Searcher {
                 // x needs a sweep; sweep it together with the next few exhausted nodes
                 batch.assign(1, x);
                 dirty.clear();
-                while (!heap.empty() && batch.size() < threads) {
+                while (!heap.empty() && batch.size() < batch_max) {
                     auto [k2, negx2, ver2] = heap.top();
                     int32_t x2 = -negx2;
                     if (ver2 != version[x2]) { heap.pop(); continue; }
@@ -400,15 +443,21 @@ struct Searcher {
                     else heap.emplace(key[z], -z, version[z]);
                 }
                 auto t1 = std::chrono::steady_clock::now();
-                parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { sweep(dirty[i], t); });
+                if (dev) {
+                    if (!sweep_on_device(dirty)) return false;
+                } else {
+                    parallel_for((int64_t)dirty.size(), threads, [&](int64_t i, unsigned t) { sweep(dirty[i], t); });
+                }
                 t_sweep += std::chrono::duration<double>(std::chrono::steady_clock::now() - t1).count();
                 n_sweep += (int64_t)dirty.size();
+                n_batch += dirty.empty() ? 0 : 1;
                 for (int32_t z : dirty) push(z);
             }
             if (chosen < 0 || key[chosen] < 2) break;
             int32_t p = chosen, q = cand[chosen][0].y;
             auto t2 = std::chrono::steady_clock::now();
-            b.apply_merge(p, q);
+            const int32_t r = b.apply_merge(p, q);
+            if (dev && !counter_merge(dev, p, q, (int32_t)(b.n + b.a() - 1), b.scratch.data(), r, dev_err)) return false;
             t_merge += std::chrono::duration<double>(std::chrono::steady_clock::now() - t2).count();
             if (progress_every > 0 && b.a() % progress_every == 0) report_progress();
             int32_t w = (int32_t)(b.n + b.a() - 1);
@@ -427,6 +476,7 @@ struct Searcher {
             rekey(w);
             push(w);
         }
+        return true;
     }
 };
 
@@ -856,7 +906,17 @@ int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t cap
         s.capacity = capacity;
         s.max_depth = max_depth;
         s.b.init(h->g, true, host_threads());
-        if (capacity > 0) s.run();
+        if (capacity > 0 && (flags & HAG_SEARCH_DEVICE) && n > 0) {
+            const Builder &b = s.b;
+            CounterInit in{n, (int64_t)b.nb.size(), capacity, h->g.ptr.data(), b.nb.data(), b.len.data(),
+                           b.norig.data(), b.prio.data(), b.gt.ptr.data(), b.gt.col.data(), b.olen.data()};
+            s.dev = counter_create(in, s.dev_err);
+            if (!s.dev) return fail(HAG_EHIP, s.dev_err);
+        }
+        const bool ok = capacity > 0 ? s.run() : true;
+        counter_destroy(s.dev);
+        s.dev = nullptr;
+        if (!ok) return fail(HAG_EHIP, s.dev_err);
         rc = finalize_from_builder(h.get(), s.b);
         if (rc) return rc;
         *out = h.release();

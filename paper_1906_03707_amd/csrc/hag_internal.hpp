@@ -71,6 +71,27 @@ struct Components {
 
 void set_error(const std::string &msg);
 
+// Pair counting of the search on the GPU (hag_search_device.hip): a device mirror of the lists
+// of Algorithm 3 that is rewritten merge by merge and answers batches of count requests.
+struct CounterInit {
+    int64_t n, e, capacity;
+    const int64_t *ptr;                        // [n+1] list offsets
+    const int32_t *nb, *len, *norig, *prio;    // lists (original members by descending prio first), lengths
+    const int64_t *out_ptr;                    // [n+1] out-lists of the original nodes ...
+    const int32_t *out_col, *olen;             // ... their entries (ascending) and current lengths
+};
+struct Found { int32_t y, c; };
+struct DeviceCounter;
+DeviceCounter *counter_create(const CounterInit &in, std::string &err);   // nullptr + err on failure
+void counter_destroy(DeviceCounter *d);
+int counter_max_batch(const DeviceCounter *d);
+// lists rows[0..r) lose p and q and gain the new node w (asynchronous; rows is copied)
+bool counter_merge(DeviceCounter *d, int32_t p, int32_t q, int32_t w, const int32_t *rows, int32_t r, std::string &err);
+// for each request s: found[s] = every (y, count) with count >= theta[s] among the nodes whose static
+// bound reaches theta[s], in no particular order; overflow[s] set instead if there are too many
+bool counter_sweep(DeviceCounter *d, int nb, const int32_t *x, const int32_t *theta,
+                   std::vector<std::vector<Found>> &found, std::vector<char> &overflow, std::string &err);
+
 }  // namespace hag
 
 struct hag_handle {

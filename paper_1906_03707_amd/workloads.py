@@ -2,7 +2,7 @@
 
 A HAG depends only on the graph, the capacity and the aggregate type, so it is searched once and
 reused (the paper's own remark on reusability).  For the 114M-edge graph of configs 3 and 5 the
-search takes about an hour of CPU time, so its merge list (canonical greedy, capacity |V|/2; every
+search takes about an hour of CPU time (a few minutes with HAG_SEARCH_DEVICE), so its merge list (canonical greedy, capacity |V|/2; every
 smaller capacity is a prefix) is stored under data/ by `python -m paper_1906_03707_amd.workloads
 --make-cache 3` and replayed with hag_from_merges.  A cached list is only trusted after the replay
 has validated it (every merge must rewrite at least one list) and the tests re-check Theorem 2.
@@ -34,8 +34,10 @@ def load_cached_merges(cfg: int):
     return z["left"], z["right"]
 
 
-def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None):
-    """HAG of BASELINE config `cfg` (capacity |V|/4 unless given), from the cache when one exists."""
+def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None, device_search=False):
+    """HAG of BASELINE config `cfg` (capacity |V|/4 unless given), from the cache when one exists.
+
+    device_search=True ignores the cache and runs Algorithm 3 with the pair counting on the GPU."""
     n = rowptr.size - 1
     cap = n // 4 if capacity is None else int(capacity)
     t0 = time.time()
@@ -43,8 +45,11 @@ def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None):
         h = binding.hag_search_batched(rowptr, col, graph_ptr, 0.25)
         how = "hag_search_batched"
     else:
-        cached = load_cached_merges(cfg) if cap > 0 else None
-        if cached is not None and cached[0].size >= cap:
+        cached = load_cached_merges(cfg) if cap > 0 and not device_search else None
+        if device_search:
+            h = binding.hag_search(rowptr, col, cap, flags=binding.HAG_SEARCH_DEVICE)
+            how = "hag_search (HAG_SEARCH_DEVICE)"
+        elif cached is not None and cached[0].size >= cap:
             h = binding.hag_from_merges(rowptr, col, cached[0][:cap], cached[1][:cap])
             how = "hag_from_merges (cached canonical merge list)"
         else:

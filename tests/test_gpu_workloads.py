@@ -209,6 +209,21 @@ def test_config3_structure(request, B, big_graph, big_hags):
 
 
 @pytest.mark.timeout(900)
+def test_config3_cached_merges_are_what_the_search_finds(request, B, big_graph):
+    """The stored merge list is the search's own output: re-derive its head on this graph (GPU-counted
+    Algorithm 3; the head holds the merges of redundancy in the thousands, which rewrite the most lists)."""
+    from paper_1906_03707_amd import workloads
+    rowptr, col = big_graph
+    k = 1500
+    progress(request, f"hag_search (pair counting on the device), capacity {k} ...")
+    h = B.hag_search(rowptr, col, k, flags=B.HAG_SEARCH_DEVICE)
+    left, right, red = h.get_merges()
+    cl, cr = workloads.load_cached_merges(3)
+    assert left.size == k and np.array_equal(left, cl[:k]) and np.array_equal(right, cr[:k])
+    progress(request, f"first {k} merges equal the cached list (redundancy {red[0]}..{red[-1]})")
+
+
+@pytest.mark.timeout(900)
 def test_config3_dcsbm_sum(request, B, big_graph, big_hags):
     rowptr, col = big_graph
     n = rowptr.size - 1

@@ -158,6 +158,19 @@ def test_validation_errors():
     assert rc == B.HAG_ESTATE and b"hag_upload" in B.lib().hag_last_error()
 
 
+def test_device_counted_search_needs_a_device():
+    # without a GPU the flag must fail loudly, not fall back to the host threads
+    torch = pytest.importorskip("torch")
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is visible: the flag works (covered by the gpu tests)")
+    rowptr, col = synth.random_graph(30, 0.4, seed=6)
+    with pytest.raises(B.HagError) as e:
+        B.hag_search(rowptr, col, 10, flags=B.HAG_SEARCH_DEVICE)
+    assert e.value.code == B.HAG_EHIP
+    # capacity 0 needs no counting at all
+    assert B.hag_search(rowptr, col, 0, flags=B.HAG_SEARCH_DEVICE).stats()["a"] == 0
+
+
 def test_empty_and_isolated():
     h = B.hag_search(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4)
     assert h.stats()["n"] == 0 and h.stats()["a"] == 0
