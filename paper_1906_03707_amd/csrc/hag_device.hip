@@ -425,42 +425,80 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     }
     __syncthreads();
 
+    // first aggregation row of every stage (rows are sorted by stage): stage st is
+    // rows [st_begin[st-1], st_begin[st])
+    __shared__ int st_begin[256];
+    for (int t = tid; t <= n_stages; t += kBlock) {
+        int lo = 0, hi = na;
+        while (lo < hi) {
+            const int mid = (lo + hi) >> 1;
+            if (l_agg_stage[mid] <= t) lo = mid + 1; else hi = mid;
+        }
+        st_begin[t] = lo;
+    }
+    __syncthreads();
+
     // Aggregation rows, stage by stage (forward: first stage first; transposed pass: last
-    // first).  A component has few of them, so a whole wavefront takes one row: its sub-groups
-    // walk interleaved slices of the list and combine with cross-lane adds.
+    // first).  A stage with many rows gives each sub-group a row, like the output rows below.
+    // A stage with few rows gives a whole wavefront to a row: its sub-groups walk interleaved
+    // slices of the list and combine with cross-lane adds.
     for (int step = 1; step <= n_stages; ++step) {
         const int st = A.reverse ? n_stages + 1 - step : step;
-        for (int jb = 0; jb < na; jb += NW) {
-            const int j = jb + wave;
-            const bool has = j < na && l_agg_stage[min(j, na - 1)] == st;
-            const int beg = has ? l_agg_ptr[j] : 0;
-            const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
-            int per = (cnt + SG - 1) / SG;
-            per = (per + 3) & ~3;
-            const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
-            for (int kb = 0; kb < q; kb += LPR) {
-                const int k = min(kb + sl, q - 1);
-                V acc{};
-                int4 acc_id = make_int4(-1, -1, -1, -1);
-                lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k,
-                                        acc, acc_id);
+        const int r0 = st_begin[st - 1], r1 = st_begin[st];
+        if (r1 - r0 > 2 * NW) {
+            for (int jb = r0; jb < r1; jb += NSG) {
+                const int j = jb + sg;
+                const bool has = j < r1;
+                const int beg = has ? l_agg_ptr[j] : 0;
+                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
+                int maxcnt = cnt;
 #pragma unroll
-                for (int off = LPR; off < kWave; off <<= 1) {
-                    V o;
-                    o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
-                    o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
-                    if (RED == R_MAX) {
-                        int4 oi;
-                        oi.x = __shfl_xor(acc_id.x, off); oi.y = __shfl_xor(acc_id.y, off);
-                        oi.z = __shfl_xor(acc_id.z, off); oi.w = __shfl_xor(acc_id.w, off);
-                        max4(acc, acc_id, o, oi);
-                    } else {
-                        add4(acc, o);
+                for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
+                for (int kb = 0; kb < q; kb += LPR) {
+                    const int k = min(kb + sl, q - 1);
+                    V acc{};
+                    int4 acc_id = make_int4(-1, -1, -1, -1);
+                    lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc,
+                                            acc_id);
+                    if (has && kb + sl < q) {
+                        *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+                        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
                     }
                 }
-                if (has && kb + sl < q && sgw == 0) {
-                    *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-                    if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
+            }
+        } else {
+            for (int jb = r0; jb < r1; jb += NW) {
+                const int j = jb + wave;
+                const bool has = j < r1;
+                const int beg = has ? l_agg_ptr[j] : 0;
+                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
+                int per = (cnt + SG - 1) / SG;
+                per = (per + 3) & ~3;
+                const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
+                for (int kb = 0; kb < q; kb += LPR) {
+                    const int k = min(kb + sl, q - 1);
+                    V acc{};
+                    int4 acc_id = make_int4(-1, -1, -1, -1);
+                    lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per),
+                                            sl, k, acc, acc_id);
+#pragma unroll
+                    for (int off = LPR; off < kWave; off <<= 1) {
+                        V o;
+                        o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
+                        o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
+                        if (RED == R_MAX) {
+                            int4 oi;
+                            oi.x = __shfl_xor(acc_id.x, off); oi.y = __shfl_xor(acc_id.y, off);
+                            oi.z = __shfl_xor(acc_id.z, off); oi.w = __shfl_xor(acc_id.w, off);
+                            max4(acc, acc_id, o, oi);
+                        } else {
+                            add4(acc, o);
+                        }
+                    }
+                    if (has && kb + sl < q && sgw == 0) {
+                        *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+                        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
+                    }
                 }
             }
         }
@@ -675,7 +713,7 @@ static CompLayout component_layout(const hag_handle *h, bool naive, bool backwar
         bytes += 2 * ((size_t)c.max_agg + 1) * 4 + entries * 2;
     }
     bytes = (bytes + 15) & ~(size_t)15;
-    if (bytes <= 64 * 1024) L.total = bytes;
+    if (bytes <= 63 * 1024) L.total = bytes;   // the kernel adds 1 KB of static LDS; 64 KB per workgroup
     return L;
 }
 

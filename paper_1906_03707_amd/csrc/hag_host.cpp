@@ -655,22 +655,44 @@ static void build_components(hag_handle *h) {
     if (c.max_nodes + c.max_agg > 4096) return;  // local ids are 16 bit and must fit LDS anyway
     // local id of every unified id
     std::vector<int32_t> local(n + a), fill(c.agg_ptr.begin(), c.agg_ptr.end() - 1);
+    // Inside LDS a barrier is cheap and every row read costs the same, so the component pass
+    // keeps the paper's two-input form: one stage per level, no fusion of levels.
     c.stage.resize(a);
     c.n_stages.assign(c.count, 0);
-    if (h->stages > 255) return;
+    if (h->levels > 255) return;
     std::vector<int32_t> slot_of(a);             // component-major index of aggregation node i
     for (int64_t v = 0; v < n; ++v) local[v] = (int32_t)v - c.node_ptr[comp_of[v]];
-    for (int32_t st = 0; st < h->stages; ++st)
-        for (int32_t i = h->stage_ptr[st]; i < h->stage_ptr[st + 1]; ++i) {   // level order: stages ascending
+    for (int32_t lv = 0; lv < h->levels; ++lv)
+        for (int32_t i = h->level_ptr[lv]; i < h->level_ptr[lv + 1]; ++i) {
             int32_t k = comp_of[n + i];
             int32_t slot = fill[k]++;
             slot_of[i] = slot;
             local[n + i] = (c.node_ptr[k + 1] - c.node_ptr[k]) + (slot - c.agg_ptr[k]);
-            c.stage[slot] = (uint8_t)(st + 1);
-            c.n_stages[k] = std::max(c.n_stages[k], (uint8_t)(st + 1));
+            c.stage[slot] = (uint8_t)(lv + 1);
+            c.n_stages[k] = std::max(c.n_stages[k], (uint8_t)(lv + 1));
         }
-    if (h->hf.col.size() >= (size_t)INT32_MAX || h->ht.col.size() >= (size_t)INT32_MAX) return;
-    // rows [row_begin, row_end) of src in the given order of rows, ids made local
+    if (h->hf.col.size() + 2 * (size_t)a >= (size_t)INT32_MAX) return;
+    // the two inputs of every aggregation node, and the consumers of every node (transposed HAG)
+    Csr pairs, consumers;
+    pairs.ptr.resize(a + 1);
+    pairs.col.resize(2 * (size_t)a);
+    for (int64_t i = 0; i <= a; ++i) pairs.ptr[i] = 2 * i;
+    for (int64_t i = 0; i < a; ++i) { pairs.col[2 * i] = h->left[i]; pairs.col[2 * i + 1] = h->right[i]; }
+    consumers.ptr.assign(n + a + 1, 0);
+    for (int32_t x : h->hf.col) consumers.ptr[x + 1]++;
+    for (int32_t x : pairs.col) consumers.ptr[x + 1]++;
+    for (int64_t x = 0; x < n + a; ++x) consumers.ptr[x + 1] += consumers.ptr[x];
+    consumers.col.resize((size_t)consumers.ptr[n + a]);
+    {
+        std::vector<int64_t> at(consumers.ptr.begin(), consumers.ptr.end() - 1);
+        for (int64_t v = 0; v < n; ++v)
+            for (int64_t i = h->hf.ptr[v]; i < h->hf.ptr[v + 1]; ++i) consumers.col[at[h->hf.col[i]]++] = (int32_t)v;
+        for (int64_t i = 0; i < a; ++i) {
+            consumers.col[at[h->left[i]]++] = (int32_t)(n + i);
+            consumers.col[at[h->right[i]]++] = (int32_t)(n + i);
+        }
+    }
+    // rows of src in the given order of rows, ids made local
     auto localise = [&](const Csr &src, const std::vector<int64_t> &rows, LocalLists &dst) {
         dst.ptr.assign(1, 0);
         dst.col.clear();
@@ -679,13 +701,13 @@ static void build_components(hag_handle *h) {
             dst.ptr.push_back((int32_t)dst.col.size());
         }
     };
-    std::vector<int64_t> orig_rows(n), agg_rows_he(a), agg_rows_ht(a);
+    std::vector<int64_t> orig_rows(n), agg_rows(a), agg_rows_t(a);
     std::iota(orig_rows.begin(), orig_rows.end(), 0);
-    for (int64_t i = 0; i < a; ++i) { agg_rows_he[slot_of[i]] = i; agg_rows_ht[slot_of[i]] = n + i; }
+    for (int64_t i = 0; i < a; ++i) { agg_rows[slot_of[i]] = i; agg_rows_t[slot_of[i]] = n + i; }
     localise(h->hf, orig_rows, c.fwd);
-    localise(h->he, agg_rows_he, c.fwd_agg);
-    localise(h->ht, orig_rows, c.bwd_orig);
-    localise(h->ht, agg_rows_ht, c.bwd_agg);
+    localise(pairs, agg_rows, c.fwd_agg);
+    localise(consumers, orig_rows, c.bwd_orig);
+    localise(consumers, agg_rows_t, c.bwd_agg);
     localise(h->g, orig_rows, c.nfwd);
     localise(h->gt, orig_rows, c.nbwd);
     for (int32_t k = 0; k < c.count; ++k) {
