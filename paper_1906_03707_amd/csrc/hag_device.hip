@@ -13,6 +13,7 @@
 #include <cstdint>
 #include <cstdlib>
 #include <string>
+#include <type_traits>
 
 #include "hag_internal.hpp"
 
@@ -96,6 +97,39 @@ __device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi)
     max1(v.z, vi.z, w.z, wi.z); max1(v.w, vi.w, w.w, wi.w);
 }
 
+// (value, id) max where the id of an aggregation row (id >= split) stands for the winning
+// original id stored beside that row, and is only looked up when a tie makes it matter.
+// acc_id is an original id, or an aggregation id whose stored winner has not been needed yet.
+// Original ids of a list arrive in ascending order before any aggregation id, so a tie
+// between two original ids keeps the accumulator.
+template <typename S>
+__device__ __forceinline__ void settle_tie1(S v, int &vi, S w, int wi, const int32_t *id_hi, int split, size_t d,
+                                            int col) {
+    if (vi >= 0 && w == v) {
+        const int other = id_hi[(size_t)(wi - split) * d + col];
+        const int mine = vi < split ? vi : id_hi[(size_t)(vi - split) * d + col];
+        vi = min(mine, other);
+    }
+}
+template <typename V>
+__device__ __forceinline__ void lazy_max4(V &v, int4 &vi, const V &w, int wi, const int32_t *id_hi, int split,
+                                          size_t d, int cb) {
+    if (wi >= split && (w.x == v.x || w.y == v.y || w.z == v.z || w.w == v.w)) {   // rare
+        settle_tie1(v.x, vi.x, w.x, wi, id_hi, split, d, cb);
+        settle_tie1(v.y, vi.y, w.y, wi, id_hi, split, d, cb + 1);
+        settle_tie1(v.z, vi.z, w.z, wi, id_hi, split, d, cb + 2);
+        settle_tie1(v.w, vi.w, w.w, wi, id_hi, split, d, cb + 3);
+    }
+    max_first4(v, vi, w, wi);   // a tie keeps the accumulator, whose id is settled above
+}
+// replace aggregation ids left in acc_id by the original ids they stand for
+__device__ __forceinline__ void resolve_ids(int4 &vi, const int32_t *id_hi, int split, size_t d, int cb) {
+    if (vi.x >= split) vi.x = id_hi[(size_t)(vi.x - split) * d + cb];
+    if (vi.y >= split) vi.y = id_hi[(size_t)(vi.y - split) * d + cb + 1];
+    if (vi.z >= split) vi.z = id_hi[(size_t)(vi.z - split) * d + cb + 2];
+    if (vi.w >= split) vi.w = id_hi[(size_t)(vi.w - split) * d + cb + 3];
+}
+
 __device__ __forceinline__ Item load_item(const Item *p) {
     const int4 raw = *reinterpret_cast<const int4 *>(p);
     Item it;
@@ -109,7 +143,7 @@ __device__ __forceinline__ Item load_item(const Item *p) {
 // idx < 0 = nothing when TAIL) for the four features at element offset cb of a row.
 // The gathered matrices are addressed as base + 32-bit byte offset when OFF32 (both matrices
 // below 4 GiB), which costs one multiply-add per row instead of 64-bit pointer arithmetic.
-template <typename T, int RED, int UNR, bool OFF32, bool TAIL>
+template <typename T, int RED, int UNR, bool OFF32, bool TAIL, bool LAZY>
 __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&idx)[UNR], int cb,
                                             typename V4<T>::type &acc, int4 &acc_id) {
     using V = typename V4<T>::type;
@@ -160,6 +194,9 @@ __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&
             // id, so a tie keeps it and "greater than" is the whole test.
 #pragma unroll
             for (int k = 0; k < UNR; ++k) max_first4(acc, acc_id, val[k], idx[k]);
+        } else if (LAZY) {
+#pragma unroll
+            for (int k = 0; k < UNR; ++k) lazy_max4(acc, acc_id, val[k], idx[k], A.id_hi, A.split, d, cb);
         } else {
 #pragma unroll
             for (int k = 0; k < UNR; ++k) {
@@ -180,7 +217,7 @@ __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&
 // the wavefront masked off).  Column ids are read LPR at a time (coalesced) and handed round
 // inside the sub-group; UNR neighbour rows are requested before the first is consumed; full
 // groups of UNR ids take a path without any per-row predicate.
-template <typename T, int RED, int LPR, int UNR, bool OFF32>
+template <typename T, int RED, int LPR, int UNR, bool OFF32, bool LAZY>
 __device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg, int cnt, int sl, int cb,
                                             typename V4<T>::type &acc, int4 &acc_id) {
     for (int base = 0; base < cnt; base += LPR) {
@@ -192,13 +229,13 @@ __device__ __forceinline__ void reduce_rows(const GatherArgs<T> &A, int64_t beg,
             int idx[UNR];
 #pragma unroll
             for (int k = 0; k < UNR; ++k) idx[k] = __shfl(mine, j + k, LPR);
-            reduce_step<T, RED, UNR, OFF32, false>(A, idx, cb, acc, acc_id);
+            reduce_step<T, RED, UNR, OFF32, false, LAZY>(A, idx, cb, acc, acc_id);
         }
         if (j < here) {
             int idx[UNR];
 #pragma unroll
             for (int k = 0; k < UNR; ++k) idx[k] = __shfl(mine, j + k, LPR);
-            reduce_step<T, RED, UNR, OFF32, true>(A, idx, cb, acc, acc_id);
+            reduce_step<T, RED, UNR, OFF32, true, LAZY>(A, idx, cb, acc, acc_id);
         }
     }
 }
@@ -236,6 +273,10 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     constexpr int SG = kWave / LPR;       // sub-groups per wavefront
     constexpr int NSG = kBlock / LPR;     // sub-groups per workgroup
     constexpr int UNR = 4;
+    // Max over fp32 rows looks up the winner stored beside an aggregation row only on a tie
+    // (exact ties are rare in real-valued features).  int32 features tie all the time, and
+    // the fold of partial slots has ids beside every row, so both read them always.
+    constexpr bool LAZY = RED == R_MAX && std::is_same<T, float>::value && ROLE != G_FOLD;
     __shared__ V red_val[kBlock];
     __shared__ int4 red_id[RED == R_MAX ? kBlock : 1];
     const int lane = threadIdx.x & (kWave - 1);
@@ -255,8 +296,9 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
         int per = (it.cnt + NSG - 1) / NSG;
         per = (per + UNR - 1) / UNR * UNR;
         const int lo = min(it.cnt, sg * per), hi = min(it.cnt, lo + per);
-        if (A.off32) reduce_rows<T, RED, LPR, UNR, true>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
-        else reduce_rows<T, RED, LPR, UNR, false>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
+        if (A.off32) reduce_rows<T, RED, LPR, UNR, true, LAZY>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
+        else reduce_rows<T, RED, LPR, UNR, false, LAZY>(A, it.beg + lo, hi - lo, sl, cb, acc, acc_id);
+        if (LAZY) resolve_ids(acc_id, A.id_hi, A.split, (size_t)A.d, cb);
         red_val[threadIdx.x] = acc;
         if (RED == R_MAX) red_id[threadIdx.x] = acc_id;
         __syncthreads();
@@ -276,8 +318,9 @@ __global__ __launch_bounds__(kBlock) void gather_kernel(GatherArgs<T> A) {
     const bool has_item = local < p_items;
     Item it{0, 0, 0};
     if (has_item) it = load_item(A.items + p_begin + local);
-    if (A.off32) reduce_rows<T, RED, LPR, UNR, true>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
-    else reduce_rows<T, RED, LPR, UNR, false>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
+    if (A.off32) reduce_rows<T, RED, LPR, UNR, true, LAZY>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
+    else reduce_rows<T, RED, LPR, UNR, false, LAZY>(A, it.beg, it.cnt, sl, cb, acc, acc_id);
+    if (LAZY) resolve_ids(acc_id, A.id_hi, A.split, (size_t)A.d, cb);
     if (has_item && col_ok) store_result<T, RED>(A, it.row, cbase, acc, acc_id);
 }
 

@@ -272,6 +272,33 @@ def test_max_ties_bit_exact(B):
         assert_equal(am, am_ref, "tied max argmax")
 
 
+@pytest.mark.parametrize("knobs", [
+    {},
+    {"HAG_STAGE_EXTRA_ROWS": "-1000000"},                                                     # one launch per level
+    {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "16", "HAG_PART_SHARE_PCT": "0"},          # rows cut by source id
+    {"HAG_BLOCK_MAX": "48", "HAG_SUB_MAX": "24"},                                             # split rows, workgroup items
+])
+def test_max_ties_through_aggregation_rows(B, monkeypatch, knobs):
+    # fp32 max looks up the winner stored beside an aggregation row only when a tie needs it: ties
+    # between original rows and aggregation rows, and between aggregation rows, in every schedule
+    for k, v in knobs.items():
+        monkeypatch.setenv(k, v)
+    rowptr, col = synth.holme_kim(2500, 12, 0.6, seed=23)
+    n = rowptr.size - 1
+    h = B.hag_search(rowptr, col, n // 2).upload()
+    assert h.stats()["levels"] >= 2
+    rng = np.random.default_rng(24)
+    for d, levels_of_value in ((8, 2), (64, 4), (132, 50)):
+        x = rng.integers(0, levels_of_value, size=(n, d)).astype(np.float32)
+        y_ref, _, am_ref = oracle.naive_forward(rowptr, col, x, "max")
+        y, am = h.forward(dev(x), "max")
+        assert_equal(y, y_ref, f"values d={d}")
+        assert_equal(am, am_ref, f"argmax d={d}")
+        gy = synth.features_f32(n, d, 25)
+        gx_ref, gs = oracle.naive_backward(rowptr, col, gy, "max", am_ref)
+        assert_close(h.backward(dev(gy), "max", argmax=am), gx_ref, gs, f"backward d={d}")
+
+
 def test_empty_graph_and_edgeless_graph(B):
     h = B.hag_search(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4).upload()
     y = h.forward(torch.empty((0, 8), device="cuda"), "sum")
