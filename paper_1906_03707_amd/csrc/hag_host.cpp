@@ -150,13 +150,41 @@ struct Builder {
     int32_t out_len(int32_t x) const { return x < n ? olen[x] : (int32_t)out_agg[x - n].size(); }
     int32_t depth_of(int32_t x) const { return x < n ? 0 : depth[x - n]; }
 
+    // |out(p) ∩ out(q)|; the common entries go to dst if given.  The merge loop is written
+    // without data-dependent branches: which list advances is close to a coin flip.
     int32_t intersect(int32_t p, int32_t q, std::vector<int32_t> *dst) const {
         const int32_t *a_ = out_ptr(p), *b_ = out_ptr(q);
-        int32_t la = out_len(p), lb = out_len(q), i = 0, j = 0, c = 0;
+        const int32_t la = out_len(p), lb = out_len(q);
+        int32_t i = 0, j = 0, c = 0;
+        if (!dst && (la > 16 * lb || lb > 16 * la)) {
+            // very unequal lengths: look every entry of the short list up in the rest of the long one
+            const int32_t *s_ = la < lb ? a_ : b_, *l_ = la < lb ? b_ : a_;
+            const int32_t ls = std::min(la, lb), ll = std::max(la, lb);
+            const int32_t *from = l_, *end = l_ + ll;
+            for (int32_t k = 0; k < ls && from < end; ++k) {
+                from = std::lower_bound(from, end, s_[k]);
+                c += (from < end && *from == s_[k]);
+            }
+            return c;
+        }
+        if (dst) {
+            dst->resize((size_t)std::min(la, lb) + 1);
+            int32_t *o = dst->data();
+            while (i < la && j < lb) {
+                const int32_t x = a_[i], y = b_[j];
+                o[c] = x;
+                c += (x == y);
+                i += (x <= y);
+                j += (y <= x);
+            }
+            dst->resize((size_t)c);
+            return c;
+        }
         while (i < la && j < lb) {
-            if (a_[i] < b_[j]) ++i;
-            else if (a_[i] > b_[j]) ++j;
-            else { if (dst) dst->push_back(a_[i]); ++c; ++i; ++j; }
+            const int32_t x = a_[i], y = b_[j];
+            c += (x == y);
+            i += (x <= y);
+            j += (y <= x);
         }
         return c;
     }
@@ -248,6 +276,7 @@ struct Searcher {
     int64_t progress_every = 0;
     std::chrono::steady_clock::time_point t_start;
     int64_t n_sweep = 0, n_batch = 0, n_refresh = 0;
+    std::atomic<int64_t> n_empty{0};
     double t_sweep = 0, t_refresh = 0, t_merge = 0;
     int64_t sweep_work = 0;
     std::vector<std::vector<int32_t>> cnt, touched;
@@ -260,8 +289,8 @@ struct Searcher {
 
     void report_progress() {
         double el = std::chrono::duration<double>(std::chrono::steady_clock::now() - t_start).count();
-        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps in %lld batches (%.1f s), %lld refreshes (%.1f s), merges %.1f s\n",
-                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, (long long)n_batch, t_sweep, (long long)n_refresh, t_refresh, t_merge);
+        std::fprintf(stderr, "[hag_search] %lld merges, redundancy %d, %.1f s, %lld sweeps (%lld empty) in %lld batches (%.1f s), %lld refreshes (%.1f s), merges %.1f s\n",
+                     (long long)b.a(), b.m_red.back(), el, (long long)n_sweep, (long long)n_empty.load(), (long long)n_batch, t_sweep, (long long)n_refresh, t_refresh, t_merge);
         if (const char *path = std::getenv("HAG_SEARCH_CHECKPOINT")) {
             std::string tmp = std::string(path) + ".tmp";
             if (FILE *f = std::fopen(tmp.c_str(), "wb")) {
@@ -335,6 +364,7 @@ struct Searcher {
             if (f.y == x || !mergeable(f.y)) continue;
             if (f.c >= theta) lst.push_back(Cand{f.y, f.c, iter});
         }
+        if (lst.empty()) n_empty++;
         std::sort(lst.begin(), lst.end(), better);
         if ((int)lst.size() > kKeep) {
             int32_t cut = lst[kKeep].c;            // first dropped count; keep only strictly larger
@@ -379,7 +409,12 @@ struct Searcher {
         e.stamp = iter;
         // partners born from y since the entry was exact (fact 2: bounded by the old entry)
         std::vector<int32_t> stack;
-        for (int32_t w : children[y]) if (born[w] >= since) stack.push_back(w);
+        {
+            // children are listed in creation order, so those born since the stamp are a suffix
+            const auto &ch = children[y];
+            auto first = std::partition_point(ch.begin(), ch.end(), [&](int32_t w) { return born[w] < since; });
+            stack.assign(first, ch.end());
+        }
         while (!stack.empty()) {
             int32_t w = stack.back();
             stack.pop_back();

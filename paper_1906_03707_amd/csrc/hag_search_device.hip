@@ -32,15 +32,15 @@ constexpr int kHotAgg = 2048;          // ... and the earliest aggregation nodes
 struct View {
     int64_t n, m;                // original nodes; n + capacity
     const int64_t *ptr;          // [n+1] list u occupies nb[ptr[u] .. ptr[u] + len[u])
-    int32_t *nb;
+    int32_t *nb;                 // members in MIRROR ids: an original node is named by its rank in the order
+                                 // (bound descending, id ascending), an aggregation node by its id (>= n)
     int32_t *len, *norig;        // current length; how many of the leading members are original nodes
-    const int32_t *rank;         // [n] position of an original node in the order (bound descending, id ascending)
-    const int32_t *by_rank;      // [n] its inverse
+    const int32_t *by_rank;      // [n] original node of each rank
     int32_t *mred;               // [capacity] creation redundancy of an aggregation node
     int64_t *out_off;            // [m] out-list of x occupies out[out_off[x] .. + olen[x]), ascending
     int32_t *out;
     int32_t *olen;
-    int32_t *cnt;                // [kMaxBatch][m] counters, all zero between batches
+    int32_t *cnt;                // [kMaxBatch][m] counters by mirror id, all zero between batches
     const int32_t *req;          // [kMaxBatch][4] node, threshold, number of original nodes whose bound reaches it, 0
     int32_t *nfound;             // [kMaxBatch]
     Found *found;                // [kMaxBatch][kFoundCap]
@@ -77,11 +77,10 @@ __global__ __launch_bounds__(256) void count_kernel(View v) {
             const int j = j0 + lane;
             bool ok = false;
             if (j < no) {
-                const int y = l[j];
-                const int rk = v.rank[y];
-                ok = rk < rank_end;
+                const int y = l[j];                  // a rank: ascending along the list
+                ok = y < rank_end;
                 if (ok) {
-                    if (rk < kHotOrig) atomicAdd(&hot[rk], 1);
+                    if (y < kHotOrig) atomicAdd(&hot[y], 1);
                     else atomicAdd(&c[y], 1);
                 }
             }
@@ -105,7 +104,7 @@ __global__ __launch_bounds__(256) void count_kernel(View v) {
     __syncthreads();
     for (int t = threadIdx.x; t < kHotOrig + kHotAgg; t += blockDim.x) {
         const int k = hot[t];
-        if (k) atomicAdd(&c[t < kHotOrig ? v.by_rank[t] : n + (t - kHotOrig)], k);
+        if (k) atomicAdd(&c[t < kHotOrig ? t : n + (t - kHotOrig)], k);
     }
 }
 
@@ -120,13 +119,13 @@ __global__ __launch_bounds__(256) void collect_kernel(View v) {
         c[y] = 0;
         if (k >= theta) {
             const int at = atomicAdd(&v.nfound[s], 1);
-            if (at < kFoundCap) v.found[(size_t)s * kFoundCap + at] = Found{(int32_t)y, k};
+            if (at < kFoundCap) v.found[(size_t)s * kFoundCap + at] = Found{y < v.n ? v.by_rank[y] : (int32_t)y, k};
         }
     }
 }
 
 // The rewrite loop of Algorithm 3 on the mirror: every list named in rows[0..r) holds p and
-// q; remove both and append w.  One wavefront per list, compacting in place: a chunk of 64
+// q (mirror ids); remove both and append w.  One wavefront per list, compacting in place: a chunk of 64
 // members is read by one instruction before any of them is written, and is written to
 // positions no later chunk reads.
 __global__ __launch_bounds__(256) void rewrite_kernel(View v, int64_t rows_at, int r, int p, int q, int w) {
@@ -149,7 +148,7 @@ __global__ __launch_bounds__(256) void rewrite_kernel(View v, int64_t rows_at, i
     if (lane == 0 && k < L) {
         l[k] = w;
         v.len[u] = k + 1;
-        v.norig[u] -= (p < v.n) + (q < v.n);
+        v.norig[u] -= (p < v.n) + (q < v.n);     // a rank is below n just as the id it stands for
     }
 }
 
@@ -209,6 +208,7 @@ struct DeviceCounter {
     int32_t *h_req = nullptr, *h_nfound = nullptr, *h_rows = nullptr;
     Found *h_eager = nullptr, *h_found = nullptr;
     std::vector<int32_t> prio_desc;   // the static bounds of the original nodes, descending
+    std::vector<int32_t> rank;        // mirror id of every original node
 };
 
 #define CNT_TRY(expr)                                                              \
@@ -233,8 +233,10 @@ static bool counter_setup(DeviceCounter *d, const CounterInit &in, std::string &
         return rc;
     };
     int64_t *ptr = nullptr;
-    int32_t *rank = nullptr, *by_rank = nullptr, *req = nullptr;
-    std::vector<int32_t> h_by_rank((size_t)n), h_rank((size_t)n);
+    int32_t *by_rank = nullptr, *req = nullptr;
+    std::vector<int32_t> h_by_rank((size_t)n);
+    std::vector<int32_t> &h_rank = d->rank;
+    h_rank.resize((size_t)n);
     for (int64_t i = 0; i < n; ++i) h_by_rank[i] = (int32_t)i;
     std::sort(h_by_rank.begin(), h_by_rank.end(),
               [&](int32_t a, int32_t b) { return in.prio[a] != in.prio[b] ? in.prio[a] > in.prio[b] : a < b; });
@@ -247,7 +249,6 @@ static bool counter_setup(DeviceCounter *d, const CounterInit &in, std::string &
     CNT_TRY(dev_alloc((void **)&d->v.nb, (size_t)e * 4));
     CNT_TRY(dev_alloc((void **)&d->v.len, (size_t)n * 4));
     CNT_TRY(dev_alloc((void **)&d->v.norig, (size_t)n * 4));
-    CNT_TRY(dev_alloc((void **)&rank, (size_t)n * 4));
     CNT_TRY(dev_alloc((void **)&by_rank, (size_t)n * 4));
     CNT_TRY(dev_alloc((void **)&d->v.mred, (size_t)in.capacity * 4));
     CNT_TRY(dev_alloc((void **)&d->v.out_off, (size_t)m * 8));
@@ -260,7 +261,6 @@ static bool counter_setup(DeviceCounter *d, const CounterInit &in, std::string &
     CNT_TRY(dev_alloc((void **)&d->v.nfound, (size_t)kMaxBatch * 4));
     CNT_TRY(dev_alloc((void **)&d->v.found, (size_t)kMaxBatch * kFoundCap * sizeof(Found)));
     d->v.ptr = ptr;
-    d->v.rank = rank;
     d->v.by_rank = by_rank;
     d->v.req = req;
     CNT_TRY(hipHostMalloc((void **)&d->h_req, (size_t)kMaxBatch * 16, hipHostMallocDefault));
@@ -270,10 +270,13 @@ static bool counter_setup(DeviceCounter *d, const CounterInit &in, std::string &
     CNT_TRY(hipHostMalloc((void **)&d->h_rows, std::max<size_t>((size_t)e * 4, 256), hipHostMallocDefault));
 
     CNT_TRY(hipMemcpyAsync(ptr, in.ptr, (size_t)(n + 1) * 8, hipMemcpyHostToDevice, d->stream));
-    CNT_TRY(hipMemcpyAsync(d->v.nb, in.nb, (size_t)e * 4, hipMemcpyHostToDevice, d->stream));
+    {
+        // the lists in mirror ids (all members are original nodes at this point), staged through h_rows
+        for (int64_t i = 0; i < e; ++i) d->h_rows[i] = h_rank[in.nb[i]];
+        CNT_TRY(hipMemcpyAsync(d->v.nb, d->h_rows, (size_t)e * 4, hipMemcpyHostToDevice, d->stream));
+    }
     CNT_TRY(hipMemcpyAsync(d->v.len, in.len, (size_t)n * 4, hipMemcpyHostToDevice, d->stream));
     CNT_TRY(hipMemcpyAsync(d->v.norig, in.norig, (size_t)n * 4, hipMemcpyHostToDevice, d->stream));
-    CNT_TRY(hipMemcpyAsync(rank, h_rank.data(), (size_t)n * 4, hipMemcpyHostToDevice, d->stream));
     CNT_TRY(hipMemcpyAsync(by_rank, h_by_rank.data(), (size_t)n * 4, hipMemcpyHostToDevice, d->stream));
     CNT_TRY(hipMemcpyAsync(d->v.out_off, in.out_ptr, (size_t)n * 8, hipMemcpyHostToDevice, d->stream));
     CNT_TRY(hipMemcpyAsync(d->v.out, in.out_col, (size_t)e * 4, hipMemcpyHostToDevice, d->stream));
@@ -320,7 +323,8 @@ bool counter_merge(DeviceCounter *d, int32_t p, int32_t q, int32_t w, const int3
     std::memcpy(stage, rows, (size_t)r * 4);
     const int64_t rows_at = d->e + d->pool_used;
     CNT_TRY(hipMemcpyAsync(v.out + rows_at, stage, (size_t)r * 4, hipMemcpyHostToDevice, d->stream));
-    hipLaunchKernelGGL(rewrite_kernel, dim3((unsigned)((r + 3) / 4)), dim3(256), 0, d->stream, v, rows_at, r, p, q, w);
+    const int32_t pm = p < v.n ? d->rank[p] : p, qm = q < v.n ? d->rank[q] : q;
+    hipLaunchKernelGGL(rewrite_kernel, dim3((unsigned)((r + 3) / 4)), dim3(256), 0, d->stream, v, rows_at, r, pm, qm, w);
     hipLaunchKernelGGL(out_remove_kernel, dim3(2), dim3(1024), 0, d->stream, v, rows_at, r, p, q, w);
     CNT_TRY(hipGetLastError());
     d->pool_used += r;
