@@ -142,6 +142,48 @@ def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     return time_steps(torch, epoch, steps, warmup)
 
 
+def sage_pool_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
+    """Per-epoch time (forward + backward) of a 2-layer GraphSAGE with the pooling aggregator of
+    Table 1: a_v = max over N(v) of relu(W1 h_u), h'_v = relu(W2 [a_v, h_v]), SoftMax loss.  Dense
+    parts are torch; the element-wise max (argmax kept for the backward pass) is hag_forward /
+    hag_backward with op "max" (or the naive-CSR baseline)."""
+    fwd = h.naive_forward if naive else h.forward
+    bwd = h.naive_backward if naive else h.backward
+
+    class MaxAgg(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, z):
+            y, am = fwd(z.contiguous(), "max")
+            ctx.am = am
+            return y
+
+        @staticmethod
+        def backward(ctx, g):
+            return bwd(g.contiguous(), "max", argmax=ctx.am)
+
+    n, d = x.shape
+    gen = torch.Generator(device="cuda").manual_seed(2)
+    dims = [d, hidden, classes]
+    pool = [(torch.randn(dims[i], hidden, device="cuda", generator=gen) / dims[i] ** 0.5).requires_grad_() for i in range(2)]
+    comb = [(torch.randn(hidden + dims[i], dims[i + 1], device="cuda", generator=gen) / (hidden + dims[i]) ** 0.5).requires_grad_()
+            for i in range(2)]
+    labels = torch.randint(0, classes, (n,), device="cuda", generator=gen)
+
+    def epoch():
+        hcur = x
+        for i in range(2):
+            a = MaxAgg.apply(torch.relu(hcur @ pool[i]))
+            hcur = torch.cat([a, hcur], dim=1) @ comb[i]
+            if i == 0:
+                hcur = torch.relu(hcur)
+        loss = torch.nn.functional.cross_entropy(hcur, labels)
+        for w in pool + comb:
+            w.grad = None
+        loss.backward()
+
+    return time_steps(torch, epoch, steps, warmup)
+
+
 def sweep_config5(torch, synth, workloads, steps, warmup):
     """BASELINE config 5: the 232,965-node graph over capacity {0, |V|/8, |V|/4, |V|/2} x feature
     dim {16, 128, 512} x {max, sum}, forward + backward.  One JSON line per point on stdout."""
@@ -196,6 +238,8 @@ def main():
     ap.add_argument("--device-search", action="store_true",
                     help="build the HAG with hag_search + HAG_SEARCH_DEVICE (pair counting on the GPU) instead of "
                          "the host search / the cached merge list; the search time is logged to stderr")
+    ap.add_argument("--sage-epoch", action="store_true",
+                    help="also time one epoch of a 2-layer GraphSAGE with the max-pooling aggregator (16 hidden dims)")
     ap.add_argument("--gcn-epoch", action="store_true",
                     help="also time a 2-layer GCN epoch (16 hidden dims, SoftMax) around the aggregation")
     ap.add_argument("--copy-calibration", action="store_true",
@@ -359,6 +403,11 @@ def main():
         f"naive {out['naive_csr']['effective_GBps']:.0f}  (peak {HBM_PEAK_GBS:.0f})")
     log(f"[bench] dominant kernel {kernel_name}: {ms_gather * 1e3:.1f} us, {gather_bytes / 1e6:.1f} MB -> {achieved:.0f} GB/s "
         f"= {100 * achieved / HBM_PEAK_GBS:.1f}% of HBM peak")
+    if args.sage_epoch:
+        e_hag = sage_pool_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=False)
+        e_naive = sage_pool_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=True)
+        out["sage_pool_epoch_ms"] = {"hag": e_hag, "naive": e_naive, "hidden": 16, "classes": 16, "layers": 2}
+        log(f"[bench] 2-layer GraphSAGE-P epoch (hidden 16): hag {e_hag:.3f} ms  naive {e_naive:.3f} ms  ({e_naive / e_hag:.2f}x)")
     if args.gcn_epoch:
         e_hag = gcn_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=False)
         e_naive = gcn_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=True)
