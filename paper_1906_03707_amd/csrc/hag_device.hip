@@ -381,28 +381,23 @@ struct CompArgs {
     const uint16_t *agg_row_col;
     const T *in;
     T *out;
-    int32_t *out_id;
     const float *scale_in, *scale_out;
     const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
     int32_t add_self;
     int32_t d, stride;           // feature width; padded row stride in LDS, in elements
-    int32_t id_rows_off;         // offset of the id rows (max), in 4-byte elements
     int32_t lists_off;           // offset of the staged aggregation lists, in bytes
     int32_t max_agg;             // most aggregation rows a component has
     int32_t use_agg, reverse;
 };
 
-// Reduce the LDS rows listed in col[beg .. beg+cnt) for the four features at column 4*k into
-// (acc, acc_id).  Called by all lanes of a wavefront with a common maxcnt.  Entries past cnt
-// read row `zrow`, which holds zeros (and id -1), so the inner loop has no branches: at LDS
-// speed the loop is bound by instruction issue, not by data.
-template <typename T, int RED, int LPR>
-__device__ __forceinline__ void lds_reduce(const T *buf, const int32_t *ids, int nv, int v0, int stride, int zrow,
-                                           const uint16_t *col, int beg, int cnt, int maxcnt, int sl, int k,
-                                           typename V4<T>::type &acc, int4 &acc_id) {
+// Add the LDS rows listed in col[beg .. beg+cnt) into acc, for the four features at column 4*k.
+// Called by all lanes of a wavefront with a common maxcnt.  Entries past cnt read row `zrow`,
+// which holds zeros, so the inner loop has no branches.
+template <typename T, int LPR>
+__device__ __forceinline__ void lds_reduce(const T *buf, int stride, int zrow, const uint16_t *col, int beg, int cnt,
+                                           int maxcnt, int sl, int k, typename V4<T>::type &acc) {
     using V = typename V4<T>::type;
     const T *colbuf = buf + 4 * k;
-    const int32_t *colids = ids + 4 * k;
     for (int base = 0; base < maxcnt; base += LPR) {
         const int mine = (base + sl < cnt) ? (int)col[beg + base + sl] : zrow;
         const int lim = min(LPR, maxcnt - base);
@@ -411,22 +406,12 @@ __device__ __forceinline__ void lds_reduce(const T *buf, const int32_t *ids, int
 #pragma unroll
             for (int t = 0; t < 4; ++t) u[t] = __shfl(mine, j + t, LPR);
 #pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const V x = *reinterpret_cast<const V *>(colbuf + u[t] * stride);
-                if (RED == R_MAX) {
-                    int4 xi;
-                    if (u[t] < nv) xi = make_int4(v0 + u[t], v0 + u[t], v0 + u[t], v0 + u[t]);
-                    else xi = *reinterpret_cast<const int4 *>(colids + (u[t] - nv) * stride);
-                    max4(acc, acc_id, x, xi);
-                } else {
-                    add4(acc, x);
-                }
-            }
+            for (int t = 0; t < 4; ++t) add4(acc, *reinterpret_cast<const V *>(colbuf + u[t] * stride));
         }
     }
 }
 
-template <typename T, int RED, int LPR>
+template <typename T, int LPR>
 __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     using V = typename V4<T>::type;
     constexpr int NSG = kBlock / LPR;      // sub-groups per workgroup
@@ -434,7 +419,6 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     constexpr int NW = kBlock / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     T *buf = reinterpret_cast<T *>(smem);
-    int32_t *ids = reinterpret_cast<int32_t *>(smem) + A.id_rows_off;       // id rows of aggregation nodes (max)
     int32_t *l_agg_ptr = reinterpret_cast<int32_t *>(smem + A.lists_off);   // [na+1], rebased
     int32_t *l_agg_stage = l_agg_ptr + A.max_agg + 1;                        // [na]
     uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_stage + A.max_agg + 1);
@@ -458,7 +442,6 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     }
     for (int k = tid; k < q; k += kBlock) {
         *reinterpret_cast<V *>(buf + zrow * stride + 4 * k) = V{};
-        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + na * stride + 4 * k) = make_int4(-1, -1, -1, -1);
     }
     if (na > 0) {
         const int e0 = A.agg_row_ptr[a0], ne = A.agg_row_ptr[a0 + na] - e0;
@@ -500,13 +483,8 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
                 for (int kb = 0; kb < q; kb += LPR) {
                     const int k = min(kb + sl, q - 1);
                     V acc{};
-                    int4 acc_id = make_int4(-1, -1, -1, -1);
-                    lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc,
-                                            acc_id);
-                    if (has && kb + sl < q) {
-                        *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-                        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
-                    }
+                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc);
+                    if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
                 }
             }
         } else {
@@ -521,27 +499,15 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
                 for (int kb = 0; kb < q; kb += LPR) {
                     const int k = min(kb + sl, q - 1);
                     V acc{};
-                    int4 acc_id = make_int4(-1, -1, -1, -1);
-                    lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per),
-                                            sl, k, acc, acc_id);
+                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k, acc);
 #pragma unroll
                     for (int off = LPR; off < kWave; off <<= 1) {
                         V o;
                         o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
                         o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
-                        if (RED == R_MAX) {
-                            int4 oi;
-                            oi.x = __shfl_xor(acc_id.x, off); oi.y = __shfl_xor(acc_id.y, off);
-                            oi.z = __shfl_xor(acc_id.z, off); oi.w = __shfl_xor(acc_id.w, off);
-                            max4(acc, acc_id, o, oi);
-                        } else {
-                            add4(acc, o);
-                        }
+                        add4(acc, o);
                     }
-                    if (has && kb + sl < q && sgw == 0) {
-                        *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-                        if (RED == R_MAX) *reinterpret_cast<int4 *>(ids + j * stride + 4 * k) = acc_id;
-                    }
+                    if (has && kb + sl < q && sgw == 0) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
                 }
             }
         }
@@ -560,8 +526,7 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
         for (int kb = 0; kb < q; kb += LPR) {
             const int k = min(kb + sl, q - 1);
             V acc{};
-            int4 acc_id = make_int4(-1, -1, -1, -1);
-            lds_reduce<T, RED, LPR>(buf, ids, nv, v0, stride, zrow, A.row_col, beg, cnt, maxcnt, sl, k, acc, acc_id);
+            lds_reduce<T, LPR>(buf, stride, zrow, A.row_col, beg, cnt, maxcnt, sl, k, acc);
             if (has && kb + sl < q) {
                 if (A.add_self) {
                     // the staged row already carries scale_in, which is the factor the own row needs
@@ -570,7 +535,6 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
                 if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
                 const size_t o = (size_t)(v0 + v) * A.d + 4 * k;
                 st4(A.out + o, acc);
-                if (RED == R_MAX) st4(A.out_id + o, acc_id);
             }
         }
     }
@@ -732,24 +696,22 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
     return HAG_OK;
 }
 
-// LDS layout of the component-local pass:
-//   [rows + zero row][id rows + "nothing" row (max)][agg ptr][agg stage][agg list ids]
+// LDS layout of the component-local pass: [rows + zero row][agg ptr][agg stage][agg list ids]
 struct CompLayout {
-    size_t id_rows_off = 0, lists_off = 0, total = 0;   // id_rows_off in 4-byte elements, the rest in bytes
+    size_t lists_off = 0, total = 0;   // bytes
 };
 // layout.total == 0: the pass does not apply to this call
 static CompLayout component_layout(const hag_handle *h, bool naive, bool backward, hag_op_t op, int64_t d) {
     CompLayout L;
     const Components &c = h->comp;
     if (!c.enabled || !h->comp_uploaded) return L;
-    // max stays on the generic kernels: their ordered comparison path is cheaper per element than
-    // the (value, id) comparison this kernel would need for every LDS row
+    // sums only.  Max stays on the generic kernels: their ordered comparison path is cheaper
+    // per element than a (value, id) comparison for every LDS row (measured: the LDS variant
+    // was the slower one), and its backward pass is a scatter, not a gather.
     if (op == HAG_MAX) return L;
     const size_t stride = (size_t)d + 4;
     const size_t rows = (size_t)c.max_nodes + (naive ? 0 : (size_t)c.max_agg) + 1;
-    L.id_rows_off = rows * stride;
     size_t bytes = rows * stride * 4;
-    if (op == HAG_MAX && !backward) bytes += ((naive ? 0 : (size_t)c.max_agg) + 1) * stride * 4;
     L.lists_off = bytes;
     if (!naive) {
         const size_t entries = backward ? c.max_entries_bwd : c.max_entries_fwd;   // aggregation lists only
@@ -760,9 +722,9 @@ static CompLayout component_layout(const hag_handle *h, bool naive, bool backwar
     return L;
 }
 
-template <typename T, int RED, bool BACKWARD>
+template <typename T, bool BACKWARD>
 static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *in, T *out,
-                            int32_t *out_id, hipStream_t s) {
+                            hipStream_t s) {
     const Components &c = h->comp;
     const CompLayout L = component_layout(h, naive, BACKWARD, op, d);
     CompArgs<T> a{};
@@ -776,7 +738,6 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.agg_row_col = aggs.d_col;
     a.in = in;
     a.out = out;
-    a.out_id = out_id;
     const float *norm = op == HAG_MEAN ? h->d_inv_deg : op == HAG_GCN ? h->d_inv_deg1 : nullptr;
     a.scale_in = BACKWARD ? norm : nullptr;
     a.scale_out = BACKWARD ? nullptr : norm;
@@ -786,16 +747,15 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.stride = (int32_t)d + 4;
     a.use_agg = naive ? 0 : 1;
     a.reverse = BACKWARD ? 1 : 0;
-    a.id_rows_off = (int32_t)L.id_rows_off;
     a.lists_off = (int32_t)L.lists_off;
     a.max_agg = c.max_agg;
     const dim3 grid((unsigned)c.count), block(kBlock);
     switch (pick_lpr(d)) {
-        case 4: hipLaunchKernelGGL((component_kernel<T, RED, 4>), grid, block, L.total, s, a); break;
-        case 8: hipLaunchKernelGGL((component_kernel<T, RED, 8>), grid, block, L.total, s, a); break;
-        case 16: hipLaunchKernelGGL((component_kernel<T, RED, 16>), grid, block, L.total, s, a); break;
-        case 32: hipLaunchKernelGGL((component_kernel<T, RED, 32>), grid, block, L.total, s, a); break;
-        default: hipLaunchKernelGGL((component_kernel<T, RED, 64>), grid, block, L.total, s, a); break;
+        case 4: hipLaunchKernelGGL((component_kernel<T, 4>), grid, block, L.total, s, a); break;
+        case 8: hipLaunchKernelGGL((component_kernel<T, 8>), grid, block, L.total, s, a); break;
+        case 16: hipLaunchKernelGGL((component_kernel<T, 16>), grid, block, L.total, s, a); break;
+        case 32: hipLaunchKernelGGL((component_kernel<T, 32>), grid, block, L.total, s, a); break;
+        default: hipLaunchKernelGGL((component_kernel<T, 64>), grid, block, L.total, s, a); break;
     }
     HIP_TRY(hipGetLastError());
     return HAG_OK;
@@ -806,7 +766,7 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
                         void *ws, hipStream_t s, uint32_t phases) {
     // a batch of small graphs: the whole pass is one launch out of LDS
     if (phases == HAG_PHASE_ALL && component_layout(h, naive, false, op, d).total > 0)
-        return launch_component<T, RED, false>(h, naive, op, d, x, y, argmax, s);
+        return launch_component<T, false>(h, naive, op, d, x, y, s);
     Workspace w = carve(h, op, d, ws);
     const int32_t n = (int32_t)h->n;
     if (!naive && (phases & HAG_PHASE_LEVELS)) {
@@ -869,7 +829,7 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
         return HAG_OK;
     }
     if (phases == HAG_PHASE_ALL && component_layout(h, naive, true, op, d).total > 0)
-        return launch_component<T, R_SUM, true>(h, naive, op, d, gy, gx, nullptr, s);
+        return launch_component<T, true>(h, naive, op, d, gy, gx, s);
     Workspace w = carve(h, op, d, ws);
     GatherArgs<T> a{};
     a.src_lo = gy;
