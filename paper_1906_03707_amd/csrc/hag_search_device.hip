@@ -12,6 +12,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <string>
 #include <vector>
@@ -209,6 +210,9 @@ struct DeviceCounter {
     Found *h_eager = nullptr, *h_found = nullptr;
     std::vector<int32_t> prio_desc;   // the static bounds of the original nodes, descending
     std::vector<int32_t> rank;        // mirror id of every original node
+    // how many results the host takes from the first copy / at all (tests lower both through
+    // HAG_SEARCH_EAGER_LIMIT / HAG_SEARCH_FOUND_LIMIT to reach the second copy and the host fallback)
+    int eager_limit = kEager, found_limit = kFoundCap;
 };
 
 #define CNT_TRY(expr)                                                              \
@@ -226,6 +230,8 @@ static bool counter_setup(DeviceCounter *d, const CounterInit &in, std::string &
     d->capacity = in.capacity;
     d->v.n = n;
     d->v.m = m;
+    if (const char *v = std::getenv("HAG_SEARCH_EAGER_LIMIT")) d->eager_limit = std::max(0, std::min(kEager, std::atoi(v)));
+    if (const char *v = std::getenv("HAG_SEARCH_FOUND_LIMIT")) d->found_limit = std::max(0, std::min(kFoundCap, std::atoi(v)));
     CNT_TRY(hipStreamCreate(&d->stream));
     auto dev_alloc = [&](void **p, size_t bytes) {
         hipError_t rc = hipMalloc(p, std::max<size_t>(bytes, 256));
@@ -364,8 +370,8 @@ bool counter_sweep(DeviceCounter *d, int nb, const int32_t *x, const int32_t *th
     bool more = false;
     for (int s = 0; s < nb; ++s) {
         const int k = d->h_nfound[s];
-        if (k > kFoundCap) { overflow[s] = 1; continue; }
-        if (k > kEager) {
+        if (k > d->found_limit) { overflow[s] = 1; continue; }
+        if (k > d->eager_limit) {
             CNT_TRY(hipMemcpyAsync(d->h_found + (size_t)s * kFoundCap, v.found + (size_t)s * kFoundCap,
                                    (size_t)k * sizeof(Found), hipMemcpyDeviceToHost, d->stream));
             more = true;
@@ -375,7 +381,7 @@ bool counter_sweep(DeviceCounter *d, int nb, const int32_t *x, const int32_t *th
     for (int s = 0; s < nb; ++s) {
         const int k = d->h_nfound[s];
         if (overflow[s] || k <= 0) continue;
-        const Found *src = k > kEager ? d->h_found + (size_t)s * kFoundCap : d->h_eager + (size_t)s * kEager;
+        const Found *src = k > d->eager_limit ? d->h_found + (size_t)s * kFoundCap : d->h_eager + (size_t)s * kEager;
         found[s].assign(src, src + k);
     }
     return true;

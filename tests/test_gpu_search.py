@@ -70,3 +70,17 @@ def test_device_search_degenerate_inputs(B):
     rp = np.array([0, 1, 3, 5, 6], dtype=np.int64)
     cl = np.array([1, 0, 2, 1, 3, 2], dtype=np.int32)
     assert B.hag_search(rp, cl, 4, flags=B.HAG_SEARCH_DEVICE).stats()["a"] == 0
+
+
+@pytest.mark.parametrize("knobs", [{"HAG_SEARCH_EAGER_LIMIT": "2"}, {"HAG_SEARCH_FOUND_LIMIT": "3"},
+                                   {"HAG_SEARCH_EAGER_LIMIT": "0", "HAG_SEARCH_FOUND_LIMIT": "8"}])
+def test_device_search_long_result_lists_and_host_fallback(B, monkeypatch, knobs):
+    # results beyond the first copy take a second one; more than the device keeps make the host count
+    # that node itself: both must leave the merge list unchanged
+    rowptr, col = synth.sbm(n_blocks=6, block=50, p_in=0.4, p_out=0.02, seed=1240)
+    n = rowptr.size - 1
+    host = B.hag_search(rowptr, col, n // 2)
+    for k, v in knobs.items():
+        monkeypatch.setenv(k, v)
+    devc = B.hag_search(rowptr, col, n // 2, flags=B.HAG_SEARCH_DEVICE)
+    assert same_merges(host.get_merges(), devc.get_merges())
