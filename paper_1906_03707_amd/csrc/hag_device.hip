@@ -644,12 +644,16 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     {
         const uint64_t row_bytes = (uint64_t)a.d * 4;
         const uint64_t lo_rows = (uint64_t)std::max<int64_t>(a.split, 1);
-        a.off32 = lo_rows * row_bytes < (1ull << 32) ? 1 : 0;
+        // HAG_OFFSET64=1 forces the 64-bit path, which otherwise only matrices of 4 GiB and more take
+        const char *e64 = std::getenv("HAG_OFFSET64");
+        const bool force64 = e64 && std::atoi(e64) != 0;
+        a.off32 = (!force64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
     }
     // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
     // eight neighbours, and needs one when a single sub-group would walk it for too long.
     {
-        static const int64_t sub_max = [] { const char *e = std::getenv("HAG_SUB_MAX"); return e ? std::atoll(e) : 0LL; }();
+        const char *esub = std::getenv("HAG_SUB_MAX");     // read per call: a test may change it
+        const int64_t sub_max = esub ? std::atoll(esub) : 0LL;
         const int64_t nsg = kBlock / pick_lpr(a.d);
         const int64_t threshold = sub_max > 0 ? sub_max : std::max<int64_t>(64, 8 * nsg);
         for (int k = 0; k < p.np; ++k) {

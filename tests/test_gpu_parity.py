@@ -105,9 +105,13 @@ def test_fused_and_unfused_stages(B, monkeypatch):
     run_all_ops(B, unfused, rowptr, col, 32, seed=32)
 
 
-def test_source_partitioned_schedule(B, monkeypatch):
+@pytest.mark.parametrize("offset64", [False, True])
+def test_source_partitioned_schedule(B, monkeypatch, offset64):
     # rows cut by source id into per-XCD segments with partial rows folded afterwards: forced on
-    # for a small graph (by default only large graphs use it), incl. hubs that are also split
+    # for a small graph (by default only large graphs use it), incl. hubs that are also split;
+    # once more with the 64-bit row addressing that matrices of 4 GiB and more take
+    if offset64:
+        monkeypatch.setenv("HAG_OFFSET64", "1")
     monkeypatch.setenv("HAG_PARTITION_MIN_ROWS", "0")
     monkeypatch.setenv("HAG_PART_MIN", "8")
     monkeypatch.setenv("HAG_BLOCK_MAX", "40")

@@ -171,6 +171,28 @@ def test_device_counted_search_needs_a_device():
     assert B.hag_search(rowptr, col, 0, flags=B.HAG_SEARCH_DEVICE).stats()["a"] == 0
 
 
+def test_search_checkpoint_holds_a_prefix_of_the_merge_list(tmp_path, monkeypatch, capfd):
+    # HAG_SEARCH_PROGRESS=<every> prints a line and, with HAG_SEARCH_CHECKPOINT=<file>, dumps the merges so
+    # far (int64 count, then left[], right[] as int32), so that a long search can be resumed by replay
+    rowptr, col = synth.sbm(n_blocks=4, block=40, p_in=0.4, p_out=0.02, seed=81)
+    n = rowptr.size - 1
+    path = tmp_path / "merges.bin"
+    monkeypatch.setenv("HAG_SEARCH_PROGRESS", "7")
+    monkeypatch.setenv("HAG_SEARCH_CHECKPOINT", str(path))
+    h = B.hag_search(rowptr, col, n // 2)
+    assert "[hag_search]" in capfd.readouterr().err
+    left, right, _ = h.get_merges()
+    raw = path.read_bytes()
+    k = int(np.frombuffer(raw[:8], dtype=np.int64)[0])
+    assert k > 0 and k % 7 == 0 and k <= left.size and len(raw) == 8 + 8 * k
+    assert np.array_equal(np.frombuffer(raw[8:8 + 4 * k], dtype=np.int32), left[:k])
+    assert np.array_equal(np.frombuffer(raw[8 + 4 * k:], dtype=np.int32), right[:k])
+    monkeypatch.delenv("HAG_SEARCH_PROGRESS")
+    monkeypatch.delenv("HAG_SEARCH_CHECKPOINT")
+    resumed = B.hag_from_merges(rowptr, col, left[:k], right[:k])
+    assert resumed.stats() == h.prefix(k).stats()
+
+
 def test_empty_and_isolated():
     h = B.hag_search(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4)
     assert h.stats()["n"] == 0 and h.stats()["a"] == 0
