@@ -518,10 +518,14 @@ struct Searcher {
 // ------------------------------------------------------------------------------------------
 // schedules
 // ------------------------------------------------------------------------------------------
+// Items are ordered by length class, longest first, and keep their row order inside a class.
+// Classes are octaves: fine enough that the sub-groups of a wavefront get items of similar
+// length, coarse enough that a class is a dense sweep over the rows, so that rows launched
+// together are neighbours and share sources (measured on the 114M-edge graph: quarter-octave
+// classes cost 5 % at d = 128 and 512, and gain 1-3 % at d = 16).
 static int length_class(int32_t cnt) {
-    if (cnt <= 16) return cnt;
-    int lg = 31 - __builtin_clz((unsigned)cnt);         // >= 4
-    return 16 + (lg - 4) * 4 + ((cnt >> (lg - 2)) & 3);  // quarter-octave classes
+    if (cnt <= 1) return cnt;
+    return 32 - __builtin_clz((unsigned)cnt);
 }
 
 // Schedule of one gather launch over rows [row_begin, row_end) of `c`.
