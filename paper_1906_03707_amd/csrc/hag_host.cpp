@@ -278,7 +278,6 @@ struct Searcher {
     int64_t n_sweep = 0, n_batch = 0, n_refresh = 0;
     std::atomic<int64_t> n_empty{0};
     double t_sweep = 0, t_refresh = 0, t_merge = 0;
-    int64_t sweep_work = 0;
     std::vector<std::vector<int32_t>> cnt, touched;
     std::vector<std::vector<Found>> found_host;
     // optional: counting on the GPU (HAG_SEARCH_DEVICE); the host lists stay authoritative
