@@ -204,13 +204,25 @@ struct Builder {
         scratch.clear();
         int32_t r = intersect(p, q, &scratch);
         int32_t w = (int32_t)(n + a());
+        // A list is ordered (original members by (prio descending, id ascending) or, without
+        // priorities, by id; then aggregation members by id), so p and q are found by bisection
+        // and taken out with two block moves; w has the largest id and goes to the end.
+        auto position = [&](const int32_t *l, int32_t no, int32_t L, int32_t x) {
+            if (x >= n) return (int32_t)(std::lower_bound(l + no, l + L, x) - l);
+            if (prio.empty()) return (int32_t)(std::lower_bound(l, l + no, x) - l);
+            return (int32_t)(std::lower_bound(l, l + no, x, [&](int32_t y, int32_t key) {
+                return prio[y] != prio[key] ? prio[y] > prio[key] : y < key;
+            }) - l);
+        };
         auto rewrite = [&](int32_t u) {
             int32_t *l = nb.data() + g->ptr[u];
-            int32_t k = 0, L = len[u];
-            for (int32_t i = 0; i < L; ++i)
-                if (l[i] != p && l[i] != q) l[k++] = l[i];
-            l[k++] = w;
-            len[u] = k;
+            const int32_t L = len[u], no = norig[u];
+            int32_t i = position(l, no, L, p), j = position(l, no, L, q);
+            if (i > j) std::swap(i, j);
+            std::memmove(l + i, l + i + 1, sizeof(int32_t) * (size_t)(j - i - 1));
+            std::memmove(l + j - 1, l + j + 1, sizeof(int32_t) * (size_t)(L - j - 1));
+            l[L - 2] = w;
+            len[u] = L - 1;
             norig[u] -= (p < n) + (q < n);
         };
         if (threads > 1 && r >= 1024) {
@@ -578,16 +590,28 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
             lists[part].push_back(Item{b0, (int32_t)(b1 - b0), (int32_t)~(p.n_slots++)});
         }
     };
+    if (np > 1) {
+        // reorder the rows that are cut by source: (id mod 8, id); rows are independent
+        const int64_t chunk = 256, chunks = (row_end - row_begin + chunk - 1) / chunk;
+        parallel_for(chunks, host_threads(), [&](int64_t ci, unsigned) {
+            const int64_t r0 = row_begin + ci * chunk, r1 = std::min(row_end, r0 + chunk);
+            for (int64_t r = r0; r < r1; ++r) {
+                const int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
+                if (cnt < part_min) continue;
+                int32_t *row = dcol.data() + beg;
+                std::sort(row, row + cnt, [](int32_t x, int32_t y) {
+                    int px = x & (kPartitions - 1), py = y & (kPartitions - 1);
+                    return px != py ? px < py : x < y;
+                });
+            }
+        });
+    }
     int rr = 0, rr_run = 0;     // whole rows go to the lists in runs of 64, which keeps neighbours together
     auto next_list = [&] { if (++rr_run == 64) { rr_run = 0; rr = (rr + 1) % np; } };
     for (int64_t r = row_begin; r < row_end; ++r) {
         int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
         if (np > 1 && cnt >= part_min) {
-            int32_t *row = dcol.data() + beg;
-            std::sort(row, row + cnt, [](int32_t x, int32_t y) {
-                int px = x & (kPartitions - 1), py = y & (kPartitions - 1);
-                return px != py ? px < py : x < y;
-            });
+            const int32_t *row = dcol.data() + beg;
             int64_t first_slot = p.n_slots, i = 0;
             while (i < cnt) {
                 int part = row[i] & (kPartitions - 1);
@@ -935,7 +959,7 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
 
 static int replay(hag_handle *h, int64_t n_merges, const int32_t *left, const int32_t *right) {
     Builder b;
-    b.init(h->g);
+    b.init(h->g, false, host_threads());
     for (int64_t i = 0; i < n_merges; ++i) {
         int64_t lim = b.n + i;
         if (left[i] < 0 || right[i] < 0 || left[i] >= lim || right[i] >= lim)
