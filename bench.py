@@ -3,7 +3,7 @@
 
 A step = one hag_forward + one hag_backward (all phases: aggregation-node levels,
 final gather; transposed levels, source gather) over one synthetic graph whose
-feature matrices already live in HBM.  The default workload is BASELINE config 2
+feature matrices already live in HBM.  The default workload is benchmark config 2
 (Holme-Kim power-law cluster graph, 56,944 nodes, D=128, capacity |V|/4, sum).
 
 Prints ONE JSON line (stdout); a human-readable breakdown goes to stderr.
@@ -185,7 +185,7 @@ def sage_pool_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
 
 
 def sweep_config5(torch, synth, workloads, steps, warmup):
-    """BASELINE config 5: the 232,965-node graph over capacity {0, |V|/8, |V|/4, |V|/2} x feature
+    """benchmark config 5: the 232,965-node graph over capacity {0, |V|/8, |V|/4, |V|/2} x feature
     dim {16, 128, 512} x {max, sum}, forward + backward.  One JSON line per point on stdout."""
     rowptr, col, _ = synth.graph_for_config(5)
     n = rowptr.size - 1
@@ -230,7 +230,7 @@ def main():
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=200)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", type=int, default=2, help="BASELINE config (1-based); 2 is the metric's workload; 5 runs the capacity x width x op sweep")
+    ap.add_argument("--config", type=int, default=2, help="benchmark config (1-based); 2 is the metric's workload; 5 runs the capacity x width x op sweep")
     ap.add_argument("--op", default="sum", choices=["sum", "mean", "max", "gcn"])
     ap.add_argument("--d", type=int, default=0, help="override the feature dimension")
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")

@@ -200,7 +200,7 @@ CONFIGS = {
 
 
 def graph_for_config(cfg: int):
-    """(rowptr, col, graph_ptr or None) of BASELINE config `cfg` (1-based)."""
+    """(rowptr, col, graph_ptr or None) of benchmark config `cfg` (1-based)."""
     if cfg == 1:
         return (*sbm(), None)
     if cfg == 2:

@@ -1,4 +1,4 @@
-"""BASELINE workloads: graph + HAG for each config, with an on-disk cache of merge lists.
+"""Benchmark workloads: graph + HAG for each config, with an on-disk cache of merge lists.
 
 A HAG depends only on the graph, the capacity and the aggregate type, so it is searched once and
 reused (the paper's own remark on reusability).  For the 114M-edge graph of configs 3 and 5 the
@@ -35,7 +35,7 @@ def load_cached_merges(cfg: int):
 
 
 def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None, device_search=False):
-    """HAG of BASELINE config `cfg` (capacity |V|/4 unless given), from the cache when one exists.
+    """HAG of benchmark config `cfg` (capacity |V|/4 unless given), from the cache when one exists.
 
     device_search=True ignores the cache and runs Algorithm 3 with the pair counting on the GPU."""
     n = rowptr.size - 1

@@ -1,4 +1,4 @@
-"""GPU parity at the full sizes of BASELINE configs 2-5, in the launch configuration bench.py times.
+"""GPU parity at the full sizes of benchmark configs 2-5, in the launch configuration bench.py times.
 
 Aggregation is element-wise in the feature index, so the oracle can compute any subset of
 output columns exactly by running on the same graph with only those columns of the input.
