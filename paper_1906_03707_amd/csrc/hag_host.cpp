@@ -261,9 +261,11 @@ struct Builder {
 // on Redundancy(x, y) (exact at the iteration `stamp`), and `tail`, an upper bound for every
 // partner that existed at x's last sweep and is not listed.  By (2) a partner created later is
 // bounded by its parents, so key[x] = max(best c, tail) bounds all of x's pairs.  When x is on
-// top of the heap its best entry is made exact by intersecting the two out-lists (cheap), the
-// children of a changed partner are looked up the same way, and only when the list is
-// exhausted (best c <= tail) is x swept again: one counting pass over the lists that hold x.
+// top of the heap its best entry is made exact by intersecting the two out-lists (cheap), every
+// descendant of that partner born since the entry was last exact is looked up the same way
+// (a node hands rows on to the nodes built from it, so only the partner's OLD count bounds
+// them, not its current one), and only when the list is exhausted (best c <= tail) is x swept
+// again: one counting pass over the lists that hold x.
 // The heap is ordered by (key descending, id ascending), entries by (c descending, id
 // ascending); this makes the accepted pair the lexicographically smallest (smaller id, larger
 // id) among the pairs of maximal redundancy, i.e. the result does not depend on the laziness.
@@ -278,6 +280,8 @@ struct Searcher {
     std::vector<int32_t> key, tail, version;
     std::vector<int64_t> mod_stamp, born;          // last iteration a node was merged / its creation
     std::vector<std::vector<int32_t>> children;    // aggregation nodes built from a node
+    std::vector<int64_t> visited;                  // refresh() that last looked at a node
+    int64_t visit_id = 0;
     int64_t iter = 1;
     using Entry = std::tuple<int32_t, int32_t, int32_t>;  // key, -id, version
     std::priority_queue<Entry> heap;
@@ -419,7 +423,10 @@ struct Searcher {
         const int32_t y = e.y;
         e.c = b.intersect(x, y, nullptr);
         e.stamp = iter;
-        // partners born from y since the entry was exact (fact 2: bounded by the old entry)
+        // Descendants of y born since the entry was exact.  Fact (2) bounds each of them by the
+        // OLD count of (x, y) only: a node hands rows on to its children, so its current count
+        // says nothing about theirs, and the whole subtree has to be looked at.  A descendant
+        // that is already listed carries a bound for its own subtree.
         std::vector<int32_t> stack;
         {
             // children are listed in creation order, so those born since the stamp are a suffix
@@ -427,17 +434,19 @@ struct Searcher {
             auto first = std::partition_point(ch.begin(), ch.end(), [&](int32_t w) { return born[w] < since; });
             stack.assign(first, ch.end());
         }
+        ++visit_id;
         while (!stack.empty()) {
             int32_t w = stack.back();
             stack.pop_back();
-            if (w == x || !mergeable(w)) continue;
+            if (visited[w] == visit_id) continue;      // reachable through both of its parents
+            visited[w] = visit_id;
             bool listed = false;
             for (const Cand &q : lst) listed |= (q.y == w);
             if (listed) continue;
-            int32_t cw = b.intersect(x, w, nullptr);
-            if (cw <= tail[x]) continue;       // and so are its descendants
-            lst.push_back(Cand{w, cw, iter});
             for (int32_t w2 : children[w]) stack.push_back(w2);
+            if (w == x || !mergeable(w)) continue;
+            int32_t cw = b.intersect(x, w, nullptr);
+            if (cw > tail[x]) lst.push_back(Cand{w, cw, iter});
         }
         std::sort(lst.begin(), lst.end(), better);
         while (!lst.empty() && lst.back().c <= tail[x]) lst.pop_back();   // covered by the tail bound
@@ -451,6 +460,7 @@ struct Searcher {
         key.assign(m, 0); tail.assign(m, 0); version.assign(m, 0);
         mod_stamp.assign(m, 0); born.assign(m, 0);
         cand.assign(m, {}); children.assign(m, {});
+        visited.assign(m, 0);
         threads = single_thread ? 1u : host_threads();
         progress_every = single_thread ? 0 : env_i64("HAG_SEARCH_PROGRESS", 0);
         kKeep = (int)std::max<int64_t>(1, env_i64("HAG_SEARCH_KEEP", 12));

@@ -59,6 +59,14 @@ def test_device_search_equals_host_search(B):
             assert host.stats() == devc.stats()
 
 
+def test_device_search_to_exhaustion(B):
+    # capacity beyond what the graph can use: long chains of aggregation nodes built on aggregation nodes
+    rowptr, col = synth.dcsbm(n=1500, n_blocks=6, mean_degree=8.5, seed=102)
+    ref = oracle.search(rowptr, col, 3000)
+    h = B.hag_search(rowptr, col, 3000, flags=B.HAG_SEARCH_DEVICE)
+    assert same_merges(h.get_merges(), (ref.left, ref.right, ref.red))
+
+
 def test_device_search_degenerate_inputs(B):
     empty = B.hag_search(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4, flags=B.HAG_SEARCH_DEVICE)
     assert empty.stats()["a"] == 0

@@ -55,6 +55,19 @@ def test_search_matches_oracle_on_sbm_blocks():
     assert np.array_equal(l, ref.left) and np.array_equal(r, ref.right) and np.array_equal(red, ref.red)
 
 
+@pytest.mark.parametrize("n,n_blocks,mean_degree,seed", [(1500, 6, 8.5, 102), (1800, 8, 10.0, 100)])
+def test_search_to_exhaustion_matches_oracle(n, n_blocks, mean_degree, seed):
+    # Capacity beyond what the graph can use: the search runs until no pair is shared twice, through long
+    # chains of aggregation nodes built on aggregation nodes.  Graphs on which a bound that pruned the
+    # descendants of a partner by that partner's current count (its rows had moved on to them) lost a pair.
+    rowptr, col = synth.dcsbm(n=n, n_blocks=n_blocks, mean_degree=mean_degree, seed=seed)
+    ref = oracle.search(rowptr, col, 2 * n)
+    h = B.hag_search(rowptr, col, 2 * n)
+    l, r, red = h.get_merges()
+    assert ref.a == l.size < 2 * n and ref.red[-1] == 2
+    assert np.array_equal(l, ref.left) and np.array_equal(r, ref.right) and np.array_equal(red, ref.red)
+
+
 def test_level_order_and_forward_form():
     rowptr, col = synth.sbm(n_blocks=3, block=40, p_in=0.5, p_out=0.02, seed=78)
     n = rowptr.size - 1
