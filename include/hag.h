@@ -105,7 +105,8 @@ typedef struct hag_stats {
  * paper has no such limit).  All pointers are host memory.  *out receives a new
  * handle (free with hag_free).  Errors: HAG_EINVAL for n < 0, capacity < 0,
  * non-monotone rowptr, col out of range, duplicates without HAG_SEARCH_DEDUP,
- * n + capacity >= 2^31; HAG_ENOMEM. */
+ * n + capacity >= 2^31; HAG_ENOMEM; HAG_EHIP (HAG_SEARCH_DEVICE only: no device, or a
+ * HIP call failed). */
 int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity,
                uint32_t flags, int32_t max_depth, hag_t **out);
 
