@@ -378,7 +378,9 @@ def main():
                    "capacity": st["a"], "levels": st["levels"], "hag_edges": st["e_hag"]},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
-                     "kernel": kernel_name, "kernel_ms": ms_gather, "algorithmic_bytes": gather_bytes},
+                     "kernel": kernel_name, "kernel_ms": ms_gather, "algorithmic_bytes": gather_bytes,
+                     # L2 fills + writes per second actually seen by the fabric (counter bytes / live kernel time)
+                     "traffic_GBps": None if traffic is None else traffic / (ms_gather * 1e-3) / 1e9},
         "effective_GBps_fwd_bwd": alg_hag / (ms_hag * 1e-3) / 1e9,
         "effective_frac_of_peak": alg_hag / (ms_hag * 1e-3) / 1e9 / HBM_PEAK_GBS,
         "naive_csr": {"ms_per_step": ms_naive, "feature_elems_per_s": 2.0 * e * d / (ms_naive * 1e-3),
