@@ -367,15 +367,20 @@ __global__ __launch_bounds__(kBlock) void level_kernel(const int32_t *__restrict
 // Component-local pass: a batch of small graphs.  One workgroup per connected component.  Its
 // feature rows and its index lists are read from HBM once into LDS, its aggregation nodes are
 // evaluated in LDS stage by stage (Algorithm 2's loop over V_A, never touching global
-// memory), and every output row is then reduced out of LDS.  The transposed pass is the same
-// code with the transposed lists and the stages in reverse order.  Rows in LDS are padded by
-// four elements so that rows do not all start in the same bank.
+// memory), and every output row is then reduced out of LDS.  The transposed pass walks the
+// transposed lists with the stages in reverse order, but splits the gradient of an aggregation
+// row in two: the part that comes from destinations depends on nothing and is summed for all
+// aggregation rows at once by the whole workgroup; only the few terms that come from other
+// aggregation rows are added stage by stage.  Rows in LDS are padded by four elements so that
+// rows do not all start in the same bank.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 struct CompArgs {
     const int32_t *meta;         // per component: first node, #nodes, first aggregation slot, #agg | #stages << 16
     const uint8_t *stage;        // stage of each aggregation slot
-    const int32_t *row_ptr;      // lists of the rows written to global memory (index: global node id)
+    // lists of the rows written to global memory: per node slot {first entry in row_col,
+    // length | local row index << 16}, each component's rows sorted longest list first
+    const int32_t *row_items;
     const uint16_t *row_col;
     const int32_t *agg_row_ptr;  // lists of the aggregation rows kept in LDS (component-major index)
     const uint16_t *agg_row_col;
@@ -385,29 +390,48 @@ struct CompArgs {
     const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
     int32_t add_self;
     int32_t d, stride;           // feature width; padded row stride in LDS, in elements
+    int32_t items_off;           // offset of the staged row items, in bytes
     int32_t lists_off;           // offset of the staged aggregation lists, in bytes
     int32_t max_agg;             // most aggregation rows a component has
     int32_t use_agg, reverse;
 };
 
 // Add the LDS rows listed in col[beg .. beg+cnt) into acc, for the four features at column 4*k.
-// Called by all lanes of a wavefront with a common maxcnt.  Entries past cnt read row `zrow`,
-// which holds zeros, so the inner loop has no branches.
+// Called by all lanes of a sub-group with a common maxcnt.  Entries past cnt read row `zrow`,
+// which holds zeros, so the inner loop has no branches.  The ids are fetched 4*LPR at a time
+// (four independent loads per lane) and the next such chunk is requested before the current
+// one is consumed, so a list costs one memory latency, not one per LPR entries.
 template <typename T, int LPR>
 __device__ __forceinline__ void lds_reduce(const T *buf, int stride, int zrow, const uint16_t *col, int beg, int cnt,
                                            int maxcnt, int sl, int k, typename V4<T>::type &acc) {
     using V = typename V4<T>::type;
+    constexpr int CH = 4 * LPR;
     const T *colbuf = buf + 4 * k;
-    for (int base = 0; base < maxcnt; base += LPR) {
-        const int mine = (base + sl < cnt) ? (int)col[beg + base + sl] : zrow;
-        const int lim = min(LPR, maxcnt - base);
-        for (int j = 0; j < lim; j += 4) {
-            int u[4];
+    int m[4], nx[4] = {zrow, zrow, zrow, zrow};
 #pragma unroll
-            for (int t = 0; t < 4; ++t) u[t] = __shfl(mine, j + t, LPR);
+    for (int t = 0; t < 4; ++t) m[t] = (t * LPR + sl < cnt) ? (int)col[beg + t * LPR + sl] : zrow;
+    for (int base = 0; base < maxcnt; base += CH) {
+        if (base + CH < maxcnt) {
 #pragma unroll
-            for (int t = 0; t < 4; ++t) add4(acc, *reinterpret_cast<const V *>(colbuf + u[t] * stride));
+            for (int t = 0; t < 4; ++t) {
+                const int e = base + CH + t * LPR + sl;
+                nx[t] = (e < cnt) ? (int)col[beg + e] : zrow;
+            }
         }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int b = base + t * LPR;
+            const int lim = min(LPR, maxcnt - b);   // <= 0 past the end
+            for (int j = 0; j < lim; j += 4) {
+                int u[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) u[r] = __shfl(m[t], j + r, LPR);
+#pragma unroll
+                for (int r = 0; r < 4; ++r) add4(acc, *reinterpret_cast<const V *>(colbuf + u[r] * stride));
+            }
+        }
+#pragma unroll
+        for (int t = 0; t < 4; ++t) m[t] = nx[t];
     }
 }
 
@@ -419,9 +443,12 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     constexpr int NW = kBlock / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
     T *buf = reinterpret_cast<T *>(smem);
+    int2 *l_items = reinterpret_cast<int2 *>(smem + A.items_off);            // [nv]
     int32_t *l_agg_ptr = reinterpret_cast<int32_t *>(smem + A.lists_off);   // [na+1], rebased
     int32_t *l_agg_stage = l_agg_ptr + A.max_agg + 1;                        // [na]
-    uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_stage + A.max_agg + 1);
+    // transposed pass only: first consumer of each list that is itself an aggregation row
+    int32_t *l_agg_mid = l_agg_stage + A.max_agg + 1;                        // [na]
+    uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_mid + (A.reverse ? A.max_agg + 1 : 0));
     const int c = blockIdx.x;
     const int4 meta = *reinterpret_cast<const int4 *>(A.meta + 4 * (size_t)c);   // v0, nv, a0, na | stages << 16
     const int v0 = meta.x, nv = meta.y, a0 = meta.z;
@@ -443,6 +470,7 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     for (int k = tid; k < q; k += kBlock) {
         *reinterpret_cast<V *>(buf + zrow * stride + 4 * k) = V{};
     }
+    for (int i = tid; i < nv; i += kBlock) l_items[i] = *reinterpret_cast<const int2 *>(A.row_items + 2 * (size_t)(v0 + i));
     if (na > 0) {
         const int e0 = A.agg_row_ptr[a0], ne = A.agg_row_ptr[a0 + na] - e0;
         for (int i = tid; i <= na; i += kBlock) l_agg_ptr[i] = A.agg_row_ptr[a0 + i] - e0;
@@ -454,6 +482,8 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     // first aggregation row of every stage (rows are sorted by stage): stage st is
     // rows [st_begin[st-1], st_begin[st])
     __shared__ int st_begin[256];
+    __shared__ int next_group;
+    if (tid == 0) next_group = 0;
     for (int t = tid; t <= n_stages; t += kBlock) {
         int lo = 0, hi = na;
         while (lo < hi) {
@@ -462,14 +492,74 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
         }
         st_begin[t] = lo;
     }
+    if (A.reverse) {
+        // a consumer list holds destinations (local ids < nv) before aggregation rows (>= nv)
+        for (int j = tid; j < na; j += kBlock) {
+            int lo = l_agg_ptr[j], hi = l_agg_ptr[j + 1];
+            while (lo < hi) {
+                const int mid = (lo + hi) >> 1;
+                if ((int)l_agg_col[mid] < nv) lo = mid + 1; else hi = mid;
+            }
+            l_agg_mid[j] = lo;
+        }
+    }
     __syncthreads();
 
-    // Aggregation rows, stage by stage (forward: first stage first; transposed pass: last
-    // first).  A stage with many rows gives each sub-group a row, like the output rows below.
+    if (A.reverse && na > 0) {
+        // Gradient rows of the aggregation nodes.  First the sum over the destinations that
+        // consume each row, for all rows at once: a wavefront per row, its sub-groups on
+        // equal slices of the list, combined with cross-lane adds.
+        for (int jb = 0; jb < na; jb += NW) {
+            const int j = jb + wave;
+            const bool has = j < na;
+            const int beg = has ? l_agg_ptr[j] : 0;
+            const int cnt = has ? l_agg_mid[j] - beg : 0;
+            int per = (cnt + SG - 1) / SG;
+            per = (per + 3) & ~3;
+            const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
+            for (int kb = 0; kb < q; kb += LPR) {
+                const int k = min(kb + sl, q - 1);
+                V acc{};
+                lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k, acc);
+#pragma unroll
+                for (int off = LPR; off < kWave; off <<= 1) {
+                    V o;
+                    o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
+                    o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
+                    add4(acc, o);
+                }
+                if (has && kb + sl < q && sgw == 0) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+            }
+        }
+        __syncthreads();
+        // Then, from the last stage but one down to the first, each row adds the finished
+        // rows of the aggregation nodes built from it (two inputs per node: short lists).
+        for (int st = n_stages - 1; st >= 1; --st) {
+            const int r0 = st_begin[st - 1], r1 = st_begin[st];
+            for (int jb = r0; jb < r1; jb += NSG) {
+                const int j = jb + sg;
+                const bool has = j < r1;
+                const int beg = has ? l_agg_mid[j] : 0;
+                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
+                int maxcnt = cnt;
+#pragma unroll
+                for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
+                for (int kb = 0; kb < q; kb += LPR) {
+                    const int k = min(kb + sl, q - 1);
+                    V acc = *reinterpret_cast<const V *>(buf + (has ? nv + j : zrow) * stride + 4 * k);
+                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc);
+                    if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+                }
+            }
+            __syncthreads();
+        }
+    }
+
+    // Forward pass: aggregation rows, stage by stage.  A stage with many rows gives each
+    // sub-group a row, like the output rows below.
     // A stage with few rows gives a whole wavefront to a row: its sub-groups walk interleaved
     // slices of the list and combine with cross-lane adds.
-    for (int step = 1; step <= n_stages; ++step) {
-        const int st = A.reverse ? n_stages + 1 - step : step;
+    for (int st = 1; st <= (A.reverse ? 0 : n_stages); ++st) {
         const int r0 = st_begin[st - 1], r1 = st_begin[st];
         if (r1 - r0 > 2 * NW) {
             for (int jb = r0; jb < r1; jb += NSG) {
@@ -515,11 +605,18 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     }
 
     // rows written to global memory: forward y[v] over Nhat_v, transposed pass gx[u] over u's consumers
-    for (int vb = 0; vb < nv; vb += NSG) {
-        const int v = vb + sg;
-        const bool has = v < nv;
-        const int beg = has ? A.row_ptr[v0 + v] : 0;
-        const int cnt = has ? A.row_ptr[v0 + v + 1] - beg : 0;
+    // Rows are taken longest first, SG at a time by whichever wavefront is free: the lists a
+    // wavefront walks side by side are then equally long, and the wavefronts finish together.
+    const int n_groups = (nv + SG - 1) / SG;
+    for (;;) {
+        int g = 0;
+        if ((tid & (kWave - 1)) == 0) g = atomicAdd(&next_group, 1);
+        g = __shfl(g, 0);
+        if (g >= n_groups) break;
+        const int slot = g * SG + sgw;
+        const bool has = slot < nv;
+        const int2 item = has ? l_items[slot] : int2{0, 0};
+        const int beg = item.x, cnt = item.y & 0xffff, v = item.y >> 16;
         int maxcnt = cnt;
 #pragma unroll
         for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
@@ -700,9 +797,9 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
     return HAG_OK;
 }
 
-// LDS layout of the component-local pass: [rows + zero row][agg ptr][agg stage][agg list ids]
+// LDS layout of the component-local pass: [rows + zero row][row items][agg ptr][agg stage]([agg mid], transposed pass)[agg list ids]
 struct CompLayout {
-    size_t lists_off = 0, total = 0;   // bytes
+    size_t items_off = 0, lists_off = 0, total = 0;   // bytes
 };
 // layout.total == 0: the pass does not apply to this call
 static CompLayout component_layout(const hag_handle *h, bool naive, bool backward, hag_op_t op, int64_t d) {
@@ -716,10 +813,12 @@ static CompLayout component_layout(const hag_handle *h, bool naive, bool backwar
     const size_t stride = (size_t)d + 4;
     const size_t rows = (size_t)c.max_nodes + (naive ? 0 : (size_t)c.max_agg) + 1;
     size_t bytes = rows * stride * 4;
+    L.items_off = bytes;
+    bytes += (size_t)c.max_nodes * 8;
     L.lists_off = bytes;
     if (!naive) {
         const size_t entries = backward ? c.max_entries_bwd : c.max_entries_fwd;   // aggregation lists only
-        bytes += 2 * ((size_t)c.max_agg + 1) * 4 + entries * 2;
+        bytes += (backward ? 3 : 2) * ((size_t)c.max_agg + 1) * 4 + entries * 2;
     }
     bytes = (bytes + 15) & ~(size_t)15;
     if (bytes <= 63 * 1024) L.total = bytes;   // the kernel adds 1 KB of static LDS; 64 KB per workgroup
@@ -736,8 +835,9 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.stage = c.d_stage;
     const LocalLists &rows = BACKWARD ? (naive ? c.nbwd : c.bwd_orig) : (naive ? c.nfwd : c.fwd);
     const LocalLists &aggs = BACKWARD ? c.bwd_agg : c.fwd_agg;
-    a.row_ptr = rows.d_ptr;
+    a.row_items = rows.d_items;
     a.row_col = rows.d_col;
+    a.items_off = (int32_t)L.items_off;
     a.agg_row_ptr = aggs.d_ptr;
     a.agg_row_col = aggs.d_col;
     a.in = in;
@@ -936,6 +1036,7 @@ int hag_upload(hag_t *h, void *stream) {
         for (LocalLists *l : {&c.fwd, &c.fwd_agg, &c.bwd_orig, &c.bwd_agg, &c.nfwd, &c.nbwd}) {
             if ((rc = upload_array(h, l->ptr, &l->d_ptr, s))) goto bad;
             if ((rc = upload_array(h, l->col, &l->d_col, s))) goto bad;
+            if ((rc = upload_array(h, l->items, &l->d_items, s))) goto bad;
         }
         h->comp_uploaded = true;
     }

@@ -786,6 +786,20 @@ static void build_components(hag_handle *h) {
     localise(consumers, agg_rows_t, c.bwd_agg);
     localise(h->g, orig_rows, c.nfwd);
     localise(h->gt, orig_rows, c.nbwd);
+    for (LocalLists *l : {&c.fwd, &c.bwd_orig, &c.nfwd, &c.nbwd}) {
+        l->items.resize(2 * (size_t)n);
+        std::vector<int32_t> o((size_t)c.max_nodes);
+        for (int32_t k = 0; k < c.count; ++k) {
+            const int32_t v0 = c.node_ptr[k], nv = c.node_ptr[k + 1] - v0;
+            auto len = [&](int32_t x) { return l->ptr[v0 + x + 1] - l->ptr[v0 + x]; };
+            std::iota(o.begin(), o.begin() + nv, 0);
+            std::stable_sort(o.begin(), o.begin() + nv, [&](int32_t x, int32_t y) { return len(x) > len(y); });
+            for (int32_t i = 0; i < nv; ++i) {
+                l->items[2 * (size_t)(v0 + i)] = l->ptr[v0 + o[i]];
+                l->items[2 * (size_t)(v0 + i) + 1] = len(o[i]) | (o[i] << 16);   // both below 4096
+            }
+        }
+    }
     for (int32_t k = 0; k < c.count; ++k) {
         int32_t a0 = c.agg_ptr[k], a1 = c.agg_ptr[k + 1];
         auto span = [&](const LocalLists &l, int32_t lo, int32_t hi) { return l.ptr[hi] - l.ptr[lo]; };

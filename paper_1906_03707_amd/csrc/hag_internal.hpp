@@ -48,8 +48,14 @@ struct Plan {
 struct LocalLists {
     std::vector<int32_t> ptr;    // [rows+1] offsets into col
     std::vector<uint16_t> col;   // local ids
+    // lists of original nodes only: the rows of each component, longest list first, stored at
+    // the component's node range as {first entry in col, length | local row index << 16}, so
+    // that rows handled side by side by one wavefront are equally long and wavefronts can take
+    // them in that order
+    std::vector<int32_t> items;  // [2*rows]
     int32_t *d_ptr = nullptr;
     uint16_t *d_col = nullptr;
+    int32_t *d_items = nullptr;
 };
 struct Components {
     bool enabled = false;
