@@ -365,23 +365,32 @@ __global__ __launch_bounds__(kBlock) void level_kernel(const int32_t *__restrict
 
 // ------------------------------------------------------------------------------------------
 // Component-local pass: a batch of small graphs.  One workgroup per connected component.  Its
-// feature rows and its index lists are read from HBM once into LDS, its aggregation nodes are
-// evaluated in LDS stage by stage (Algorithm 2's loop over V_A, never touching global
-// memory), and every output row is then reduced out of LDS.  The transposed pass walks the
-// transposed lists with the stages in reverse order, but splits the gradient of an aggregation
-// row in two: the part that comes from destinations depends on nothing and is summed for all
-// aggregation rows at once by the whole workgroup; only the few terms that come from other
-// aggregation rows are added stage by stage.  Rows in LDS are padded by four elements so that
-// rows do not all start in the same bank.
+// feature rows and the short lists of its aggregation nodes are read from HBM once into LDS,
+// its aggregation nodes are evaluated in LDS stage by stage (Algorithm 2's loop over V_A,
+// never touching global memory), and every output row is then reduced out of LDS.  The
+// transposed pass walks the transposed lists with the stages in reverse order, but splits the
+// gradient of an aggregation row in two: the part that comes from destinations depends on
+// nothing and is summed in the same walk as the original rows that no aggregation node
+// consumes (all these lists are long and alike); only the few terms that come from other
+// aggregation rows are then added stage by stage, and the remaining original rows follow.
+// A workgroup is short-lived and several share a compute unit, so what bounds the pass is the
+// number of dependent LDS / memory round trips per workgroup as much as the LDS bytes moved:
+// list ids are requested one step ahead of their use, the lists of the first rows already
+// while the rows are staged, and independent reductions are batched.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 struct CompArgs {
     const int32_t *meta;         // per component: first node, #nodes, first aggregation slot, #agg | #stages << 16
-    const uint8_t *stage;        // stage of each aggregation slot
+    const uint8_t *stage;        // stage of each aggregation slot (ascending inside a component)
     // lists of the rows written to global memory: per node slot {first entry in row_col,
     // length | local row index << 16}, each component's rows sorted longest list first
     const int32_t *row_items;
     const uint16_t *row_col;
+    // Transposed pass over a HAG: the items of a component (at slot v0 + a0) cover its
+    // aggregation rows too (row index >= nv: the sum over the destinations that consume the
+    // row, kept in LDS); the first row_split[c] items depend on no aggregation row, the others
+    // are the original rows that aggregation nodes consume.  NULL: nv items at slot v0.
+    const int32_t *row_split;
     const int32_t *agg_row_ptr;  // lists of the aggregation rows kept in LDS (component-major index)
     const uint16_t *agg_row_col;
     const T *in;
@@ -389,45 +398,81 @@ struct CompArgs {
     const float *scale_in, *scale_out;
     const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
     int32_t add_self;
-    int32_t d, stride;           // feature width; padded row stride in LDS, in elements
-    int32_t items_off;           // offset of the staged row items, in bytes
+    int32_t d, stride;           // feature width; row stride in LDS, in elements
     int32_t lists_off;           // offset of the staged aggregation lists, in bytes
     int32_t max_agg;             // most aggregation rows a component has
     int32_t use_agg, reverse;
+    int32_t pairs;               // forward pass: every staged list has exactly two entries
 };
 
+// Value of lane J of the caller's sub-group of LPR lanes.  A sub-group of 16 lanes is one row of
+// the data-parallel-primitive network and one of 4 lanes is a quad, so there the broadcast is
+// a plain vector move that leaves the LDS pipe to the row reads; other widths use the
+// cross-lane read through LDS.  All lanes of the wavefront must be active.
+template <int LPR, int J>
+__device__ __forceinline__ int sub_bcast(int v) {
+    if constexpr (LPR == 16) return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, false);   // row_newbcast:J
+    else if constexpr (LPR == 4) return __builtin_amdgcn_update_dpp(0, v, J * 0x55, 0xf, 0xf, false);  // quad_perm:[J,J,J,J]
+    else return __shfl(v, J, LPR);
+}
+
+// acc += the LDS rows whose ids lanes J0..J0+3 of the sub-group hold in m
+template <typename T, int LPR, int J0>
+__device__ __forceinline__ void lds_add4rows(const T *colbuf, int stride, int m, typename V4<T>::type &acc) {
+    using V = typename V4<T>::type;
+    const int u0 = sub_bcast<LPR, J0>(m), u1 = sub_bcast<LPR, J0 + 1>(m);
+    const int u2 = sub_bcast<LPR, J0 + 2>(m), u3 = sub_bcast<LPR, J0 + 3>(m);
+    const V a = *reinterpret_cast<const V *>(colbuf + u0 * stride);
+    const V b = *reinterpret_cast<const V *>(colbuf + u1 * stride);
+    const V c = *reinterpret_cast<const V *>(colbuf + u2 * stride);
+    const V e = *reinterpret_cast<const V *>(colbuf + u3 * stride);
+    add4(acc, a); add4(acc, b); add4(acc, c); add4(acc, e);
+}
+
+// A lane's share of entries [first, first + 4*LPR) of the list col[beg .. beg+cnt): four ids,
+// `zrow` (a row of zeros) past the end.
+template <int LPR>
+__device__ __forceinline__ void load_ids(int (&m)[4], const uint16_t *col, int beg, int cnt, int first, int sl, int zrow) {
+#pragma unroll
+    for (int t = 0; t < 4; ++t) {
+        const int e = first + t * LPR + sl;
+        m[t] = (e < cnt) ? (int)col[beg + e] : zrow;
+    }
+}
+
 // Add the LDS rows listed in col[beg .. beg+cnt) into acc, for the four features at column 4*k.
-// Called by all lanes of a sub-group with a common maxcnt.  Entries past cnt read row `zrow`,
-// which holds zeros, so the inner loop has no branches.  The ids are fetched 4*LPR at a time
-// (four independent loads per lane) and the next such chunk is requested before the current
-// one is consumed, so a list costs one memory latency, not one per LPR entries.
+// Called by all lanes of a wavefront with a common maxcnt; m holds the first 4*LPR ids
+// (load_ids with first = 0).  Entries past cnt read the zero row, so the inner loop has no
+// branches.  The next 4*LPR ids are requested before the current ones are consumed.
 template <typename T, int LPR>
 __device__ __forceinline__ void lds_reduce(const T *buf, int stride, int zrow, const uint16_t *col, int beg, int cnt,
-                                           int maxcnt, int sl, int k, typename V4<T>::type &acc) {
+                                           int maxcnt, int sl, int k, const int (&m0)[4],
+                                           typename V4<T>::type &acc) {
     using V = typename V4<T>::type;
     constexpr int CH = 4 * LPR;
     const T *colbuf = buf + 4 * k;
-    int m[4], nx[4] = {zrow, zrow, zrow, zrow};
-#pragma unroll
-    for (int t = 0; t < 4; ++t) m[t] = (t * LPR + sl < cnt) ? (int)col[beg + t * LPR + sl] : zrow;
+    int m[4] = {m0[0], m0[1], m0[2], m0[3]}, nx[4] = {zrow, zrow, zrow, zrow};
     for (int base = 0; base < maxcnt; base += CH) {
-        if (base + CH < maxcnt) {
-#pragma unroll
-            for (int t = 0; t < 4; ++t) {
-                const int e = base + CH + t * LPR + sl;
-                nx[t] = (e < cnt) ? (int)col[beg + e] : zrow;
-            }
-        }
+        if (base + CH < maxcnt) load_ids<LPR>(nx, col, beg, cnt, base + CH, sl, zrow);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int b = base + t * LPR;
             const int lim = min(LPR, maxcnt - b);   // <= 0 past the end
-            for (int j = 0; j < lim; j += 4) {
-                int u[4];
+            if constexpr (LPR == 16) {
+                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, stride, m[t], acc);
+                if (lim > 4) lds_add4rows<T, LPR, 4>(colbuf, stride, m[t], acc);
+                if (lim > 8) lds_add4rows<T, LPR, 8>(colbuf, stride, m[t], acc);
+                if (lim > 12) lds_add4rows<T, LPR, 12>(colbuf, stride, m[t], acc);
+            } else if constexpr (LPR == 4) {
+                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, stride, m[t], acc);
+            } else {
+                for (int j = 0; j < lim; j += 4) {
+                    int u[4];
 #pragma unroll
-                for (int r = 0; r < 4; ++r) u[r] = __shfl(m[t], j + r, LPR);
+                    for (int r = 0; r < 4; ++r) u[r] = __shfl(m[t], j + r, LPR);
 #pragma unroll
-                for (int r = 0; r < 4; ++r) add4(acc, *reinterpret_cast<const V *>(colbuf + u[r] * stride));
+                    for (int r = 0; r < 4; ++r) add4(acc, *reinterpret_cast<const V *>(colbuf + u[r] * stride));
+                }
             }
         }
 #pragma unroll
@@ -435,20 +480,115 @@ __device__ __forceinline__ void lds_reduce(const T *buf, int stride, int zrow, c
     }
 }
 
-template <typename T, int LPR>
-__global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
+// largest value of x over the sub-groups of the caller's wavefront (x is the same in all lanes
+// of a sub-group); the result is wave-uniform
+template <int LPR>
+__device__ __forceinline__ int wave_max_over_subgroups(int x) {
+    int r = 0;
+#pragma unroll
+    for (int s = 0; s < kWave / LPR; ++s) r = max(r, __builtin_amdgcn_readlane(x, s * LPR));
+    return r;
+}
+
+// A wavefront's walk over the rows it reduces: rows come SG = 64/LPR at a time ("group"), group
+// g goes to wavefront g mod NW.  The walk keeps the item and the first list ids of the current
+// group and the item of the next one in registers, each requested a step before it is needed.
+template <int LPR>
+struct RowPipe {
+    static constexpr int SG = kWave / LPR;
+    int2 item, item_next;
+    int ids[4];
+    int n_groups;
+    __device__ __forceinline__ int2 load_item(const int32_t *items, int count, int g, int sgw) const {
+        const int slot = g * SG + sgw;
+        return (g < n_groups && slot < count) ? *reinterpret_cast<const int2 *>(items + 2 * (size_t)slot) : int2{0, 0};
+    }
+    __device__ __forceinline__ void start(const int32_t *items, int count, const uint16_t *col, int wave, int nw, int sgw,
+                                          int sl, int zrow) {
+        n_groups = (count + SG - 1) / SG;
+        item = load_item(items, count, wave, sgw);
+        item_next = load_item(items, count, wave + nw, sgw);
+        load_ids<LPR>(ids, col, item.x, item.y & 0xffff, 0, sl, zrow);
+    }
+};
+
+// Reduce `count` rows, described by items {first list entry, length | row << 16}, out of LDS.
+// A row index below nv is an original node: the result goes to global memory (with the
+// epilogue of the op); an index from nv on is an aggregation row and stays in LDS.
+template <typename T, int LPR, int NW>
+__device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, RowPipe<LPR> &pipe, const int32_t *items,
+                                               int count, const uint16_t *col, int v0, int nv, int zrow, int wave,
+                                               int sgw, int sl) {
     using V = typename V4<T>::type;
-    constexpr int NSG = kBlock / LPR;      // sub-groups per workgroup
-    constexpr int SG = kWave / LPR;        // sub-groups per wavefront
-    constexpr int NW = kBlock / kWave;
+    constexpr int SG = kWave / LPR;
+    const int q = A.d / 4, stride = A.stride;
+    for (int g = wave; g < pipe.n_groups; g += NW) {
+        // the lists of this wavefront's next group and the item of the one after it
+        int ids_next[4];
+        load_ids<LPR>(ids_next, col, pipe.item_next.x, pipe.item_next.y & 0xffff, 0, sl, zrow);
+        const int2 item_after = pipe.load_item(items, count, g + 2 * NW, sgw);
+        const bool has = g * SG + sgw < count;
+        const int beg = pipe.item.x, cnt = pipe.item.y & 0xffff, v = pipe.item.y >> 16;
+        const int maxcnt = wave_max_over_subgroups<LPR>(cnt);
+        for (int kb = 0; kb < q; kb += LPR) {
+            const int k = min(kb + sl, q - 1);
+            V acc{};
+            lds_reduce<T, LPR>(buf, stride, zrow, col, beg, cnt, maxcnt, sl, k, pipe.ids, acc);
+            if (has && kb + sl < q) {
+                if (v >= nv) {
+                    *reinterpret_cast<V *>(buf + v * stride + 4 * k) = acc;
+                } else {
+                    if (A.add_self) {
+                        // the staged row already carries scale_in, which is the factor the own row needs
+                        add4(acc, *reinterpret_cast<const V *>(buf + v * stride + 4 * k));
+                    }
+                    if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
+                    st4(A.out + (size_t)(v0 + v) * A.d + 4 * k, acc);
+                }
+            }
+        }
+        pipe.item = pipe.item_next;
+        pipe.item_next = item_after;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) pipe.ids[t] = ids_next[t];
+    }
+}
+
+// Aggregation rows [r0, r1) of one stage, a sub-group per row: row j becomes the sum of the LDS
+// rows in its staged list (plus its present content if `accumulate`).
+template <typename T, int LPR, int NSG>
+__device__ __forceinline__ void component_stage(const CompArgs<T> &A, T *buf, const int32_t *l_agg_ptr,
+                                                const uint16_t *l_agg_col, int r0, int r1, int nv, int zrow, int sg,
+                                                int sl, bool accumulate) {
+    using V = typename V4<T>::type;
+    const int q = A.d / 4, stride = A.stride;
+    for (int jb = r0; jb < r1; jb += NSG) {
+        const int j = jb + sg;
+        const bool has = j < r1;
+        const int beg = has ? l_agg_ptr[j] : 0;
+        const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
+        const int maxcnt = wave_max_over_subgroups<LPR>(cnt);
+        int m[4];
+        load_ids<LPR>(m, l_agg_col, beg, cnt, 0, sl, zrow);
+        for (int kb = 0; kb < q; kb += LPR) {
+            const int k = min(kb + sl, q - 1);
+            V acc = *reinterpret_cast<const V *>(buf + (has && accumulate ? nv + j : zrow) * stride + 4 * k);
+            lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, m, acc);
+            if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+        }
+    }
+}
+
+template <typename T, int LPR, int BLOCK>
+__global__ __launch_bounds__(BLOCK) void component_kernel(CompArgs<T> A) {
+    using V = typename V4<T>::type;
+    constexpr int NSG = BLOCK / LPR;       // sub-groups per workgroup
+    constexpr int NW = BLOCK / kWave;
     extern __shared__ __align__(16) unsigned char smem[];
+    __shared__ int st_begin[64];           // stage st is aggregation rows [st_begin[st-1], st_begin[st])
     T *buf = reinterpret_cast<T *>(smem);
-    int2 *l_items = reinterpret_cast<int2 *>(smem + A.items_off);            // [nv]
     int32_t *l_agg_ptr = reinterpret_cast<int32_t *>(smem + A.lists_off);   // [na+1], rebased
-    int32_t *l_agg_stage = l_agg_ptr + A.max_agg + 1;                        // [na]
-    // transposed pass only: first consumer of each list that is itself an aggregation row
-    int32_t *l_agg_mid = l_agg_stage + A.max_agg + 1;                        // [na]
-    uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_mid + (A.reverse ? A.max_agg + 1 : 0));
+    uint16_t *l_agg_col = reinterpret_cast<uint16_t *>(l_agg_ptr + A.max_agg + 1);
     const int c = blockIdx.x;
     const int4 meta = *reinterpret_cast<const int4 *>(A.meta + 4 * (size_t)c);   // v0, nv, a0, na | stages << 16
     const int v0 = meta.x, nv = meta.y, a0 = meta.z;
@@ -459,181 +599,77 @@ __global__ __launch_bounds__(kBlock) void component_kernel(CompArgs<T> A) {
     const int tid = threadIdx.x, sg = tid / LPR, sl = tid % LPR;
     const int wave = tid / kWave, sgw = (tid & (kWave - 1)) / LPR;
 
+    // Rows are taken SG at a time, longest list first, group g by wavefront g mod NW.  The
+    // first group's lists are requested now, the second group's items too.
+    const int32_t *items = A.row_items + 2 * (size_t)(A.row_split ? v0 + a0 : v0);
+    const int n_first = A.row_split ? A.row_split[c] : nv;       // rows that wait for no aggregation row
+    const int n_second = A.row_split ? nv + na - n_first : 0;    // rows that do
+    RowPipe<LPR> pipe;
+    pipe.start(items, n_first, A.row_col, wave, NW, sgw, sl, zrow);
+
     // stage the component: rows (forward: activations; transposed pass: seeds), the zero row,
     // and the short lists of its aggregation rows
-    for (int i = tid; i < nv * q; i += kBlock) {
+    for (int i = tid; i < nv * q; i += BLOCK) {
         const int r = i / q, k = i - r * q;
         V x = ld4(A.in + (size_t)(v0 + r) * A.d + 4 * k);
         if (A.scale_in) scale4(x, A.scale_in[v0 + r]);
         *reinterpret_cast<V *>(buf + r * stride + 4 * k) = x;
     }
-    for (int k = tid; k < q; k += kBlock) {
+    for (int k = tid; k < q; k += BLOCK) {
         *reinterpret_cast<V *>(buf + zrow * stride + 4 * k) = V{};
     }
-    for (int i = tid; i < nv; i += kBlock) l_items[i] = *reinterpret_cast<const int2 *>(A.row_items + 2 * (size_t)(v0 + i));
     if (na > 0) {
         const int e0 = A.agg_row_ptr[a0], ne = A.agg_row_ptr[a0 + na] - e0;
-        for (int i = tid; i <= na; i += kBlock) l_agg_ptr[i] = A.agg_row_ptr[a0 + i] - e0;
-        for (int i = tid; i < na; i += kBlock) l_agg_stage[i] = A.stage[a0 + i];
-        for (int i = tid; i < ne; i += kBlock) l_agg_col[i] = A.agg_row_col[e0 + i];
+        for (int i = tid; i <= na; i += BLOCK) l_agg_ptr[i] = A.agg_row_ptr[a0 + i] - e0;
+        for (int i = tid; i < ne; i += BLOCK) l_agg_col[i] = A.agg_row_col[e0 + i];
+        // every stage 1..n_stages of a component has rows, sorted by stage
+        for (int j = tid; j < na; j += BLOCK) {
+            const int s0 = A.stage[a0 + j];
+            const int s1 = (j + 1 < na) ? (int)A.stage[a0 + j + 1] : n_stages + 1;
+            for (int t = s0; t < s1; ++t) st_begin[t] = j + 1;
+        }
+        if (tid == 0) st_begin[0] = 0;
     }
     __syncthreads();
 
-    // first aggregation row of every stage (rows are sorted by stage): stage st is
-    // rows [st_begin[st-1], st_begin[st])
-    __shared__ int st_begin[256];
-    __shared__ int next_group;
-    if (tid == 0) next_group = 0;
-    for (int t = tid; t <= n_stages; t += kBlock) {
-        int lo = 0, hi = na;
-        while (lo < hi) {
-            const int mid = (lo + hi) >> 1;
-            if (l_agg_stage[mid] <= t) lo = mid + 1; else hi = mid;
-        }
-        st_begin[t] = lo;
-    }
-    if (A.reverse) {
-        // a consumer list holds destinations (local ids < nv) before aggregation rows (>= nv)
-        for (int j = tid; j < na; j += kBlock) {
-            int lo = l_agg_ptr[j], hi = l_agg_ptr[j + 1];
-            while (lo < hi) {
-                const int mid = (lo + hi) >> 1;
-                if ((int)l_agg_col[mid] < nv) lo = mid + 1; else hi = mid;
-            }
-            l_agg_mid[j] = lo;
-        }
-    }
-    __syncthreads();
-
-    if (A.reverse && na > 0) {
-        // Gradient rows of the aggregation nodes.  First the sum over the destinations that
-        // consume each row, for all rows at once: a wavefront per row, its sub-groups on
-        // equal slices of the list, combined with cross-lane adds.
-        for (int jb = 0; jb < na; jb += NW) {
-            const int j = jb + wave;
-            const bool has = j < na;
-            const int beg = has ? l_agg_ptr[j] : 0;
-            const int cnt = has ? l_agg_mid[j] - beg : 0;
-            int per = (cnt + SG - 1) / SG;
-            per = (per + 3) & ~3;
-            const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
-            for (int kb = 0; kb < q; kb += LPR) {
-                const int k = min(kb + sl, q - 1);
-                V acc{};
-                lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k, acc);
-#pragma unroll
-                for (int off = LPR; off < kWave; off <<= 1) {
-                    V o;
-                    o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
-                    o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
-                    add4(acc, o);
-                }
-                if (has && kb + sl < q && sgw == 0) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-            }
-        }
-        __syncthreads();
-        // Then, from the last stage but one down to the first, each row adds the finished
-        // rows of the aggregation nodes built from it (two inputs per node: short lists).
-        for (int st = n_stages - 1; st >= 1; --st) {
-            const int r0 = st_begin[st - 1], r1 = st_begin[st];
-            for (int jb = r0; jb < r1; jb += NSG) {
-                const int j = jb + sg;
-                const bool has = j < r1;
-                const int beg = has ? l_agg_mid[j] : 0;
-                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
-                int maxcnt = cnt;
-#pragma unroll
-                for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
-                for (int kb = 0; kb < q; kb += LPR) {
-                    const int k = min(kb + sl, q - 1);
-                    V acc = *reinterpret_cast<const V *>(buf + (has ? nv + j : zrow) * stride + 4 * k);
-                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc);
-                    if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-                }
-            }
-            __syncthreads();
-        }
-    }
-
-    // Forward pass: aggregation rows, stage by stage.  A stage with many rows gives each
-    // sub-group a row, like the output rows below.
-    // A stage with few rows gives a whole wavefront to a row: its sub-groups walk interleaved
-    // slices of the list and combine with cross-lane adds.
+    // Forward pass: aggregation rows, stage by stage (Algorithm 2's loop over V_A; the host
+    // may have expanded the lists down to original rows, then there is a single stage).
     for (int st = 1; st <= (A.reverse ? 0 : n_stages); ++st) {
         const int r0 = st_begin[st - 1], r1 = st_begin[st];
-        if (r1 - r0 > 2 * NW) {
-            for (int jb = r0; jb < r1; jb += NSG) {
-                const int j = jb + sg;
-                const bool has = j < r1;
-                const int beg = has ? l_agg_ptr[j] : 0;
-                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
-                int maxcnt = cnt;
-#pragma unroll
-                for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
-                for (int kb = 0; kb < q; kb += LPR) {
-                    const int k = min(kb + sl, q - 1);
-                    V acc{};
-                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, acc);
-                    if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
+        if (A.pairs) {
+            // two-input form: list j is entries 2j and 2j+1
+            for (int j = r0 + sg; j < r1; j += NSG) {
+                const uint32_t pair = *reinterpret_cast<const uint32_t *>(l_agg_col + 2 * j);
+                const int a = (int)(pair & 0xffffu), b = (int)(pair >> 16);
+                for (int k = sl; k < q; k += LPR) {
+                    V x = *reinterpret_cast<const V *>(buf + a * stride + 4 * k);
+                    add4(x, *reinterpret_cast<const V *>(buf + b * stride + 4 * k));
+                    *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = x;
                 }
             }
         } else {
-            for (int jb = r0; jb < r1; jb += NW) {
-                const int j = jb + wave;
-                const bool has = j < r1;
-                const int beg = has ? l_agg_ptr[j] : 0;
-                const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
-                int per = (cnt + SG - 1) / SG;
-                per = (per + 3) & ~3;
-                const int lo = min(cnt, sgw * per), hi = min(cnt, lo + per);
-                for (int kb = 0; kb < q; kb += LPR) {
-                    const int k = min(kb + sl, q - 1);
-                    V acc{};
-                    lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg + lo, hi - lo, min(cnt, per), sl, k, acc);
-#pragma unroll
-                    for (int off = LPR; off < kWave; off <<= 1) {
-                        V o;
-                        o.x = __shfl_xor(acc.x, off); o.y = __shfl_xor(acc.y, off);
-                        o.z = __shfl_xor(acc.z, off); o.w = __shfl_xor(acc.w, off);
-                        add4(acc, o);
-                    }
-                    if (has && kb + sl < q && sgw == 0) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
-                }
-            }
+            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, r0, r1, nv, zrow, sg, sl, false);
         }
         __syncthreads();
     }
 
-    // rows written to global memory: forward y[v] over Nhat_v, transposed pass gx[u] over u's consumers
-    // Rows are taken longest first, SG at a time by whichever wavefront is free: the lists a
-    // wavefront walks side by side are then equally long, and the wavefronts finish together.
-    const int n_groups = (nv + SG - 1) / SG;
-    for (;;) {
-        int g = 0;
-        if ((tid & (kWave - 1)) == 0) g = atomicAdd(&next_group, 1);
-        g = __shfl(g, 0);
-        if (g >= n_groups) break;
-        const int slot = g * SG + sgw;
-        const bool has = slot < nv;
-        const int2 item = has ? l_items[slot] : int2{0, 0};
-        const int beg = item.x, cnt = item.y & 0xffff, v = item.y >> 16;
-        int maxcnt = cnt;
-#pragma unroll
-        for (int off = LPR; off < kWave; off <<= 1) maxcnt = max(maxcnt, __shfl_xor(maxcnt, off));
-        for (int kb = 0; kb < q; kb += LPR) {
-            const int k = min(kb + sl, q - 1);
-            V acc{};
-            lds_reduce<T, LPR>(buf, stride, zrow, A.row_col, beg, cnt, maxcnt, sl, k, acc);
-            if (has && kb + sl < q) {
-                if (A.add_self) {
-                    // the staged row already carries scale_in, which is the factor the own row needs
-                    add4(acc, *reinterpret_cast<const V *>(buf + v * stride + 4 * k));
-                }
-                if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
-                const size_t o = (size_t)(v0 + v) * A.d + 4 * k;
-                st4(A.out + o, acc);
-            }
+    // forward: y[v] over Nhat_v.  Transposed pass: gx[u] over u's consumers for the rows that
+    // no aggregation node consumes, and the destination part of every aggregation row.
+    component_rows<T, LPR, NW>(A, buf, pipe, items, n_first, A.row_col, v0, nv, zrow, wave, sgw, sl);
+
+    if (n_second > 0) {
+        pipe.start(items + 2 * (size_t)n_first, n_second, A.row_col, wave, NW, sgw, sl, zrow);
+        __syncthreads();
+        // From the last stage but one down to the first, each aggregation row adds the
+        // finished rows of the aggregation nodes built from it (none of this when the host
+        // has expanded the lists of the rows below to all aggregation nodes above them).
+        for (int st = n_stages - 1; st >= 1; --st) {
+            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, st_begin[st - 1], st_begin[st], nv, zrow, sg, sl, true);
+            __syncthreads();
         }
+        // the original rows that aggregation nodes consume
+        component_rows<T, LPR, NW>(A, buf, pipe, items + 2 * (size_t)n_first, n_second, A.row_col, v0, nv, zrow, wave,
+                                   sgw, sl);
     }
 }
 
@@ -797,10 +833,17 @@ static int check_common(const hag_handle *h, hag_op_t op, hag_dtype_t dt, int64_
     return HAG_OK;
 }
 
-// LDS layout of the component-local pass: [rows + zero row][row items][agg ptr][agg stage]([agg mid], transposed pass)[agg list ids]
+// LDS layout of the component-local pass: [rows + zero row][agg ptr][agg list ids]
 struct CompLayout {
-    size_t items_off = 0, lists_off = 0, total = 0;   // bytes
+    size_t stride = 0;                                 // row stride in LDS, in elements
+    size_t lists_off = 0, total = 0;                   // bytes
 };
+// Padding of an LDS row, in elements (a multiple of 4).  Read per call: a test may change it.
+static size_t component_pad() {
+    const char *e = std::getenv("HAG_COMPONENT_PAD");
+    const long v = e ? std::atol(e) : 0;
+    return (size_t)(v < 0 ? 0 : v > 64 ? 64 : v) & ~(size_t)3;
+}
 // layout.total == 0: the pass does not apply to this call
 static CompLayout component_layout(const hag_handle *h, bool naive, bool backward, hag_op_t op, int64_t d) {
     CompLayout L;
@@ -810,18 +853,17 @@ static CompLayout component_layout(const hag_handle *h, bool naive, bool backwar
     // per element than a (value, id) comparison for every LDS row (measured: the LDS variant
     // was the slower one), and its backward pass is a scatter, not a gather.
     if (op == HAG_MAX) return L;
-    const size_t stride = (size_t)d + 4;
+    const size_t stride = (size_t)d + component_pad();
+    L.stride = stride;
     const size_t rows = (size_t)c.max_nodes + (naive ? 0 : (size_t)c.max_agg) + 1;
     size_t bytes = rows * stride * 4;
-    L.items_off = bytes;
-    bytes += (size_t)c.max_nodes * 8;
     L.lists_off = bytes;
     if (!naive) {
         const size_t entries = backward ? c.max_entries_bwd : c.max_entries_fwd;   // aggregation lists only
-        bytes += (backward ? 3 : 2) * ((size_t)c.max_agg + 1) * 4 + entries * 2;
+        bytes += ((size_t)c.max_agg + 1) * 4 + ((entries + 1) & ~(size_t)1) * 2;
     }
     bytes = (bytes + 15) & ~(size_t)15;
-    if (bytes <= 63 * 1024) L.total = bytes;   // the kernel adds 1 KB of static LDS; 64 KB per workgroup
+    if (bytes <= 63 * 1024) L.total = bytes;   // the kernel adds 256 B of static LDS; 64 KB per workgroup
     return L;
 }
 
@@ -833,11 +875,11 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     CompArgs<T> a{};
     a.meta = c.d_meta;
     a.stage = c.d_stage;
-    const LocalLists &rows = BACKWARD ? (naive ? c.nbwd : c.bwd_orig) : (naive ? c.nfwd : c.fwd);
+    const LocalLists &rows = BACKWARD ? (naive ? c.nbwd : c.bwd_all) : (naive ? c.nfwd : c.fwd);
     const LocalLists &aggs = BACKWARD ? c.bwd_agg : c.fwd_agg;
     a.row_items = rows.d_items;
     a.row_col = rows.d_col;
-    a.items_off = (int32_t)L.items_off;
+    a.row_split = rows.d_split;
     a.agg_row_ptr = aggs.d_ptr;
     a.agg_row_col = aggs.d_col;
     a.in = in;
@@ -848,19 +890,29 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.add_self = op == HAG_GCN ? 1 : 0;
     a.self_scale = nullptr;
     a.d = (int32_t)d;
-    a.stride = (int32_t)d + 4;
+    a.stride = (int32_t)L.stride;
     a.use_agg = naive ? 0 : 1;
     a.reverse = BACKWARD ? 1 : 0;
+    a.pairs = (!BACKWARD && !c.expanded) ? 1 : 0;
     a.lists_off = (int32_t)L.lists_off;
     a.max_agg = c.max_agg;
-    const dim3 grid((unsigned)c.count), block(kBlock);
+    // A workgroup whose LDS footprint lets fewer than 8 of them share a compute unit brings 8
+    // wavefronts instead of 4, so that the unit still holds its 32 wavefronts: the pass spends
+    // much of its time waiting (staging, short dependent stages), not moving LDS bytes.
+    bool wide = L.total + 256 > (160 * 1024) / 8;
+    if (const char *e = std::getenv("HAG_COMPONENT_WIDE")) wide = std::atoi(e) != 0;   // read per call
+    const dim3 grid((unsigned)c.count), block(wide ? 2 * kBlock : kBlock);
+#define HAG_COMPONENT_LAUNCH(LPR_)                                                                                \
+    if (wide) hipLaunchKernelGGL((component_kernel<T, LPR_, 2 * kBlock>), grid, block, L.total, s, a);           \
+    else hipLaunchKernelGGL((component_kernel<T, LPR_, kBlock>), grid, block, L.total, s, a)
     switch (pick_lpr(d)) {
-        case 4: hipLaunchKernelGGL((component_kernel<T, 4>), grid, block, L.total, s, a); break;
-        case 8: hipLaunchKernelGGL((component_kernel<T, 8>), grid, block, L.total, s, a); break;
-        case 16: hipLaunchKernelGGL((component_kernel<T, 16>), grid, block, L.total, s, a); break;
-        case 32: hipLaunchKernelGGL((component_kernel<T, 32>), grid, block, L.total, s, a); break;
-        default: hipLaunchKernelGGL((component_kernel<T, 64>), grid, block, L.total, s, a); break;
+        case 4: HAG_COMPONENT_LAUNCH(4); break;
+        case 8: HAG_COMPONENT_LAUNCH(8); break;
+        case 16: HAG_COMPONENT_LAUNCH(16); break;
+        case 32: HAG_COMPONENT_LAUNCH(32); break;
+        default: HAG_COMPONENT_LAUNCH(64); break;
     }
+#undef HAG_COMPONENT_LAUNCH
     HIP_TRY(hipGetLastError());
     return HAG_OK;
 }
@@ -1033,7 +1085,8 @@ int hag_upload(hag_t *h, void *stream) {
         Components &c = h->comp;
         if ((rc = upload_array(h, c.meta, &c.d_meta, s))) goto bad;
         if ((rc = upload_array(h, c.stage, &c.d_stage, s))) goto bad;
-        for (LocalLists *l : {&c.fwd, &c.fwd_agg, &c.bwd_orig, &c.bwd_agg, &c.nfwd, &c.nbwd}) {
+        for (LocalLists *l : {&c.fwd, &c.fwd_agg, &c.bwd_all, &c.bwd_agg, &c.nfwd, &c.nbwd}) {
+            if ((rc = upload_array(h, l->split, &l->d_split, s))) goto bad;
             if ((rc = upload_array(h, l->ptr, &l->d_ptr, s))) goto bad;
             if ((rc = upload_array(h, l->col, &l->d_col, s))) goto bad;
             if ((rc = upload_array(h, l->items, &l->d_items, s))) goto bad;

@@ -731,11 +731,10 @@ static void build_components(hag_handle *h) {
     if (c.max_nodes + c.max_agg > 4096) return;  // local ids are 16 bit and must fit LDS anyway
     // local id of every unified id
     std::vector<int32_t> local(n + a), fill(c.agg_ptr.begin(), c.agg_ptr.end() - 1);
-    // Inside LDS a barrier is cheap and every row read costs the same, so the component pass
-    // keeps the paper's two-input form: one stage per level, no fusion of levels.
+    // One stage per level, in the paper's two-input form (unless the lists are expanded, below)
     c.stage.resize(a);
     c.n_stages.assign(c.count, 0);
-    if (h->levels > 255) return;
+    if (h->levels > 63) return;                  // the kernel keeps one offset per level in LDS
     std::vector<int32_t> slot_of(a);             // component-major index of aggregation node i
     for (int64_t v = 0; v < n; ++v) local[v] = (int32_t)v - c.node_ptr[comp_of[v]];
     for (int32_t lv = 0; lv < h->levels; ++lv)
@@ -754,6 +753,49 @@ static void build_components(hag_handle *h) {
     pairs.col.resize(2 * (size_t)a);
     for (int64_t i = 0; i <= a; ++i) pairs.ptr[i] = 2 * i;
     for (int64_t i = 0; i < a; ++i) { pairs.col[2 * i] = h->left[i]; pairs.col[2 * i + 1] = h->right[i]; }
+    // Expanded form: every aggregation row as the sum of the original rows it covers
+    // (Section 3.1: aggr(w) is the aggregate over cover(w)), so that all of them are computed
+    // in one stage, and, transposed, every original row that aggregation nodes consume takes
+    // the destination parts of all aggregation nodes above it.  Used when the covers are
+    // small (a handful of nodes each), which removes every dependent stage but one.
+    Csr cover;
+    bool expanded = true;
+    {
+        const int64_t forced = env_i64("HAG_COMPONENT_EXPAND", -1);
+        const size_t limit = forced == 1 ? (size_t)INT32_MAX / 2 : forced == 0 ? 0 : 4 * (size_t)a + 64;
+        cover.ptr.assign(1, 0);
+        for (int64_t i = 0; i < a && expanded; ++i) {
+            for (int32_t u : {h->left[i], h->right[i]}) {
+                if (u < n) {
+                    cover.col.push_back(u);
+                } else {
+                    // u's cover is already complete and lies before the insertion point
+                    const size_t b = (size_t)cover.ptr[u - n], e = (size_t)cover.ptr[u - n + 1];
+                    cover.col.reserve(cover.col.size() + (e - b));
+                    for (size_t t = b; t < e; ++t) cover.col.push_back(cover.col[t]);
+                }
+            }
+            cover.ptr.push_back((int64_t)cover.col.size());
+            if (cover.col.size() > limit) expanded = false;
+        }
+        if (a == 0) expanded = false;
+    }
+    if (expanded) {
+        std::fill(c.stage.begin(), c.stage.end(), (uint8_t)1);
+        for (int32_t k = 0; k < c.count; ++k) c.n_stages[k] = agg_count[k] > 0 ? 1 : 0;
+    }
+    c.expanded = expanded;
+    // aggregation nodes above every original node (those whose cover holds it)
+    Csr above;
+    if (expanded) {
+        above.ptr.assign(n + 1, 0);
+        for (int32_t u : cover.col) above.ptr[u + 1]++;
+        for (int64_t u = 0; u < n; ++u) above.ptr[u + 1] += above.ptr[u];
+        above.col.resize(cover.col.size());
+        std::vector<int64_t> at(above.ptr.begin(), above.ptr.end() - 1);
+        for (int64_t i = 0; i < a; ++i)
+            for (int64_t t = cover.ptr[i]; t < cover.ptr[i + 1]; ++t) above.col[at[cover.col[t]]++] = (int32_t)(n + i);
+    }
     consumers.ptr.assign(n + a + 1, 0);
     for (int32_t x : h->hf.col) consumers.ptr[x + 1]++;
     for (int32_t x : pairs.col) consumers.ptr[x + 1]++;
@@ -781,12 +823,69 @@ static void build_components(hag_handle *h) {
     std::iota(orig_rows.begin(), orig_rows.end(), 0);
     for (int64_t i = 0; i < a; ++i) { agg_rows[slot_of[i]] = i; agg_rows_t[slot_of[i]] = n + i; }
     localise(h->hf, orig_rows, c.fwd);
-    localise(pairs, agg_rows, c.fwd_agg);
-    localise(consumers, orig_rows, c.bwd_orig);
-    localise(consumers, agg_rows_t, c.bwd_agg);
+    localise(expanded ? cover : pairs, agg_rows, c.fwd_agg);
+    LocalLists bwd_orig;
+    localise(consumers, orig_rows, bwd_orig);
+    // consumers of an aggregation row: destinations first (they were filled in first), then
+    // aggregation nodes; the two parts are used apart
+    LocalLists bwd_agg_full;
+    localise(consumers, agg_rows_t, bwd_agg_full);
+    std::vector<int32_t> agg_mid((size_t)a);
+    c.bwd_agg.ptr.assign(1, 0);
+    c.bwd_agg.col.clear();
+    for (int64_t slot = 0; slot < a; ++slot) {
+        const int32_t k = comp_of[agg_rows_t[slot]], nv = c.node_ptr[k + 1] - c.node_ptr[k];
+        int32_t m = bwd_agg_full.ptr[slot];
+        while (m < bwd_agg_full.ptr[slot + 1] && bwd_agg_full.col[m] < nv) ++m;
+        agg_mid[slot] = m;
+        if (!expanded)
+            c.bwd_agg.col.insert(c.bwd_agg.col.end(), bwd_agg_full.col.begin() + m,
+                                 bwd_agg_full.col.begin() + bwd_agg_full.ptr[slot + 1]);
+        c.bwd_agg.ptr.push_back((int32_t)c.bwd_agg.col.size());
+    }
     localise(h->g, orig_rows, c.nfwd);
     localise(h->gt, orig_rows, c.nbwd);
-    for (LocalLists *l : {&c.fwd, &c.bwd_orig, &c.nfwd, &c.nbwd}) {
+    {
+        // transposed pass: one item list per component over original and aggregation rows
+        LocalLists &l = c.bwd_all;
+        const int32_t off_agg = (int32_t)bwd_orig.col.size();
+        l.col = bwd_orig.col;
+        l.col.insert(l.col.end(), bwd_agg_full.col.begin(), bwd_agg_full.col.end());
+        l.items.resize(2 * (size_t)(n + a));
+        l.split.resize((size_t)c.count);
+        struct Row { int32_t beg, len, row; };
+        std::vector<Row> first, second;
+        for (int32_t k = 0; k < c.count; ++k) {
+            const int32_t v0 = c.node_ptr[k], nv = c.node_ptr[k + 1] - v0, a0 = c.agg_ptr[k], a1 = c.agg_ptr[k + 1];
+            first.clear();
+            second.clear();
+            for (int32_t j = a0; j < a1; ++j)
+                first.push_back({off_agg + bwd_agg_full.ptr[j], agg_mid[j] - bwd_agg_full.ptr[j], nv + (j - a0)});
+            for (int32_t v = 0; v < nv; ++v) {
+                const int32_t b = bwd_orig.ptr[v0 + v], e = bwd_orig.ptr[v0 + v + 1];
+                const bool feeds_agg = e > b && bwd_orig.col[e - 1] >= nv;   // aggregation consumers come last
+                if (feeds_agg && expanded) {
+                    // destinations, then every aggregation node above v instead of the direct ones
+                    const int32_t nb = (int32_t)l.col.size();
+                    for (int32_t t = b; t < e && bwd_orig.col[t] < nv; ++t) l.col.push_back(bwd_orig.col[t]);
+                    for (int64_t t = above.ptr[v0 + v]; t < above.ptr[v0 + v + 1]; ++t)
+                        l.col.push_back((uint16_t)local[above.col[t]]);
+                    second.push_back({nb, (int32_t)l.col.size() - nb, v});
+                } else {
+                    (feeds_agg ? second : first).push_back({b, e - b, v});
+                }
+            }
+            auto longer = [](const Row &x, const Row &y) { return x.len > y.len; };
+            std::stable_sort(first.begin(), first.end(), longer);
+            std::stable_sort(second.begin(), second.end(), longer);
+            l.split[k] = (int32_t)first.size();
+            int32_t *o = l.items.data() + 2 * (size_t)(v0 + a0);
+            for (const std::vector<Row> *part : {&first, &second})
+                for (const Row &r : *part) { *o++ = r.beg; *o++ = r.len | (r.row << 16); }
+        }
+    }
+    if (c.bwd_all.col.size() >= (size_t)INT32_MAX) return;
+    for (LocalLists *l : {&c.fwd, &c.nfwd, &c.nbwd}) {
         l->items.resize(2 * (size_t)n);
         std::vector<int32_t> o((size_t)c.max_nodes);
         for (int32_t k = 0; k < c.count; ++k) {

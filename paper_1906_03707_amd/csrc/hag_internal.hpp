@@ -53,12 +53,16 @@ struct LocalLists {
     // that rows handled side by side by one wavefront are equally long and wavefronts can take
     // them in that order
     std::vector<int32_t> items;  // [2*rows]
+    // transposed HAG lists only (see bwd_all): items per component that wait for no aggregation row
+    std::vector<int32_t> split;  // [components]
     int32_t *d_ptr = nullptr;
     uint16_t *d_col = nullptr;
     int32_t *d_items = nullptr;
+    int32_t *d_split = nullptr;
 };
 struct Components {
     bool enabled = false;
+    bool expanded = false;                   // aggregation lists are expressed over original rows (one stage)
     int32_t count = 0;
     int32_t max_nodes = 0, max_agg = 0;      // largest nv and na over the components
     // most aggregation-list entries one component has, per pass (sizes their LDS staging area)
@@ -68,7 +72,12 @@ struct Components {
     std::vector<uint8_t> stage;              // [a] stage of the node (1-based), component-major
     std::vector<uint8_t> n_stages;           // [count] last stage the component takes part in
     LocalLists fwd, fwd_agg;                 // Nhat_v of original nodes; staged inputs of aggregation nodes
-    LocalLists bwd_orig, bwd_agg;            // consumers of original nodes / of aggregation nodes (staged form)
+    LocalLists bwd_agg;                      // per aggregation node, the aggregation nodes that consume it
+    // Transposed pass: col = consumers of original nodes, then those of aggregation nodes; the
+    // items of component k sit at slot node_ptr[k] + agg_ptr[k] and cover its original rows
+    // (whole list) and its aggregation rows (the destinations that consume them, row index >= its node count):
+    // first the split[k] rows that no aggregation node consumes, then the others.
+    LocalLists bwd_all;
     LocalLists nfwd, nbwd;                   // the input graph and its transpose (naive baseline)
     std::vector<int32_t> meta;               // [4*count] first node, #nodes, first slot, #agg | #stages << 16
     int32_t *d_meta = nullptr;

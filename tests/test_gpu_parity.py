@@ -142,10 +142,13 @@ def ragged_batch(sizes, p, seed):
     return rowptr, cols.astype(np.int32), np.concatenate([[0], np.cumsum(sizes)]).astype(np.int64)
 
 
+@pytest.mark.parametrize("expand", ["0", "1"])
 @pytest.mark.parametrize("d", [16, 64, 260])
-def test_component_local_pass_on_graph_batches(B, d, monkeypatch):
+def test_component_local_pass_on_graph_batches(B, d, expand, monkeypatch):
     # a batch of small graphs runs as one launch per pass out of LDS (one workgroup per graph):
-    # ragged sizes incl. isolated nodes and graphs without aggregation nodes, all ops and dtypes
+    # ragged sizes incl. isolated nodes and graphs without aggregation nodes, all ops and dtypes;
+    # aggregation rows stage by stage in two-input form ("0") or expanded to original rows ("1")
+    monkeypatch.setenv("HAG_COMPONENT_EXPAND", expand)
     sizes = np.random.default_rng(61).integers(1, 41, size=150)
     rowptr, col, gp = ragged_batch(sizes, 0.6, seed=62)
     assert rowptr.size - 1 >= 1024
