@@ -29,6 +29,8 @@ MEASURED_TRAFFIC_BYTES = {
     ("config2:holme_kim56944", 128, "sum"): 309411 * 2048 + 28472 * 1024,
     # profiles/pmc_config3_dcsbm232965_d128_sum.txt: FETCH_SIZE 6639360 x 2048 B + WRITE_SIZE 898966 x 1024 B
     ("config3:dcsbm232965", 128, "sum"): 6639360 * 2048 + 898966 * 1024,
+    # profiles/pmc_config4_er_batch5000x74_d64_sum.txt (component_kernel, hag_forward): FETCH_SIZE 74199 x 2048 B + WRITE_SIZE 92500 x 1024 B
+    ("config4:er_batch5000x74", 64, "sum"): 74199 * 2048 + 92500 * 1024,
 }
 
 
@@ -341,19 +343,28 @@ def main():
     ms_naive_cold = time_cold(step_naive)
     copy_gbps = copy_ceiling_GBps()
 
-    # dominant kernel: the final gather of hag_forward (one launch per step), timed inside the step
+    # dominant kernel, timed inside the step: the final gather of hag_forward (one launch per step), or, for a
+    # batch of small graphs, the one launch that is the whole forward pass and serves every row read from LDS
     P = binding
-    ms_gather = time_kernel(
-        torch,
-        lambda: h.forward_phases(x, P.HAG_PHASE_LEVELS, op, y=y, argmax=am),
-        lambda: h.forward_phases(x, P.HAG_PHASE_GATHER, op, y=y, argmax=am),
-        lambda: (h.forward_phases(x, P.HAG_PHASE_FOLD, op, y=y, argmax=am), h.backward(gy, op, argmax=am, gx=gx)),
-        args.steps, args.warmup)
     row = 4 * d
-    gather_bytes = (row + 4) * st["h"] + (row + 16) * n       # row reads + index reads, row writes + schedule
-    if op == "max":
-        gather_bytes += row * n                               # argmax rows written beside the values
-    kernel_name = f"gather_kernel<float, {1 if op == 'max' else 0}, {min(64, max(4, 1 << (max(d // 4, 1) - 1).bit_length()))}, 0>"
+    lpr = min(64, max(4, 1 << (max(d // 4, 1) - 1).bit_length()))
+    component_pass = st.get("components", 0) > 0 and op != "max" and os.environ.get("HAG_COMPONENT", "1") != "0"
+    if component_pass:
+        ms_gather = time_kernel(torch, lambda: None, lambda: h.forward(x, op, y=y, argmax=am),
+                                lambda: h.backward(gy, op, argmax=am, gx=gx), args.steps, args.warmup)
+        gather_bytes = h.algorithmic_bytes(0, op, d)
+        kernel_name = f"component_kernel<float, {lpr}, 256, 0>"
+    else:
+        ms_gather = time_kernel(
+            torch,
+            lambda: h.forward_phases(x, P.HAG_PHASE_LEVELS, op, y=y, argmax=am),
+            lambda: h.forward_phases(x, P.HAG_PHASE_GATHER, op, y=y, argmax=am),
+            lambda: (h.forward_phases(x, P.HAG_PHASE_FOLD, op, y=y, argmax=am), h.backward(gy, op, argmax=am, gx=gx)),
+            args.steps, args.warmup)
+        gather_bytes = (row + 4) * st["h"] + (row + 16) * n   # row reads + index reads, row writes + schedule
+        if op == "max":
+            gather_bytes += row * n                           # argmax rows written beside the values
+        kernel_name = f"gather_kernel<float, {1 if op == 'max' else 0}, {lpr}, 0>"
     achieved = gather_bytes / (ms_gather * 1e-3) / 1e9
     workload = f"config{cfg}:{synth.CONFIGS[cfg]['name']}"
     traffic = MEASURED_TRAFFIC_BYTES.get((workload, d, op))

@@ -579,7 +579,9 @@ __device__ __forceinline__ void component_stage(const CompArgs<T> &A, T *buf, co
     }
 }
 
-template <typename T, int LPR, int BLOCK>
+// ROLE only gives each use its own symbol in profiles: 0 = HAG forward, 1 = HAG transposed
+// pass, 2 = input graph forward (baseline), 3 = its transposed pass.
+template <typename T, int LPR, int BLOCK, int ROLE>
 __global__ __launch_bounds__(BLOCK) void component_kernel(CompArgs<T> A) {
     using V = typename V4<T>::type;
     constexpr int NSG = BLOCK / LPR;       // sub-groups per workgroup
@@ -896,15 +898,12 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.pairs = (!BACKWARD && !c.expanded) ? 1 : 0;
     a.lists_off = (int32_t)L.lists_off;
     a.max_agg = c.max_agg;
-    // A workgroup whose LDS footprint lets fewer than 8 of them share a compute unit brings 8
-    // wavefronts instead of 4, so that the unit still holds its 32 wavefronts: the pass spends
-    // much of its time waiting (staging, short dependent stages), not moving LDS bytes.
-    bool wide = L.total + 256 > (160 * 1024) / 8;
-    if (const char *e = std::getenv("HAG_COMPONENT_WIDE")) wide = std::atoi(e) != 0;   // read per call
-    const dim3 grid((unsigned)c.count), block(wide ? 2 * kBlock : kBlock);
-#define HAG_COMPONENT_LAUNCH(LPR_)                                                                                \
-    if (wide) hipLaunchKernelGGL((component_kernel<T, LPR_, 2 * kBlock>), grid, block, L.total, s, a);           \
-    else hipLaunchKernelGGL((component_kernel<T, LPR_, kBlock>), grid, block, L.total, s, a)
+    // 4 wavefronts per workgroup: 8 were measured slower even where LDS lets only 6 workgroups share
+    // a compute unit (fewer, longer row groups per wavefront balance worse)
+    const dim3 grid((unsigned)c.count), block(kBlock);
+#define HAG_COMPONENT_LAUNCH(LPR_)                                                                                  \
+    if (naive) hipLaunchKernelGGL((component_kernel<T, LPR_, kBlock, 2 + (BACKWARD ? 1 : 0)>), grid, block, L.total, s, a); \
+    else hipLaunchKernelGGL((component_kernel<T, LPR_, kBlock, BACKWARD ? 1 : 0>), grid, block, L.total, s, a)
     switch (pick_lpr(d)) {
         case 4: HAG_COMPONENT_LAUNCH(4); break;
         case 8: HAG_COMPONENT_LAUNCH(8); break;
