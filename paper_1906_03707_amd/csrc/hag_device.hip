@@ -840,7 +840,9 @@ struct CompLayout {
     size_t stride = 0;                                 // row stride in LDS, in elements
     size_t lists_off = 0, total = 0;                   // bytes
 };
-// Padding of an LDS row, in elements (a multiple of 4).  Read per call: a test may change it.
+// Padding of an LDS row, in elements (a multiple of 4); none by default: 16-byte LDS reads of
+// whole rows by sub-groups of lanes were measured fastest when the row stride is the row
+// itself, and any padding made them collide in the banks.  Read per call.
 static size_t component_pad() {
     const char *e = std::getenv("HAG_COMPONENT_PAD");
     const long v = e ? std::atol(e) : 0;

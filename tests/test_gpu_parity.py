@@ -223,12 +223,22 @@ def test_self_loops_and_dedup(B):
     run_all_ops(B, h, rp2, c2, 32, seed=52)
 
 
-def test_forward_backward_inside_a_hip_graph(B):
+@pytest.mark.parametrize("kind", ["power_law", "graph_batch"])
+def test_forward_backward_inside_a_hip_graph(B, kind):
     # the device entry points allocate nothing, never synchronise and clear memory with kernels, so a
     # whole step can be captured once and replayed; every replay must reproduce the eager result
-    rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=71)
-    n, d = rowptr.size - 1, 64
-    h = B.hag_search(rowptr, col, n // 4).upload()
+    # (graph_batch: sum / mean run as the one-launch component-local pass, max on the generic kernels)
+    if kind == "power_law":
+        rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=71)
+        n = rowptr.size - 1
+        h = B.hag_search(rowptr, col, n // 4).upload()
+    else:
+        sizes = np.random.default_rng(74).integers(8, 41, size=120)
+        rowptr, col, gp = ragged_batch(sizes, 0.6, seed=75)
+        n = rowptr.size - 1
+        h = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+        assert h.stats()["components"] >= 64
+    d = 64
     assert h.stats()["levels"] >= 2
     x = dev(synth.features_f32(n, d, 72))
     gy = dev(synth.features_f32(n, d, 73))
