@@ -411,32 +411,42 @@ struct CompArgs {
 // cross-lane read through LDS.  All lanes of the wavefront must be active.
 template <int LPR, int J>
 __device__ __forceinline__ int sub_bcast(int v) {
-    if constexpr (LPR == 16) return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, false);   // row_newbcast:J
-    else if constexpr (LPR == 4) return __builtin_amdgcn_update_dpp(0, v, J * 0x55, 0xf, 0xf, false);  // quad_perm:[J,J,J,J]
+    // every lane is written, so the "old" operand and the bound control do not matter; zero
+    // fill lets the compiler fold the move into the instruction that consumes it
+    if constexpr (LPR == 16) return __builtin_amdgcn_update_dpp(0, v, 0x150 + J, 0xf, 0xf, true);   // row_newbcast:J
+    else if constexpr (LPR == 4) return __builtin_amdgcn_update_dpp(0, v, J * 0x55, 0xf, 0xf, true);  // quad_perm:[J,J,J,J]
     else return __shfl(v, J, LPR);
 }
 
-// acc += the LDS rows whose ids lanes J0..J0+3 of the sub-group hold in m
+// acc += the LDS rows whose byte offsets lanes J0..J0+3 of the sub-group hold in m
 template <typename T, int LPR, int J0>
-__device__ __forceinline__ void lds_add4rows(const T *colbuf, int stride, int m, typename V4<T>::type &acc) {
+__device__ __forceinline__ void lds_add4rows(const unsigned char *colbuf, int m, typename V4<T>::type &acc) {
     using V = typename V4<T>::type;
     const int u0 = sub_bcast<LPR, J0>(m), u1 = sub_bcast<LPR, J0 + 1>(m);
     const int u2 = sub_bcast<LPR, J0 + 2>(m), u3 = sub_bcast<LPR, J0 + 3>(m);
-    const V a = *reinterpret_cast<const V *>(colbuf + u0 * stride);
-    const V b = *reinterpret_cast<const V *>(colbuf + u1 * stride);
-    const V c = *reinterpret_cast<const V *>(colbuf + u2 * stride);
-    const V e = *reinterpret_cast<const V *>(colbuf + u3 * stride);
+    const V a = *reinterpret_cast<const V *>(colbuf + u0);
+    const V b = *reinterpret_cast<const V *>(colbuf + u1);
+    const V c = *reinterpret_cast<const V *>(colbuf + u2);
+    const V e = *reinterpret_cast<const V *>(colbuf + u3);
     add4(acc, a); add4(acc, b); add4(acc, c); add4(acc, e);
 }
 
-// A lane's share of entries [first, first + 4*LPR) of the list col[beg .. beg+cnt): four ids,
-// `zrow` (a row of zeros) past the end.
+// Row ids and what a list entry becomes in registers: the byte offset of its LDS row, so that
+// the multiplication is done once per entry by the lane that loaded it, not once per row read.
+struct RowOffsets {
+    int row_bytes;   // LDS row stride in bytes
+    int zero;        // offset of the row of zeros / "nothing"
+};
+
+// A lane's share of entries [first, first + 4*LPR) of the list col[beg .. beg+cnt): four row
+// offsets, that of the zero row past the end.
 template <int LPR>
-__device__ __forceinline__ void load_ids(int (&m)[4], const uint16_t *col, int beg, int cnt, int first, int sl, int zrow) {
+__device__ __forceinline__ void load_ids(int (&m)[4], const uint16_t *col, int beg, int cnt, int first, int sl,
+                                         RowOffsets ro) {
 #pragma unroll
     for (int t = 0; t < 4; ++t) {
         const int e = first + t * LPR + sl;
-        m[t] = (e < cnt) ? (int)col[beg + e] : zrow;
+        m[t] = (e < cnt) ? (int)col[beg + e] * ro.row_bytes : ro.zero;
     }
 }
 
@@ -445,33 +455,33 @@ __device__ __forceinline__ void load_ids(int (&m)[4], const uint16_t *col, int b
 // (load_ids with first = 0).  Entries past cnt read the zero row, so the inner loop has no
 // branches.  The next 4*LPR ids are requested before the current ones are consumed.
 template <typename T, int LPR>
-__device__ __forceinline__ void lds_reduce(const T *buf, int stride, int zrow, const uint16_t *col, int beg, int cnt,
+__device__ __forceinline__ void lds_reduce(const T *buf, RowOffsets ro, const uint16_t *col, int beg, int cnt,
                                            int maxcnt, int sl, int k, const int (&m0)[4],
                                            typename V4<T>::type &acc) {
     using V = typename V4<T>::type;
     constexpr int CH = 4 * LPR;
-    const T *colbuf = buf + 4 * k;
-    int m[4] = {m0[0], m0[1], m0[2], m0[3]}, nx[4] = {zrow, zrow, zrow, zrow};
+    const unsigned char *colbuf = reinterpret_cast<const unsigned char *>(buf + 4 * k);
+    int m[4] = {m0[0], m0[1], m0[2], m0[3]}, nx[4] = {ro.zero, ro.zero, ro.zero, ro.zero};
     for (int base = 0; base < maxcnt; base += CH) {
-        if (base + CH < maxcnt) load_ids<LPR>(nx, col, beg, cnt, base + CH, sl, zrow);
+        if (base + CH < maxcnt) load_ids<LPR>(nx, col, beg, cnt, base + CH, sl, ro);
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             const int b = base + t * LPR;
             const int lim = min(LPR, maxcnt - b);   // <= 0 past the end
             if constexpr (LPR == 16) {
-                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, stride, m[t], acc);
-                if (lim > 4) lds_add4rows<T, LPR, 4>(colbuf, stride, m[t], acc);
-                if (lim > 8) lds_add4rows<T, LPR, 8>(colbuf, stride, m[t], acc);
-                if (lim > 12) lds_add4rows<T, LPR, 12>(colbuf, stride, m[t], acc);
+                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, m[t], acc);
+                if (lim > 4) lds_add4rows<T, LPR, 4>(colbuf, m[t], acc);
+                if (lim > 8) lds_add4rows<T, LPR, 8>(colbuf, m[t], acc);
+                if (lim > 12) lds_add4rows<T, LPR, 12>(colbuf, m[t], acc);
             } else if constexpr (LPR == 4) {
-                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, stride, m[t], acc);
+                if (lim > 0) lds_add4rows<T, LPR, 0>(colbuf, m[t], acc);
             } else {
                 for (int j = 0; j < lim; j += 4) {
                     int u[4];
 #pragma unroll
                     for (int r = 0; r < 4; ++r) u[r] = __shfl(m[t], j + r, LPR);
 #pragma unroll
-                    for (int r = 0; r < 4; ++r) add4(acc, *reinterpret_cast<const V *>(colbuf + u[r] * stride));
+                    for (int r = 0; r < 4; ++r) add4(acc, *reinterpret_cast<const V *>(colbuf + u[r]));
                 }
             }
         }
@@ -504,11 +514,11 @@ struct RowPipe {
         return (g < n_groups && slot < count) ? *reinterpret_cast<const int2 *>(items + 2 * (size_t)slot) : int2{0, 0};
     }
     __device__ __forceinline__ void start(const int32_t *items, int count, const uint16_t *col, int wave, int nw, int sgw,
-                                          int sl, int zrow) {
+                                          int sl, RowOffsets ro) {
         n_groups = (count + SG - 1) / SG;
         item = load_item(items, count, wave, sgw);
         item_next = load_item(items, count, wave + nw, sgw);
-        load_ids<LPR>(ids, col, item.x, item.y & 0xffff, 0, sl, zrow);
+        load_ids<LPR>(ids, col, item.x, item.y & 0xffff, 0, sl, ro);
     }
 };
 
@@ -517,7 +527,7 @@ struct RowPipe {
 // epilogue of the op); an index from nv on is an aggregation row and stays in LDS.
 template <typename T, int LPR, int NW>
 __device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, RowPipe<LPR> &pipe, const int32_t *items,
-                                               int count, const uint16_t *col, int v0, int nv, int zrow, int wave,
+                                               int count, const uint16_t *col, int v0, int nv, RowOffsets ro, int wave,
                                                int sgw, int sl) {
     using V = typename V4<T>::type;
     constexpr int SG = kWave / LPR;
@@ -525,7 +535,7 @@ __device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, Row
     for (int g = wave; g < pipe.n_groups; g += NW) {
         // the lists of this wavefront's next group and the item of the one after it
         int ids_next[4];
-        load_ids<LPR>(ids_next, col, pipe.item_next.x, pipe.item_next.y & 0xffff, 0, sl, zrow);
+        load_ids<LPR>(ids_next, col, pipe.item_next.x, pipe.item_next.y & 0xffff, 0, sl, ro);
         const int2 item_after = pipe.load_item(items, count, g + 2 * NW, sgw);
         const bool has = g * SG + sgw < count;
         const int beg = pipe.item.x, cnt = pipe.item.y & 0xffff, v = pipe.item.y >> 16;
@@ -533,7 +543,7 @@ __device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, Row
         for (int kb = 0; kb < q; kb += LPR) {
             const int k = min(kb + sl, q - 1);
             V acc{};
-            lds_reduce<T, LPR>(buf, stride, zrow, col, beg, cnt, maxcnt, sl, k, pipe.ids, acc);
+            lds_reduce<T, LPR>(buf, ro, col, beg, cnt, maxcnt, sl, k, pipe.ids, acc);
             if (has && kb + sl < q) {
                 if (v >= nv) {
                     *reinterpret_cast<V *>(buf + v * stride + 4 * k) = acc;
@@ -558,7 +568,8 @@ __device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, Row
 // rows in its staged list (plus its present content if `accumulate`).
 template <typename T, int LPR, int NSG>
 __device__ __forceinline__ void component_stage(const CompArgs<T> &A, T *buf, const int32_t *l_agg_ptr,
-                                                const uint16_t *l_agg_col, int r0, int r1, int nv, int zrow, int sg,
+                                                const uint16_t *l_agg_col, int r0, int r1, int nv, int zrow,
+                                                RowOffsets ro, int sg,
                                                 int sl, bool accumulate) {
     using V = typename V4<T>::type;
     const int q = A.d / 4, stride = A.stride;
@@ -569,11 +580,11 @@ __device__ __forceinline__ void component_stage(const CompArgs<T> &A, T *buf, co
         const int cnt = has ? l_agg_ptr[j + 1] - beg : 0;
         const int maxcnt = wave_max_over_subgroups<LPR>(cnt);
         int m[4];
-        load_ids<LPR>(m, l_agg_col, beg, cnt, 0, sl, zrow);
+        load_ids<LPR>(m, l_agg_col, beg, cnt, 0, sl, ro);
         for (int kb = 0; kb < q; kb += LPR) {
             const int k = min(kb + sl, q - 1);
             V acc = *reinterpret_cast<const V *>(buf + (has && accumulate ? nv + j : zrow) * stride + 4 * k);
-            lds_reduce<T, LPR>(buf, stride, zrow, l_agg_col, beg, cnt, maxcnt, sl, k, m, acc);
+            lds_reduce<T, LPR>(buf, ro, l_agg_col, beg, cnt, maxcnt, sl, k, m, acc);
             if (has && kb + sl < q) *reinterpret_cast<V *>(buf + (nv + j) * stride + 4 * k) = acc;
         }
     }
@@ -598,6 +609,7 @@ __global__ __launch_bounds__(BLOCK) void component_kernel(CompArgs<T> A) {
     const int n_stages = A.use_agg ? (meta.w >> 16) : 0;
     const int q = A.d / 4, stride = A.stride;
     const int zrow = nv + na;              // a row of zeros / "nothing"
+    const RowOffsets ro{stride * (int)sizeof(T), zrow * stride * (int)sizeof(T)};
     const int tid = threadIdx.x, sg = tid / LPR, sl = tid % LPR;
     const int wave = tid / kWave, sgw = (tid & (kWave - 1)) / LPR;
 
@@ -607,7 +619,7 @@ __global__ __launch_bounds__(BLOCK) void component_kernel(CompArgs<T> A) {
     const int n_first = A.row_split ? A.row_split[c] : nv;       // rows that wait for no aggregation row
     const int n_second = A.row_split ? nv + na - n_first : 0;    // rows that do
     RowPipe<LPR> pipe;
-    pipe.start(items, n_first, A.row_col, wave, NW, sgw, sl, zrow);
+    pipe.start(items, n_first, A.row_col, wave, NW, sgw, sl, ro);
 
     // stage the component: rows (forward: activations; transposed pass: seeds), the zero row,
     // and the short lists of its aggregation rows
@@ -650,27 +662,28 @@ __global__ __launch_bounds__(BLOCK) void component_kernel(CompArgs<T> A) {
                 }
             }
         } else {
-            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, r0, r1, nv, zrow, sg, sl, false);
+            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, r0, r1, nv, zrow, ro, sg, sl, false);
         }
         __syncthreads();
     }
 
     // forward: y[v] over Nhat_v.  Transposed pass: gx[u] over u's consumers for the rows that
     // no aggregation node consumes, and the destination part of every aggregation row.
-    component_rows<T, LPR, NW>(A, buf, pipe, items, n_first, A.row_col, v0, nv, zrow, wave, sgw, sl);
+    component_rows<T, LPR, NW>(A, buf, pipe, items, n_first, A.row_col, v0, nv, ro, wave, sgw, sl);
 
     if (n_second > 0) {
-        pipe.start(items + 2 * (size_t)n_first, n_second, A.row_col, wave, NW, sgw, sl, zrow);
+        pipe.start(items + 2 * (size_t)n_first, n_second, A.row_col, wave, NW, sgw, sl, ro);
         __syncthreads();
         // From the last stage but one down to the first, each aggregation row adds the
         // finished rows of the aggregation nodes built from it (none of this when the host
         // has expanded the lists of the rows below to all aggregation nodes above them).
         for (int st = n_stages - 1; st >= 1; --st) {
-            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, st_begin[st - 1], st_begin[st], nv, zrow, sg, sl, true);
+            component_stage<T, LPR, NSG>(A, buf, l_agg_ptr, l_agg_col, st_begin[st - 1], st_begin[st], nv, zrow, ro, sg, sl,
+                                         true);
             __syncthreads();
         }
         // the original rows that aggregation nodes consume
-        component_rows<T, LPR, NW>(A, buf, pipe, items + 2 * (size_t)n_first, n_second, A.row_col, v0, nv, zrow, wave,
+        component_rows<T, LPR, NW>(A, buf, pipe, items + 2 * (size_t)n_first, n_second, A.row_col, v0, nv, ro, wave,
                                    sgw, sl);
     }
 }
