@@ -56,12 +56,38 @@ struct GatherArgs {
     const float *self_scale;  // ... after being multiplied by self_scale[item.row], if given
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
+    // streaming (non-temporal) accesses: bit 0 stores of partial rows, bit 1 stores of final
+    // rows, bit 2 loads of the rows a fold launch adds up.  Partial rows are written once and
+    // read once; kept out of the caches they leave the gathered matrices there.
+    int32_t nt;
 };
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
 __device__ __forceinline__ int4 ld4(const int32_t *p) { return *reinterpret_cast<const int4 *>(p); }
 __device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
 __device__ __forceinline__ void st4(int32_t *p, int4 v) { *reinterpret_cast<int4 *>(p) = v; }
+
+typedef float f4v_t __attribute__((ext_vector_type(4)));
+typedef int i4v_t __attribute__((ext_vector_type(4)));
+// streaming stores: the row is not read again by this launch and should not displace the
+// gathered matrices from the caches
+__device__ __forceinline__ void st4_stream(float *p, float4 v) {
+    f4v_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<f4v_t *>(p));
+}
+__device__ __forceinline__ void st4_stream(int32_t *p, int4 v) {
+    i4v_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<i4v_t *>(p));
+}
+
+__device__ __forceinline__ float4 ld4_stream(const float *p) {
+    const f4v_t x = __builtin_nontemporal_load(reinterpret_cast<const f4v_t *>(p));
+    return make_float4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ int4 ld4_stream(const int32_t *p) {
+    const i4v_t x = __builtin_nontemporal_load(reinterpret_cast<const i4v_t *>(p));
+    return make_int4(x.x, x.y, x.z, x.w);
+}
 
 __device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
 // int32 sums wrap modulo 2^32: add as unsigned
@@ -179,7 +205,7 @@ __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&
 #pragma unroll
         for (int k = 0; k < UNR; ++k) {
             val[k] = V{};
-            if (!TAIL || idx[k] >= 0) val[k] = ld4(ptr[k]);
+            if (!TAIL || idx[k] >= 0) val[k] = (A.nt & 4) ? ld4_stream(ptr[k]) : ld4(ptr[k]);
         }
     }
     if (A.in_scale) {
@@ -252,11 +278,11 @@ __device__ __forceinline__ void store_result(const GatherArgs<T> &A, int row, in
         }
         if (A.out_scale) scale4(acc, A.out_scale[row]);
         const size_t o = (size_t)(row - A.out_off) * d + cbase;
-        st4(A.out + o, acc);
+        if (A.nt & 2) st4_stream(A.out + o, acc); else st4(A.out + o, acc);
         if (RED == R_MAX) st4(A.out_id + o, acc_id);
     } else {
         const size_t o = (size_t)(~row) * d + cbase;
-        st4(A.part + o, acc);
+        if (A.nt & 1) st4_stream(A.part + o, acc); else st4(A.part + o, acc);
         if (RED == R_MAX) st4(A.part_id + o, acc_id);
     }
 }
@@ -376,7 +402,8 @@ __global__ __launch_bounds__(kBlock) void level_kernel(const int32_t *__restrict
 // A workgroup is short-lived and several share a compute unit, so what bounds the pass is the
 // number of dependent LDS / memory round trips per workgroup as much as the LDS bytes moved:
 // list ids are requested one step ahead of their use, the lists of the first rows already
-// while the rows are staged, and independent reductions are batched.
+// while the rows are staged.  In the row loop a read costs one add that moves the row's byte
+// offset across lanes, one 16-byte LDS read and four adds; rows are not padded.
 // ------------------------------------------------------------------------------------------
 template <typename T>
 struct CompArgs {
@@ -793,6 +820,7 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         const uint64_t row_bytes = (uint64_t)a.d * 4;
         const uint64_t lo_rows = (uint64_t)std::max<int64_t>(a.split, 1);
         // HAG_OFFSET64=1 forces the 64-bit path, which otherwise only matrices of 4 GiB and more take
+        { const char *ent = std::getenv("HAG_STREAM"); a.nt = ent ? std::atoi(ent) : 5; }   // read per call
         const char *e64 = std::getenv("HAG_OFFSET64");
         const bool force64 = e64 && std::atoi(e64) != 0;
         a.off32 = (!force64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
@@ -813,10 +841,13 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     a.col = d_col;
     a.part = (T *)w.part;
     a.part_id = (int32_t *)w.part_id;
+    const int nt_all = a.nt;
+    a.nt = nt_all & 3;
     int rc = (phases & HAG_PHASE_GATHER) ? launch_gather<T, RED, ROLE>(a, s) : HAG_OK;
     if (rc) return rc;
     if (!p.combine.empty() && (phases & HAG_PHASE_FOLD)) {
         GatherArgs<T> c = a;
+        c.nt = nt_all & 6;
         c.items = p.d_combine;
         c.np = 1;
         c.seg[0].begin = 0;
