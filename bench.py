@@ -25,10 +25,10 @@ HBM_PEAK_GBS = 8000.0  # MI355X HBM3E, published
 # HBM bytes per launch of the dominant kernel measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # (scaled by a copy kernel of known size); the summaries are in profiles/.  None = not measured.
 MEASURED_TRAFFIC_BYTES = {
-    # profiles/pmc_config2_holme_kim56944_d128_sum.txt: FETCH_SIZE 309411 x 2048 B + WRITE_SIZE 28472 x 1024 B
-    ("config2:holme_kim56944", 128, "sum"): 309411 * 2048 + 28472 * 1024,
-    # profiles/pmc_config3_dcsbm232965_d128_sum.txt: FETCH_SIZE 6639360 x 2048 B + WRITE_SIZE 898966 x 1024 B
-    ("config3:dcsbm232965", 128, "sum"): 6639360 * 2048 + 898966 * 1024,
+    # profiles/pmc_config2_holme_kim56944_d128_sum.txt: FETCH_SIZE 310933 x 2048 B + WRITE_SIZE 28472 x 1024 B
+    ("config2:holme_kim56944", 128, "sum"): 310933 * 2048 + 28472 * 1024,
+    # profiles/pmc_config3_dcsbm232965_d128_sum.txt: FETCH_SIZE 6438940 x 2048 B + WRITE_SIZE 898966 x 1024 B
+    ("config3:dcsbm232965", 128, "sum"): 6438940 * 2048 + 898966 * 1024,
     # profiles/pmc_config4_er_batch5000x74_d64_sum.txt (component_kernel, hag_forward): FETCH_SIZE 74199 x 2048 B + WRITE_SIZE 92500 x 1024 B
     ("config4:er_batch5000x74", 64, "sum"): 74199 * 2048 + 92500 * 1024,
 }

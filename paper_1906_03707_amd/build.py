@@ -3,6 +3,7 @@ from __future__ import annotations
 
 import os
 import subprocess
+import sys
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 ROOT = os.path.dirname(HERE)
@@ -20,14 +21,45 @@ def build_library(force: bool = True, verbose: bool = False) -> str:
     cmd = [
         hipcc, "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",
         "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
-        "-Wall", "-Wno-unused-function",
+        "-Wall", "-Wno-unused-function", "-Rpass-analysis=kernel-resource-usage",
         "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(HERE, "csrc"),
         *SOURCES, "-o", LIB, "-lpthread",
     ]
     if verbose:
         print(" ".join(cmd))
-    subprocess.check_call(cmd)
+    r = subprocess.run(cmd, stderr=subprocess.PIPE, text=True)
+    usage = check_resource_usage(r.stderr)
+    if r.returncode != 0:
+        raise subprocess.CalledProcessError(r.returncode, cmd)
+    if verbose:
+        for name, u in sorted(usage.items()):
+            print(f"{name}: {u.get('VGPRs', '?')} VGPRs, {u.get('LDS Size [bytes/block]', '?')} B LDS")
     return LIB
+
+
+def check_resource_usage(stderr: str) -> dict:
+    """Parse the compiler's per-kernel resource remarks; print everything else it said.
+
+    A kernel that touches scratch memory (register spills, or its argument block copied to the
+    stack because of a run-time choice the optimiser could not resolve) runs several times slower
+    without failing any test, so it fails the build instead."""
+    usage, name = {}, None
+    for line in stderr.splitlines():
+        if "[-Rpass-analysis=kernel-resource-usage]" not in line:
+            if "packed-fp32-ops" not in line and line.strip():
+                print(line, file=sys.stderr)          # ordinary warnings and errors
+            continue
+        text = line.split("remark:", 1)[1].rsplit("[-Rpass", 1)[0].strip()
+        if text.startswith("Function Name:"):
+            name = text.split(":", 1)[1].strip()
+            usage[name] = {}
+        elif name and ":" in text:
+            k, v = text.rsplit(":", 1)
+            usage[name][k.strip()] = v.strip()
+    bad = {n: u["ScratchSize [bytes/lane]"] for n, u in usage.items() if u.get("ScratchSize [bytes/lane]", "0") != "0"}
+    if bad:
+        raise RuntimeError("kernels that use scratch memory (bytes per lane): " + ", ".join(f"{n}: {b}" for n, b in bad.items()))
+    return usage
 
 
 if __name__ == "__main__":

@@ -56,10 +56,7 @@ struct GatherArgs {
     const float *self_scale;  // ... after being multiplied by self_scale[item.row], if given
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
-    // streaming (non-temporal) accesses: bit 0 stores of partial rows, bit 1 stores of final
-    // rows, bit 2 loads of the rows a fold launch adds up.  Partial rows are written once and
-    // read once; kept out of the caches they leave the gathered matrices there.
-    int32_t nt;
+    int32_t stream_hi;        // rows of src_hi are read once (fold of partial rows): streaming loads
 };
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -205,7 +202,7 @@ __device__ __forceinline__ void reduce_step(const GatherArgs<T> &A, const int (&
 #pragma unroll
         for (int k = 0; k < UNR; ++k) {
             val[k] = V{};
-            if (!TAIL || idx[k] >= 0) val[k] = (A.nt & 4) ? ld4_stream(ptr[k]) : ld4(ptr[k]);
+            if (!TAIL || idx[k] >= 0) val[k] = A.stream_hi ? ld4_stream(ptr[k]) : ld4(ptr[k]);
         }
     }
     if (A.in_scale) {
@@ -278,12 +275,15 @@ __device__ __forceinline__ void store_result(const GatherArgs<T> &A, int row, in
         }
         if (A.out_scale) scale4(acc, A.out_scale[row]);
         const size_t o = (size_t)(row - A.out_off) * d + cbase;
-        if (A.nt & 2) st4_stream(A.out + o, acc); else st4(A.out + o, acc);
+        st4(A.out + o, acc);
         if (RED == R_MAX) st4(A.out_id + o, acc_id);
     } else {
         const size_t o = (size_t)(~row) * d + cbase;
-        if (A.nt & 1) st4_stream(A.part + o, acc); else st4(A.part + o, acc);
-        if (RED == R_MAX) st4(A.part_id + o, acc_id);
+        // written once, read once by the fold launch: kept out of the caches, partial rows
+        // leave the gathered matrices there (unconditional: a run-time choice between the two
+        // store forms made the compiler keep the kernel's arguments in scratch memory)
+        st4_stream(A.part + o, acc);
+        if (RED == R_MAX) st4_stream(A.part_id + o, acc_id);
     }
 }
 
@@ -820,7 +820,6 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         const uint64_t row_bytes = (uint64_t)a.d * 4;
         const uint64_t lo_rows = (uint64_t)std::max<int64_t>(a.split, 1);
         // HAG_OFFSET64=1 forces the 64-bit path, which otherwise only matrices of 4 GiB and more take
-        { const char *ent = std::getenv("HAG_STREAM"); a.nt = ent ? std::atoi(ent) : 5; }   // read per call
         const char *e64 = std::getenv("HAG_OFFSET64");
         const bool force64 = e64 && std::atoi(e64) != 0;
         a.off32 = (!force64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
@@ -841,13 +840,12 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     a.col = d_col;
     a.part = (T *)w.part;
     a.part_id = (int32_t *)w.part_id;
-    const int nt_all = a.nt;
-    a.nt = nt_all & 3;
+    a.stream_hi = 0;
     int rc = (phases & HAG_PHASE_GATHER) ? launch_gather<T, RED, ROLE>(a, s) : HAG_OK;
     if (rc) return rc;
     if (!p.combine.empty() && (phases & HAG_PHASE_FOLD)) {
         GatherArgs<T> c = a;
-        c.nt = nt_all & 6;
+        c.stream_hi = 1;
         c.items = p.d_combine;
         c.np = 1;
         c.seg[0].begin = 0;
