@@ -259,3 +259,20 @@ def test_stage_fusion_and_component_detection(monkeypatch):
     assert h3.workspace_bytes("sum", B.HAG_F32, 64) >= a * 64 * 4
     assert h3.workspace_bytes("max", B.HAG_F32, 64) >= 2 * a * 64 * 4
     assert h3.workspace_bytes("sum", B.HAG_F32, 128) > h3.workspace_bytes("sum", B.HAG_F32, 64)
+
+
+def test_build_rejects_kernels_that_use_scratch_memory():
+    # build.py reads the compiler's per-kernel resource remarks: a kernel whose arguments or
+    # registers end up in scratch memory still passes every parity test, only several times slower
+    from paper_1906_03707_amd.build import check_resource_usage
+
+    def remarks(scratch):
+        rows = ["Function Name: _ZN3hag13gather_kernelIfLi1ELi32ELi0EEEvNS_10GatherArgsIT_EE", "    VGPRs: 62",
+                f"    ScratchSize [bytes/lane]: {scratch}", "    LDS Size [bytes/block]: 8192"]
+        return "\n".join(f"x.hip:271:1: remark: {r} [-Rpass-analysis=kernel-resource-usage]" for r in rows)
+
+    usage = check_resource_usage(remarks(0))
+    (name, u), = usage.items()
+    assert name.startswith("_ZN3hag13gather_kernel") and u["VGPRs"] == "62" and u["LDS Size [bytes/block]"] == "8192"
+    with pytest.raises(RuntimeError, match="scratch"):
+        check_resource_usage(remarks(344))
