@@ -430,6 +430,7 @@ struct CompArgs {
     int32_t max_agg;             // most aggregation rows a component has
     int32_t use_agg, reverse;
     int32_t pairs;               // forward pass: every staged list has exactly two entries
+    int32_t stream_out;          // output rows are written with streaming stores
 };
 
 // Value of lane J of the caller's sub-group of LPR lanes.  A sub-group of 16 lanes is one row of
@@ -580,7 +581,8 @@ __device__ __forceinline__ void component_rows(const CompArgs<T> &A, T *buf, Row
                         add4(acc, *reinterpret_cast<const V *>(buf + v * stride + 4 * k));
                     }
                     if (A.scale_out) scale4(acc, A.scale_out[v0 + v]);
-                    st4(A.out + (size_t)(v0 + v) * A.d + 4 * k, acc);
+                    if (A.stream_out) st4_stream(A.out + (size_t)(v0 + v) * A.d + 4 * k, acc);
+                    else st4(A.out + (size_t)(v0 + v) * A.d + 4 * k, acc);
                 }
             }
         }
@@ -940,6 +942,7 @@ static int launch_component(const hag_handle *h, bool naive, hag_op_t op, int64_
     a.use_agg = naive ? 0 : 1;
     a.reverse = BACKWARD ? 1 : 0;
     a.pairs = (!BACKWARD && !c.expanded) ? 1 : 0;
+    { const char *e = std::getenv("HAG_STREAM_OUTPUT"); a.stream_out = e ? std::atoi(e) : 0; }   // read per call
     a.lists_off = (int32_t)L.lists_off;
     a.max_agg = c.max_agg;
     // 4 wavefronts per workgroup: 8 were measured slower even where LDS lets only 6 workgroups share
