@@ -2,6 +2,7 @@
 from __future__ import annotations
 
 import os
+import re
 import subprocess
 import sys
 
@@ -43,12 +44,16 @@ def check_resource_usage(stderr: str) -> dict:
     A kernel that touches scratch memory (register spills, or its argument block copied to the
     stack because of a run-time choice the optimiser could not resolve) runs several times slower
     without failing any test, so it fails the build instead."""
-    usage, name = {}, None
+    usage, name, after_remark = {}, None, False
     for line in stderr.splitlines():
         if "[-Rpass-analysis=kernel-resource-usage]" not in line:
-            if "packed-fp32-ops" not in line and line.strip():
+            snippet = re.match(r"\s*(\d+\s*)?\|", line) is not None       # source excerpt under a diagnostic
+            if not (snippet and after_remark) and "packed-fp32-ops" not in line and line.strip():
                 print(line, file=sys.stderr)          # ordinary warnings and errors
+            if not snippet:
+                after_remark = False
             continue
+        after_remark = True
         text = line.split("remark:", 1)[1].rsplit("[-Rpass", 1)[0].strip()
         if text.startswith("Function Name:"):
             name = text.split(":", 1)[1].strip()
