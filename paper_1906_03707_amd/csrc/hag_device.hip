@@ -832,7 +832,12 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         const char *esub = std::getenv("HAG_SUB_MAX");     // read per call: a test may change it
         const int64_t sub_max = esub ? std::atoll(esub) : 0LL;
         const int64_t nsg = kBlock / pick_lpr(a.d);
-        const int64_t threshold = sub_max > 0 ? sub_max : std::max<int64_t>(64, 8 * nsg);
+        // A launch too small to fill the device with one sub-group per row (the stages of
+        // a small HAG) lasts as long as its longest single-sub-group row: there a row gets
+        // a workgroup much sooner.
+        const int64_t n_all = p.part_begin[p.np] - p.part_begin[0];
+        const bool small_launch = n_all <= 256 * 8 * nsg;
+        const int64_t threshold = sub_max > 0 ? sub_max : small_launch ? 16 : std::max<int64_t>(64, 8 * nsg);
         for (int k = 0; k < p.np; ++k) {
             a.seg[k].begin = p.part_begin[k];
             a.seg[k].n_items = p.part_begin[k + 1] - p.part_begin[k];
