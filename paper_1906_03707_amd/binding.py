@@ -125,6 +125,7 @@ class Hag:
     def __init__(self, handle):
         self._h = ctypes.c_void_p(handle)
         self._ws = {}
+        self._n = None
 
     def __del__(self):
         try:
@@ -175,15 +176,44 @@ class Hag:
     def _workspace(self, op, t):
         import torch
         nbytes = self.workspace_bytes(op, _dtype_code(t), t.shape[1])
-        key = (t.device.index,)
+        # one buffer per (device, stream): calls enqueued on different streams may overlap
+        key = (t.device.index, torch.cuda.current_stream(t.device).cuda_stream)
         ws = self._ws.get(key)
         if ws is None or ws.numel() < nbytes:
             ws = torch.empty(max(nbytes, 16), dtype=torch.uint8, device=t.device)
             self._ws[key] = ws
         return ws
 
+    def _check_args(self, what, a, op, out, argmax, workspace, needs_argmax):
+        """Everything the C ABI cannot check from raw pointers: the library takes no row count, so a
+        matrix with too few rows, a narrower dtype or a short workspace would make a kernel read or
+        write out of bounds."""
+        import torch
+        if op not in OPS:
+            raise ValueError(f"unknown op {op!r}")
+        if self._n is None:
+            self._n = self.stats()["n"]
+        if a.dim() != 2 or a.shape[0] != self._n:
+            raise ValueError(f"{what} must have shape [{self._n}, d], got {tuple(a.shape)}")
+        code = _dtype_code(a)
+        for name, t in (("output", out),):
+            if t is not None and (t.shape != a.shape or t.dtype != a.dtype or t.device != a.device):
+                raise ValueError(f"{name} must match {what}: shape {tuple(a.shape)}, dtype {a.dtype}, device {a.device}; "
+                                 f"got {tuple(t.shape)}, {t.dtype}, {t.device}")
+        if argmax is not None and (argmax.shape != a.shape or argmax.dtype != torch.int32 or argmax.device != a.device):
+            raise ValueError(f"argmax must be int32 of shape {tuple(a.shape)} on {a.device}, got {argmax.dtype} "
+                             f"{tuple(argmax.shape)} on {argmax.device}")
+        if needs_argmax and argmax is None:
+            raise ValueError("argmax is required for max")
+        if workspace is not None:
+            need = self.workspace_bytes(op, code, a.shape[1])
+            have = workspace.numel() * workspace.element_size()
+            if have < need or workspace.device != a.device:
+                raise ValueError(f"workspace holds {have} bytes on {workspace.device}, {need} needed on {a.device}")
+
     def _fwd(self, fn, x, op, y, argmax, workspace, *extra):
         import torch
+        self._check_args("x", x, op, y, argmax, workspace, False)
         n, d = x.shape
         if y is None:
             y = torch.empty_like(x)
@@ -196,6 +226,7 @@ class Hag:
 
     def _bwd(self, fn, gy, op, argmax, gx, workspace, *extra):
         import torch
+        self._check_args("gy", gy, op, gx, argmax, workspace, op == "max")
         n, d = gy.shape
         if gx is None:
             gx = torch.empty_like(gy)

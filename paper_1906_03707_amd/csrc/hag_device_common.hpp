@@ -1,0 +1,216 @@
+// Shared by the device translation units of libhag: argument blocks of the kernels, small
+// vector helpers, and the launch functions each unit defines for the others.
+#pragma once
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstdlib>
+#include <string>
+#include <type_traits>
+
+#include "hag_internal.hpp"
+
+namespace hag {
+
+constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes
+constexpr int kWave = 64;
+
+enum { R_SUM = 0, R_MAX = 1 };
+// which phase a gather launch belongs to: only a tag, so that every phase has a kernel symbol
+// of its own in profiler output
+enum { G_HAG_FWD = 0, G_HAG_BWD_LEVEL = 1, G_HAG_BWD_SRC = 2, G_NAIVE_FWD = 3, G_NAIVE_BWD = 4, G_FOLD = 5, G_HAG_FWD_STAGE = 6 };
+
+template <typename T> struct V4;
+template <> struct V4<float> { using type = float4; };
+template <> struct V4<int32_t> { using type = int4; };
+
+template <typename T>
+struct GatherArgs {
+    const Item *items;
+    int np;                   // 1 or kPartitions: workgroup b works on partition b mod np
+    struct {
+        int64_t begin;        // first item of the partition
+        int64_t n_block;      // its first n_block items take one workgroup each
+        int64_t n_items;      // all its items
+    } seg[kPartitions];
+    const int32_t *col;
+    const T *src_lo;          // rows of ids < split
+    const T *src_hi;          // rows of ids >= split, row (id - split)
+    const int32_t *id_hi;     // R_MAX: winning original ids stored beside src_hi rows
+    int32_t split;
+    T *out;                   // final rows, row (item.row - out_off)
+    int32_t *out_id;          // R_MAX
+    int32_t out_off;
+    T *part;                  // partial slots of split rows
+    int32_t *part_id;         // R_MAX
+    const float *in_scale;    // optional: multiplies rows of ids < split (mean, transposed pass)
+    const float *out_scale;   // optional: multiplies final rows (mean, forward), indexed by item.row
+    const T *self;            // optional: row item.row of this matrix is added to a final row (gcn) ...
+    const float *self_scale;  // ... after being multiplied by self_scale[item.row], if given
+    int32_t d;
+    int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
+    int32_t stream_hi;        // rows of src_hi are read once (fold of partial rows): streaming loads
+};
+
+__device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
+__device__ __forceinline__ int4 ld4(const int32_t *p) { return *reinterpret_cast<const int4 *>(p); }
+__device__ __forceinline__ void st4(float *p, float4 v) { *reinterpret_cast<float4 *>(p) = v; }
+__device__ __forceinline__ void st4(int32_t *p, int4 v) { *reinterpret_cast<int4 *>(p) = v; }
+
+typedef float f4v_t __attribute__((ext_vector_type(4)));
+typedef int i4v_t __attribute__((ext_vector_type(4)));
+// streaming stores: the row is not read again by this launch and should not displace the
+// gathered matrices from the caches
+__device__ __forceinline__ void st4_stream(float *p, float4 v) {
+    f4v_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<f4v_t *>(p));
+}
+__device__ __forceinline__ void st4_stream(int32_t *p, int4 v) {
+    i4v_t x = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(x, reinterpret_cast<i4v_t *>(p));
+}
+
+__device__ __forceinline__ float4 ld4_stream(const float *p) {
+    const f4v_t x = __builtin_nontemporal_load(reinterpret_cast<const f4v_t *>(p));
+    return make_float4(x.x, x.y, x.z, x.w);
+}
+__device__ __forceinline__ int4 ld4_stream(const int32_t *p) {
+    const i4v_t x = __builtin_nontemporal_load(reinterpret_cast<const i4v_t *>(p));
+    return make_int4(x.x, x.y, x.z, x.w);
+}
+
+__device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
+// int32 sums wrap modulo 2^32: add as unsigned
+__device__ __forceinline__ void add4(int4 &a, const int4 &b) {
+    a.x = (int)((unsigned)a.x + (unsigned)b.x); a.y = (int)((unsigned)a.y + (unsigned)b.y);
+    a.z = (int)((unsigned)a.z + (unsigned)b.z); a.w = (int)((unsigned)a.w + (unsigned)b.w);
+}
+__device__ __forceinline__ void scale4(float4 &a, float s) { a.x *= s; a.y *= s; a.z *= s; a.w *= s; }
+__device__ __forceinline__ void scale4(int4 &, float) {}
+
+// (value, id) max with ties to the smaller id; id < 0 means "nothing yet"
+template <typename S>
+__device__ __forceinline__ void max1(S &v, int &vi, S w, int wi) {
+    bool take = (wi >= 0) && (vi < 0 || w > v || (w == v && wi < vi));
+    v = take ? w : v;
+    vi = take ? wi : vi;
+}
+// the same when the candidate's id is known to exceed every id already folded in
+template <typename S>
+__device__ __forceinline__ void max_first1(S &v, int &vi, S w, int wi) {
+    bool take = (wi >= 0) && (vi < 0 || w > v);
+    v = take ? w : v;
+    vi = take ? wi : vi;
+}
+template <typename V>
+__device__ __forceinline__ void max_first4(V &v, int4 &vi, const V &w, int wi) {
+    max_first1(v.x, vi.x, w.x, wi); max_first1(v.y, vi.y, w.y, wi);
+    max_first1(v.z, vi.z, w.z, wi); max_first1(v.w, vi.w, w.w, wi);
+}
+template <typename V>
+__device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi) {
+    max1(v.x, vi.x, w.x, wi.x); max1(v.y, vi.y, w.y, wi.y);
+    max1(v.z, vi.z, w.z, wi.z); max1(v.w, vi.w, w.w, wi.w);
+}
+
+// (value, id) max where the id of an aggregation row (id >= split) stands for the winning
+// original id stored beside that row, and is only looked up when a tie makes it matter.
+// acc_id is an original id, or an aggregation id whose stored winner has not been needed yet.
+// Original ids of a list arrive in ascending order before any aggregation id, so a tie
+// between two original ids keeps the accumulator.
+template <typename S>
+__device__ __forceinline__ void settle_tie1(S v, int &vi, S w, int wi, const int32_t *id_hi, int split, size_t d,
+                                            int col) {
+    if (vi >= 0 && w == v) {
+        const int other = id_hi[(size_t)(wi - split) * d + col];
+        const int mine = vi < split ? vi : id_hi[(size_t)(vi - split) * d + col];
+        vi = min(mine, other);
+    }
+}
+template <typename V>
+__device__ __forceinline__ void lazy_max4(V &v, int4 &vi, const V &w, int wi, const int32_t *id_hi, int split,
+                                          size_t d, int cb) {
+    if (wi >= split && (w.x == v.x || w.y == v.y || w.z == v.z || w.w == v.w)) {   // rare
+        settle_tie1(v.x, vi.x, w.x, wi, id_hi, split, d, cb);
+        settle_tie1(v.y, vi.y, w.y, wi, id_hi, split, d, cb + 1);
+        settle_tie1(v.z, vi.z, w.z, wi, id_hi, split, d, cb + 2);
+        settle_tie1(v.w, vi.w, w.w, wi, id_hi, split, d, cb + 3);
+    }
+    max_first4(v, vi, w, wi);   // a tie keeps the accumulator, whose id is settled above
+}
+// replace aggregation ids left in acc_id by the original ids they stand for
+__device__ __forceinline__ void resolve_ids(int4 &vi, const int32_t *id_hi, int split, size_t d, int cb) {
+    if (vi.x >= split) vi.x = id_hi[(size_t)(vi.x - split) * d + cb];
+    if (vi.y >= split) vi.y = id_hi[(size_t)(vi.y - split) * d + cb + 1];
+    if (vi.z >= split) vi.z = id_hi[(size_t)(vi.z - split) * d + cb + 2];
+    if (vi.w >= split) vi.w = id_hi[(size_t)(vi.w - split) * d + cb + 3];
+}
+
+__device__ __forceinline__ Item load_item(const Item *p) {
+    const int4 raw = *reinterpret_cast<const int4 *>(p);
+    Item it;
+    it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)raw.y << 32);
+    it.cnt = raw.z;
+    it.row = raw.w;
+    return it;
+}
+
+
+template <typename T>
+struct CompArgs {
+    const int32_t *meta;         // per component: first node, #nodes, first aggregation slot, #agg | #stages << 16
+    const uint8_t *stage;        // stage of each aggregation slot (ascending inside a component)
+    // lists of the rows written to global memory: per node slot {first entry in row_col,
+    // length | local row index << 16}, each component's rows sorted longest list first
+    const int32_t *row_items;
+    const uint16_t *row_col;
+    // Transposed pass over a HAG: the items of a component (at slot v0 + a0) cover its
+    // aggregation rows too (row index >= nv: the sum over the destinations that consume the
+    // row, kept in LDS); the first row_split[c] items depend on no aggregation row, the others
+    // are the original rows that aggregation nodes consume.  NULL: nv items at slot v0.
+    const int32_t *row_split;
+    const int32_t *agg_row_ptr;  // lists of the aggregation rows kept in LDS (component-major index)
+    const uint16_t *agg_row_col;
+    const T *in;
+    T *out;
+    const float *scale_in, *scale_out;
+    const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
+    int32_t add_self;
+    int32_t d, stride;           // feature width; row stride in LDS, in elements
+    int32_t lists_off;           // offset of the staged aggregation lists, in bytes
+    int32_t max_agg;             // most aggregation rows a component has
+    int32_t use_agg, reverse;
+    int32_t pairs;               // forward pass: every staged list has exactly two entries
+    int32_t stream_out;          // output rows are written with streaming stores
+};
+
+static inline int hip_fail(hipError_t e, const char *what) {
+    set_error(std::string(what) + ": " + hipGetErrorString(e));
+    return HAG_EHIP;
+}
+#define HIP_TRY(expr)                                   \
+    do {                                                \
+        hipError_t _e = (expr);                         \
+        if (_e != hipSuccess) return hip_fail(_e, #expr); \
+    } while (0)
+
+// lanes that share one feature row: the power of two that covers d/4 float4 columns, 4..64
+static inline int pick_lpr(int64_t d) {
+    int64_t q = d / 4;
+    int l = 4;
+    while (l < 64 && l < q) l <<= 1;
+    return l;
+}
+
+// Defined in the gather units (one per element type and reduction), used by hag_device.hip.
+template <typename T, int RED, int ROLE>
+int launch_gather(const GatherArgs<T> &a, hipStream_t s);
+
+// Defined in the component units (one per element type).  role: 0 = HAG forward, 1 = HAG
+// transposed pass, 2 = input graph forward (baseline), 3 = its transposed pass.
+template <typename T>
+int launch_component_kernel(const CompArgs<T> &a, int role, int64_t d, unsigned components, size_t lds_bytes,
+                            hipStream_t s);
+
+}  // namespace hag

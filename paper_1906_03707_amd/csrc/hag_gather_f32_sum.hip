@@ -1,0 +1,12 @@
+// gather-reduce, f32 features, sum
+#include "hag_gather.inc"
+
+namespace hag {
+template int launch_gather<float, R_SUM, 0>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 1>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 2>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 3>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 4>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 5>(const GatherArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUM, 6>(const GatherArgs<float> &, hipStream_t);
+}

@@ -8,7 +8,9 @@
 #include <cmath>
 #include <cstdlib>
 #include <cstring>
+#include <exception>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <numeric>
 #include <queue>
@@ -39,6 +41,9 @@ static unsigned host_threads() {
     return std::max(1u, std::min(t, 64u));
 }
 
+// Runs f(i, thread) for i in [0, n) on up to `threads` threads.  An exception thrown by f (in
+// practice std::bad_alloc) stops the remaining work and is rethrown on the calling thread after
+// all workers have joined, so that the entry points' own handlers turn it into a status code.
 template <class F>
 static void parallel_for(int64_t n, unsigned threads, F f) {
     threads = (unsigned)std::min<int64_t>(threads, std::max<int64_t>(n, 1));
@@ -47,16 +52,30 @@ static void parallel_for(int64_t n, unsigned threads, F f) {
         return;
     }
     std::atomic<int64_t> next{0};
+    std::atomic<bool> failed{false};
+    std::exception_ptr first;
+    std::mutex first_lock;
     std::vector<std::thread> pool;
-    for (unsigned t = 0; t < threads; ++t)
-        pool.emplace_back([&, t] {
+    auto work = [&](unsigned t) {
+        try {
             for (;;) {
                 int64_t i = next.fetch_add(1);
-                if (i >= n) break;
+                if (i >= n || failed.load(std::memory_order_relaxed)) break;
                 f(i, t);
             }
-        });
+        } catch (...) {
+            std::lock_guard<std::mutex> g(first_lock);
+            if (!first) first = std::current_exception();
+            failed.store(true);
+        }
+    };
+    try {
+        for (unsigned t = 1; t < threads; ++t) pool.emplace_back(work, t);
+    } catch (...) {   // could not start every worker: the ones that run finish the job
+    }
+    work(0u);
     for (auto &th : pool) th.join();
+    if (first) std::rethrow_exception(first);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -923,6 +942,16 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
     h->m_left = b.m_left;
     h->m_right = b.m_right;
     h->m_red = b.m_red;
+    {
+        hag_knobs &k = h->knobs;
+        k.sub_max = env_i64("HAG_SUB_MAX", 0);
+        k.offset64 = env_i64("HAG_OFFSET64", 0) != 0;
+        const int64_t pad = env_i64("HAG_COMPONENT_PAD", 0);
+        k.component_pad = (int32_t)((pad < 0 ? 0 : pad > 64 ? 64 : pad) & ~(int64_t)3);
+        k.stream_output = env_i64("HAG_STREAM_OUTPUT", 0) != 0;
+        k.fuse_max_items = env_i64("HAG_FUSE_MAX_ITEMS", 262144);
+        k.spin_limit = env_i64("HAG_SPIN_LIMIT", 1 << 22);
+    }
     // depth(original) = 0, depth(w) = 1 + max over its inputs; creation order is topological
     std::vector<int32_t> order(a);
     std::iota(order.begin(), order.end(), 0);
@@ -1124,8 +1153,10 @@ int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t cap
             s.dev = counter_create(in, s.dev_err);
             if (!s.dev) return fail(HAG_EHIP, s.dev_err);
         }
+        // released on every way out of this scope, exceptions included
+        std::unique_ptr<DeviceCounter, void (*)(DeviceCounter *)> dev_guard(s.dev, counter_destroy);
         const bool ok = capacity > 0 ? s.run() : true;
-        counter_destroy(s.dev);
+        dev_guard.reset();
         s.dev = nullptr;
         if (!ok) return fail(HAG_EHIP, s.dev_err);
         rc = finalize_from_builder(h.get(), s.b);
@@ -1134,6 +1165,8 @@ int hag_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t cap
         return HAG_OK;
     } catch (const std::bad_alloc &) {
         return fail(HAG_ENOMEM, "out of host memory");
+    } catch (const std::exception &ex) {   // e.g. a worker thread could not be started
+        return fail(HAG_ENOMEM, std::string("host resources exhausted: ") + ex.what());
     }
 }
 
@@ -1194,6 +1227,8 @@ int hag_search_batched(int64_t n, const int64_t *rowptr, const int32_t *col, int
         return HAG_OK;
     } catch (const std::bad_alloc &) {
         return fail(HAG_ENOMEM, "out of host memory");
+    } catch (const std::exception &ex) {   // e.g. a worker thread could not be started
+        return fail(HAG_ENOMEM, std::string("host resources exhausted: ") + ex.what());
     }
 }
 
@@ -1213,6 +1248,8 @@ int hag_from_merges(int64_t n, const int64_t *rowptr, const int32_t *col, int64_
         return HAG_OK;
     } catch (const std::bad_alloc &) {
         return fail(HAG_ENOMEM, "out of host memory");
+    } catch (const std::exception &ex) {   // e.g. a worker thread could not be started
+        return fail(HAG_ENOMEM, std::string("host resources exhausted: ") + ex.what());
     }
 }
 
@@ -1230,6 +1267,8 @@ int hag_prefix(const hag_t *src, int64_t n_merges, hag_t **out) {
         return HAG_OK;
     } catch (const std::bad_alloc &) {
         return fail(HAG_ENOMEM, "out of host memory");
+    } catch (const std::exception &ex) {   // e.g. a worker thread could not be started
+        return fail(HAG_ENOMEM, std::string("host resources exhausted: ") + ex.what());
     }
 }
 

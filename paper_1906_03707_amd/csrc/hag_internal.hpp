@@ -109,8 +109,20 @@ bool counter_sweep(DeviceCounter *d, int nb, const int32_t *x, const int32_t *th
 
 }  // namespace hag
 
+// Test and tuning knobs of the launch path.  They come from the environment ONCE, when a handle is
+// built; the launch path itself never reads the environment.
+struct hag_knobs {
+    int64_t sub_max = 0;        // HAG_SUB_MAX: longest row one sub-group takes (0 = default rule)
+    bool offset64 = false;      // HAG_OFFSET64: force the 64-bit row addressing of matrices >= 4 GiB
+    int32_t component_pad = 0;  // HAG_COMPONENT_PAD: padding of an LDS row, in elements (multiple of 4, <= 64)
+    bool stream_output = false; // HAG_STREAM_OUTPUT: component pass writes output rows with streaming stores
+    int64_t fuse_max_items = 0; // HAG_FUSE_MAX_ITEMS: largest pass (schedule items) that runs as one launch
+    int64_t spin_limit = 0;     // HAG_SPIN_LIMIT: polls a workgroup of the one-launch pass waits for a stage
+};
+
 struct hag_handle {
     int64_t n = 0, e = 0, a = 0;
+    hag_knobs knobs;
     int32_t levels = 0;
     hag::Csr g;    // input graph: rows = destinations
     hag::Csr gt;   // its transpose: rows = sources, cols = destinations

@@ -31,7 +31,7 @@ def load_cached_merges(cfg: int):
     if not os.path.exists(p):
         return None
     z = np.load(p)
-    return z["left"], z["right"]
+    return z["left"], z["right"], z["red"]
 
 
 def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None, device_search=False):
@@ -51,6 +51,9 @@ def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None, de
             how = "hag_search (HAG_SEARCH_DEVICE)"
         elif cached is not None and cached[0].size >= cap:
             h = binding.hag_from_merges(rowptr, col, cached[0][:cap], cached[1][:cap])
+            # the replay counts the lists each merge rewrites: they must be the logged redundancies
+            if not np.array_equal(h.get_merges()[2], cached[2][:cap]):
+                raise RuntimeError(f"{cache_path(cfg)} does not belong to this graph: replayed redundancies differ")
             how = "hag_from_merges (cached canonical merge list)"
         else:
             h = binding.hag_search(rowptr, col, cap)

@@ -156,11 +156,13 @@ def test_component_local_pass_on_graph_batches(B, d, expand, monkeypatch):
     assert h.stats()["a"] > 100 and h.stats()["levels"] >= 2
     assert h.stats()["components"] >= 64            # the component-local pass is the one that runs
     run_all_ops(B, h, rowptr, col, d, seed=63 + d)
-    # streaming stores of the output rows (a per-call knob) change nothing but the cache policy
+    # streaming stores of the output rows (a knob read when a handle is built) change nothing but
+    # the cache policy
     xf = dev(synth.features_f32(rowptr.size - 1, d, 6))
     want_y, want_gx = h.forward(xf, "sum"), h.backward(xf, "mean")
     monkeypatch.setenv("HAG_STREAM_OUTPUT", "1")
-    assert torch.equal(h.forward(xf, "sum"), want_y) and torch.equal(h.backward(xf, "mean"), want_gx)
+    hs = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+    assert torch.equal(hs.forward(xf, "sum"), want_y) and torch.equal(hs.backward(xf, "mean"), want_gx)
     monkeypatch.delenv("HAG_STREAM_OUTPUT")
     # the same handle through the generic kernels must agree bit for bit on int32
     monkeypatch.setenv("HAG_COMPONENT", "0")

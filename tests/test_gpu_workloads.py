@@ -37,6 +37,23 @@ def oracle_view(h):
     return oracle.Hag(h.stats()["n"], f["agg_left"], f["agg_right"], f["hrowptr"], f["hcol"])
 
 
+def sample_columns(d, k, seed):
+    """k feature columns of d for the sampled comparison: a kernel lane owns four consecutive
+    columns (one 16-byte vector), so the sample holds every position inside such a vector, even
+    and odd vectors, the first and the last column; the rest is a seeded random choice."""
+    must = [0, 1, 2, 3, 5, 6, d - 1, d - 4, d - 3, d - 2, d // 2 + 1, d // 2 + 7]
+    cols = []
+    for c in must:
+        if 0 <= c < d and c not in cols:
+            cols.append(c)
+    cols = cols[:k]
+    rest = np.setdiff1d(np.arange(d), cols)
+    extra = np.random.default_rng(seed).choice(rest, size=max(0, min(k, d) - len(cols)), replace=False)
+    cols = np.sort(np.concatenate([np.asarray(cols, dtype=np.int64), extra.astype(np.int64)]))
+    assert {int(c) % 4 for c in cols} == {0, 1, 2, 3} and any((int(c) // 4) % 2 for c in cols)
+    return cols
+
+
 def check_columns(h, rowptr, col, d, op, cols, seed, check_naive=True):
     """Forward + backward of the HAG path (and the naive-CSR GPU kernels) at feature width d,
     compared with the oracle on the columns `cols`."""
@@ -206,6 +223,33 @@ def test_config3_structure(request, B, big_graph, big_hags):
     assert st["aggr_naive"] - st["aggr_hag"] == int((red.astype(np.int64) - 1).sum())
     progress(request, f"config 3 HAG: aggregations {st['aggr_naive']} -> {st['aggr_hag']}, levels {st['levels']}, "
                       f"stages {st['stages']}, redundancy {red[0]}..{red[-1]}")
+    # Deep in the stored list: merge k must be a maximal pair of the HAG that its first k merges give.
+    # The oracle recounts Redundancy (Algorithm 3) of that pair on the replayed lists, and of other
+    # pairs among the most-shared nodes, which may not exceed it.
+    from paper_1906_03707_amd import workloads
+    z = np.load(workloads.cache_path(3))
+    cl, cr, cred = z["left"], z["right"], z["red"]
+    for k in (n // 8, n // 4):
+        hk = big_hags[k]
+        _, _, red_k = hk.get_merges()
+        assert np.array_equal(red_k, cred[:k])                # the replay reproduces every logged redundancy
+        f = hk.get_forward()
+        # creation-order ids -> the level-order ids of this prefix (stable sort by depth)
+        depth = np.zeros(n + k, dtype=np.int64)
+        for i in range(k):
+            depth[n + i] = 1 + max(depth[cl[i]], depth[cr[i]])
+        order = np.argsort(depth[n:], kind="stable")
+        newid = np.arange(n + k, dtype=np.int64)
+        newid[n + order] = n + np.arange(k)
+        p, q = int(newid[cl[k]]), int(newid[cr[k]])
+        progress(request, f"oracle recount of merge {k}: pair ({cl[k]}, {cr[k]}), logged redundancy {cred[k]} ...")
+        assert oracle.redundancy(n, f["hrowptr"], f["hcol"], p, q) == cred[k]
+        uses = np.bincount(f["hcol"], minlength=n + k)
+        hot = np.argsort(-uses, kind="stable")[:12]
+        rng = np.random.default_rng(k)
+        for _ in range(24):
+            a, b = rng.choice(hot, size=2, replace=False)
+            assert oracle.redundancy(n, f["hrowptr"], f["hcol"], int(a), int(b)) <= cred[k]
 
 
 @pytest.mark.timeout(900)
@@ -218,7 +262,7 @@ def test_config3_cached_merges_are_what_the_search_finds(request, B, big_graph):
     progress(request, f"hag_search (pair counting on the device), capacity {k} ...")
     h = B.hag_search(rowptr, col, k, flags=B.HAG_SEARCH_DEVICE)
     left, right, red = h.get_merges()
-    cl, cr = workloads.load_cached_merges(3)
+    cl, cr, _ = workloads.load_cached_merges(3)
     assert left.size == k and np.array_equal(left, cl[:k]) and np.array_equal(right, cr[:k])
     progress(request, f"first {k} merges equal the cached list (redundancy {red[0]}..{red[-1]})")
 
@@ -228,7 +272,7 @@ def test_config3_dcsbm_sum(request, B, big_graph, big_hags):
     rowptr, col = big_graph
     n = rowptr.size - 1
     h = big_hags[n // 4].upload()
-    cols = np.arange(0, 128, 8)                                           # 16 of 128 columns, all rows
+    cols = sample_columns(128, 16, 303)                                   # 16 of 128 columns, all rows
     ref = sampled_reference(request, rowptr, col, 128, "sum", cols, synth.SEED_BASE + 3 + 1000)
     compare_with_reference(h, ref, 128, "sum", cols)
     compare_with_reference(h, ref, 128, "sum", cols, naive=True)
@@ -238,7 +282,7 @@ def test_config3_dcsbm_sum(request, B, big_graph, big_hags):
 @pytest.mark.parametrize("d,op", [(16, "max"), (16, "sum"), (128, "max"), (128, "sum"), (512, "max"), (512, "sum")])
 def test_config5_capacity_and_width_sweep(request, B, big_graph, big_hags, d, op):
     rowptr, col = big_graph
-    cols = np.arange(0, d, max(d // 8, 1))[:8]                            # 8 sampled columns, all rows
+    cols = sample_columns(d, 8, 500 + d)                                  # 8 sampled columns, all rows
     ref = sampled_reference(request, rowptr, col, d, op, cols, synth.SEED_BASE + 5 + 1000 + d)
     for cap, h in big_hags.items():
         progress(request, f"config 5: d={d} {op} capacity {cap}")

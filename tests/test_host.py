@@ -276,3 +276,35 @@ def test_build_rejects_kernels_that_use_scratch_memory():
     assert name.startswith("_ZN3hag13gather_kernel") and u["VGPRs"] == "62" and u["LDS Size [bytes/block]"] == "8192"
     with pytest.raises(RuntimeError, match="scratch"):
         check_resource_usage(remarks(344))
+
+
+def test_binding_rejects_misshaped_tensors_before_the_call():
+    # the C ABI takes raw pointers and no row count: the binding must refuse anything that would
+    # make a kernel run out of bounds (checked on CPU tensors: the refusal comes before any launch)
+    import torch
+
+    rowptr, col = synth.random_graph(40, 0.2, seed=3)
+    h = B.hag_search(rowptr, col, 10)
+    n = 40
+    ok = torch.zeros((n, 8), dtype=torch.float32)
+    with pytest.raises(ValueError, match="shape"):
+        h.forward(torch.zeros((n - 1, 8), dtype=torch.float32))
+    with pytest.raises(ValueError, match="shape"):
+        h.backward(torch.zeros((n + 5, 8), dtype=torch.float32))
+    with pytest.raises(ValueError, match="output"):
+        h.forward(ok, y=torch.zeros((n, 8), dtype=torch.float16))
+    with pytest.raises(ValueError, match="output"):
+        h.forward(ok, y=torch.zeros((n, 4), dtype=torch.float32))
+    with pytest.raises(ValueError, match="argmax"):
+        h.forward(ok, "max", argmax=torch.zeros((n, 8), dtype=torch.int64))
+    with pytest.raises(ValueError, match="argmax"):
+        h.backward(ok, "max")
+    with pytest.raises(ValueError, match="workspace"):
+        h.forward(ok, workspace=torch.zeros(16, dtype=torch.uint8))
+    with pytest.raises(ValueError, match="unknown op"):
+        h.forward(ok, "prod")
+    with pytest.raises(TypeError):
+        h.forward(torch.zeros((n, 8), dtype=torch.float64))
+    # a well-formed call on CPU tensors still never reaches the library
+    with pytest.raises(ValueError, match="GPU"):
+        h.forward(ok, workspace=torch.zeros(1 << 20, dtype=torch.uint8))

@@ -131,6 +131,24 @@ def test_naive_max_vs_reduceat_and_bruteforce():
             if am[v, f] >= 0:
                 ref[am[v, f], f] += float(gy[v, f])
     np.testing.assert_allclose(gx, ref, atol=1e-12)
+    # the int32 form of the same backward pass, incl. sums that wrap: scattering to the wrong row,
+    # or to the right row of the wrong feature, changes single elements, not only column sums
+    xi = synth.features_i32(n, d, 24, lo=-3, hi=3)                 # few distinct values: many ties
+    gi = synth.features_i32(n, d, 25, lo=-2**31, hi=2**31 - 1)     # sums overflow
+    yi, _, ami = oracle.naive_forward(rowptr, col, xi, "max")
+    for v in np.nonzero(nonempty)[0]:
+        nb = col[rowptr[v]:rowptr[v + 1]]
+        for f in range(d):
+            assert yi[v, f] == xi[nb, f].max()
+            assert ami[v, f] == nb[xi[nb, f] == yi[v, f]].min()    # ties: smallest original id
+    gxi, _ = oracle.naive_backward(rowptr, col, gi, "max", ami)
+    refi = np.zeros((n, d), dtype=np.int64)
+    for v in range(n):
+        for f in range(d):
+            if ami[v, f] >= 0:
+                refi[ami[v, f], f] += int(gi[v, f])
+    assert np.array_equal(gxi.astype(np.int64) & 0xFFFFFFFF, refi & 0xFFFFFFFF)
+    assert np.any(refi != refi.astype(np.int32))                   # some sums did wrap
 
 
 def test_max_ties_go_to_smallest_original_id():
