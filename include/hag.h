@@ -32,6 +32,13 @@
  * copied during the call.  Device arrays (x, y, gy, gx, argmax, workspace) are
  * caller-owned device memory and must not alias each other.
  *
+ * Memory kind.  Device arrays must be ordinary device memory (hipMalloc: coarse-grained).  The
+ * max backward pass accumulates with hardware floating-point atomics, which fine-grained or
+ * host-mapped memory does not support.
+ *
+ * Environment.  The launch path never reads the environment.  Tuning and test knobs (HAG_* variables,
+ * listed in the project documentation) are read once, when a handle is built.
+ *
  * Execution.  Device entry points enqueue kernels on `stream` (a hipStream_t
  * passed as void*, NULL = the default stream) and return without synchronising;
  * they allocate nothing.  All functions return a status (0 = HAG_OK); the
@@ -201,6 +208,21 @@ int hag_naive_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d
  * row one write, plus index reads), for roofline accounting.  which: 0 hag_forward,
  * 1 hag_backward, 2 hag_naive_forward, 3 hag_naive_backward. */
 int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d);
+
+/* Measurement helpers (nothing of the paper's method): kernels that only move bytes in the
+ * access shape of the aggregation kernels, so that a benchmark run can state the ceilings its
+ * roofline fractions are measured against.
+ * hag_probe_rows: every sub-group of lanes (as many lanes as a row of d fp32 features has
+ * 16-byte vectors, a power of two from 4 to 64) of `workgroups` 256-thread workgroups reads
+ * `reads` pseudo-random rows of the device matrix src [n_rows, d] (n_rows a power of two,
+ * d a multiple of 4 up to 256, reads a multiple of 4) and writes its sum to sink (device,
+ * workgroups * 1024 floats).  The matrix size decides which memory level serves the rows;
+ * from_lds != 0 copies as many rows as fit 64 KB into LDS first and reads those instead.
+ * Returns the number of row bytes read (>= 0) or a negative status.
+ * hag_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte granularity. */
+int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads, int32_t from_lds,
+                       int64_t workgroups, void *sink, void *stream);
+int hag_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
 
 const char *hag_last_error(void);
 

@@ -27,7 +27,7 @@ EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
-    "hag_algorithmic_bytes", "hag_last_error",
+    "hag_algorithmic_bytes", "hag_last_error", "hag_probe_rows", "hag_probe_copy",
 ]
 
 
@@ -77,6 +77,9 @@ def lib():
         L.hag_algorithmic_bytes.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64]
         L.hag_algorithmic_bytes.restype = i64
         L.hag_last_error.restype = ctypes.c_char_p
+        L.hag_probe_rows.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
+        L.hag_probe_rows.restype = i64
+        L.hag_probe_copy.argtypes = [vp, vp, i64, vp]
         _lib = L
     return _lib
 
@@ -278,3 +281,20 @@ def hag_from_merges(rowptr, col, left, right, flags=0) -> Hag:
     _check(lib().hag_from_merges(rowptr.size - 1, rowptr.ctypes.data, col.ctypes.data, left.size,
                                  left.ctypes.data, right.ctypes.data, flags, ctypes.byref(out)))
     return Hag(out.value)
+
+
+def probe_rows(src, n_rows, d, reads, from_lds, workgroups, sink) -> int:
+    """hag_probe_rows on torch device tensors; returns the row bytes the launch reads."""
+    if src.numel() < n_rows * d or sink.numel() < workgroups * 1024:
+        raise ValueError("probe buffers too small")
+    rc = lib().hag_probe_rows(_dev_ptr(src), int(n_rows), int(d), int(reads), int(bool(from_lds)), int(workgroups),
+                              _dev_ptr(sink), _stream_ptr())
+    if rc < 0:
+        _check(rc)
+    return int(rc)
+
+
+def probe_copy(src, dst, nbytes):
+    if src.numel() * src.element_size() < nbytes or dst.numel() * dst.element_size() < nbytes:
+        raise ValueError("copy buffers too small")
+    _check(lib().hag_probe_copy(_dev_ptr(src), _dev_ptr(dst), int(nbytes), _stream_ptr()))

@@ -1,0 +1,122 @@
+// Measurement helpers of libhag: kernels that only move bytes, in the access shape of the
+// aggregation kernels, so that a benchmark run can state the ceilings its roofline fractions
+// are measured against (rows served by L2, by the memory-side cache, by HBM, by LDS; a plain
+// streaming copy).  They compute nothing of the method.
+#include "hag_device_common.hpp"
+
+namespace hag {
+
+// cheap integer hash: the row a sub-group reads in step i
+__device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
+    x ^= x >> 16;
+    x *= 0x7feb352dU;
+    x ^= x >> 15;
+    x *= 0x846ca68bU;
+    x ^= x >> 16;
+    return x;
+}
+
+// Every sub-group of LPR lanes reads `reads` pseudo-random rows of a [n_rows, d] fp32 matrix, four
+// rows in flight, each row as one contiguous run of 16-byte loads (the gather kernel's access
+// shape without its index loads), and adds them up.  n_rows must be a power of two.
+//   LDS = false: rows come from global memory; the matrix size decides which level serves them;
+//   LDS = true:  the workgroup first copies rows [0, lds_rows) into LDS and reads those.
+template <int LPR, bool LDS>
+__global__ __launch_bounds__(kBlock) void probe_rows_kernel(const float *__restrict__ src, uint32_t row_mask, int32_t d,
+                                                            int32_t reads, int32_t lds_rows, float *__restrict__ sink) {
+    extern __shared__ __align__(16) unsigned char probe_smem[];
+    float *buf = reinterpret_cast<float *>(probe_smem);
+    const int lane = threadIdx.x & (kWave - 1);
+    const int sl = lane % LPR;
+    const int q = d / 4;
+    const int cb = min(sl, q - 1) * 4;
+    const uint32_t group = (uint32_t)((blockIdx.x * kBlock + threadIdx.x) / LPR);
+    if (LDS) {
+        for (int i = threadIdx.x; i < lds_rows * q; i += kBlock)
+            *reinterpret_cast<float4 *>(buf + 4 * (size_t)i) = ld4(src + 4 * (size_t)i);
+        __syncthreads();
+    }
+    float4 acc{};
+    const uint32_t mask = LDS ? (uint32_t)(lds_rows - 1) : row_mask;
+    for (int i = 0; i < reads; i += 4) {
+        uint32_t r[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) r[k] = probe_hash(group * 0x9e3779b9U + (uint32_t)(i + k)) & mask;
+        float4 v[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            if (LDS) v[k] = *reinterpret_cast<const float4 *>(buf + (size_t)r[k] * d + cb);
+            else v[k] = ld4(src + (size_t)r[k] * d + cb);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) add4(acc, v[k]);
+    }
+    st4(sink + 4 * ((size_t)blockIdx.x * kBlock + threadIdx.x), acc);
+}
+
+// grid-stride streaming copy, 16 bytes per lane and step
+__global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4 *__restrict__ src, float4 *__restrict__ dst,
+                                                            int64_t n16) {
+    const int64_t stride = (int64_t)gridDim.x * kBlock;
+    for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
+}
+
+template <bool LDS>
+static int launch_probe_rows(int lpr, unsigned groups, size_t lds_bytes, hipStream_t s, const float *src, uint32_t mask,
+                             int32_t d, int32_t reads, int32_t lds_rows, float *sink) {
+    const dim3 grid(groups), block(kBlock);
+    switch (lpr) {
+        case 4: hipLaunchKernelGGL((probe_rows_kernel<4, LDS>), grid, block, lds_bytes, s, src, mask, d, reads, lds_rows, sink); break;
+        case 8: hipLaunchKernelGGL((probe_rows_kernel<8, LDS>), grid, block, lds_bytes, s, src, mask, d, reads, lds_rows, sink); break;
+        case 16: hipLaunchKernelGGL((probe_rows_kernel<16, LDS>), grid, block, lds_bytes, s, src, mask, d, reads, lds_rows, sink); break;
+        case 32: hipLaunchKernelGGL((probe_rows_kernel<32, LDS>), grid, block, lds_bytes, s, src, mask, d, reads, lds_rows, sink); break;
+        default: hipLaunchKernelGGL((probe_rows_kernel<64, LDS>), grid, block, lds_bytes, s, src, mask, d, reads, lds_rows, sink); break;
+    }
+    HIP_TRY(hipGetLastError());
+    return HAG_OK;
+}
+
+}  // namespace hag
+
+using namespace hag;
+
+extern "C" {
+
+int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads, int32_t from_lds, int64_t workgroups,
+                       void *sink, void *stream) {
+    if (!src || !sink) { set_error("NULL pointer"); return HAG_EINVAL; }
+    if (((uintptr_t)src | (uintptr_t)sink) & 15) { set_error("pointers must be 16-byte aligned"); return HAG_EINVAL; }
+    if (d <= 0 || d % 4 != 0 || d > 256) { set_error("d must be a multiple of 4 in [4, 256]"); return HAG_EINVAL; }
+    if (n_rows <= 0 || (n_rows & (n_rows - 1)) != 0 || n_rows > (1LL << 31)) { set_error("n_rows must be a power of two"); return HAG_EINVAL; }
+    if (reads <= 0 || reads % 4 != 0 || reads > (1 << 24)) { set_error("reads must be a positive multiple of 4"); return HAG_EINVAL; }
+    if (workgroups <= 0 || workgroups > (1 << 20)) { set_error("workgroups out of range"); return HAG_EINVAL; }
+    const int lpr = pick_lpr(d);
+    const int64_t groups_per_wg = kBlock / lpr;
+    int rc;
+    if (from_lds) {
+        // as many rows as fit 64 KB, a power of two, at most n_rows
+        int64_t lds_rows = 1;
+        while (lds_rows * 2 * d * 4 <= 64 * 1024 && lds_rows * 2 <= n_rows) lds_rows *= 2;
+        rc = launch_probe_rows<true>(lpr, (unsigned)workgroups, (size_t)(lds_rows * d * 4), (hipStream_t)stream,
+                                     (const float *)src, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
+    } else {
+        rc = launch_probe_rows<false>(lpr, (unsigned)workgroups, 0, (hipStream_t)stream, (const float *)src,
+                                      (uint32_t)(n_rows - 1), (int32_t)d, (int32_t)reads, 0, (float *)sink);
+    }
+    if (rc) return rc;
+    return workgroups * groups_per_wg * reads * d * 4;   // bytes of rows read
+}
+
+int hag_probe_copy(const void *src, void *dst, int64_t bytes, void *stream) {
+    if (!src || !dst) { set_error("NULL pointer"); return HAG_EINVAL; }
+    if ((((uintptr_t)src | (uintptr_t)dst) & 15) || bytes <= 0 || bytes % 16 != 0) {
+        set_error("pointers and size must be multiples of 16 bytes");
+        return HAG_EINVAL;
+    }
+    hipLaunchKernelGGL(probe_copy_kernel, dim3(256 * 16), dim3(kBlock), 0, (hipStream_t)stream, (const float4 *)src,
+                       (float4 *)dst, bytes / 16);
+    HIP_TRY(hipGetLastError());
+    return HAG_OK;
+}
+
+}  // extern "C"
