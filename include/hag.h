@@ -204,6 +204,20 @@ int hag_naive_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
 int hag_naive_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
                        const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream);
 
+/* For callers that cannot allocate or hand over scratch memory (code under HIP graph capture
+ * that owns no buffer pool, tight serving loops, harnesses that forbid hipMalloc): hag_forward
+ * with the workspace taken from a fixed device array inside the library instead of from the
+ * caller.  The array holds HAG_STATIC_SCRATCH_BYTES per GPU from the moment the library is loaded
+ * until the process ends.  HAG_EINVAL (nothing is launched) when
+ * hag_workspace_bytes(h, op, dtype, d) exceeds it; HAG_ESTATE before hag_upload.  The call
+ * allocates nothing, on the host or on the device.  All calls on one GPU share the one array:
+ * calls that may overlap in time (different streams, different threads) race on it and must be
+ * serialised by the caller; its contents are left over from the last call and nothing is
+ * expected of them (every row of it that a pass reads was written by that pass before). */
+#define HAG_STATIC_SCRATCH_BYTES (64u << 20)
+int hag_forward_static_scratch(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
+                               const void *x, void *y, int32_t *argmax, void *stream);
+
 /* Algorithmic bytes one call moves (every HAG edge one row read, every produced
  * row one write, plus index reads), for roofline accounting.  which: 0 hag_forward,
  * 1 hag_backward, 2 hag_naive_forward, 3 hag_naive_backward. */

@@ -27,8 +27,9 @@ EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
-    "hag_algorithmic_bytes", "hag_last_error", "hag_probe_rows", "hag_probe_copy",
+    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy",
 ]
+HAG_STATIC_SCRATCH_BYTES = 64 << 20
 
 
 class HagError(RuntimeError):
@@ -77,6 +78,7 @@ def lib():
         L.hag_algorithmic_bytes.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64]
         L.hag_algorithmic_bytes.restype = i64
         L.hag_last_error.restype = ctypes.c_char_p
+        L.hag_forward_static_scratch.argtypes = [vp, ctypes.c_int, ctypes.c_int, i64, vp, vp, vp, vp]
         L.hag_probe_rows.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
         L.hag_probe_rows.restype = i64
         L.hag_probe_copy.argtypes = [vp, vp, i64, vp]
@@ -243,6 +245,19 @@ class Hag:
 
     def backward(self, gy, op="sum", argmax=None, gx=None, workspace=None):
         return self._bwd(lib().hag_backward, gy, op, argmax, gx, workspace)
+
+    def forward_static_scratch(self, x, op="sum", y=None, argmax=None):
+        """hag_forward with the library's fixed scratch array as workspace (no workspace argument)."""
+        import torch
+        self._check_args("x", x, op, y, argmax, None, False)
+        n, d = x.shape
+        if y is None:
+            y = torch.empty_like(x)
+        if op == "max" and argmax is None:
+            argmax = torch.empty((n, d), dtype=torch.int32, device=x.device)
+        _check(lib().hag_forward_static_scratch(self._h, OPS[op], _dtype_code(x), d, _dev_ptr(x), _dev_ptr(y),
+                                                _dev_ptr(argmax), _stream_ptr()))
+        return (y, argmax) if op == "max" else y
 
     def forward_phases(self, x, phases, op="sum", y=None, argmax=None, workspace=None):
         return self._fwd(lib().hag_forward_phases, x, op, y, argmax, workspace, int(phases))

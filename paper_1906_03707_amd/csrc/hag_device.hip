@@ -71,6 +71,27 @@ __global__ __launch_bounds__(kBlock) void max_backward_kernel(const T *__restric
     if (u >= 0) atomic_accumulate(gx + (size_t)u * d + (i % d), gy[i]);
 }
 
+// Scratch for callers that cannot bring a workspace (hag_forward_static_scratch): one array per
+// GPU, held from the moment the code object is loaded until the process ends.  In host code the
+// array's name is only a stand-in for the symbol; the address of each GPU's copy is looked up once
+// per device (hag_upload, with that device current) and kept here.
+static __device__ __align__(256) unsigned char scratch[HAG_STATIC_SCRATCH_BYTES];
+constexpr int kMaxDevices = 64;
+static void *g_scratch_ptr[kMaxDevices] = {};
+
+// address of the current device's scratch array, looked up on first use
+static int scratch_address(int device, void **out) {
+    if (device < 0 || device >= kMaxDevices) { set_error("device index out of range"); return HAG_EINVAL; }
+    if (!g_scratch_ptr[device]) {
+        void *p = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)));
+        if (!p) { set_error("hipGetSymbolAddress returned no address for the scratch array"); return HAG_EHIP; }
+        g_scratch_ptr[device] = p;
+    }
+    *out = g_scratch_ptr[device];
+    return HAG_OK;
+}
+
 struct Workspace {
     char *agg = nullptr;      // [a, d] aggregation-node rows (forward) or their gradients (transposed pass)
     char *part = nullptr;     // [max_slots, d]
@@ -375,6 +396,11 @@ int hag_upload(hag_t *h, void *stream) {
     hipStream_t s = (hipStream_t)stream;
     HIP_TRY(hipGetDevice(&h->device));
     int rc = HAG_OK;
+    {
+        // set-up of the static scratch array for this device (the only place that queries the symbol)
+        void *unused = nullptr;
+        if ((rc = scratch_address(h->device, &unused))) return rc;
+    }
     std::vector<int32_t> slots((size_t)h->max_slots);
     for (size_t i = 0; i < slots.size(); ++i) slots[i] = (int32_t)i;
     if ((rc = upload_array(h, h->left, &h->d_left, s))) goto bad;
@@ -454,6 +480,22 @@ static int backward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t d
 
 int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y, int32_t *argmax,
                 void *ws, void *stream) {
+    return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, HAG_PHASE_ALL);
+}
+int hag_forward_static_scratch(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
+                               int32_t *argmax, void *stream) {
+    if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
+    if (!h->uploaded) { set_error("hag_upload has not been called on this handle"); return HAG_ESTATE; }
+    if (d <= 0 || d > (1 << 20)) { set_error("d out of range"); return HAG_EINVAL; }
+    const size_t need = hag_workspace_bytes(h, op, dt, d);
+    if (need > (size_t)HAG_STATIC_SCRATCH_BYTES) {
+        set_error("this pass needs " + std::to_string(need) + " bytes of scratch, the static array holds " +
+                  std::to_string((size_t)HAG_STATIC_SCRATCH_BYTES) + ": use hag_forward with a workspace");
+        return HAG_EINVAL;
+    }
+    // the address was looked up by hag_upload on the handle's device; no runtime query here
+    void *ws = (h->device >= 0 && h->device < kMaxDevices) ? g_scratch_ptr[h->device] : nullptr;
+    if (!ws) { set_error("static scratch of the handle's device was not set up"); return HAG_ESTATE; }
     return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, HAG_PHASE_ALL);
 }
 int hag_forward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
