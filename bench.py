@@ -365,6 +365,9 @@ def main():
                     help="also time one epoch of a 2-layer GraphSAGE with the max-pooling aggregator (16 hidden dims)")
     ap.add_argument("--gcn-epoch", action="store_true",
                     help="also time a 2-layer GCN epoch (16 hidden dims, SoftMax) around the aggregation")
+    ap.add_argument("--one-launch", action="store_true",
+                    help="run the HAG passes with the one-launch schedule (all stages and the gather over V in a single "
+                         "kernel launch; off by default because it measures slower)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy (hag_probe_copy: known traffic) so that rocprofv3 --pmc "
                          "FETCH_SIZE / WRITE_SIZE readings of the same run can be scaled")
@@ -393,6 +396,8 @@ def main():
     st = h.stats()
     n, e = st["n"], st["e"]
     h.upload()
+    if args.one_launch:
+        h.set_option(binding.HAG_OPT_ONE_LAUNCH_MAX_ITEMS, 1 << 20)
     seed = synth.SEED_BASE + cfg
     x = torch.from_numpy(synth.features_f32(n, d, seed + 1000)).cuda()
     gy = torch.from_numpy(synth.features_f32(n, d, seed + 2000)).cuda()
@@ -539,6 +544,7 @@ def main():
         "cold_cache_ms_per_step": {"hag": ms_hag_cold, "naive": ms_naive_cold},
         "hip_graph_replay_ms_per_step": {"hag": ms_hag_graph, "naive": ms_naive_graph},
         "ceilings_GBps": ceil,
+        "one_launch_schedule": bool(args.one_launch),
     }
     log(f"[bench] {workload} D={d} op={op}: N={n} E={e} A={st['a']} levels={st['levels']} E^={st['e_hag']}")
     log(f"[bench] fwd+bwd  hag {ms_hag:.4f} ms  naive {ms_naive:.4f} ms  speedup {ms_naive / ms_hag:.3f}x "

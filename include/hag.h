@@ -54,7 +54,7 @@
 extern "C" {
 #endif
 
-typedef struct hag_handle hag_t; /* opaque; immutable after construction except hag_upload */
+typedef struct hag_handle hag_t; /* opaque; immutable after construction except hag_upload and hag_set_option */
 
 /* Table 1, set Aggregate.  HAG_GCN is the GCN row's Update up to the weight matrix, fused
  * into the aggregation: y[v] = (sum over N(v) of x[u] + x[v]) / (|N(v)| + 1); f32 only. */
@@ -66,7 +66,8 @@ enum {
     HAG_EINVAL = -1,  /* bad argument (message says which) */
     HAG_ENOMEM = -2,  /* host or device allocation failed */
     HAG_EHIP = -3,    /* a HIP runtime call failed (message holds the HIP error string) */
-    HAG_ESTATE = -4   /* device entry point called before hag_upload */
+    HAG_ESTATE = -4,  /* device entry point called before hag_upload */
+    HAG_ETIMEOUT = -5 /* hag_check: a one-launch pass gave up waiting; its output is not valid */
 };
 
 enum {
@@ -183,6 +184,35 @@ int hag_forward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
  * gx is overwritten. */
 int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
                  const void *gy, const int32_t *argmax, void *gx, void *workspace, void *stream);
+
+/* The one-launch schedule (optional, off by default).  hag_forward and hag_backward can run
+ * Algorithm 2's loop over V_A and its final loop (resp. their transposes) as ONE kernel launch:
+ * workgroups draw units of work, phase by phase, from a device-wide ticket counter, and a unit of
+ * a later phase waits, inside the kernel, until every unit of the earlier phases has been counted as
+ * finished.  The wait is bounded; if it ever gives up the pass still runs to its end (every access
+ * in bounds) but its output is not valid, and hag_check reports it.  The pass keeps a few words of
+ * device state per handle, so while this schedule is in use calls on ONE handle must not overlap in
+ * time (enqueue them on one stream, or order the streams).  It is taken when: no row is cut into
+ * pieces, d <= 256, at most 7 stages, and the pass has at most HAG_OPT_ONE_LAUNCH_MAX_ITEMS rows.
+ * On MI355X it is slower than one launch per stage (a device-wide atomic update of one address
+ * completes about every 9 ns whoever issues it, and a pass needs one per unit of work; rows handed
+ * from one phase to the next must bypass the per-XCD L2s), hence off by default.
+ *
+ * hag_set_option changes a handle's launch options (host state only; affects later calls):
+ *   HAG_OPT_ONE_LAUNCH_MAX_ITEMS  largest pass, in rows, that takes the one-launch schedule (0 = never, the
+ *                                 default; the environment's HAG_FUSE_MAX_ITEMS when the handle was built);
+ *   HAG_OPT_SPIN_LIMIT            polls, about a microsecond apart, after which a wait gives up (default 262144);
+ *   HAG_OPT_TEST_WAIT_UNREACHABLE tests only: every wait is for a count that cannot be reached, so it gives up
+ *                                 after the spin limit and hag_check must report HAG_ETIMEOUT;
+ *   HAG_OPT_DETERMINISTIC_MAX_BACKWARD  non-zero: the backward pass of max adds up in a fixed order
+ *                                 (a gather over the transposed input graph filtered by argmax) instead
+ *                                 of with atomics; slower, bit-reproducible.
+ * hag_check synchronises `stream` and returns HAG_OK, or HAG_ETIMEOUT if a one-launch pass on this handle
+ * gave up waiting since the last check (and clears that state). */
+enum { HAG_OPT_ONE_LAUNCH_MAX_ITEMS = 1, HAG_OPT_SPIN_LIMIT = 2, HAG_OPT_TEST_WAIT_UNREACHABLE = 3,
+       HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 4 };
+int hag_set_option(hag_t *h, int32_t option, int64_t value);
+int hag_check(const hag_t *h, void *stream);
 
 /* The same two calls restricted to some of their phases, for per-kernel timing: a later
  * phase reads what an earlier call left in `workspace`.  HAG_PHASE_LEVELS = the

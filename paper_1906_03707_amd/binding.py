@@ -18,7 +18,8 @@ LIB_PATH = os.environ.get("HAG_LIB", os.path.join(_HERE, "libhag.so"))
 
 HAG_SUM, HAG_MEAN, HAG_MAX, HAG_GCN = 0, 1, 2, 3
 HAG_F32, HAG_I32 = 0, 1
-HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE = 0, -1, -2, -3, -4
+HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE, HAG_ETIMEOUT = 0, -1, -2, -3, -4, -5
+HAG_OPT_ONE_LAUNCH_MAX_ITEMS, HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE, HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 1, 2, 3, 4
 HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP, HAG_SEARCH_DEVICE = 1, 2, 4
 HAG_PHASE_LEVELS, HAG_PHASE_GATHER, HAG_PHASE_FOLD, HAG_PHASE_ALL = 1, 2, 4, 7
 OPS = {"sum": HAG_SUM, "mean": HAG_MEAN, "max": HAG_MAX, "gcn": HAG_GCN}
@@ -27,7 +28,7 @@ EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
-    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy",
+    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_set_option", "hag_check",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -82,6 +83,8 @@ def lib():
         L.hag_probe_rows.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
         L.hag_probe_rows.restype = i64
         L.hag_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.hag_set_option.argtypes = [vp, i32, i64]
+        L.hag_check.argtypes = [vp, vp]
         _lib = L
     return _lib
 
@@ -174,6 +177,14 @@ class Hag:
     def upload(self):
         _check(lib().hag_upload(self._h, _stream_ptr()))
         return self
+
+    def set_option(self, option, value):
+        _check(lib().hag_set_option(self._h, int(option), int(value)))
+        return self
+
+    def check(self):
+        """Synchronises the current stream; raises HagError(HAG_ETIMEOUT) if a one-launch pass gave up waiting."""
+        _check(lib().hag_check(self._h, _stream_ptr()))
 
     def workspace_bytes(self, op, dtype_code, d) -> int:
         return int(lib().hag_workspace_bytes(self._h, OPS[op], dtype_code, int(d)))

@@ -9,6 +9,8 @@
 // heavy-tailed.
 #include "hag_device_common.hpp"
 
+#include <vector>
+
 namespace hag {
 
 // One level of aggregation nodes (Algorithm 2, the loop over V_A): every node has exactly
@@ -117,6 +119,85 @@ static Workspace carve(const hag_handle *h, hag_op_t op, int64_t d, void *base) 
     return w;
 }
 
+// Longest item that a single sub-group of lanes takes; longer ones get a whole workgroup.
+static int64_t block_threshold(const hag_handle *h, const Plan &p, int64_t d) {
+    const int64_t sub_max = h->knobs.sub_max;
+    const int64_t nsg = kBlock / pick_lpr(d);
+    // A launch too small to fill the device with one sub-group per row (the stages of
+    // a small HAG) lasts as long as its longest single-sub-group row: there a row gets
+    // a workgroup much sooner.
+    const int64_t n_all = p.part_begin[p.np] - p.part_begin[0];
+    const bool small_launch = n_all <= 256 * 8 * nsg;
+    return sub_max > 0 ? sub_max : small_launch ? 16 : std::max<int64_t>(64, 8 * nsg);
+}
+
+// Whether a pass over `plans` (its phases in execution order) can run as one launch: a small
+// HAG whose launches are short against the gaps between them, no row cut into pieces (the fold
+// of partial rows would be one more phase per launch), feature columns in one chunk.
+static bool fusable(const hag_handle *h, int64_t d, const std::vector<const Plan *> &plans) {
+    if (h->knobs.fuse_max_items <= 0 || !h->d_sync || h->a == 0 || d > 256) return false;
+    if ((int)plans.size() > kMaxPhases || plans.size() < 2) return false;
+    int64_t items = 0;
+    for (const Plan *p : plans) {
+        if (p->np != 1 || !p->combine.empty() || p->items.empty()) return false;
+        items += (int64_t)p->items.size();
+    }
+    return items <= h->knobs.fuse_max_items;
+}
+
+// Fill the phase table of a one-launch pass and enqueue it.  `outs[k]` describes where phase k
+// writes: all but the last write aggregation rows (unified ids, offset n).
+template <typename T, int RED, int ROLE>
+static int run_fused(const hag_handle *h, const std::vector<const Plan *> &plans, const std::vector<const int32_t *> &cols,
+                     GatherArgs<T> base, T *agg_out, int32_t *agg_out_id, T *final_out, int32_t *final_out_id,
+                     hipStream_t s) {
+    FusedArgs<T> f{};
+    const int lpr = pick_lpr(base.d);
+    const int64_t per_block = (kBlock / kWave) * (kWave / lpr);
+    int64_t blocks = 0;
+    const int np = (int)plans.size();
+    for (int k = 0; k < np; ++k) {
+        const Plan &p = *plans[k];
+        auto &ph = f.ph[k];
+        ph.items = p.d_items;
+        ph.col = cols[k];
+        ph.n_items = (int64_t)p.items.size();
+        ph.n_block = long_items(p, 0, block_threshold(h, p, base.d));
+        const bool last = k == np - 1;
+        ph.out = last ? final_out : agg_out;
+        ph.out_id = last ? final_out_id : agg_out_id;
+        ph.out_off = last ? 0 : (int32_t)h->n;
+        ph.block_begin = (int32_t)blocks;
+        blocks += ph.n_block + (ph.n_items - ph.n_block + per_block - 1) / per_block;
+    }
+    if (blocks > (1 << 24)) { set_error("launch too large"); return HAG_EINVAL; }
+    f.n_phases = np;
+    f.total_blocks = (int32_t)blocks;
+    // As many workgroups as the device holds at once (8 per compute unit); each draws one unit per
+    // ticket unless that would be more than 16 tickets per workgroup.
+    f.chunk = (int32_t)std::min<int64_t>(std::max<int64_t>(blocks / (256 * 8 * 16), 1), 16);
+    f.grid = (int32_t)std::min<int64_t>((blocks + f.chunk - 1) / f.chunk, 256 * 8);
+    f.out_scale = base.out_scale;
+    f.self = base.self;
+    f.self_scale = base.self_scale;
+    base.out_scale = nullptr;
+    base.self = nullptr;
+    base.self_scale = nullptr;
+    {
+        const uint64_t row_bytes = (uint64_t)base.d * 4;
+        const uint64_t lo_rows = (uint64_t)std::max<int64_t>(base.split, 1);
+        base.off32 = (!h->knobs.offset64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
+    }
+    base.part = nullptr;
+    base.part_id = nullptr;
+    base.stream_hi = 0;
+    base.spin_limit = (int32_t)std::min<int64_t>(std::max<int64_t>(h->knobs.spin_limit, 1), INT32_MAX);
+    base.wait_bias = h->knobs.wait_unreachable ? (1 << 30) : 0;
+    f.base = base;
+    f.sync = h->d_sync;
+    return launch_fused<T, RED, ROLE>(f, s);
+}
+
 // run one schedule: the gather itself, then the fold of split rows
 template <typename T, int RED, int ROLE>
 static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, GatherArgs<T> a, const Workspace &w,
@@ -134,14 +215,7 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
     // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
     // eight neighbours, and needs one when a single sub-group would walk it for too long.
     {
-        const int64_t sub_max = h->knobs.sub_max;
-        const int64_t nsg = kBlock / pick_lpr(a.d);
-        // A launch too small to fill the device with one sub-group per row (the stages of
-        // a small HAG) lasts as long as its longest single-sub-group row: there a row gets
-        // a workgroup much sooner.
-        const int64_t n_all = p.part_begin[p.np] - p.part_begin[0];
-        const bool small_launch = n_all <= 256 * 8 * nsg;
-        const int64_t threshold = sub_max > 0 ? sub_max : small_launch ? 16 : std::max<int64_t>(64, 8 * nsg);
+        const int64_t threshold = block_threshold(h, p, a.d);
         for (int k = 0; k < p.np; ++k) {
             a.seg[k].begin = p.part_begin[k];
             a.seg[k].n_items = p.part_begin[k + 1] - p.part_begin[k];
@@ -260,6 +334,25 @@ static int forward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d,
         return launch_component<T, false>(h, naive, op, d, x, y, s);
     Workspace w = carve(h, op, d, ws);
     const int32_t n = (int32_t)h->n;
+    if (!naive && phases == HAG_PHASE_ALL) {
+        // a small HAG: aggregation-node stages and the gather over V as one launch
+        std::vector<const Plan *> plans;
+        std::vector<const int32_t *> cols;
+        for (int32_t st = 0; st < h->stages; ++st) { plans.push_back(&h->p_fwd_stage[st]); cols.push_back(h->d_ecol); }
+        plans.push_back(&h->p_fwd);
+        cols.push_back(h->d_hcol);
+        if (fusable(h, d, plans)) {
+            GatherArgs<T> b{};
+            b.src_lo = x;
+            b.src_hi = (const T *)w.agg;
+            b.id_hi = (const int32_t *)w.agg_id;
+            b.split = n;
+            b.d = (int32_t)d;
+            b.out_scale = op == HAG_MEAN ? h->d_inv_deg : op == HAG_GCN ? h->d_inv_deg1 : nullptr;
+            b.self = op == HAG_GCN ? x : nullptr;
+            return run_fused<T, RED, G_HAG_FWD>(h, plans, cols, b, (T *)w.agg, (int32_t *)w.agg_id, y, argmax, s);
+        }
+    }
     if (!naive && (phases & HAG_PHASE_LEVELS)) {
         for (int32_t st = 0; st < h->stages; ++st) {
             const int32_t first = h->stage_ptr[st], last = h->stage_ptr[st + 1];
@@ -337,6 +430,18 @@ static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d
         if (!(phases & (HAG_PHASE_GATHER | HAG_PHASE_FOLD))) return HAG_OK;
         return run_plan<T, R_SUM, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s, phases);
     }
+    if (phases == HAG_PHASE_ALL) {
+        std::vector<const Plan *> plans;
+        std::vector<const int32_t *> cols;
+        for (int32_t st = h->stages - 1; st >= 0; --st) { plans.push_back(&h->p_bwd_stage[st]); cols.push_back(h->d_tcol); }
+        plans.push_back(&h->p_bwd_src);
+        cols.push_back(h->d_tcol);
+        if (fusable(h, d, plans)) {
+            GatherArgs<T> b = a;
+            if (op == HAG_GCN) { b.self = gy; b.self_scale = h->d_inv_deg1; }
+            return run_fused<T, R_SUM, G_HAG_BWD_SRC>(h, plans, cols, b, (T *)w.agg, nullptr, gx, nullptr, s);
+        }
+    }
     // deepest stage first: its consumers are destinations only; an earlier stage may also be
     // consumed by aggregation nodes of later stages, whose gradient rows are complete by then
     for (int32_t st = h->stages - 1; st >= 0 && (phases & HAG_PHASE_LEVELS); --st) {
@@ -413,6 +518,12 @@ int hag_upload(hag_t *h, void *stream) {
     if ((rc = upload_array(h, slots, &h->d_slot_ids, s))) goto bad;
     if ((rc = upload_array(h, h->inv_deg, &h->d_inv_deg, s))) goto bad;
     if ((rc = upload_array(h, h->inv_deg1, &h->d_inv_deg1, s))) goto bad;
+    {
+        // ticket, finished count and give-up flag of the one-launch schedule: zero between launches
+        std::vector<int32_t> zeros(kSyncWords, 0);
+        if ((rc = upload_array(h, zeros, &h->d_sync, s))) goto bad;
+        (void)hipStreamSynchronize(s);   // `zeros` goes out of scope
+    }
     if ((rc = upload_plan(h, h->p_fwd, s))) goto bad;
     for (auto &p : h->p_bwd_stage)
         if ((rc = upload_plan(h, p, s))) goto bad;
@@ -498,6 +609,36 @@ int hag_forward_static_scratch(const hag_t *h, hag_op_t op, hag_dtype_t dt, int6
     if (!ws) { set_error("static scratch of the handle's device was not set up"); return HAG_ESTATE; }
     return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, HAG_PHASE_ALL);
 }
+int hag_set_option(hag_t *h, int32_t option, int64_t value) {
+    if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
+    switch (option) {
+        case HAG_OPT_ONE_LAUNCH_MAX_ITEMS: h->knobs.fuse_max_items = std::max<int64_t>(value, 0); return HAG_OK;
+        case HAG_OPT_SPIN_LIMIT: h->knobs.spin_limit = std::max<int64_t>(value, 1); return HAG_OK;
+        case HAG_OPT_TEST_WAIT_UNREACHABLE: h->knobs.wait_unreachable = value != 0; return HAG_OK;
+        case HAG_OPT_DETERMINISTIC_MAX_BACKWARD: h->knobs.deterministic_max_backward = value != 0; return HAG_OK;
+    }
+    set_error("unknown option");
+    return HAG_EINVAL;
+}
+
+int hag_check(const hag_t *h, void *stream) {
+    if (!h) { set_error("handle is NULL"); return HAG_EINVAL; }
+    if (!h->uploaded) { set_error("hag_upload has not been called on this handle"); return HAG_ESTATE; }
+    hipStream_t s = (hipStream_t)stream;
+    std::vector<int32_t> words(kSyncWords, 0);
+    HIP_TRY(hipMemcpyAsync(words.data(), h->d_sync, sizeof(int32_t) * kSyncWords, hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    bool clean = true;
+    for (int k = 0; k < kSyncWords; ++k) clean = clean && words[k] == 0;
+    if (clean) return HAG_OK;
+    // a wait gave up (or a launch did not finish): put the words back to zero for the next launch
+    HIP_TRY(hipMemsetAsync(h->d_sync, 0, sizeof(int32_t) * kSyncWords, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    set_error(words[kSyncGaveUp] ? "a one-launch pass gave up waiting for its earlier phases: its output is not valid"
+                       : "a one-launch pass did not run to its end");
+    return HAG_ETIMEOUT;
+}
+
 int hag_forward_phases(const hag_t *h, hag_op_t op, hag_dtype_t dt, int64_t d, const void *x, void *y,
                        int32_t *argmax, void *ws, void *stream, uint32_t phases) {
     return forward_entry(h, false, op, dt, d, x, y, argmax, ws, stream, phases);

@@ -51,6 +51,54 @@ struct GatherArgs {
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
     int32_t stream_hi;        // rows of src_hi are read once (fold of partial rows): streaming loads
+    // One-launch schedule only (sync_complete NULL otherwise): an item marked as depending on earlier
+    // phases waits until sync_complete[k] > wait_bias for every earlier phase k < wait_n, polling at
+    // most spin_limit times in all; a wait that gives up sets *sync_gave_up and goes on (every access
+    // stays in bounds; the result is then not valid).
+    const int32_t *sync_complete;
+    int32_t *sync_gave_up;
+    int32_t coherent_out;     // this phase's rows are read by later phases of the same launch
+    int32_t wait_n;
+    int32_t wait_bias;        // 0; tests make it large, so that no phase ever counts as complete
+    int32_t spin_limit;
+};
+
+// One pass (all aggregation-node stages and the gather over V) as a single launch.  Workgroups
+// take tickets in the order they start; ticket ranges map to phases, earlier phases first, so
+// whatever a workgroup waits for belongs to workgroups that are already running and never wait
+// for it.
+constexpr int kMaxPhases = 8;
+// Layout of the schedule's device words.  What is polled (the completion flags) sits in cache lines of
+// its own, apart from what is updated with atomics (ticket, counts): thousands of waiting wavefronts
+// reading a line would otherwise hold up the very updates they wait for.
+constexpr int kSyncLine = 32;   // words per 128-byte line
+constexpr int kSyncTicket = 0, kSyncFinished = kSyncLine, kSyncGaveUp = 2 * kSyncLine, kSyncDone = 4 * kSyncLine,
+              kSyncComplete = kSyncDone + kMaxPhases * kSyncLine, kSyncWords = kSyncComplete + kMaxPhases * kSyncLine;
+template <typename T>
+struct FusedArgs {
+    GatherArgs<T> base;       // everything the phases share; the per-phase fields below overwrite theirs
+    struct Phase {
+        const Item *items;
+        const int32_t *col;
+        int64_t n_block, n_items;
+        T *out;
+        int32_t *out_id;
+        int32_t out_off;
+        int32_t block_begin;  // first ticket of the phase = number of workgroups of all earlier phases
+    } ph[kMaxPhases];
+    int32_t n_phases;
+    int32_t total_blocks;     // units of work (one workgroup's worth each) over all phases
+    int32_t chunk;            // consecutive units a workgroup draws per ticket
+    int32_t grid;             // workgroups launched
+    // epilogue of the last phase (the rows of V)
+    const float *out_scale;
+    const T *self;
+    const float *self_scale;
+    // device words ticket, finished, gave_up, done[k], complete[k] (k < kMaxPhases; offsets kSync*, one
+    // 128-byte line each): all but gave_up are zero at launch and put back to zero by the last
+    // workgroup of the launch to finish; done[k] counts the finished workgroups of phase k, whose
+    // last one sets complete[k]
+    int32_t *sync;
 };
 
 __device__ __forceinline__ float4 ld4(const float *p) { return *reinterpret_cast<const float4 *>(p); }
@@ -78,6 +126,43 @@ __device__ __forceinline__ float4 ld4_stream(const float *p) {
 __device__ __forceinline__ int4 ld4_stream(const int32_t *p) {
     const i4v_t x = __builtin_nontemporal_load(reinterpret_cast<const i4v_t *>(p));
     return make_int4(x.x, x.y, x.z, x.w);
+}
+
+// Rows that one phase of a one-launch pass writes and a later phase of the same launch reads, on
+// another compute unit and possibly another XCD: element-wise device-scope accesses, which are
+// written through to, and read from, the level all XCDs share instead of a private cache.
+__device__ __forceinline__ float4 ld4_coherent(const float *p) {
+    float4 v;
+    v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+__device__ __forceinline__ int4 ld4_coherent(const int32_t *p) {
+    int4 v;
+    v.x = __hip_atomic_load(p + 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.y = __hip_atomic_load(p + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.z = __hip_atomic_load(p + 2, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    v.w = __hip_atomic_load(p + 3, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return v;
+}
+__device__ __forceinline__ void st4_coherent(float *p, float4 v) {
+    __hip_atomic_store(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+__device__ __forceinline__ void st4_coherent(int32_t *p, int4 v) {
+    __hip_atomic_store(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+template <bool COH>
+__device__ __forceinline__ int ld1_id(const int32_t *p) {
+    if constexpr (COH) return __hip_atomic_load(p, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    else return *p;
 }
 
 __device__ __forceinline__ void add4(float4 &a, const float4 &b) { a.x += b.x; a.y += b.y; a.z += b.z; a.w += b.w; }
@@ -119,38 +204,45 @@ __device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi)
 // acc_id is an original id, or an aggregation id whose stored winner has not been needed yet.
 // Original ids of a list arrive in ascending order before any aggregation id, so a tie
 // between two original ids keeps the accumulator.
-template <typename S>
+template <bool COH, typename S>
 __device__ __forceinline__ void settle_tie1(S v, int &vi, S w, int wi, const int32_t *id_hi, int split, size_t d,
                                             int col) {
     if (vi >= 0 && w == v) {
-        const int other = id_hi[(size_t)(wi - split) * d + col];
-        const int mine = vi < split ? vi : id_hi[(size_t)(vi - split) * d + col];
+        const int other = ld1_id<COH>(id_hi + (size_t)(wi - split) * d + col);
+        const int mine = vi < split ? vi : ld1_id<COH>(id_hi + (size_t)(vi - split) * d + col);
         vi = min(mine, other);
     }
 }
-template <typename V>
+template <bool COH, typename V>
 __device__ __forceinline__ void lazy_max4(V &v, int4 &vi, const V &w, int wi, const int32_t *id_hi, int split,
                                           size_t d, int cb) {
     if (wi >= split && (w.x == v.x || w.y == v.y || w.z == v.z || w.w == v.w)) {   // rare
-        settle_tie1(v.x, vi.x, w.x, wi, id_hi, split, d, cb);
-        settle_tie1(v.y, vi.y, w.y, wi, id_hi, split, d, cb + 1);
-        settle_tie1(v.z, vi.z, w.z, wi, id_hi, split, d, cb + 2);
-        settle_tie1(v.w, vi.w, w.w, wi, id_hi, split, d, cb + 3);
+        settle_tie1<COH>(v.x, vi.x, w.x, wi, id_hi, split, d, cb);
+        settle_tie1<COH>(v.y, vi.y, w.y, wi, id_hi, split, d, cb + 1);
+        settle_tie1<COH>(v.z, vi.z, w.z, wi, id_hi, split, d, cb + 2);
+        settle_tie1<COH>(v.w, vi.w, w.w, wi, id_hi, split, d, cb + 3);
     }
     max_first4(v, vi, w, wi);   // a tie keeps the accumulator, whose id is settled above
 }
 // replace aggregation ids left in acc_id by the original ids they stand for
+template <bool COH>
 __device__ __forceinline__ void resolve_ids(int4 &vi, const int32_t *id_hi, int split, size_t d, int cb) {
-    if (vi.x >= split) vi.x = id_hi[(size_t)(vi.x - split) * d + cb];
-    if (vi.y >= split) vi.y = id_hi[(size_t)(vi.y - split) * d + cb + 1];
-    if (vi.z >= split) vi.z = id_hi[(size_t)(vi.z - split) * d + cb + 2];
-    if (vi.w >= split) vi.w = id_hi[(size_t)(vi.w - split) * d + cb + 3];
+    if (vi.x >= split) vi.x = ld1_id<COH>(id_hi + (size_t)(vi.x - split) * d + cb);
+    if (vi.y >= split) vi.y = ld1_id<COH>(id_hi + (size_t)(vi.y - split) * d + cb + 1);
+    if (vi.z >= split) vi.z = ld1_id<COH>(id_hi + (size_t)(vi.z - split) * d + cb + 2);
+    if (vi.w >= split) vi.w = ld1_id<COH>(id_hi + (size_t)(vi.w - split) * d + cb + 3);
 }
 
-__device__ __forceinline__ Item load_item(const Item *p) {
+struct DevItem {
+    int64_t beg;
+    int32_t cnt, row;
+    bool depends;             // reads rows produced by an earlier phase of the pass
+};
+__device__ __forceinline__ DevItem load_item(const Item *p) {
     const int4 raw = *reinterpret_cast<const int4 *>(p);
-    Item it;
-    it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)raw.y << 32);
+    DevItem it;
+    it.beg = ((int64_t)(uint32_t)raw.x) | ((int64_t)(raw.y & 0x3fffffff) << 32);
+    it.depends = (raw.y >> 30) & 1;          // kItemDependsBit
     it.cnt = raw.z;
     it.row = raw.w;
     return it;
@@ -206,6 +298,9 @@ static inline int pick_lpr(int64_t d) {
 // Defined in the gather units (one per element type and reduction), used by hag_device.hip.
 template <typename T, int RED, int ROLE>
 int launch_gather(const GatherArgs<T> &a, hipStream_t s);
+// ROLE: G_HAG_FWD (forward pass) or G_HAG_BWD_SRC (transposed pass)
+template <typename T, int RED, int ROLE>
+int launch_fused(const FusedArgs<T> &a, hipStream_t s);
 
 // Defined in the component units (one per element type).  role: 0 = HAG forward, 1 = HAG
 // transposed pass, 2 = input graph forward (baseline), 3 = its transposed pass.

@@ -9,4 +9,6 @@ template int launch_gather<float, R_SUM, 3>(const GatherArgs<float> &, hipStream
 template int launch_gather<float, R_SUM, 4>(const GatherArgs<float> &, hipStream_t);
 template int launch_gather<float, R_SUM, 5>(const GatherArgs<float> &, hipStream_t);
 template int launch_gather<float, R_SUM, 6>(const GatherArgs<float> &, hipStream_t);
+template int launch_fused<float, R_SUM, G_HAG_FWD>(const FusedArgs<float> &, hipStream_t);
+template int launch_fused<float, R_SUM, G_HAG_BWD_SRC>(const FusedArgs<float> &, hipStream_t);
 }

@@ -22,6 +22,10 @@ struct Item {
     int32_t row;
 };
 static_assert(sizeof(Item) == 16, "Item is loaded as one 16-byte vector");
+// Set in Item::beg when the item's entries include ids >= the launch's split, i.e. rows that an
+// earlier phase of the same pass produces (they come last in the item's entries).  Only the
+// one-launch schedule looks at it: such an item waits for the earlier phases.
+constexpr int64_t kItemDependsBit = (int64_t)1 << 62;
 
 // Schedule of one gather launch (plus the optional second launch that folds the
 // partial slots of split rows).
@@ -35,6 +39,9 @@ struct Plan {
     std::vector<int64_t> part_begin;
     std::vector<Item> combine;   // per split row: beg = first slot, cnt = #slots, row = output row
     int64_t n_slots = 0;
+    // items of a length class up to this one are not ordered by class (see build_plan): the
+    // launch may only hand whole workgroups to items of longer classes
+    int min_block_class = 0;
     // device copies
     Item *d_items = nullptr;
     Item *d_combine = nullptr;
@@ -116,8 +123,10 @@ struct hag_knobs {
     bool offset64 = false;      // HAG_OFFSET64: force the 64-bit row addressing of matrices >= 4 GiB
     int32_t component_pad = 0;  // HAG_COMPONENT_PAD: padding of an LDS row, in elements (multiple of 4, <= 64)
     bool stream_output = false; // HAG_STREAM_OUTPUT: component pass writes output rows with streaming stores
-    int64_t fuse_max_items = 0; // HAG_FUSE_MAX_ITEMS: largest pass (schedule items) that runs as one launch
-    int64_t spin_limit = 0;     // HAG_SPIN_LIMIT: polls a workgroup of the one-launch pass waits for a stage
+    int64_t fuse_max_items = 0; // HAG_FUSE_MAX_ITEMS: largest pass (schedule items) that runs as one launch (0: never)
+    int64_t spin_limit = 0;     // HAG_SPIN_LIMIT: polls a wavefront of the one-launch pass waits for earlier phases
+    bool wait_unreachable = false;      // test only: the awaited count can never be reached, so every wait gives up
+    bool deterministic_max_backward = false;
 };
 
 struct hag_handle {
@@ -164,13 +173,15 @@ struct hag_handle {
     int32_t *d_hcol = nullptr, *d_tcol = nullptr, *d_gcol = nullptr, *d_gtcol = nullptr, *d_ecol = nullptr;
     int32_t *d_slot_ids = nullptr;
     float *d_inv_deg = nullptr, *d_inv_deg1 = nullptr;
+    int32_t *d_sync = nullptr;   // {ticket, done, gave_up, -} of the one-launch schedule; zero between launches
     std::vector<void *> d_allocs;
 };
 
 namespace hag {
 // hag_host.cpp
 int finalize(hag_handle *h, uint32_t flags);  // levels, forward form, transposes, schedules, stats
-void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p, bool partition);
+void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p, bool partition,
+                int64_t split);
 int64_t long_items(const Plan &p, int k, int64_t threshold);
 // hag_device.hip
 void free_device(hag_handle *h);

@@ -361,3 +361,92 @@ def test_config1_sbm_sum_f32_and_i32(B):
     l, r, red = h.get_merges()
     assert np.array_equal(l, ref.left) and np.array_equal(r, ref.right) and np.array_equal(red, ref.red)
     run_all_ops(B, h, rowptr, col, 64, seed=synth.SEED_BASE + 1001, ops=("sum",))
+
+
+# ------------------------------------------------------------------------------------------------
+# the one-launch schedule: Algorithm 2's loop over V_A and its final loop (resp. their transposes)
+# as a single kernel launch whose later phases wait inside the kernel for the earlier ones
+# ------------------------------------------------------------------------------------------------
+def one_launch_graphs(B, monkeypatch):
+    """(name, rowptr, col, handle) of small HAGs with one stage and with several dependent stages, with the
+    one-launch schedule (off by default) switched on."""
+    monkeypatch.setenv("HAG_FUSE_MAX_ITEMS", "262144")
+    out = []
+    rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=81)
+    out.append(("power-law, fused levels", rowptr, col, B.hag_search(rowptr, col, 750)))
+    monkeypatch.setenv("HAG_STAGE_EXTRA_ROWS", "-1000000")            # one stage per level: a chain of phases
+    rowptr, col = synth.sbm(n_blocks=4, block=60, p_in=0.5, p_out=0.02, seed=82)
+    h = B.hag_search(rowptr, col, rowptr.size - 1)
+    assert 3 <= h.stats()["stages"] == h.stats()["levels"] <= 7
+    out.append(("sbm, one phase per level", rowptr, col, h))
+    monkeypatch.delenv("HAG_STAGE_EXTRA_ROWS")
+    monkeypatch.delenv("HAG_FUSE_MAX_ITEMS")
+    return out
+
+
+def test_one_launch_pass_matches_oracle_and_per_stage_launches(B, monkeypatch):
+    for name, rowptr, col, h in one_launch_graphs(B, monkeypatch):
+        n = rowptr.size - 1
+        for d in (16, 64, 256):
+            run_all_ops(B, h, rowptr, col, d, seed=83 + d)
+            h.check()                                                  # no wait gave up
+            # the same handle with one launch per stage: the same additions in the same order
+            x, xi = dev(synth.features_f32(n, d, 84)), dev(synth.features_i32(n, d, 85))
+            one = [h.forward(x, "sum"), h.backward(x, "mean"), h.forward(x, "gcn"), h.backward(xi, "sum"), *h.forward(x, "max"),
+                   *h.forward(xi, "max")]
+            h.set_option(B.HAG_OPT_ONE_LAUNCH_MAX_ITEMS, 0)
+            per = [h.forward(x, "sum"), h.backward(x, "mean"), h.forward(x, "gcn"), h.backward(xi, "sum"), *h.forward(x, "max"),
+                   *h.forward(xi, "max")]
+            h.set_option(B.HAG_OPT_ONE_LAUNCH_MAX_ITEMS, 262144)
+            for k, (a, b) in enumerate(zip(one, per)):
+                assert torch.equal(a, b), (name, d, k)
+
+
+def test_one_launch_pass_replayed_from_a_hip_graph(B, monkeypatch):
+    # the pass resets its own ticket and count (no memset node): replays, with eager work and
+    # synchronisations in between, must all give the eager result
+    name, rowptr, col, h = one_launch_graphs(B, monkeypatch)[1]
+    n, d = rowptr.size - 1, 64
+    h.upload()
+    x, gy = dev(synth.features_f32(n, d, 86)), dev(synth.features_f32(n, d, 87))
+    y, gx = torch.empty_like(x), torch.empty_like(x)
+    want_y, want_gx = h.forward(x, "sum").clone(), h.backward(gy, "sum").clone()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        h.forward(x, "sum", y=y)
+        h.backward(gy, "sum", gx=gx)
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        h.forward(x, "sum", y=y)
+        h.backward(gy, "sum", gx=gx)
+    for rep in range(4):
+        y.fill_(-1.0)
+        gx.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(y, want_y) and torch.equal(gx, want_gx), rep
+        assert torch.equal(h.forward(x, "sum"), want_y)               # eager work between the replays
+        torch.cuda.synchronize()
+    h.check()
+
+
+def test_one_launch_pass_bounded_wait_gives_up_and_reports(B, monkeypatch):
+    # forced from the host: the awaited count is made unreachable and the spin limit tiny, so every
+    # wait ends by giving up; the kernel still runs to its end and hag_check reports it
+    name, rowptr, col, h = one_launch_graphs(B, monkeypatch)[0]
+    n, d = rowptr.size - 1, 32
+    h.upload()
+    x = dev(synth.features_f32(n, d, 88))
+    want = h.forward(x, "sum").clone()
+    h.check()
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 1).set_option(B.HAG_OPT_SPIN_LIMIT, 4)
+    h.forward(x, "sum")
+    h.backward(x, "sum")
+    with pytest.raises(B.HagError) as ei:
+        h.check()
+    assert ei.value.code == B.HAG_ETIMEOUT
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 0).set_option(B.HAG_OPT_SPIN_LIMIT, 1 << 18)
+    assert torch.equal(h.forward(x, "sum"), want)                      # the next pass is sound again
+    h.check()
