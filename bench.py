@@ -199,21 +199,10 @@ def cpu_baseline(oracle, synth, rowptr, col, h, d, seed, budget_s=24.0):
 
 def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     """Per-epoch time (forward + backward) of a 2-layer GCN with `hidden` hidden dims and a SoftMax
-    loss, the model of the paper's end-to-end measurement (Section 5.3), on the synthetic graph.
-    Each layer is h' = relu(gcn_agg(h W)): W is linear, so the layer transforms first and aggregates
-    at the narrow width.  Dense parts (h W, SoftMax) are torch; the aggregation is hag_forward /
-    hag_backward with op "gcn" (or the naive-CSR baseline)."""
-    fwd = h.naive_forward if naive else h.forward
-    bwd = h.naive_backward if naive else h.backward
-
-    class Agg(torch.autograd.Function):
-        @staticmethod
-        def forward(ctx, z):
-            return fwd(z.contiguous(), "gcn")
-
-        @staticmethod
-        def backward(ctx, g):
-            return bwd(g.contiguous(), "gcn")
+    loss, the model of the paper's end-to-end measurement (Section 5.3), on the synthetic graph
+    (paper_1906_03707_amd.layers.gcn2_loss: dense parts torch, aggregation hag_forward / hag_backward
+    with op "gcn", or the naive-CSR baseline)."""
+    from paper_1906_03707_amd import layers
 
     n, d = x.shape
     gen = torch.Generator(device="cuda").manual_seed(1)
@@ -222,9 +211,7 @@ def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     labels = torch.randint(0, classes, (n,), device="cuda", generator=gen)
 
     def epoch():
-        h1 = torch.relu(Agg.apply(x @ w1))
-        logits = Agg.apply(h1 @ w2)
-        loss = torch.nn.functional.cross_entropy(logits, labels)
+        loss = layers.gcn2_loss(h, x, w1, w2, labels, naive=naive)
         w1.grad = w2.grad = None
         loss.backward()
 
@@ -233,22 +220,9 @@ def gcn_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
 
 def sage_pool_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     """Per-epoch time (forward + backward) of a 2-layer GraphSAGE with the pooling aggregator of
-    Table 1: a_v = max over N(v) of relu(W1 h_u), h'_v = relu(W2 [a_v, h_v]), SoftMax loss.  Dense
-    parts are torch; the element-wise max (argmax kept for the backward pass) is hag_forward /
-    hag_backward with op "max" (or the naive-CSR baseline)."""
-    fwd = h.naive_forward if naive else h.forward
-    bwd = h.naive_backward if naive else h.backward
-
-    class MaxAgg(torch.autograd.Function):
-        @staticmethod
-        def forward(ctx, z):
-            y, am = fwd(z.contiguous(), "max")
-            ctx.am = am
-            return y
-
-        @staticmethod
-        def backward(ctx, g):
-            return bwd(g.contiguous(), "max", argmax=ctx.am)
+    Table 1 (paper_1906_03707_amd.layers.sage_pool2_loss: dense parts torch; the element-wise max,
+    argmax kept for the backward pass, is hag_forward / hag_backward with op "max", or the baseline)."""
+    from paper_1906_03707_amd import layers
 
     n, d = x.shape
     gen = torch.Generator(device="cuda").manual_seed(2)
@@ -259,13 +233,7 @@ def sage_pool_epoch_ms(torch, h, x, hidden, classes, steps, warmup, naive):
     labels = torch.randint(0, classes, (n,), device="cuda", generator=gen)
 
     def epoch():
-        hcur = x
-        for i in range(2):
-            a = MaxAgg.apply(torch.relu(hcur @ pool[i]))
-            hcur = torch.cat([a, hcur], dim=1) @ comb[i]
-            if i == 0:
-                hcur = torch.relu(hcur)
-        loss = torch.nn.functional.cross_entropy(hcur, labels)
+        loss = layers.sage_pool2_loss(h, x, pool, comb, labels, naive=naive)
         for w in pool + comb:
             w.grad = None
         loss.backward()

@@ -140,6 +140,22 @@ int hag_from_merges(int64_t n, const int64_t *rowptr, const int32_t *col,
  * tie-break is prefix-stable, so this is the HAG of a smaller capacity). */
 int hag_prefix(const hag_t *h, int64_t n_merges, hag_t **out);
 
+/* Algorithm 3 for a SEQUENTIAL Aggregate (ordered neighbour lists, e.g. an LSTM aggregator): only common
+ * prefixes can be shared (Section 3.1), Redundancy(v1, v2) is the number of nodes whose current list
+ * starts with (v1, v2) (the sequential branch of Redundancy in the listing), and a merge replaces that
+ * leading pair by a new node w in exactly those lists, w standing for the ordered cover
+ * (cover(v1), cover(v2)) of Equation 2.  Stops at `capacity` merges or when the best redundancy is <= 1;
+ * ties go to the lexicographically smallest (v1, v2).  With capacity >= |E| the result has the fewest
+ * aggregations any equivalent HAG can have (Theorem 3).  Host only; there is no device path for
+ * sequential aggregators.
+ * In: rowptr [n+1], col [rowptr[n]]: row v is the ORDERED list N(v) (a node may occur more than once).
+ * Out (caller arrays): left/right/redundancy [min(capacity, rowptr[n])]: merge i created node n+i from
+ * (left[i], right[i]) with that redundancy; *n_merges; hrowptr [n+1], hcol [rowptr[n]]: the final
+ * ordered lists (only a list's first entry can be an aggregation node).  HAG_EINVAL on malformed input. */
+int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity,
+                   int64_t *n_merges, int32_t *left, int32_t *right, int32_t *redundancy,
+                   int64_t *hrowptr, int32_t *hcol);
+
 void hag_free(hag_t *h);
 
 int hag_stats(const hag_t *h, hag_stats_t *out);

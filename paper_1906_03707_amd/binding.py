@@ -28,7 +28,7 @@ EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
-    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_set_option", "hag_check",
+    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_set_option", "hag_check", "hag_seq_search",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -83,6 +83,7 @@ def lib():
         L.hag_probe_rows.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
         L.hag_probe_rows.restype = i64
         L.hag_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.hag_seq_search.argtypes = [i64, vp, vp, i64, ctypes.POINTER(i64), vp, vp, vp, vp, vp]
         L.hag_set_option.argtypes = [vp, i32, i64]
         L.hag_check.argtypes = [vp, vp]
         _lib = L
@@ -324,3 +325,17 @@ def probe_copy(src, dst, nbytes):
     if src.numel() * src.element_size() < nbytes or dst.numel() * dst.element_size() < nbytes:
         raise ValueError("copy buffers too small")
     _check(lib().hag_probe_copy(_dev_ptr(src), _dev_ptr(dst), int(nbytes), _stream_ptr()))
+
+
+def hag_seq_search(rowptr, col, capacity):
+    """Algorithm 3 for a sequential Aggregate (ordered lists): (left, right, redundancy, hrowptr, hcol)."""
+    rowptr, col = _np(rowptr, np.int64), _np(col, np.int32)
+    n, e = rowptr.size - 1, int(rowptr[-1]) if rowptr.size else 0
+    cap = int(min(max(capacity, 0), e))
+    left, right, red = (np.zeros(max(cap, 1), dtype=np.int32) for _ in range(3))
+    hrowptr = np.zeros(n + 1, dtype=np.int64)
+    hcol = np.zeros(max(e, 1), dtype=np.int32)
+    a = ctypes.c_int64()
+    _check(lib().hag_seq_search(n, rowptr.ctypes.data, col.ctypes.data, int(capacity), ctypes.byref(a), left.ctypes.data,
+                                right.ctypes.data, red.ctypes.data, hrowptr.ctypes.data, hcol.ctypes.data))
+    return left[:a.value], right[:a.value], red[:a.value], hrowptr, hcol[:hrowptr[n]]
