@@ -242,7 +242,8 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         c.src_hi = (const T *)w.part;
         c.id_hi = (const int32_t *)w.part_id;
         c.in_scale = nullptr;
-        rc = launch_gather<T, RED, G_FOLD>(c, s);
+        constexpr int FOLD_RED = RED == R_SUMIF ? R_SUM : RED;   // partial rows of a filtered sum are plain sums
+        rc = launch_gather<T, FOLD_RED, G_FOLD>(c, s);
     }
     return rc;
 }
@@ -401,6 +402,22 @@ template <typename T>
 static int backward_impl(const hag_handle *h, bool naive, hag_op_t op, int64_t d, const T *gy, const int32_t *argmax,
                          T *gx, void *ws, hipStream_t s, uint32_t phases) {
     const int32_t n = (int32_t)h->n;
+    if (op == HAG_MAX && h->knobs.deterministic_max_backward) {
+        // gx[u, f] = sum over the consumers v of u of gy[v, f] where argmax[v, f] == u: a gather over the
+        // transposed input graph in a fixed order (no atomics), at the price of reading the argmax row
+        // of every consumer: about as much traffic as a forward pass
+        if (h->n == 0) return HAG_OK;
+        Workspace w = carve(h, HAG_SUM, d, ws);
+        GatherArgs<T> a{};
+        a.src_lo = gy;
+        a.split = n;
+        a.filter = argmax;
+        a.slot_row = h->p_naive_bwd.d_slot_row;
+        a.d = (int32_t)d;
+        a.out = gx;
+        a.out_off = 0;
+        return run_plan<T, R_SUMIF, G_NAIVE_BWD>(h, h->p_naive_bwd, h->d_gtcol, a, w, s, phases);
+    }
     if (op == HAG_MAX) {
         int64_t total = h->n * d;
         if (total == 0 || !(phases & HAG_PHASE_GATHER)) return HAG_OK;
@@ -532,6 +549,7 @@ int hag_upload(hag_t *h, void *stream) {
     if ((rc = upload_plan(h, h->p_bwd_src, s))) goto bad;
     if ((rc = upload_plan(h, h->p_naive_fwd, s))) goto bad;
     if ((rc = upload_plan(h, h->p_naive_bwd, s))) goto bad;
+    if ((rc = upload_array(h, h->p_naive_bwd.slot_row, &h->p_naive_bwd.d_slot_row, s))) goto bad;
     if (h->comp.enabled) {
         Components &c = h->comp;
         if ((rc = upload_array(h, c.meta, &c.d_meta, s))) goto bad;
@@ -580,7 +598,8 @@ static int forward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt
 
 static int backward_entry(const hag_t *h, bool naive, hag_op_t op, hag_dtype_t dt, int64_t d, const void *gy,
                           const int32_t *argmax, void *gx, void *ws, void *stream, uint32_t phases) {
-    int rc = check_common(h, op, dt, d, gy, gx, ws, op != HAG_MAX && hag_workspace_bytes(h, op, dt, d) > 0);
+    const bool needs_ws = (op != HAG_MAX || (h && h->knobs.deterministic_max_backward)) && hag_workspace_bytes(h, op, dt, d) > 0;
+    int rc = check_common(h, op, dt, d, gy, gx, ws, needs_ws);
     if (rc) return rc;
     if (op == HAG_MAX && !argmax && h->n > 0) { set_error("argmax is required for max"); return HAG_EINVAL; }
     if (gy == gx && h->n > 0) { set_error("gy and gx must not alias"); return HAG_EINVAL; }

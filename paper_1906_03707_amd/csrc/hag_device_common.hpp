@@ -16,7 +16,10 @@ namespace hag {
 constexpr int kBlock = 256;  // 4 wavefronts of 64 lanes
 constexpr int kWave = 64;
 
-enum { R_SUM = 0, R_MAX = 1 };
+// R_SUMIF: sum of the rows' elements whose entry in a second, int32 matrix (GatherArgs::filter, same
+// shape and row index as src_lo) equals the id of the output row: the backward pass of max as a
+// gather, gx[u, f] = sum over consumers v of u of gy[v, f] where argmax[v, f] == u, in a fixed order
+enum { R_SUM = 0, R_MAX = 1, R_SUMIF = 2 };
 // which phase a gather launch belongs to: only a tag, so that every phase has a kernel symbol
 // of its own in profiler output
 enum { G_HAG_FWD = 0, G_HAG_BWD_LEVEL = 1, G_HAG_BWD_SRC = 2, G_NAIVE_FWD = 3, G_NAIVE_BWD = 4, G_FOLD = 5, G_HAG_FWD_STAGE = 6 };
@@ -51,6 +54,8 @@ struct GatherArgs {
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
     int32_t stream_hi;        // rows of src_hi are read once (fold of partial rows): streaming loads
+    const int32_t *filter;    // R_SUMIF: [rows of src_lo, d]
+    const int32_t *slot_row;  // R_SUMIF: output row of every partial slot
     // One-launch schedule only (sync_complete NULL otherwise): an item marked as depending on earlier
     // phases waits until sync_complete[k] > wait_bias for every earlier phase k < wait_n, polling at
     // most spin_limit times in all; a wait that gives up sets *sync_gave_up and goes on (every access

@@ -11,4 +11,5 @@ template int launch_gather<float, R_SUM, 5>(const GatherArgs<float> &, hipStream
 template int launch_gather<float, R_SUM, 6>(const GatherArgs<float> &, hipStream_t);
 template int launch_fused<float, R_SUM, G_HAG_FWD>(const FusedArgs<float> &, hipStream_t);
 template int launch_fused<float, R_SUM, G_HAG_BWD_SRC>(const FusedArgs<float> &, hipStream_t);
+template int launch_gather<float, R_SUMIF, G_NAIVE_BWD>(const GatherArgs<float> &, hipStream_t);
 }

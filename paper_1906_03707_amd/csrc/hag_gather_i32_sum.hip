@@ -11,4 +11,5 @@ template int launch_gather<int32_t, R_SUM, 5>(const GatherArgs<int32_t> &, hipSt
 template int launch_gather<int32_t, R_SUM, 6>(const GatherArgs<int32_t> &, hipStream_t);
 template int launch_fused<int32_t, R_SUM, G_HAG_FWD>(const FusedArgs<int32_t> &, hipStream_t);
 template int launch_fused<int32_t, R_SUM, G_HAG_BWD_SRC>(const FusedArgs<int32_t> &, hipStream_t);
+template int launch_gather<int32_t, R_SUMIF, G_NAIVE_BWD>(const GatherArgs<int32_t> &, hipStream_t);
 }

@@ -709,6 +709,7 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
         return cx > cy;
     };
     p.min_block_class = bucket_rows > 0 ? kShortClass : 0;
+    p.slot_row = slot_row;
     p.part_begin.assign(np + 1, 0);
     for (int k = 0; k < np; ++k) {
         std::stable_sort(lists[k].begin(), lists[k].end(), before);

@@ -42,6 +42,8 @@ struct Plan {
     // items of a length class up to this one are not ordered by class (see build_plan): the
     // launch may only hand whole workgroups to items of longer classes
     int min_block_class = 0;
+    std::vector<int32_t> slot_row;   // output row of every partial slot
+    int32_t *d_slot_row = nullptr;
     // device copies
     Item *d_items = nullptr;
     Item *d_combine = nullptr;

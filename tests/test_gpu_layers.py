@@ -61,7 +61,7 @@ def check_recorded_calls(rowptr, col, record, op):
 def test_two_layer_gcn_forward_and_backward(B, naive):
     from paper_1906_03707_amd import layers
     for name, rowptr, col, h in graphs(B):
-        n, d, hidden, classes = rowptr.size - 1, 64, 16, 7
+        n, d, hidden, classes = rowptr.size - 1, 64, 16, 8
         rng = np.random.default_rng(93)
         x = synth.features_f32(n, d, 94)
         w1 = (rng.standard_normal((d, hidden)) / d ** 0.5).astype(np.float32)

@@ -450,3 +450,37 @@ def test_one_launch_pass_bounded_wait_gives_up_and_reports(B, monkeypatch):
     h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 0).set_option(B.HAG_OPT_SPIN_LIMIT, 1 << 18)
     assert torch.equal(h.forward(x, "sum"), want)                      # the next pass is sound again
     h.check()
+
+
+def test_deterministic_max_backward_is_bit_reproducible_and_matches_oracle(B, monkeypatch):
+    # the backward pass of max as a gather over the transposed input graph filtered by argmax (no atomics):
+    # int32 bit-exact, fp32 within tolerance and identical from run to run; also with rows cut into pieces
+    for env in ({}, {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "8", "HAG_BLOCK_MAX": "40"}):
+        for k, v in env.items():
+            monkeypatch.setenv(k, v)
+        rowptr, col = synth.holme_kim(2500, 9, 0.5, seed=97)
+        n = rowptr.size - 1
+        h = B.hag_search(rowptr, col, n // 4).upload()
+        for k in env:
+            monkeypatch.delenv(k)
+        for d in (16, 64, 260):
+            x, gy = synth.features_f32(n, d, 98), synth.features_f32(n, d, 99)
+            xi, gi = synth.features_i32(n, d, 98, lo=-5, hi=5), synth.features_i32(n, d, 99)
+            for feats, grads in ((x, gy), (xi, gi)):
+                y, am = h.forward(dev(feats), "max")
+                _, _, am_ref = oracle.naive_forward(rowptr, col, feats, "max")
+                assert_equal(am, am_ref, "argmax")
+                gx_ref, gs = oracle.naive_backward(rowptr, col, grads, "max", am_ref)
+                atomic = h.backward(dev(grads), "max", argmax=am)
+                h.set_option(B.HAG_OPT_DETERMINISTIC_MAX_BACKWARD, 1)
+                det = [h.backward(dev(grads), "max", argmax=am).clone() for _ in range(3)]
+                det_naive = h.naive_backward(dev(grads), "max", argmax=am)
+                h.set_option(B.HAG_OPT_DETERMINISTIC_MAX_BACKWARD, 0)
+                torch.cuda.synchronize()
+                assert torch.equal(det[0], det[1]) and torch.equal(det[0], det[2]) and torch.equal(det[0], det_naive)
+                if feats.dtype == np.int32:
+                    assert_equal(det[0], gx_ref, f"deterministic i32 d={d}")
+                    assert_equal(atomic, gx_ref, f"atomic i32 d={d}")
+                else:
+                    assert_close(det[0], gx_ref, gs, f"deterministic f32 d={d}")
+                    assert_close(atomic, gx_ref, gs, f"atomic f32 d={d}")
