@@ -277,7 +277,7 @@ int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d)
  * `reads` pseudo-random rows of the device matrix src [n_rows, d] (n_rows a power of two,
  * d a multiple of 4 up to 256, reads a multiple of 4) and writes its sum to sink (device,
  * workgroups * 1024 floats).  The matrix size decides which memory level serves the rows;
- * from_lds != 0 copies as many rows as fit 64 KB into LDS first and reads those instead.
+ * from_lds != 0 copies as many rows as fit 16 KB into LDS first and reads those instead.
  * Returns the number of row bytes read (>= 0) or a negative status.
  * hag_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte granularity. */
 int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads, int32_t from_lds,

@@ -274,7 +274,8 @@ struct CompArgs {
     const float *scale_in, *scale_out;
     const float *self_scale;     // gcn: the node's own staged row times self_scale[v] (1 if NULL) is added
     int32_t add_self;
-    int32_t d, stride;           // feature width; row stride in LDS, in elements
+    int32_t d, stride;           // feature columns this workgroup handles (columns blockIdx.y * d ...); row stride in LDS, in elements
+    int32_t gd;                  // row stride of the matrices in global memory, in elements (the full feature width)
     int32_t lists_off;           // offset of the staged aggregation lists, in bytes
     int32_t max_agg;             // most aggregation rows a component has
     int32_t use_agg, reverse;
@@ -310,7 +311,7 @@ int launch_fused(const FusedArgs<T> &a, hipStream_t s);
 // Defined in the component units (one per element type).  role: 0 = HAG forward, 1 = HAG
 // transposed pass, 2 = input graph forward (baseline), 3 = its transposed pass.
 template <typename T>
-int launch_component_kernel(const CompArgs<T> &a, int role, int64_t d, unsigned components, size_t lds_bytes,
-                            hipStream_t s);
+int launch_component_kernel(const CompArgs<T> &a, int role, int64_t d, unsigned components, unsigned column_parts,
+                            size_t lds_bytes, hipStream_t s);
 
 }  // namespace hag

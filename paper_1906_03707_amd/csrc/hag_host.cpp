@@ -978,6 +978,8 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
         const int64_t pad = env_i64("HAG_COMPONENT_PAD", 0);
         k.component_pad = (int32_t)((pad < 0 ? 0 : pad > 64 ? 64 : pad) & ~(int64_t)3);
         k.stream_output = env_i64("HAG_STREAM_OUTPUT", 0) != 0;
+        k.component_parts = env_i64("HAG_COMPONENT_PARTS", 0);
+        k.component_extra_lds = std::max<int64_t>(env_i64("HAG_COMPONENT_EXTRA_LDS", 0), 0) & ~(int64_t)15;
         k.fuse_max_items = env_i64("HAG_FUSE_MAX_ITEMS", 0);   // off: measured slower than one launch per stage
         k.spin_limit = env_i64("HAG_SPIN_LIMIT", 1 << 18);
     }

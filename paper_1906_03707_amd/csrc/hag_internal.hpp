@@ -125,6 +125,8 @@ struct hag_knobs {
     bool offset64 = false;      // HAG_OFFSET64: force the 64-bit row addressing of matrices >= 4 GiB
     int32_t component_pad = 0;  // HAG_COMPONENT_PAD: padding of an LDS row, in elements (multiple of 4, <= 64)
     bool stream_output = false; // HAG_STREAM_OUTPUT: component pass writes output rows with streaming stores
+    int64_t component_parts = 0;      // HAG_COMPONENT_PARTS: column parts of the component pass (2 or 4; default none)
+    int64_t component_extra_lds = 0;  // HAG_COMPONENT_EXTRA_LDS: unused LDS bytes added per workgroup (occupancy experiments)
     int64_t fuse_max_items = 0; // HAG_FUSE_MAX_ITEMS: largest pass (schedule items) that runs as one launch (0: never)
     int64_t spin_limit = 0;     // HAG_SPIN_LIMIT: polls a wavefront of the one-launch pass waits for earlier phases
     bool wait_unreachable = false;      // test only: the awaited count can never be reached, so every wait gives up

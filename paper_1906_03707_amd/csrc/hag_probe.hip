@@ -37,19 +37,36 @@ __global__ __launch_bounds__(kBlock) void probe_rows_kernel(const float *__restr
         __syncthreads();
     }
     float4 acc{};
-    const uint32_t mask = LDS ? (uint32_t)(lds_rows - 1) : row_mask;
-    for (int i = 0; i < reads; i += 4) {
-        uint32_t r[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) r[k] = probe_hash(group * 0x9e3779b9U + (uint32_t)(i + k)) & mask;
-        float4 v[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            if (LDS) v[k] = *reinterpret_cast<const float4 *>(buf + (size_t)r[k] * d + cb);
-            else v[k] = ld4(src + (size_t)r[k] * d + cb);
+    if (LDS) {
+        // Row numbers come from a linear congruential sequence, two per step, and are turned into byte
+        // offsets with 24-bit multiplies: a dozen vector instructions per four row reads, so that the
+        // loop is limited by the LDS reads and not by the arithmetic around them.
+        const uint32_t mask = (uint32_t)(lds_rows - 1);        // at most 4095
+        const uint32_t row_bytes = (uint32_t)d * 4u, col_bytes = (uint32_t)cb * 4u;
+        const unsigned char *base = probe_smem + col_bytes;
+        uint32_t a = probe_hash(group * 0x9e3779b9U + 1u);
+        for (int i = 0; i < reads; i += 4) {
+            a = a * 1664525u + 1013904223u;
+            const uint32_t o0 = __umul24((a >> 20) & mask, row_bytes), o1 = __umul24((a >> 8) & mask, row_bytes);
+            a = a * 1664525u + 1013904223u;
+            const uint32_t o2 = __umul24((a >> 20) & mask, row_bytes), o3 = __umul24((a >> 8) & mask, row_bytes);
+            const float4 v0 = *reinterpret_cast<const float4 *>(base + o0);
+            const float4 v1 = *reinterpret_cast<const float4 *>(base + o1);
+            const float4 v2 = *reinterpret_cast<const float4 *>(base + o2);
+            const float4 v3 = *reinterpret_cast<const float4 *>(base + o3);
+            add4(acc, v0); add4(acc, v1); add4(acc, v2); add4(acc, v3);
         }
+    } else {
+        for (int i = 0; i < reads; i += 4) {
+            uint32_t r[4];
 #pragma unroll
-        for (int k = 0; k < 4; ++k) add4(acc, v[k]);
+            for (int k = 0; k < 4; ++k) r[k] = probe_hash(group * 0x9e3779b9U + (uint32_t)(i + k)) & row_mask;
+            float4 v[4];
+#pragma unroll
+            for (int k = 0; k < 4; ++k) v[k] = ld4(src + (size_t)r[k] * d + cb);
+#pragma unroll
+            for (int k = 0; k < 4; ++k) add4(acc, v[k]);
+        }
     }
     st4(sink + 4 * ((size_t)blockIdx.x * kBlock + threadIdx.x), acc);
 }
@@ -94,9 +111,10 @@ int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads
     const int64_t groups_per_wg = kBlock / lpr;
     int rc;
     if (from_lds) {
-        // as many rows as fit 64 KB, a power of two, at most n_rows
+        // as many rows as fit 16 KB (so that eight workgroups share a compute unit, like the kernels
+        // this stands for), a power of two, at most n_rows
         int64_t lds_rows = 1;
-        while (lds_rows * 2 * d * 4 <= 64 * 1024 && lds_rows * 2 <= n_rows) lds_rows *= 2;
+        while (lds_rows * 2 * d * 4 <= 16 * 1024 && lds_rows * 2 <= n_rows) lds_rows *= 2;
         rc = launch_probe_rows<true>(lpr, (unsigned)workgroups, (size_t)(lds_rows * d * 4), (hipStream_t)stream,
                                      (const float *)src, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
     } else {

@@ -126,6 +126,27 @@ def test_source_partitioned_schedule(B, monkeypatch, offset64):
     run_all_ops(B, h, rowptr, col, 128, seed=45)
 
 
+@pytest.mark.parametrize("parts", ["2", "4"])
+def test_component_local_pass_with_feature_columns_cut_in_parts(B, parts, monkeypatch):
+    # the component pass with each component handled by 2 or 4 workgroups, one per part of the feature
+    # columns (chosen by occupancy in real runs, forced here), must agree with the oracle and, bit for
+    # bit, with the uncut pass
+    sizes = np.random.default_rng(64).integers(1, 41, size=150)
+    rowptr, col, gp = ragged_batch(sizes, 0.6, seed=65)
+    whole = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+    monkeypatch.setenv("HAG_COMPONENT_PARTS", parts)
+    cut = B.hag_search_batched(rowptr, col, gp, 0.25).upload()
+    monkeypatch.delenv("HAG_COMPONENT_PARTS")
+    assert cut.stats()["components"] >= 64
+    for d in (32, 64, 128):
+        run_all_ops(B, cut, rowptr, col, d, seed=66 + d, ops=("sum", "mean", "gcn"))
+        x = dev(synth.features_f32(rowptr.size - 1, d, 67))
+        for op in ("sum", "mean", "gcn"):
+            assert torch.equal(cut.forward(x, op), whole.forward(x, op)), (d, op)
+            assert torch.equal(cut.backward(x, op), whole.backward(x, op)), (d, op)
+            assert torch.equal(cut.naive_forward(x, op), whole.naive_forward(x, op)), (d, op)
+
+
 def ragged_batch(sizes, p, seed):
     """Disjoint G(size, p) graphs of the given sizes (size 1 = an isolated node), block-diagonal CSR."""
     rng = np.random.default_rng(seed)
