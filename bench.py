@@ -33,11 +33,11 @@ LDS_PEAK_GBS = 256 * 64 * 4 * 2.4
 # file (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for --copy-calibration's
 # known copy); the summaries are in profiles/.  Not measured by the run that prints them.
 PROFILED_TRAFFIC = {
-    ("config2:holme_kim56944", 128, "sum"): dict(fetch=310933 * 2048, write=28472 * 1024,
+    ("config2:holme_kim56944", 128, "sum"): dict(fetch=310122 * 2048, write=28472 * 1024,
                                                   source="profiles/pmc_config2_holme_kim56944_d128_sum.txt"),
-    ("config3:dcsbm232965", 128, "sum"): dict(fetch=6438940 * 2048, write=898966 * 1024,
+    ("config3:dcsbm232965", 128, "sum"): dict(fetch=6265120 * 2048, write=898966 * 1024,
                                                source="profiles/pmc_config3_dcsbm232965_d128_sum.txt"),
-    ("config4:er_batch5000x74", 64, "sum"): dict(fetch=74199 * 2048, write=92500 * 1024,
+    ("config4:er_batch5000x74", 64, "sum"): dict(fetch=74078 * 2048, write=92500 * 1024,
                                                   source="profiles/pmc_config4_er_batch5000x74_d64_sum.txt"),
 }
 
@@ -326,6 +326,9 @@ def main():
     ap.add_argument("--capacity", type=int, default=-1, help="override the HAG capacity (default |V|/4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-others", action="store_true", help="skip the short runs of configs 1, 2 and 4")
+    ap.add_argument("--no-ceilings", action="store_true",
+                    help="skip the probe kernels that measure the machine's ceilings (profiler runs); the roofline then "
+                         "carries the derived peak only")
     ap.add_argument("--device-search", action="store_true",
                     help="build the HAG with hag_search + HAG_SEARCH_DEVICE (pair counting on the GPU) instead of "
                          "the host search / the cached merge list; the search time is logged to stderr")
@@ -433,7 +436,7 @@ def main():
         ms_gather = time_kernel(torch, lambda: None, lambda: h.forward(x, op, y=y, argmax=am),
                                 lambda: h.backward(gy, op, argmax=am, gx=gx), args.steps, args.warmup)
         gather_bytes = h.algorithmic_bytes(0, op, d)
-        kernel_name = f"component_kernel<float, {lpr}, 256, 0>"
+        kernel_name = f"component_kernel<float, {lpr}, 256, 0>"   # the whole forward pass
     else:
         ms_gather = time_kernel(
             torch,
@@ -447,32 +450,36 @@ def main():
         kernel_name = f"gather_kernel<float, {1 if op == 'max' else 0}, {lpr}, 0>"
     achieved = gather_bytes / (ms_gather * 1e-3) / 1e9
     workload = f"config{cfg}:{synth.CONFIGS[cfg]['name']}"
-    ceil = measure_ceilings(torch, binding, d)
+    ceil = measure_ceilings(torch, binding, d) if not args.no_ceilings else None
 
     # Which limit binds.  Rows of a cache-resident matrix never reach HBM, so algorithmic bytes per second may
     # exceed the HBM peak: the gather is then priced against what the L2s can hand to the compute units (peak
     # derived from unit counts and clock; beside it what hag_probe_rows reaches on this machine), the
     # component pass against the LDS read rate.  The HBM-equivalent figure stays as a key of its own.
+    def measured(key):
+        return None if ceil is None else ceil[key]
+
     if component_pass:
-        bound, peak, ceiling = "lds", LDS_PEAK_GBS, ceil["lds_rows_GBps"]
+        bound, peak, ceiling = "lds", LDS_PEAK_GBS, measured("lds_rows_GBps")
         # every list entry is one LDS row read; staging adds one LDS write per row of the matrix
         achieved_bound = (row * st["e_hag"] + row * (n + st["a"])) / (ms_gather * 1e-3) / 1e9
     elif achieved > HBM_PEAK_GBS * 0.6:
-        bound, peak, ceiling = "l2", L2_PEAK_GBS, ceil["l2_resident_rows_GBps"]
+        bound, peak, ceiling = "l2", L2_PEAK_GBS, measured("l2_resident_rows_GBps")
         achieved_bound = achieved
     else:
-        bound, peak, ceiling = "hbm", HBM_PEAK_GBS, ceil["hbm_rows_GBps"]
+        bound, peak, ceiling = "hbm", HBM_PEAK_GBS, measured("hbm_rows_GBps")
         achieved_bound = achieved
     prof = PROFILED_TRAFFIC.get((workload, d, op)) if args.capacity < 0 else None
     roofline = {"bound": bound, "achieved": achieved_bound, "peak": peak, "unit": "GB/s", "frac": achieved_bound / peak,
                 "traffic": None if prof is None else prof["fetch"] + prof["write"],
                 "kernel": kernel_name, "kernel_ms": ms_gather, "algorithmic_bytes": gather_bytes,
-                "measured_ceiling": ceiling, "frac_of_measured_ceiling": achieved_bound / ceiling,
+                "measured_ceiling": ceiling, "frac_of_measured_ceiling": None if ceiling is None else achieved_bound / ceiling,
                 "hbm_equivalent_frac": achieved / HBM_PEAK_GBS}
     if prof is not None:
         roofline["traffic_source"] = prof["source"] + " (a separate rocprofv3 --pmc run, not this run)"
         # L2 fills of the launch against what random rows out of the memory-side cache reach on this machine
-        roofline["l2_fill"] = {"bytes": prof["fetch"], "measured_ceiling": ceil["infinity_cache_rows_GBps"]}
+        roofline["l2_fill"] = {"bytes": prof["fetch"], "achieved": prof["fetch"] / (ms_gather * 1e-3) / 1e9, "unit": "GB/s",
+                               "measured_ceiling": measured("infinity_cache_rows_GBps")}
 
     alg_hag = h.algorithmic_bytes(0, op, d) + h.algorithmic_bytes(1, op, d)
     alg_naive = h.algorithmic_bytes(2, op, d) + h.algorithmic_bytes(3, op, d)
@@ -520,14 +527,15 @@ def main():
     log(f"[bench] fwd only hag {ms_fwd:.4f} ms  naive {ms_nfwd:.4f} ms")
     log(f"[bench] replayed from a HIP graph: hag {ms_hag_graph:.4f} ms  naive {ms_naive_graph:.4f} ms")
     log(f"[bench] cold caches (after a 1 GiB write sweep): hag {ms_hag_cold:.4f} ms  naive {ms_naive_cold:.4f} ms")
-    log(f"[bench] ceilings (rows of {ceil['row_width']} floats, GB/s): L2-resident {ceil['l2_resident_rows_GBps']:.0f}  "
-        f"memory-side cache {ceil['infinity_cache_rows_GBps']:.0f}  HBM {ceil['hbm_rows_GBps']:.0f}  LDS {ceil['lds_rows_GBps']:.0f}  "
-        f"1 GiB copy {ceil['copy_1GiB_read_plus_write_GBps']:.0f}")
+    if ceil is not None:
+        log(f"[bench] ceilings (rows of {ceil['row_width']} floats, GB/s): L2-resident {ceil['l2_resident_rows_GBps']:.0f}  "
+            f"memory-side cache {ceil['infinity_cache_rows_GBps']:.0f}  HBM {ceil['hbm_rows_GBps']:.0f}  LDS {ceil['lds_rows_GBps']:.0f}  "
+            f"1 GiB copy {ceil['copy_1GiB_read_plus_write_GBps']:.0f}")
     log(f"[bench] effective (algorithmic) GB/s fwd+bwd: hag {out['effective_GBps_fwd_bwd']:.0f}  "
         f"naive {out['naive_csr']['effective_GBps']:.0f}  (HBM peak {HBM_PEAK_GBS:.0f})")
     log(f"[bench] dominant kernel {kernel_name}: {ms_gather * 1e3:.1f} us, {gather_bytes / 1e6:.1f} MB -> {achieved_bound:.0f} GB/s "
-        f"= {100 * achieved_bound / peak:.1f}% of the {bound} limit ({peak:.0f}), {100 * achieved_bound / ceiling:.1f}% of the "
-        f"measured ceiling ({ceiling:.0f})")
+        f"= {100 * achieved_bound / peak:.1f}% of the {bound} limit ({peak:.0f})"
+        + ("" if ceiling is None else f", {100 * achieved_bound / ceiling:.1f}% of the measured ceiling ({ceiling:.0f})"))
     if args.sage_epoch:
         e_hag = sage_pool_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=False)
         e_naive = sage_pool_epoch_ms(torch, h, x, 16, 16, max(args.steps // 4, 5), 3, naive=True)
