@@ -237,6 +237,9 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         c.seg[0].n_block = 0;
         c.seg[0].n_items = (int64_t)p.combine.size();
         c.col = h->d_slot_ids;
+        // partial results of a float max may still hold aggregation ids (see gather_body)
+        c.late_id = (RED == R_MAX && std::is_same<T, float>::value) ? a.id_hi : nullptr;
+        c.late_split = a.split;
         c.split = 0;               // every id refers to a partial slot
         c.src_lo = nullptr;
         c.src_hi = (const T *)w.part;

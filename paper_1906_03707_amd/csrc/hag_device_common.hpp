@@ -54,6 +54,10 @@ struct GatherArgs {
     int32_t d;
     int32_t off32;            // both gathered matrices are smaller than 4 GiB: 32-bit byte offsets
     int32_t stream_hi;        // rows of src_hi are read once (fold of partial rows): streaming loads
+    // Fold of partial (value, id) rows of a float max: a stored id >= late_split is an aggregation
+    // node standing for the winner stored in late_id (row id - late_split); NULL: stored ids are final
+    const int32_t *late_id;
+    int32_t late_split;
     const int32_t *filter;    // R_SUMIF: [rows of src_lo, d]
     const int32_t *slot_row;  // R_SUMIF: output row of every partial slot
     // One-launch schedule only (sync_complete NULL otherwise): an item marked as depending on earlier
@@ -228,6 +232,27 @@ __device__ __forceinline__ void lazy_max4(V &v, int4 &vi, const V &w, int wi, co
         settle_tie1<COH>(v.w, vi.w, w.w, wi, id_hi, split, d, cb + 3);
     }
     max_first4(v, vi, w, wi);   // a tie keeps the accumulator, whose id is settled above
+}
+// (value, id) max of partial results whose ids may still be aggregation ids (>= split) standing for the
+// winner stored in `late`: a tie between two such partial results is settled on the original ids
+template <typename S>
+__device__ __forceinline__ void late_max1(S &v, int &vi, S w, int wi, const int32_t *late, int split, size_t d, int col) {
+    if (wi < 0) return;
+    if (vi >= 0 && w == v && (wi >= split || vi >= split)) {   // rare
+        if (wi >= split) wi = late[(size_t)(wi - split) * d + col];
+        if (vi >= split) vi = late[(size_t)(vi - split) * d + col];
+    }
+    const bool take = vi < 0 || w > v || (w == v && wi < vi);
+    v = take ? w : v;
+    vi = take ? wi : vi;
+}
+template <typename V>
+__device__ __forceinline__ void late_max4(V &v, int4 &vi, const V &w, const int4 &wi, const int32_t *late, int split,
+                                          size_t d, int cb) {
+    late_max1(v.x, vi.x, w.x, wi.x, late, split, d, cb);
+    late_max1(v.y, vi.y, w.y, wi.y, late, split, d, cb + 1);
+    late_max1(v.z, vi.z, w.z, wi.z, late, split, d, cb + 2);
+    late_max1(v.w, vi.w, w.w, wi.w, late, split, d, cb + 3);
 }
 // replace aggregation ids left in acc_id by the original ids they stand for
 template <bool COH>
