@@ -72,6 +72,32 @@ def time_steps(torch, fn, steps, warmup):
     return statistics.median(a.elapsed_time(b) for a, b in ev), wall
 
 
+def time_interleaved(torch, fn_a, fn_b, steps, warmup, blocks=4):
+    """Per-step event times of two paths measured alternately: after `warmup` untimed steps of each, `steps`
+    timed steps of each in `blocks` alternating runs (a, b, a, b, ...), so that a slow drift of the machine (clocks,
+    what else shares it) lands on both.  Returns ((median_a, wall_mean_a), (median_b, wall_mean_b)) in ms."""
+    for _ in range(warmup):
+        fn_a()
+    for _ in range(warmup):
+        fn_b()
+    per = [steps // blocks + (1 if i < steps % blocks else 0) for i in range(blocks)]
+    samples, wall = ([], []), [0.0, 0.0]
+    for n_block in per:
+        for which, fn in ((0, fn_a), (1, fn_b)):
+            fn()                                   # one untimed step after the switch of paths
+            ev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(n_block)]
+            torch.cuda.synchronize()
+            t0 = time.perf_counter()
+            for a, b in ev:
+                a.record()
+                fn()
+                b.record()
+            torch.cuda.synchronize()
+            wall[which] += time.perf_counter() - t0
+            samples[which].extend(a.elapsed_time(b) for a, b in ev)
+    return tuple((statistics.median(samples[w]), wall[w] / steps * 1e3) for w in (0, 1))
+
+
 def time_kernel(torch, pre, fn, post, steps, warmup):
     """Median duration (ms) of `fn` inside the full step, bracketed by events on the launch stream."""
     for _ in range(warmup):
@@ -302,8 +328,7 @@ def short_workload(torch, binding, synth, workloads, cfg, steps, warmup):
         h.naive_forward(x, "sum", y=y)
         h.naive_backward(gy, "sum", gx=gx)
 
-    ms_h, _ = time_steps(torch, step_hag, steps, warmup)
-    ms_n, _ = time_steps(torch, step_naive, steps, warmup)
+    (ms_h, _), (ms_n, _) = time_interleaved(torch, step_hag, step_naive, steps, warmup)
     red = st["aggr_naive"] / max(st["aggr_hag"], 1)
     log(f"[bench] config {cfg} (d={d}, sum): hag {ms_h:.4f} ms  naive {ms_n:.4f} ms  speedup {ms_n / ms_h:.3f}x  "
         f"(aggregations {red:.3f}x fewer)")
@@ -403,9 +428,9 @@ def main():
             tot += a.elapsed_time(b)
         return tot / reps
 
-    # the timed region: exactly `steps` steps after `warmup` untimed ones
-    ms_hag, ms_hag_wall = time_steps(torch, step_hag, args.steps, args.warmup)
-    ms_naive, ms_naive_wall = time_steps(torch, step_naive, args.steps, args.warmup)
+    # the timed region: exactly `steps` steps after `warmup` untimed ones, in four runs that alternate with the
+    # baseline's (the machine's clocks drift by a few per cent over seconds: both paths get the same share of it)
+    (ms_hag, ms_hag_wall), (ms_naive, ms_naive_wall) = time_interleaved(torch, step_hag, step_naive, args.steps, args.warmup)
     ms_fwd, _ = time_steps(torch, lambda: h.forward(x, op, y=y, argmax=am), args.steps, args.warmup)
     ms_nfwd, _ = time_steps(torch, lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
 
@@ -503,7 +528,8 @@ def main():
         "config": {"workload": workload, "nodes": n, "edges": e, "feature_dim": d, "op": op,
                    "capacity": st["a"], "levels": st["levels"], "hag_edges": st["e_hag"]},
         "roofline": roofline,
-        "timing": "median of per-step event pairs on the launch stream over the timed steps",
+        "timing": "median of per-step event pairs on the launch stream over the timed steps, taken in four runs that "
+                  "alternate with the naive baseline's",
         "ms_per_step_wall_mean": ms_hag_wall,
         "effective_GBps_fwd_bwd": alg_hag / (ms_hag * 1e-3) / 1e9,
         "effective_frac_of_hbm_peak": alg_hag / (ms_hag * 1e-3) / 1e9 / HBM_PEAK_GBS,
