@@ -295,8 +295,7 @@ def sweep_config5(torch, synth, workloads, steps, warmup):
                     h.naive_forward(x, op, y=y, argmax=a)
                     h.naive_backward(gy, op, argmax=a, gx=gx)
 
-                ms_h = time_steps(torch, step_hag, steps, warmup)[0]
-                ms_n = time_steps(torch, step_naive, steps, warmup)[0]
+                (ms_h, _), (ms_n, _) = time_interleaved(torch, step_hag, step_naive, steps, warmup, blocks=2)
                 red = st["aggr_naive"] / max(st["aggr_hag"], 1)
                 log(f"[bench] {cap:8d} {d:6d}  {op:4s} {ms_h:8.3f}  {ms_n:8.3f}  {ms_n / ms_h:6.3f}x  {red:6.3f}x")
                 print(json.dumps({"workload": "config5:dcsbm232965_sweep", "capacity": cap, "feature_dim": d, "op": op,
@@ -431,11 +430,11 @@ def main():
     # the timed region: exactly `steps` steps after `warmup` untimed ones, in four runs that alternate with the
     # baseline's (the machine's clocks drift by a few per cent over seconds: both paths get the same share of it)
     (ms_hag, ms_hag_wall), (ms_naive, ms_naive_wall) = time_interleaved(torch, step_hag, step_naive, args.steps, args.warmup)
-    ms_fwd, _ = time_steps(torch, lambda: h.forward(x, op, y=y, argmax=am), args.steps, args.warmup)
-    ms_nfwd, _ = time_steps(torch, lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
+    (ms_fwd, _), (ms_nfwd, _) = time_interleaved(torch, lambda: h.forward(x, op, y=y, argmax=am),
+                                                 lambda: h.naive_forward(x, op, y=y, argmax=am), args.steps, args.warmup)
 
-    def time_graph_replay(fn):
-        """The same step captured once into a HIP graph and replayed (no per-launch host work)."""
+    def capture(fn):
+        """The same step captured once into a HIP graph (replayed without per-launch host work)."""
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
@@ -444,10 +443,11 @@ def main():
         g = torch.cuda.CUDAGraph()
         with torch.cuda.graph(g):
             fn()
-        return time_steps(torch, g.replay, args.steps, args.warmup)[0]
+        return g
 
-    ms_hag_graph = time_graph_replay(step_hag)
-    ms_naive_graph = time_graph_replay(step_naive)
+    g_hag, g_naive = capture(step_hag), capture(step_naive)
+    (ms_hag_graph, _), (ms_naive_graph, _) = time_interleaved(torch, g_hag.replay, g_naive.replay, args.steps, args.warmup)
+    del g_hag, g_naive
     ms_hag_cold = time_cold(step_hag)
     ms_naive_cold = time_cold(step_naive)
 

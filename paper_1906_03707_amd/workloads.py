@@ -75,9 +75,38 @@ def make_cache(cfg: int, capacity=None, device=False):
     print(f"wrote {cache_path(cfg)}: {left.size} merges, redundancy {red[0]}..{red[-1]}")
 
 
+def staging_share(cfg: int, tile_rows=(64, 256, 1024), staged_rows=(64, 128, 256, 512), sample=400, log=print):
+    """How many of a gather's row reads a workgroup could serve from LDS if it staged, per tile of
+    consecutive destination rows, the source rows that the tile's lists name most often: the share of
+    list entries that are a repeat of one of the tile's `staged_rows` most frequent sources.  Host
+    analysis only (no kernel does this); printed for the input graph and for the HAG's final lists."""
+    rowptr, col, _ = synth.graph_for_config(cfg)
+    n = rowptr.size - 1
+    f = build_hag(cfg, rowptr, col).get_forward()
+    rng = np.random.default_rng(0)
+
+    def share(ptr, cols, t, k):
+        tiles = rng.choice((n + t - 1) // t, size=min(sample, (n + t - 1) // t), replace=False)
+        total = served = 0
+        for i in tiles:
+            c = cols[ptr[i * t]:ptr[min(n, (i + 1) * t)]]
+            cnt = np.sort(np.unique(c, return_counts=True)[1])[::-1][:k]
+            total += c.size
+            served += int((cnt[cnt >= 2] - 1).sum())
+        return served / max(total, 1)
+
+    for t in tile_rows:
+        for k in staged_rows:
+            log(f"tile of {t} rows, {k} staged rows: input graph {share(rowptr, col, t, k):.3f}  "
+                f"HAG {share(f['hrowptr'], f['hcol'], t, k):.3f}")
+
+
 if __name__ == "__main__":
+    if len(sys.argv) >= 3 and sys.argv[1] == "--staging-share":
+        staging_share(int(sys.argv[2]))
+        sys.exit(0)
     args = [a for a in sys.argv[1:] if a != "--device"]
     if len(args) >= 2 and args[0] == "--make-cache":
         make_cache(int(args[1]), int(args[2]) if len(args) > 2 else None, device="--device" in sys.argv)
     else:
-        sys.exit("usage: python -m paper_1906_03707_amd.workloads --make-cache <config> [capacity] [--device]")
+        sys.exit("usage: python -m paper_1906_03707_amd.workloads --make-cache <config> [capacity] [--device] | --staging-share <config>")
