@@ -142,10 +142,13 @@ def measure_ceilings(torch, binding, d):
             r *= 2
         return r
 
-    out["l2_resident_rows_GBps"] = rate(pow2_rows(2 << 20), 512, False)        # 2 MB: every XCD's L2 holds all of it
-    out["infinity_cache_rows_GBps"] = rate(pow2_rows(128 << 20), 256, False)   # 128 MB: misses L2, fits the 256 MB memory-side cache
-    out["hbm_rows_GBps"] = rate(pow2_rows(4 << 30), 128, False)                # 4 GB: served by HBM
-    out["lds_rows_GBps"] = rate(pow2_rows(1 << 20), 2048, True)
+    out["l2_resident_rows_GBps"] = rate(pow2_rows(2 << 20), 512, 0)        # 2 MB: every XCD's L2 holds all of it
+    out["infinity_cache_rows_GBps"] = rate(pow2_rows(128 << 20), 256, 0)   # 128 MB: misses L2, fits the 256 MB memory-side cache
+    out["hbm_rows_GBps"] = rate(pow2_rows(4 << 30), 128, 0)                # 4 GB: served by HBM
+    out["lds_rows_GBps"] = rate(pow2_rows(1 << 20), 2048, 1)
+    # what a row accumulator kept in LDS would cost: a row added into an LDS row by read-add-write, by LDS atomics
+    out["lds_row_accumulate_GBps"] = rate(pow2_rows(1 << 20), 2048, 2)
+    out["lds_row_atomic_add_GBps"] = rate(pow2_rows(1 << 20), 128, 3)
     n = 1 << 30
     src = torch.empty(n // 4, dtype=torch.float32, device="cuda").normal_()
     dst = torch.empty_like(src)

@@ -220,13 +220,15 @@ int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
  *   HAG_OPT_SPIN_LIMIT            polls, about a microsecond apart, after which a wait gives up (default 262144);
  *   HAG_OPT_TEST_WAIT_UNREACHABLE tests only: every wait is for a count that cannot be reached, so it gives up
  *                                 after the spin limit and hag_check must report HAG_ETIMEOUT;
+ *   HAG_OPT_PARTITION_SHIFT       0..7: in a launch whose long rows are cut into 8 classes of source ids, workgroup b takes
+ *                                 the sources of class (b + shift) mod 8 (any value gives the same results);
  *   HAG_OPT_DETERMINISTIC_MAX_BACKWARD  non-zero: the backward pass of max adds up in a fixed order
  *                                 (a gather over the transposed input graph filtered by argmax) instead
  *                                 of with atomics; slower, bit-reproducible.
  * hag_check synchronises `stream` and returns HAG_OK, or HAG_ETIMEOUT if a one-launch pass on this handle
  * gave up waiting since the last check (and clears that state). */
 enum { HAG_OPT_ONE_LAUNCH_MAX_ITEMS = 1, HAG_OPT_SPIN_LIMIT = 2, HAG_OPT_TEST_WAIT_UNREACHABLE = 3,
-       HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 4 };
+       HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 4, HAG_OPT_PARTITION_SHIFT = 5 };
 int hag_set_option(hag_t *h, int32_t option, int64_t value);
 int hag_check(const hag_t *h, void *stream);
 
@@ -277,8 +279,11 @@ int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d)
  * `reads` pseudo-random rows of the device matrix src [n_rows, d] (n_rows a power of two,
  * d a multiple of 4 up to 256, reads a multiple of 4) and writes its sum to sink (device,
  * workgroups * 1024 floats).  The matrix size decides which memory level serves the rows;
- * from_lds != 0 copies as many rows as fit 16 KB into LDS first and reads those instead.
- * Returns the number of row bytes read (>= 0) or a negative status.
+ * from_lds = 1 copies as many rows as fit 16 KB into LDS first and reads those instead;
+ * from_lds = 2 adds a row held in registers into pseudo-random LDS rows instead (each sub-group
+ * into rows of its own: 16-byte read, add, 16-byte write), from_lds = 3 does the same with LDS
+ * atomic adds: what accumulators kept in LDS cost per row.
+ * Returns the number of row bytes read or accumulated (>= 0) or a negative status.
  * hag_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte granularity. */
 int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads, int32_t from_lds,
                        int64_t workgroups, void *sink, void *stream);

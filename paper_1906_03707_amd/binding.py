@@ -20,6 +20,7 @@ HAG_SUM, HAG_MEAN, HAG_MAX, HAG_GCN = 0, 1, 2, 3
 HAG_F32, HAG_I32 = 0, 1
 HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE, HAG_ETIMEOUT = 0, -1, -2, -3, -4, -5
 HAG_OPT_ONE_LAUNCH_MAX_ITEMS, HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE, HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 1, 2, 3, 4
+HAG_OPT_PARTITION_SHIFT = 5
 HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP, HAG_SEARCH_DEVICE = 1, 2, 4
 HAG_PHASE_LEVELS, HAG_PHASE_GATHER, HAG_PHASE_FOLD, HAG_PHASE_ALL = 1, 2, 4, 7
 OPS = {"sum": HAG_SUM, "mean": HAG_MEAN, "max": HAG_MAX, "gcn": HAG_GCN}
@@ -314,7 +315,7 @@ def probe_rows(src, n_rows, d, reads, from_lds, workgroups, sink) -> int:
     """hag_probe_rows on torch device tensors; returns the row bytes the launch reads."""
     if src.numel() < n_rows * d or sink.numel() < workgroups * 1024:
         raise ValueError("probe buffers too small")
-    rc = lib().hag_probe_rows(_dev_ptr(src), int(n_rows), int(d), int(reads), int(bool(from_lds)), int(workgroups),
+    rc = lib().hag_probe_rows(_dev_ptr(src), int(n_rows), int(d), int(reads), int(from_lds), int(workgroups),
                               _dev_ptr(sink), _stream_ptr())
     if rc < 0:
         _check(rc)

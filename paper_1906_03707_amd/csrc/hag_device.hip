@@ -204,6 +204,7 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
                     hipStream_t s, uint32_t phases = HAG_PHASE_ALL) {
     a.items = p.d_items;
     a.np = p.np;
+    a.part_shift = p.np > 1 ? (int)(((h->knobs.part_shift % p.np) + p.np) % p.np) : 0;
     // rows of ids < split live in a matrix of `split` rows, the others in one of at most
     // n + a (aggregation rows) or max_slots (partial rows) rows
     {
@@ -660,6 +661,7 @@ int hag_set_option(hag_t *h, int32_t option, int64_t value) {
         case HAG_OPT_SPIN_LIMIT: h->knobs.spin_limit = std::max<int64_t>(value, 1); return HAG_OK;
         case HAG_OPT_TEST_WAIT_UNREACHABLE: h->knobs.wait_unreachable = value != 0; return HAG_OK;
         case HAG_OPT_DETERMINISTIC_MAX_BACKWARD: h->knobs.deterministic_max_backward = value != 0; return HAG_OK;
+        case HAG_OPT_PARTITION_SHIFT: h->knobs.part_shift = (int32_t)(value & 7); return HAG_OK;
     }
     set_error("unknown option");
     return HAG_EINVAL;

@@ -31,7 +31,8 @@ template <> struct V4<int32_t> { using type = int4; };
 template <typename T>
 struct GatherArgs {
     const Item *items;
-    int np;                   // 1 or kPartitions: workgroup b works on partition b mod np
+    int np;                   // 1 or kPartitions: workgroup b works on partition (b + part_shift) mod np
+    int part_shift;           // 0 <= part_shift < np
     struct {
         int64_t begin;        // first item of the partition
         int64_t n_block;      // its first n_block items take one workgroup each

@@ -579,26 +579,43 @@ static int length_class(int32_t cnt) {
 // sub-group of lanes is decided at launch time (see long_items()).
 //
 // Source partitioning.  MI355X has 8 XCDs with a private 4 MB L2 each, and workgroups are
-// handed to XCDs round-robin, so workgroup b runs on XCD b mod 8.  When the gathered matrix
-// is much larger than one L2, every row of at least `part_min` entries is cut by SOURCE id
-// (id mod 8) into 8 segments and segment k is scheduled on workgroups with b mod 8 == k:
+// handed to XCDs round-robin, so the workgroups b of one residue mod 8 share an XCD.  When the
+// gathered matrix is much larger than one L2, every row of at least `part_min` entries is cut by
+// the class of the SOURCE id (source_class) into 8 segments and segment k is scheduled on workgroups with b mod 8 == k:
 // each L2 then only ever sees one eighth of the source rows, which raises its hit rate.
 // `dcol` (a copy of c.col) is reordered inside such rows so that a segment is contiguous.
 // The segments write partial rows that the fold launch adds up.  Items of unpartitioned rows
 // are dealt round-robin to the 8 lists.
+// The class (0..7) of a source row: which partition, and so which XCD's L2, reads it.  Runs of
+// 2^shift consecutive ids share a class and the run number is folded three bits at a time, so that
+// no address bit of a row is the same for all rows of a class.  (With the class taken from the low
+// bits of the id, all rows one XCD reads agree in address bits 9..11 when a row has 512 bytes;
+// measured on MI355X, such a launch is 5 % slower or faster depending on the parity of class minus
+// XCD number, and 15 % slower at 64-byte rows, where two classes also share every cache line.)
+// shift < 0 selects that old rule, for comparison.
+static inline int source_class(int32_t id, int shift) {
+    const uint32_t u = (uint32_t)id;
+    if (shift < 0) return (int)(u & 7u);
+    const uint32_t w = u >> shift;
+    return (int)((w ^ (w >> 3) ^ (w >> 6) ^ (w >> 9) ^ (w >> 12) ^ (w >> 15) ^ (w >> 18) ^ (w >> 21) ^ (w >> 24)) & 7u);
+}
+
 void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int64_t row_end, Plan &p,
                 bool partition, int64_t split) {
+    const int class_shift = (int)std::min<int64_t>(env_i64("HAG_PART_CLASS_SHIFT", 5), 20);
     const int64_t block_max = env_i64("HAG_BLOCK_MAX", 2048);
-    const int64_t part_min = env_i64("HAG_PART_MIN", 128);
+    const int64_t part_min = env_i64("HAG_PART_MIN", 64);
     // cutting by source only pays when the rows long enough to be cut hold most of the entries;
     // otherwise keep one list, which also keeps neighbouring rows on neighbouring workgroups
     if (partition) {
-        int64_t total = c.ptr[row_end] - c.ptr[row_begin], in_long = 0;
+        int64_t total = c.ptr[row_end] - c.ptr[row_begin], in_long = 0, n_long = 0;
         for (int64_t r = row_begin; r < row_end; ++r) {
             int64_t cnt = c.ptr[r + 1] - c.ptr[r];
-            if (cnt >= part_min) in_long += cnt;
+            if (cnt >= part_min) { in_long += cnt; ++n_long; }
         }
-        partition = total > 0 && in_long * 100 >= total * env_i64("HAG_PART_SHARE_PCT", 30);
+        // ... and are long enough on average that an eighth of a row is still worth a partial row
+        partition = total > 0 && in_long * 100 >= total * env_i64("HAG_PART_SHARE_PCT", 30) &&
+                    in_long >= n_long * env_i64("HAG_PART_MEAN_MIN", 128);
     }
     const int np = partition ? kPartitions : 1;
     std::vector<std::vector<Item>> lists(np);
@@ -622,7 +639,7 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
         }
     };
     if (np > 1) {
-        // reorder the rows that are cut by source: (id mod 8, id); rows are independent
+        // reorder the rows that are cut by source: (class, id); rows are independent
         const int64_t chunk = 256, chunks = (row_end - row_begin + chunk - 1) / chunk;
         parallel_for(chunks, host_threads(), [&](int64_t ci, unsigned) {
             const int64_t r0 = row_begin + ci * chunk, r1 = std::min(row_end, r0 + chunk);
@@ -630,8 +647,8 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
                 const int64_t beg = c.ptr[r], cnt = c.ptr[r + 1] - beg;
                 if (cnt < part_min) continue;
                 int32_t *row = dcol.data() + beg;
-                std::sort(row, row + cnt, [](int32_t x, int32_t y) {
-                    int px = x & (kPartitions - 1), py = y & (kPartitions - 1);
+                std::sort(row, row + cnt, [class_shift](int32_t x, int32_t y) {
+                    int px = source_class(x, class_shift), py = source_class(y, class_shift);
                     return px != py ? px < py : x < y;
                 });
             }
@@ -645,9 +662,9 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
             const int32_t *row = dcol.data() + beg;
             int64_t first_slot = p.n_slots, i = 0;
             while (i < cnt) {
-                int part = row[i] & (kPartitions - 1);
+                int part = source_class(row[i], class_shift);
                 int64_t j = i;
-                while (j < cnt && (row[j] & (kPartitions - 1)) == part) ++j;
+                while (j < cnt && source_class(row[j], class_shift) == part) ++j;
                 cut(part, beg + i, j - i, true, r);
                 i = j;
             }
@@ -695,7 +712,7 @@ void build_plan(const Csr &c, std::vector<int32_t> &dcol, int64_t row_begin, int
     // (measured on the 114M-edge graph, d = 128, forward + backward: 5.74 -> 5.58 ms with the HAG,
     // 6.05 -> 5.92 ms without, for buckets of 2048 to 8192 rows; 32768: 5.61 / 5.98.)  Only for
     // plans cut by source: elsewhere rows are short and the length classes keep wavefronts balanced.
-    const int64_t bucket_rows = np > 1 ? env_i64("HAG_BUCKET_ROWS", 8192) : 0;
+    const int64_t bucket_rows = np > 1 ? env_i64("HAG_BUCKET_ROWS", 4096) : 0;
     constexpr int kShortClass = 7;                        // lengths 64..127
     auto true_row = [&](const Item &it) -> int64_t { return it.row >= 0 ? it.row : slot_row[(size_t)~it.row]; };
     auto before = [&](const Item &x, const Item &y) {
@@ -980,6 +997,7 @@ static int finalize_from_builder(hag_handle *h, Builder &b) {
         k.stream_output = env_i64("HAG_STREAM_OUTPUT", 0) != 0;
         k.component_parts = env_i64("HAG_COMPONENT_PARTS", 0);
         k.component_extra_lds = std::max<int64_t>(env_i64("HAG_COMPONENT_EXTRA_LDS", 0), 0) & ~(int64_t)15;
+        k.part_shift = (int32_t)(env_i64("HAG_PART_SHIFT", 0) & 7);
         k.fuse_max_items = env_i64("HAG_FUSE_MAX_ITEMS", 0);   // off: measured slower than one launch per stage
         k.spin_limit = env_i64("HAG_SPIN_LIMIT", 1 << 18);
     }

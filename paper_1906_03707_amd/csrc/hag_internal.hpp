@@ -29,7 +29,7 @@ constexpr int64_t kItemDependsBit = (int64_t)1 << 62;
 
 // Schedule of one gather launch (plus the optional second launch that folds the
 // partial slots of split rows).
-constexpr int kPartitions = 8;   // XCDs of the device; workgroup b runs on XCD b mod 8
+constexpr int kPartitions = 8;   // XCDs of the device; workgroups b of one residue mod 8 share an XCD
 
 struct Plan {
     // items of partition k are items[part_begin[k] .. part_begin[k+1]), each partition sorted by
@@ -131,6 +131,7 @@ struct hag_knobs {
     int64_t spin_limit = 0;     // HAG_SPIN_LIMIT: polls a wavefront of the one-launch pass waits for earlier phases
     bool wait_unreachable = false;      // test only: the awaited count can never be reached, so every wait gives up
     bool deterministic_max_backward = false;
+    int32_t part_shift = 0;     // HAG_PART_SHIFT: workgroup b of a partitioned launch takes the sources of class (b + shift) mod 8
 };
 
 struct hag_handle {

@@ -19,9 +19,13 @@ __device__ __forceinline__ uint32_t probe_hash(uint32_t x) {
 // Every sub-group of LPR lanes reads `reads` pseudo-random rows of a [n_rows, d] fp32 matrix, four
 // rows in flight, each row as one contiguous run of 16-byte loads (the gather kernel's access
 // shape without its index loads), and adds them up.  n_rows must be a power of two.
-//   LDS = false: rows come from global memory; the matrix size decides which level serves them;
-//   LDS = true:  the workgroup first copies rows [0, lds_rows) into LDS and reads those.
-template <int LPR, bool LDS>
+//   LDS = 0: rows come from global memory; the matrix size decides which level serves them;
+//   LDS = 1: the workgroup first copies rows [0, lds_rows) into LDS and reads those;
+//   LDS = 2: instead of reading, every sub-group adds a row held in registers into pseudo-random
+//            LDS rows of its own (rows g, g + groups, ...: no two sub-groups touch the same row) with
+//            a 16-byte read, four adds and a 16-byte write: what an accumulator kept in LDS costs;
+//   LDS = 3: the same with four LDS atomic adds per lane instead of the read and the write.
+template <int LPR, int LDS>
 __global__ __launch_bounds__(kBlock) void probe_rows_kernel(const float *__restrict__ src, uint32_t row_mask, int32_t d,
                                                             int32_t reads, int32_t lds_rows, float *__restrict__ sink) {
     extern __shared__ __align__(16) unsigned char probe_smem[];
@@ -37,7 +41,31 @@ __global__ __launch_bounds__(kBlock) void probe_rows_kernel(const float *__restr
         __syncthreads();
     }
     float4 acc{};
-    if (LDS) {
+    if (LDS >= 2) {
+        constexpr int kGroups = kBlock / LPR;                        // sub-groups of the workgroup
+        const uint32_t own = (uint32_t)(threadIdx.x / LPR);
+        const uint32_t mask = (uint32_t)(lds_rows / kGroups - 1);    // lds_rows / kGroups is a power of two >= 1
+        const uint32_t row_bytes = (uint32_t)d * 4u;
+        unsigned char *base = probe_smem + (uint32_t)cb * 4u;
+        uint32_t a = probe_hash(group * 0x9e3779b9U + 1u);
+        const float4 v = ld4(src + cb);
+        for (int i = 0; i < reads; ++i) {
+            a = a * 1664525u + 1013904223u;
+            float *p = reinterpret_cast<float *>(base + __umul24(((a >> 16) & mask) * kGroups + own, row_bytes));
+            if (LDS == 2) {
+                float4 t = *reinterpret_cast<float4 *>(p);
+                add4(t, v);
+                *reinterpret_cast<float4 *>(p) = t;
+            } else {
+                __hip_atomic_fetch_add(p + 0, v.x, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(p + 1, v.y, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(p + 2, v.z, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+                __hip_atomic_fetch_add(p + 3, v.w, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_WORKGROUP);
+            }
+        }
+        __syncthreads();
+        acc = *reinterpret_cast<const float4 *>(base + __umul24(own, row_bytes));
+    } else if (LDS) {
         // Row numbers come from a linear congruential sequence, two per step, and are turned into byte
         // offsets with 24-bit multiplies: a dozen vector instructions per four row reads, so that the
         // loop is limited by the LDS reads and not by the arithmetic around them.
@@ -78,7 +106,7 @@ __global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4 *__rest
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
-template <bool LDS>
+template <int LDS>
 static int launch_probe_rows(int lpr, unsigned groups, size_t lds_bytes, hipStream_t s, const float *src, uint32_t mask,
                              int32_t d, int32_t reads, int32_t lds_rows, float *sink) {
     const dim3 grid(groups), block(kBlock);
@@ -110,16 +138,22 @@ int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads
     const int lpr = pick_lpr(d);
     const int64_t groups_per_wg = kBlock / lpr;
     int rc;
+    if (from_lds < 0 || from_lds > 3) { set_error("from_lds must be 0..3"); return HAG_EINVAL; }
     if (from_lds) {
         // as many rows as fit 16 KB (so that eight workgroups share a compute unit, like the kernels
-        // this stands for), a power of two, at most n_rows
+        // this stands for), a power of two, at most n_rows; the accumulating forms need a row per sub-group
         int64_t lds_rows = 1;
         while (lds_rows * 2 * d * 4 <= 16 * 1024 && lds_rows * 2 <= n_rows) lds_rows *= 2;
-        rc = launch_probe_rows<true>(lpr, (unsigned)workgroups, (size_t)(lds_rows * d * 4), (hipStream_t)stream,
-                                     (const float *)src, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
+        if (from_lds >= 2 && lds_rows < groups_per_wg) { set_error("n_rows too small for an LDS row per sub-group"); return HAG_EINVAL; }
+        const size_t lds_bytes = (size_t)(lds_rows * d * 4);
+        const hipStream_t s = (hipStream_t)stream;
+        const float *f = (const float *)src;
+        if (from_lds == 1) rc = launch_probe_rows<1>(lpr, (unsigned)workgroups, lds_bytes, s, f, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
+        else if (from_lds == 2) rc = launch_probe_rows<2>(lpr, (unsigned)workgroups, lds_bytes, s, f, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
+        else rc = launch_probe_rows<3>(lpr, (unsigned)workgroups, lds_bytes, s, f, 0u, (int32_t)d, (int32_t)reads, (int32_t)lds_rows, (float *)sink);
     } else {
-        rc = launch_probe_rows<false>(lpr, (unsigned)workgroups, 0, (hipStream_t)stream, (const float *)src,
-                                      (uint32_t)(n_rows - 1), (int32_t)d, (int32_t)reads, 0, (float *)sink);
+        rc = launch_probe_rows<0>(lpr, (unsigned)workgroups, 0, (hipStream_t)stream, (const float *)src,
+                                  (uint32_t)(n_rows - 1), (int32_t)d, (int32_t)reads, 0, (float *)sink);
     }
     if (rc) return rc;
     return workgroups * groups_per_wg * reads * d * 4;   // bytes of rows read

@@ -75,7 +75,7 @@ def make_cache(cfg: int, capacity=None, device=False):
     print(f"wrote {cache_path(cfg)}: {left.size} merges, redundancy {red[0]}..{red[-1]}")
 
 
-def staging_share(cfg: int, tile_rows=(64, 256, 1024), staged_rows=(64, 128, 256, 512), sample=400, log=print):
+def staging_share(cfg: int, tile_rows=(64, 128, 256, 1024), staged_rows=(64, 128, 256, 512), sample=400, log=print):
     """How many of a gather's row reads a workgroup could serve from LDS if it staged, per tile of
     consecutive destination rows, the source rows that the tile's lists name most often: the share of
     list entries that are a repeat of one of the tile's `staged_rows` most frequent sources.  Host
@@ -95,7 +95,19 @@ def staging_share(cfg: int, tile_rows=(64, 256, 1024), staged_rows=(64, 128, 256
             served += int((cnt[cnt >= 2] - 1).sum())
         return served / max(total, 1)
 
+    def reuse(ptr, cols, t):
+        tiles = rng.choice((n + t - 1) // t, size=min(sample, (n + t - 1) // t), replace=False)
+        total = distinct = 0
+        for i in tiles:
+            c = cols[ptr[i * t]:ptr[min(n, (i + 1) * t)]]
+            total += c.size
+            distinct += np.unique(c).size
+        return total / max(distinct, 1)
+
     for t in tile_rows:
+        # the upper limit of any scheme that keeps a tile's accumulators on chip and reads every source once per tile
+        log(f"tile of {t} rows: list entries per distinct source: input graph {reuse(rowptr, col, t):.2f}  "
+            f"HAG {reuse(f['hrowptr'], f['hcol'], t):.2f}")
         for k in staged_rows:
             log(f"tile of {t} rows, {k} staged rows: input graph {share(rowptr, col, t, k):.3f}  "
                 f"HAG {share(f['hrowptr'], f['hcol'], t, k):.3f}")

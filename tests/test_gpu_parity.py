@@ -114,12 +114,19 @@ def test_source_partitioned_schedule(B, monkeypatch, offset64):
         monkeypatch.setenv("HAG_OFFSET64", "1")
     monkeypatch.setenv("HAG_PARTITION_MIN_ROWS", "0")
     monkeypatch.setenv("HAG_PART_MIN", "8")
+    monkeypatch.setenv("HAG_PART_MEAN_MIN", "0")
+    monkeypatch.setenv("HAG_PART_SHIFT", "3")           # workgroup b takes source class (b + 3) mod 8: same results
     monkeypatch.setenv("HAG_BLOCK_MAX", "40")
     rowptr, col = synth.holme_kim(1500, 9, 0.5, seed=41)
     n = rowptr.size - 1
     assert np.diff(rowptr).max() > 100
     h = B.hag_search(rowptr, col, n // 4)
     run_all_ops(B, h, rowptr, col, 64, seed=42)
+    # the cut is really in effect: its partial rows make the workspace larger than without it
+    monkeypatch.setenv("HAG_PARTITION", "0")
+    h_plain = B.hag_search(rowptr, col, n // 4).upload()
+    monkeypatch.delenv("HAG_PARTITION")
+    assert h.workspace_bytes("sum", 0, 64) > h_plain.workspace_bytes("sum", 0, 64)
     run_all_ops(B, h, rowptr, col, 16, seed=43, ops=("sum", "max"), dtypes=("f32",))
     rowptr, col = synth.random_graph(300, 0.2, seed=44, directed=True)
     h = B.hag_search(rowptr, col, 150)
@@ -321,7 +328,7 @@ def test_max_ties_bit_exact(B):
 @pytest.mark.parametrize("knobs", [
     {},
     {"HAG_STAGE_EXTRA_ROWS": "-1000000"},                                                     # one launch per level
-    {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "16", "HAG_PART_SHARE_PCT": "0"},          # rows cut by source id
+    {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "16", "HAG_PART_SHARE_PCT": "0", "HAG_PART_MEAN_MIN": "0"},   # rows cut by source id
     {"HAG_BLOCK_MAX": "48", "HAG_SUB_MAX": "24"},                                             # split rows, workgroup items
 ])
 def test_max_ties_through_aggregation_rows(B, monkeypatch, knobs):
@@ -476,7 +483,7 @@ def test_one_launch_pass_bounded_wait_gives_up_and_reports(B, monkeypatch):
 def test_deterministic_max_backward_is_bit_reproducible_and_matches_oracle(B, monkeypatch):
     # the backward pass of max as a gather over the transposed input graph filtered by argmax (no atomics):
     # int32 bit-exact, fp32 within tolerance and identical from run to run; also with rows cut into pieces
-    for env in ({}, {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "8", "HAG_BLOCK_MAX": "40"}):
+    for env in ({}, {"HAG_PARTITION_MIN_ROWS": "0", "HAG_PART_MIN": "8", "HAG_PART_MEAN_MIN": "0", "HAG_BLOCK_MAX": "40"}):
         for k, v in env.items():
             monkeypatch.setenv(k, v)
         rowptr, col = synth.holme_kim(2500, 9, 0.5, seed=97)

@@ -16,8 +16,8 @@ torch = pytest.importorskip("torch")
 pytestmark = pytest.mark.gpu
 
 TOL = 1e-5
-KNOBS = ("HAG_PARTITION_MIN_ROWS", "HAG_PART_MIN", "HAG_PART_SHARE_PCT", "HAG_BLOCK_MAX", "HAG_SUB_MAX",
-         "HAG_STAGE_EXTRA_ROWS")
+KNOBS = ("HAG_PARTITION_MIN_ROWS", "HAG_PART_MIN", "HAG_PART_SHARE_PCT", "HAG_PART_MEAN_MIN", "HAG_PART_CLASS_SHIFT",
+         "HAG_PART_SHIFT", "HAG_BLOCK_MAX", "HAG_SUB_MAX", "HAG_STAGE_EXTRA_ROWS")
 
 
 @pytest.fixture(scope="module")
@@ -74,7 +74,9 @@ def test_random_graphs_widths_and_schedules(B, monkeypatch, chunk):
             monkeypatch.delenv(k, raising=False)
         env = {}
         if rng.random() < 0.5:
-            env.update(HAG_PARTITION_MIN_ROWS="0", HAG_PART_MIN=str(rng.choice([4, 16, 64])), HAG_PART_SHARE_PCT="0")
+            env.update(HAG_PARTITION_MIN_ROWS="0", HAG_PART_MIN=str(rng.choice([4, 16, 64])), HAG_PART_SHARE_PCT="0",
+                       HAG_PART_MEAN_MIN="0", HAG_PART_CLASS_SHIFT=str(rng.choice([-1, 0, 2, 5])),
+                       HAG_PART_SHIFT=str(rng.integers(0, 8)))
         if rng.random() < 0.5:
             env["HAG_BLOCK_MAX"] = str(rng.choice([16, 40, 200]))
         if rng.random() < 0.4:

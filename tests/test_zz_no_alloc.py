@@ -31,6 +31,7 @@ def test_static_scratch_forward_matches_forward_on_two_calls_in_a_row(B, monkeyp
     # as the aggregation rows
     monkeypatch.setenv("HAG_PARTITION_MIN_ROWS", "0")
     monkeypatch.setenv("HAG_PART_MIN", "8")
+    monkeypatch.setenv("HAG_PART_MEAN_MIN", "0")
     monkeypatch.setenv("HAG_BLOCK_MAX", "40")
     cases = []
     for n, m, d, seed in ((3000, 9, 64, 71), (700, 6, 32, 72)):          # the second input is the smaller one
