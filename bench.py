@@ -33,11 +33,11 @@ LDS_PEAK_GBS = 256 * 64 * 4 * 2.4
 # file (FETCH_SIZE, WRITE_SIZE, scaled by what the same counters read for --copy-calibration's
 # known copy); the summaries are in profiles/.  Not measured by the run that prints them.
 PROFILED_TRAFFIC = {
-    ("config2:holme_kim56944", 128, "sum"): dict(fetch=310122 * 2048, write=28472 * 1024,
+    ("config2:holme_kim56944", 128, "sum"): dict(fetch=310725 * 2048, write=28472 * 1024,
                                                   source="profiles/pmc_config2_holme_kim56944_d128_sum.txt"),
-    ("config3:dcsbm232965", 128, "sum"): dict(fetch=6265120 * 2048, write=898966 * 1024,
+    ("config3:dcsbm232965", 128, "sum"): dict(fetch=6014900 * 2048, write=931865 * 1024,
                                                source="profiles/pmc_config3_dcsbm232965_d128_sum.txt"),
-    ("config4:er_batch5000x74", 64, "sum"): dict(fetch=74078 * 2048, write=92500 * 1024,
+    ("config4:er_batch5000x74", 64, "sum"): dict(fetch=74111 * 2048, write=92500 * 1024,
                                                   source="profiles/pmc_config4_er_batch5000x74_d64_sum.txt"),
 }
 

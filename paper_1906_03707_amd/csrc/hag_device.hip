@@ -186,7 +186,8 @@ static int run_fused(const hag_handle *h, const std::vector<const Plan *> &plans
     {
         const uint64_t row_bytes = (uint64_t)base.d * 4;
         const uint64_t lo_rows = (uint64_t)std::max<int64_t>(base.split, 1);
-        base.off32 = (!h->knobs.offset64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
+        base.off32 = (!h->knobs.offset64 && lo_rows * row_bytes < (1ull << 32) && lo_rows <= (1ull << 24) &&
+                      row_bytes < (1ull << 24)) ? 1 : 0;
     }
     base.part = nullptr;
     base.part_id = nullptr;
@@ -211,7 +212,8 @@ static int run_plan(const hag_handle *h, const Plan &p, const int32_t *d_col, Ga
         const uint64_t row_bytes = (uint64_t)a.d * 4;
         const uint64_t lo_rows = (uint64_t)std::max<int64_t>(a.split, 1);
         // the knob forces the 64-bit path, which otherwise only matrices of 4 GiB and more take
-        a.off32 = (!h->knobs.offset64 && lo_rows * row_bytes < (1ull << 32)) ? 1 : 0;
+        a.off32 = (!h->knobs.offset64 && lo_rows * row_bytes < (1ull << 32) && lo_rows <= (1ull << 24) &&
+                   row_bytes < (1ull << 24)) ? 1 : 0;
     }
     // A row is worth a whole workgroup when each of its 256/LPR sub-groups still gets about
     // eight neighbours, and needs one when a single sub-group would walk it for too long.

@@ -203,6 +203,15 @@ __device__ __forceinline__ void max_first4(V &v, int4 &vi, const V &w, int wi) {
     max_first1(v.x, vi.x, w.x, wi); max_first1(v.y, vi.y, w.y, wi);
     max_first1(v.z, vi.z, w.z, wi); max_first1(v.w, vi.w, w.w, wi);
 }
+// the same for a candidate known to be valid, with the emptiness of the accumulator given as a flag
+template <typename V>
+__device__ __forceinline__ void max_filled4(V &v, int4 &vi, const V &w, int wi, bool empty) {
+    const bool tx = empty | (w.x > v.x), ty = empty | (w.y > v.y), tz = empty | (w.z > v.z), tw = empty | (w.w > v.w);
+    v.x = tx ? w.x : v.x; vi.x = tx ? wi : vi.x;
+    v.y = ty ? w.y : v.y; vi.y = ty ? wi : vi.y;
+    v.z = tz ? w.z : v.z; vi.z = tz ? wi : vi.z;
+    v.w = tw ? w.w : v.w; vi.w = tw ? wi : vi.w;
+}
 template <typename V>
 __device__ __forceinline__ void max4(V &v, int4 &vi, const V &w, const int4 &wi) {
     max1(v.x, vi.x, w.x, wi.x); max1(v.y, vi.y, w.y, wi.y);
