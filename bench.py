@@ -310,6 +310,59 @@ def sweep_config5(torch, synth, workloads, steps, warmup):
         torch.cuda.empty_cache()
 
 
+FP32_MFMA_PEAK_TFLOPS = 157.3
+
+
+def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup):
+    """LSTM aggregator over ordered neighbour lists (Section 3.1's sequential Aggregate): every node's list is its
+    first `first_k` neighbours in ascending id order; the plain lists against prefix HAGs of capacity |V|/4 and
+    unlimited.  One step = one forward pass (all cell evaluations of the plan)."""
+    import numpy as np
+    rowptr, col, _ = synth.graph_for_config(cfg)
+    n = rowptr.size - 1
+    take = np.minimum(np.diff(rowptr), first_k)
+    rp = np.concatenate([[0], np.cumsum(take)]).astype(np.int64)
+    cl = col[np.repeat(rowptr[:-1], take) + (np.arange(rp[-1]) - np.repeat(rp[:-1], take))].astype(np.int32)
+    rng = np.random.default_rng(synth.SEED_BASE + 100 * cfg + 7)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    x = dev(rng.normal(size=(n, d)))
+    w_ih, w_hh, b = dev(rng.normal(0, 0.3, (4 * hidden, d))), dev(rng.normal(0, 0.3, (4 * hidden, hidden))), dev(rng.normal(0, 0.3, 4 * hidden))
+    out = torch.empty((n, hidden), dtype=torch.float32, device="cuda")
+    plans = {"lists": binding.SeqHag(rp, cl, 0).upload(), "hag_quarter": binding.SeqHag(rp, cl, n // 4).upload(),
+             "hag_unlimited": binding.SeqHag(rp, cl, int(cl.size)).upload()}
+    # what the matrix cores deliver on this machine for the instruction the kernel uses
+    sink = torch.empty(256 * 8 * 256, dtype=torch.float32, device="cuda")
+    binding.probe_mfma_f32(2000, 256 * 8, sink)
+    ea, eb = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ea.record()
+    probe_flops = sum(binding.probe_mfma_f32(20000, 256 * 8, sink) for _ in range(3))
+    eb.record()
+    torch.cuda.synchronize()
+    mfma_ceiling = probe_flops / (ea.elapsed_time(eb) * 1e-3) / 1e12
+    log(f"[bench] fp32 matrix-core probe: {mfma_ceiling:.1f} TFLOP/s (published peak {FP32_MFMA_PEAK_TFLOPS})")
+    flops_per_cell = 2.0 * 4 * hidden * (d + hidden)
+    res = {"workload": f"config{cfg}:{synth.CONFIGS[cfg]['name']}, first {first_k} neighbours in id order", "nodes": n,
+           "list_entries": int(cl.size), "d": d, "hidden": hidden, "flops_per_cell": flops_per_cell,
+           "measured_fp32_matrix_TFLOPs": mfma_ceiling, "plans": {}}
+    base = lambda: plans["lists"].lstm_forward(x, w_ih, w_hh, b, out=out)
+    for name, p in plans.items():
+        fn = (lambda p=p: p.lstm_forward(x, w_ih, w_hh, b, out=out))
+        if name == "lists":
+            ms, _ = time_steps(torch, fn, steps, warmup)
+            ms_base = ms
+        else:
+            (ms, _), (ms_base, _) = time_interleaved(torch, fn, base, steps, warmup)
+        tf = p.cells * flops_per_cell / (ms * 1e-3) / 1e12
+        res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.ranks, "ms_per_pass": ms,
+                              "lists_ms_per_pass": ms_base, "speedup_vs_lists": ms_base / ms,
+                              "cells_fewer": plans["lists"].cells / max(p.cells, 1), "tflops": tf,
+                              "frac_of_fp32_matrix_peak": tf / FP32_MFMA_PEAK_TFLOPS, "frac_of_measured_ceiling": tf / mfma_ceiling}
+        log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.ranks} launches, "
+            f"{ms:.3f} ms per pass ({ms_base / ms:.2f}x the plain lists' speed), {tf:.1f} TFLOP/s = "
+            f"{100 * tf / FP32_MFMA_PEAK_TFLOPS:.1f}% of the fp32 matrix-core peak")
+    return res
+
+
 def short_workload(torch, binding, synth, workloads, cfg, steps, warmup):
     """Forward + backward of one of the smaller configs, HAG against the naive-CSR kernels: the figures
     that ride along with the main workload's line."""
@@ -363,6 +416,9 @@ def main():
                     help="also time one epoch of a 2-layer GraphSAGE with the max-pooling aggregator (16 hidden dims)")
     ap.add_argument("--gcn-epoch", action="store_true",
                     help="also time a 2-layer GCN epoch (16 hidden dims, SoftMax) around the aggregation")
+    ap.add_argument("--seq-lstm", action="store_true",
+                    help="time the LSTM aggregator over ordered lists (first 16 neighbours of --config 4 or 2, d = hidden = --d or 64): "
+                         "plain lists against prefix HAGs")
     ap.add_argument("--one-launch", action="store_true",
                     help="run the HAG passes with the one-launch schedule (all stages and the gather over V in a single "
                          "kernel launch; off by default because it measures slower)")
@@ -383,6 +439,14 @@ def main():
     binding.lib()
     torch.cuda.set_device(0)
     cfg = args.config
+    if args.seq_lstm:
+        c = cfg if cfg in (1, 2, 4) else 4
+        width = args.d if args.d else 64
+        res = seq_lstm_bench(torch, binding, synth, c, 16, width, width, max(args.steps // 2, 5), 3)
+        print(json.dumps({"metric": "LSTM aggregator over ordered lists, forward: cell evaluations/s", "unit": "cells/s",
+                          "value": res["plans"]["hag_quarter"]["cells"] / (res["plans"]["hag_quarter"]["ms_per_pass"] * 1e-3),
+                          "n_gpus": 1, "dtype": "f32", "data": "synthetic", "config": res}), flush=True)
+        return
     if cfg == 5:
         sweep_config5(torch, synth, workloads, max(min(args.steps, 10), 3), 2)
         return

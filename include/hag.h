@@ -146,8 +146,7 @@ int hag_prefix(const hag_t *h, int64_t n_merges, hag_t **out);
  * leading pair by a new node w in exactly those lists, w standing for the ordered cover
  * (cover(v1), cover(v2)) of Equation 2.  Stops at `capacity` merges or when the best redundancy is <= 1;
  * ties go to the lexicographically smallest (v1, v2).  With capacity >= |E| the result has the fewest
- * aggregations any equivalent HAG can have (Theorem 3).  Host only; there is no device path for
- * sequential aggregators.
+ * aggregations any equivalent HAG can have (Theorem 3).  Host only; hag_seq_create below builds on it.
  * In: rowptr [n+1], col [rowptr[n]]: row v is the ORDERED list N(v) (a node may occur more than once).
  * Out (caller arrays): left/right/redundancy [min(capacity, rowptr[n])]: merge i created node n+i from
  * (left[i], right[i]) with that redundancy; *n_merges; hrowptr [n+1], hcol [rowptr[n]]: the final
@@ -155,6 +154,33 @@ int hag_prefix(const hag_t *h, int64_t n_merges, hag_t **out);
 int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity,
                    int64_t *n_merges, int32_t *left, int32_t *right, int32_t *redundancy,
                    int64_t *hrowptr, int32_t *hcol);
+
+/* Device path for a sequential Aggregate: an LSTM aggregator over ORDERED neighbour lists (Section 3.1),
+ *     (h_0, c_0) = 0,  (h_t, c_t) = cell(x[u_t], h_{t-1}, c_{t-1}) for N(v) = (u_1, ..., u_k),  a_v = h_k
+ * (a_v = 0 for an empty list), cell = the standard LSTM step: gates = w_ih x + w_hh h + b split into
+ * input, forget, cell and output gate, c' = sigmoid(f) c + sigmoid(i) tanh(g), h' = sigmoid(o) tanh(c').
+ * hag_seq_create (host): capacity > 0 runs hag_seq_search with that capacity and plans the evaluation of
+ * the resulting prefix HAG in the order of Algorithm 2 -- every shared prefix (an aggregation node of
+ * Equation 2's ordered cover, or the one-element prefix a list or a merge starts from) is evaluated once,
+ * then every node continues from the state of its list's head; capacity = 0 plans the plain lists with
+ * nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
+ * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: dependent launches of one pass (the longest
+ * chain of evaluations); hag_seq_merges: aggregation nodes.  hag_seq_upload copies the plan to the current
+ * device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
+ * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
+ * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights and one (h, c) state row per
+ * shared prefix and per node).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
+ * `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload, HAG_EINVAL otherwise. */
+typedef struct hag_seq hag_seq_t;
+int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out);
+void hag_seq_free(hag_seq_t *h);
+int64_t hag_seq_cells(const hag_seq_t *h);
+int64_t hag_seq_ranks(const hag_seq_t *h);
+int64_t hag_seq_merges(const hag_seq_t *h);
+int hag_seq_upload(hag_seq_t *h);
+size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
+int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,
+                         const float *w_hh, const float *b, float *a_out, void *workspace, void *stream);
 
 void hag_free(hag_t *h);
 
@@ -284,10 +310,14 @@ int64_t hag_algorithmic_bytes(const hag_t *h, int which, hag_op_t op, int64_t d)
  * into rows of its own: 16-byte read, add, 16-byte write), from_lds = 3 does the same with LDS
  * atomic adds: what accumulators kept in LDS cost per row.
  * Returns the number of row bytes read or accumulated (>= 0) or a negative status.
- * hag_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte granularity. */
+ * hag_probe_copy: dst[0..bytes) = src[0..bytes), device pointers, 16-byte granularity.
+ * hag_probe_mfma_f32: every wavefront of `workgroups` 256-thread workgroups issues iters x 4 independent
+ * v_mfma_f32_32x32x2_f32 on register operands and writes a checksum to sink (device, workgroups * 256
+ * floats); returns the flops of the launch: the fp32 matrix-core rate the LSTM aggregator is priced against. */
 int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads, int32_t from_lds,
                        int64_t workgroups, void *sink, void *stream);
 int hag_probe_copy(const void *src, void *dst, int64_t bytes, void *stream);
+int64_t hag_probe_mfma_f32(int64_t iters, int64_t workgroups, void *sink, void *stream);
 
 const char *hag_last_error(void);
 

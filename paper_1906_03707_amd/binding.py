@@ -29,7 +29,9 @@ EXPORTS = [
     "hag_search", "hag_search_batched", "hag_from_merges", "hag_prefix", "hag_free", "hag_stats",
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
-    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_set_option", "hag_check", "hag_seq_search",
+    "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_probe_mfma_f32", "hag_set_option", "hag_check", "hag_seq_search",
+    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
+    "hag_seq_lstm_forward",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
 
@@ -84,7 +86,19 @@ def lib():
         L.hag_probe_rows.argtypes = [vp, i64, i64, i64, i32, i64, vp, vp]
         L.hag_probe_rows.restype = i64
         L.hag_probe_copy.argtypes = [vp, vp, i64, vp]
+        L.hag_probe_mfma_f32.argtypes = [i64, i64, vp, vp]
+        L.hag_probe_mfma_f32.restype = i64
         L.hag_seq_search.argtypes = [i64, vp, vp, i64, ctypes.POINTER(i64), vp, vp, vp, vp, vp]
+        L.hag_seq_create.argtypes = [i64, vp, vp, i64, ctypes.POINTER(vp)]
+        L.hag_seq_free.argtypes = [vp]
+        L.hag_seq_free.restype = None
+        for name in ("hag_seq_cells", "hag_seq_ranks", "hag_seq_merges"):
+            getattr(L, name).argtypes = [vp]
+            getattr(L, name).restype = i64
+        L.hag_seq_upload.argtypes = [vp]
+        L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
+        L.hag_seq_workspace_bytes.restype = ctypes.c_size_t
+        L.hag_seq_lstm_forward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
         L.hag_set_option.argtypes = [vp, i32, i64]
         L.hag_check.argtypes = [vp, vp]
         _lib = L
@@ -328,6 +342,16 @@ def probe_copy(src, dst, nbytes):
     _check(lib().hag_probe_copy(_dev_ptr(src), _dev_ptr(dst), int(nbytes), _stream_ptr()))
 
 
+def probe_mfma_f32(iters, workgroups, sink) -> int:
+    """hag_probe_mfma_f32; returns the flops of the launch."""
+    if sink.numel() * sink.element_size() < workgroups * 1024:
+        raise ValueError("sink too small")
+    rc = lib().hag_probe_mfma_f32(int(iters), int(workgroups), _dev_ptr(sink), _stream_ptr())
+    if rc < 0:
+        _check(int(rc))
+    return int(rc)
+
+
 def hag_seq_search(rowptr, col, capacity):
     """Algorithm 3 for a sequential Aggregate (ordered lists): (left, right, redundancy, hrowptr, hcol)."""
     rowptr, col = _np(rowptr, np.int64), _np(col, np.int32)
@@ -340,3 +364,64 @@ def hag_seq_search(rowptr, col, capacity):
     _check(lib().hag_seq_search(n, rowptr.ctypes.data, col.ctypes.data, int(capacity), ctypes.byref(a), left.ctypes.data,
                                 right.ctypes.data, red.ctypes.data, hrowptr.ctypes.data, hcol.ctypes.data))
     return left[:a.value], right[:a.value], red[:a.value], hrowptr, hcol[:hrowptr[n]]
+
+
+class SeqHag:
+    """Plan of an LSTM aggregator over ordered neighbour lists (hag_seq_create): a prefix HAG when capacity > 0,
+    the plain lists when capacity == 0."""
+
+    def __init__(self, rowptr, col, capacity):
+        rowptr, col = _np(rowptr, np.int64), _np(col, np.int32)
+        self.n = rowptr.size - 1
+        h = ctypes.c_void_p()
+        _check(lib().hag_seq_create(self.n, rowptr.ctypes.data, col.ctypes.data, int(capacity), ctypes.byref(h)))
+        self._h = h
+        self._ws = {}
+
+    def __del__(self):
+        if getattr(self, "_h", None):
+            lib().hag_seq_free(self._h)
+            self._h = None
+
+    @property
+    def cells(self) -> int:
+        return int(lib().hag_seq_cells(self._h))
+
+    @property
+    def ranks(self) -> int:
+        return int(lib().hag_seq_ranks(self._h))
+
+    @property
+    def merges(self) -> int:
+        return int(lib().hag_seq_merges(self._h))
+
+    def upload(self):
+        _check(lib().hag_seq_upload(self._h))
+        return self
+
+    def workspace_bytes(self, d, hidden) -> int:
+        return int(lib().hag_seq_workspace_bytes(self._h, int(d), int(hidden)))
+
+    def lstm_forward(self, x, w_ih, w_hh, b, out=None, workspace=None):
+        """a [n, H] = LSTM aggregate of every node's ordered list; torch float32 device tensors."""
+        import torch
+        hidden, d = int(w_hh.shape[1]), int(x.shape[1])
+        for name, t, shape in (("x", x, (self.n, d)), ("w_ih", w_ih, (4 * hidden, d)), ("w_hh", w_hh, (4 * hidden, hidden)),
+                               ("b", b, (4 * hidden,))):
+            if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"{name} must be a contiguous float32 device tensor of shape {shape}")
+        if out is None:
+            out = torch.empty((self.n, hidden), dtype=torch.float32, device=x.device)
+        elif tuple(out.shape) != (self.n, hidden) or out.dtype != torch.float32 or not out.is_contiguous() or out.device != x.device:
+            raise ValueError("out must be a contiguous float32 tensor [n, hidden] on x's device")
+        need = self.workspace_bytes(d, hidden)
+        if workspace is None:
+            key = (x.device, torch.cuda.current_stream(x.device).cuda_stream, d, hidden)
+            workspace = self._ws.get(key)
+            if workspace is None:
+                workspace = self._ws[key] = torch.empty(max(need, 16), dtype=torch.uint8, device=x.device)
+        elif workspace.numel() * workspace.element_size() < need or workspace.device != x.device:
+            raise ValueError("workspace too small or on another device")
+        _check(lib().hag_seq_lstm_forward(self._h, d, hidden, _dev_ptr(x), _dev_ptr(w_ih), _dev_ptr(w_hh), _dev_ptr(b),
+                                          _dev_ptr(out), _dev_ptr(workspace), _stream_ptr()))
+        return out

@@ -11,7 +11,7 @@ ROOT = os.path.dirname(HERE)
 LIB = os.path.join(HERE, "libhag.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = [os.path.join(HERE, "csrc", f) for f in (
-    "hag_host.cpp", "hag_seq.cpp", "hag_device.hip", "hag_search_device.hip", "hag_probe.hip",
+    "hag_host.cpp", "hag_seq.cpp", "hag_device.hip", "hag_search_device.hip", "hag_probe.hip", "hag_seq_device.hip",
     # the gather and component kernels are instantiated for many widths and roles: one unit per
     # element type (and reduction) so that they compile side by side
     "hag_gather_f32_sum.hip", "hag_gather_f32_max.hip", "hag_gather_i32_sum.hip", "hag_gather_i32_max.hip",

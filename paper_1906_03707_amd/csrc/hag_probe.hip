@@ -106,6 +106,24 @@ __global__ __launch_bounds__(kBlock) void probe_copy_kernel(const float4 *__rest
     for (int64_t i = (int64_t)blockIdx.x * kBlock + threadIdx.x; i < n16; i += stride) dst[i] = src[i];
 }
 
+// fp32 matrix-core throughput: every wavefront issues `iters` rounds of four independent
+// v_mfma_f32_32x32x2_f32 (4096 flops each) on register operands; nothing but the matrix pipe is used
+typedef float probe_acc_t __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(kBlock) void probe_mfma_f32_kernel(int32_t iters, float *__restrict__ sink) {
+    probe_acc_t a0 = {0}, a1 = {0}, a2 = {0}, a3 = {0};
+    const float x = (float)(threadIdx.x & 7) * 0.125f, y = 1.0f / (float)(1 + (threadIdx.x & 3));
+    for (int i = 0; i < iters; ++i) {
+        a0 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, y, a0, 0, 0, 0);
+        a1 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, x, a1, 0, 0, 0);
+        a2 = __builtin_amdgcn_mfma_f32_32x32x2f32(x, x, a2, 0, 0, 0);
+        a3 = __builtin_amdgcn_mfma_f32_32x32x2f32(y, y, a3, 0, 0, 0);
+    }
+    float r = 0.f;
+#pragma unroll
+    for (int k = 0; k < 16; ++k) r += a0[k] + a1[k] + a2[k] + a3[k];
+    sink[(size_t)blockIdx.x * kBlock + threadIdx.x] = r;
+}
+
 template <int LDS>
 static int launch_probe_rows(int lpr, unsigned groups, size_t lds_bytes, hipStream_t s, const float *src, uint32_t mask,
                              int32_t d, int32_t reads, int32_t lds_rows, float *sink) {
@@ -157,6 +175,15 @@ int64_t hag_probe_rows(const void *src, int64_t n_rows, int64_t d, int64_t reads
     }
     if (rc) return rc;
     return workgroups * groups_per_wg * reads * d * 4;   // bytes of rows read
+}
+
+int64_t hag_probe_mfma_f32(int64_t iters, int64_t workgroups, void *sink, void *stream) {
+    if (!sink || ((uintptr_t)sink & 15)) { set_error("sink must be a 16-byte aligned device pointer"); return HAG_EINVAL; }
+    if (iters <= 0 || iters > (1 << 24) || workgroups <= 0 || workgroups > (1 << 20)) { set_error("iters or workgroups out of range"); return HAG_EINVAL; }
+    hipLaunchKernelGGL(probe_mfma_f32_kernel, dim3((unsigned)workgroups), dim3(kBlock), 0, (hipStream_t)stream, (int32_t)iters,
+                       (float *)sink);
+    HIP_TRY(hipGetLastError());
+    return workgroups * (kBlock / kWave) * iters * 4 * 4096;   // flops
 }
 
 int hag_probe_copy(const void *src, void *dst, int64_t bytes, void *stream) {

@@ -1,0 +1,386 @@
+// Device path for a SEQUENTIAL Aggregate (Section 3.1): an LSTM aggregator over ordered neighbour
+// lists, run over a prefix HAG found by hag_seq_search (or over the plain lists).
+//
+// Every evaluation of the LSTM cell is a "job": (input row, state it continues, state it writes).
+// A prefix HAG turns the lists into a forest of jobs: the state after the one-element prefix (u) is
+// a job without a predecessor, an aggregation node w = (v1, v2) is the job "state of v1, then x[v2]"
+// (Equation 2: cover(w) = (cover(v1), cover(v2))), and every v continues from the state of its
+// list's head through the rest of its list (Algorithm 2: aggregation nodes first, then the nodes of
+// V).  Jobs are ranked by the length of the chain behind them; one launch evaluates all jobs of a
+// rank as a gathered matrix product on the matrix cores:
+//     gates^T [4H, jobs] = Wp [4H, D+H] . Z^T [D+H, jobs],    Z[j] = (x[in_j], h[prev_j]),
+// 32 gate rows x 32 jobs per wavefront tile with v_mfma_f32_32x32x2_f32 (fp32 in, fp32 out).  The rows of
+// Wp are ordered (hidden unit, gate), so a lane ends up holding all four gates of its hidden units
+// for its job and the cell's element-wise part runs in registers.  A wavefront keeps its slice of
+// Wp in registers for the whole launch; the gathered rows of a tile of jobs are staged in LDS.
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cstdint>
+#include <cstring>
+#include <new>
+#include <vector>
+
+#include "hag_device_common.hpp"
+
+struct hag_seq {
+    int64_t n = 0, e = 0, n_merges = 0, n_states = 0;
+    std::vector<int32_t> jobs;        // 3 per job: input row, previous state (-1: none), written state
+    std::vector<int64_t> rank_ptr;    // jobs of rank t: [rank_ptr[t], rank_ptr[t+1])
+    std::vector<int32_t> final_state; // per node: state row holding a_v, -1 for an empty list
+    int32_t *d_jobs = nullptr, *d_final = nullptr;
+    int device = -1;
+};
+
+namespace hag {
+
+constexpr int kSeqJobs = 32;      // jobs per tile
+constexpr int kSeqMaxK = 128;     // D + H at most
+
+struct SeqArgs {
+    const int32_t *jobs;   // this rank's jobs
+    int64_t n_jobs;
+    const float *x;        // [n, d]
+    const float *wp;       // [4H, KP] packed weights, rows (unit, gate), columns (input, hidden, zero padding)
+    const float *bp;       // [4H] packed bias
+    float *h, *c;          // [n_states, H]
+    int32_t d, hidden, kp;
+};
+
+// Wp / bp from the usual layout: w_ih [4H, D], w_hh [4H, H], b [4H], gate-major rows (input, forget,
+// cell, output gate).
+__global__ __launch_bounds__(256) void seq_pack_kernel(const float *__restrict__ w_ih, const float *__restrict__ w_hh,
+                                                      const float *__restrict__ b, float *__restrict__ wp,
+                                                      float *__restrict__ bp, int d, int hidden, int kp) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int64_t total = (int64_t)4 * hidden * kp;
+    if (i >= total) return;
+    const int r = (int)(i / kp), k = (int)(i % kp);
+    const int unit = r >> 2, gate = r & 3, src_row = gate * hidden + unit;
+    float v = 0.f;
+    if (k < d) v = w_ih[(size_t)src_row * d + k];
+    else if (k < d + hidden) v = w_hh[(size_t)src_row * hidden + (k - d)];
+    wp[i] = v;
+    if (k == 0) bp[r] = b[src_row];
+}
+
+// Gate functions on the hardware's exp2 and reciprocal: absolute error of a few 1e-7 on outputs in (0, 1) and
+// (-1, 1), against ~150 instructions per hidden unit for the library versions, which made the element-wise
+// part as long as the matrix products.
+__device__ __forceinline__ float seq_sigmoid(float z) { return __builtin_amdgcn_rcpf(1.f + __expf(-z)); }
+__device__ __forceinline__ float seq_tanh(float z) {
+    const float e = __expf(-2.f * fabsf(z));             // in (0, 1]: no overflow, no cancellation in 1 + e
+    return copysignf((1.f - e) * __builtin_amdgcn_rcpf(1.f + e), z);
+}
+
+typedef float seq_acc_t __attribute__((ext_vector_type(16)));
+
+// One rank of jobs.  KSTEPS = KP / 2 matrix-core steps per tile; TPW gate tiles (of 8 hidden units)
+// per wavefront, 4 wavefronts per workgroup: hidden <= 32 * TPW.
+template <int KSTEPS, int TPW>
+__global__ __launch_bounds__(256, 2) void seq_lstm_kernel(SeqArgs A) {
+    constexpr int KP = 2 * KSTEPS, ZS = KP + 2;            // row stride of the staged inputs: even, and 2 banks apart per job
+    __shared__ float z[kSeqJobs * ZS];
+    __shared__ float hs[kSeqJobs * (32 * TPW + 1)];   // new h of the tile, [job][unit]
+    __shared__ float cs[kSeqJobs * (32 * TPW + 1)];
+    constexpr int HS = 32 * TPW + 1;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int hidden = A.hidden, d = A.d, n_tiles = hidden / 8;
+    // this wavefront's slice of the packed weights, in the operand layout of the matrix instruction:
+    // lane l supplies row (l % 32) of the tile and column 2 * step + l / 32
+    float wreg[TPW][KSTEPS];
+#pragma unroll
+    for (int t = 0; t < TPW; ++t) {
+        const int tile = wave * TPW + t;
+#pragma unroll
+        for (int s = 0; s < KSTEPS; ++s)
+            wreg[t][s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
+    }
+    const int64_t n_job_tiles = (A.n_jobs + kSeqJobs - 1) / kSeqJobs;
+    // Staging is done by 8 threads per job, 16 bytes at a time, and runs one tile ahead: the rows of the
+    // next tile are requested before the matrix products of this one and written to LDS after its results
+    // have left, so their latency hides behind the products.  (A job's own state row may be its input and
+    // its output; no other job of the same launch reads or writes it, so reading ahead is safe.)
+    constexpr int ZV = KP / 32, CV = TPW;                  // 16-byte vectors per thread: inputs, previous cell state
+    const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;
+    int in_row = -1, prev = -1, out = -1;
+    float4 zr[ZV], cr[CV];
+    auto fetch = [&](int64_t jt) {
+        const int64_t job = jt * kSeqJobs + sj;
+        in_row = prev = out = -1;
+        if (jt < n_job_tiles && job < A.n_jobs) {
+            in_row = A.jobs[job * 3]; prev = A.jobs[job * 3 + 1]; out = A.jobs[job * 3 + 2];
+        }
+#pragma unroll
+        for (int i = 0; i < ZV; ++i) {
+            const int k = part * 4 + 32 * i;
+            zr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (in_row >= 0) {
+                if (k < d) zr[i] = *reinterpret_cast<const float4 *>(A.x + (size_t)in_row * d + k);
+                else if (k < d + hidden && prev >= 0) zr[i] = *reinterpret_cast<const float4 *>(A.h + (size_t)prev * hidden + (k - d));
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < CV; ++i) {
+            const int u = part * 4 + 32 * i;
+            cr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (in_row >= 0 && prev >= 0 && u < hidden) cr[i] = *reinterpret_cast<const float4 *>(A.c + (size_t)prev * hidden + u);
+        }
+    };
+    fetch(blockIdx.x);
+    for (int64_t jt = blockIdx.x; jt < n_job_tiles; jt += gridDim.x) {
+        // rows of z are only 8-byte aligned: two 8-byte stores per vector
+#pragma unroll
+        for (int i = 0; i < ZV; ++i) {
+            const int k = part * 4 + 32 * i;
+            *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(zr[i].x, zr[i].y);
+            *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(zr[i].z, zr[i].w);
+        }
+#pragma unroll
+        for (int i = 0; i < CV; ++i) {
+            const int u = part * 4 + 32 * i;
+            if (u < hidden) { cs[sj * HS + u] = cr[i].x; cs[sj * HS + u + 1] = cr[i].y; cs[sj * HS + u + 2] = cr[i].z; cs[sj * HS + u + 3] = cr[i].w; }
+        }
+        const int out_now = in_row >= 0 ? out : -1;
+        __syncthreads();
+        fetch(jt + gridDim.x);
+        seq_acc_t acc[TPW];
+#pragma unroll
+        for (int t = 0; t < TPW; ++t)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
+        // the operand of the step after next is read from LDS before the products of this step are issued
+        const float *zl = &z[(lane & 31) * ZS + (lane >> 5)];
+        float b0 = zl[0], b1 = zl[2];
+#pragma unroll
+        for (int s = 0; s < KSTEPS; s += 2) {
+            const float n0 = s + 2 < KSTEPS ? zl[2 * s + 4] : 0.f, n1 = s + 2 < KSTEPS ? zl[2 * s + 6] : 0.f;
+            __builtin_amdgcn_sched_barrier(0);          // keep the read above the products below
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[t][s], b0, acc[t], 0, 0, 0);
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[t][s + 1], b1, acc[t], 0, 0, 0);
+            b0 = n0; b1 = n1;
+        }
+        // element-wise part: lane l holds, for job l % 32, gate rows 8 * (r / 4) + 4 * (l / 32) + r % 4 of each
+        // tile, i.e. the four gates (r % 4) of hidden units 2 * (r / 4) + l / 32 of the tile
+        {
+            const int j = lane & 31;
+#pragma unroll
+            for (int t = 0; t < TPW; ++t) {
+                const int tile = wave * TPW + t;
+                if (tile < n_tiles) {
+#pragma unroll
+                    for (int m = 0; m < 4; ++m) {
+                        const int unit = tile * 8 + 2 * m + (lane >> 5);
+                        const float gi = acc[t][4 * m + 0] + A.bp[unit * 4 + 0];
+                        const float gf = acc[t][4 * m + 1] + A.bp[unit * 4 + 1];
+                        const float gg = acc[t][4 * m + 2] + A.bp[unit * 4 + 2];
+                        const float go = acc[t][4 * m + 3] + A.bp[unit * 4 + 3];
+                        const float c_prev = cs[j * HS + unit];   // staged above; this lane is the only one to touch the element
+                        const float c_new = seq_sigmoid(gf) * c_prev + seq_sigmoid(gi) * seq_tanh(gg);
+                        cs[j * HS + unit] = c_new;
+                        hs[j * HS + unit] = seq_sigmoid(go) * seq_tanh(c_new);
+                    }
+                }
+            }
+        }
+        __syncthreads();
+        // write the new states, rows contiguous: 8 threads per job
+        if (out_now >= 0) {
+            for (int u = part * 4; u < hidden; u += 32) {
+                const float *ph = &hs[sj * HS + u], *pc = &cs[sj * HS + u];
+                *reinterpret_cast<float4 *>(A.h + (size_t)out_now * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
+                *reinterpret_cast<float4 *>(A.c + (size_t)out_now * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
+__global__ __launch_bounds__(256) void seq_output_kernel(const int32_t *__restrict__ final_state, const float *__restrict__ h,
+                                                        float *__restrict__ out, int64_t n, int hidden) {
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n * hidden) return;
+    const int64_t v = i / hidden;
+    const int s = final_state[v];
+    out[i] = s >= 0 ? h[(size_t)s * hidden + (i % hidden)] : 0.f;
+}
+
+}  // namespace hag
+
+using namespace hag;
+
+extern "C" {
+
+int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, int64_t *n_merges, int32_t *left,
+                   int32_t *right, int32_t *redundancy, int64_t *hrowptr, int32_t *hcol);
+
+int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out) {
+    if (!out) { set_error("out is NULL"); return HAG_EINVAL; }
+    *out = nullptr;
+    if (n < 0 || capacity < 0 || !rowptr) { set_error("n < 0, capacity < 0 or rowptr is NULL"); return HAG_EINVAL; }
+    try {
+        const int64_t e = rowptr[n];
+        std::vector<int64_t> hrowptr(n + 1, 0);
+        std::vector<int32_t> hcol((size_t)std::max<int64_t>(e, 1));
+        const int64_t cap = std::min(capacity, e);
+        std::vector<int32_t> left((size_t)std::max<int64_t>(cap, 1)), right(left.size()), red(left.size());
+        int64_t a = 0;
+        // capacity 0 still goes through the search: it validates the lists and copies them
+        int rc = hag_seq_search(n, rowptr, col, cap, &a, left.data(), right.data(), red.data(), hrowptr.data(), hcol.data());
+        if (rc) return rc;
+        if (n + a + e + n >= (int64_t)INT32_MAX) { set_error("too many states for 32-bit ids"); return HAG_EINVAL; }
+        auto *h = new hag_seq();
+        h->n = n; h->e = e; h->n_merges = a;
+        const bool share = capacity > 0;
+        // state rows: one-element prefixes in use, aggregation nodes, one running row per node
+        std::vector<int32_t> first_id(n, -1);
+        int32_t n_first = 0;
+        auto need_first = [&](int32_t u) { if (first_id[u] < 0) first_id[u] = n_first++; };
+        if (share) {
+            for (int64_t i = 0; i < a; ++i) if (left[i] < n) need_first(left[i]);
+            for (int64_t v = 0; v < n; ++v)
+                if (hrowptr[v + 1] > hrowptr[v] && hcol[hrowptr[v]] < n) need_first(hcol[hrowptr[v]]);
+        }
+        const int32_t agg0 = n_first, run0 = (int32_t)(n_first + a);
+        h->n_states = (int64_t)run0 + n;
+        std::vector<int32_t> rank_of_state((size_t)h->n_states, 0);
+        struct J { int32_t x, prev, out, rank; };
+        std::vector<J> js;
+        js.reserve((size_t)(e + n_first));
+        for (int64_t u = 0; u < n; ++u)
+            if (first_id[u] >= 0) js.push_back(J{(int32_t)u, -1, first_id[u], 0});
+        auto state_of = [&](int32_t id) { return id < n ? first_id[id] : agg0 + (id - (int32_t)n); };
+        for (int64_t i = 0; i < a; ++i) {
+            const int32_t prev = state_of(left[i]), out_s = agg0 + (int32_t)i;
+            const int32_t r = rank_of_state[prev] + 1;
+            rank_of_state[out_s] = r;
+            js.push_back(J{right[i], prev, out_s, r});
+        }
+        h->final_state.assign(n, -1);
+        for (int64_t v = 0; v < n; ++v) {
+            const int64_t b0 = hrowptr[v], b1 = hrowptr[v + 1];
+            if (b1 == b0) continue;
+            const int32_t mine = run0 + (int32_t)v;
+            int32_t cur, r;
+            int64_t i = b0;
+            if (share) { cur = state_of(hcol[b0]); r = rank_of_state[cur]; i = b0 + 1; }
+            else { cur = -1; r = -1; }
+            for (; i < b1; ++i) {
+                js.push_back(J{hcol[i], cur, mine, ++r});
+                cur = mine;
+            }
+            h->final_state[v] = cur;
+        }
+        int32_t ranks = 0;
+        for (const J &j : js) ranks = std::max(ranks, j.rank + 1);
+        h->rank_ptr.assign((size_t)ranks + 1, 0);
+        for (const J &j : js) ++h->rank_ptr[(size_t)j.rank + 1];
+        for (int32_t t = 0; t < ranks; ++t) h->rank_ptr[(size_t)t + 1] += h->rank_ptr[t];
+        std::vector<int64_t> at(h->rank_ptr.begin(), h->rank_ptr.end() - 1);
+        h->jobs.resize(js.size() * 3);
+        for (const J &j : js) {
+            const int64_t p = at[j.rank]++;
+            h->jobs[p * 3] = j.x; h->jobs[p * 3 + 1] = j.prev; h->jobs[p * 3 + 2] = j.out;
+        }
+        *out = h;
+        return HAG_OK;
+    } catch (const std::bad_alloc &) {
+        set_error("out of host memory");
+        return HAG_ENOMEM;
+    } catch (const std::exception &ex) {
+        set_error(ex.what());
+        return HAG_EINVAL;
+    }
+}
+
+void hag_seq_free(hag_seq_t *h) {
+    if (!h) return;
+    if (h->d_jobs) (void)hipFree(h->d_jobs);
+    if (h->d_final) (void)hipFree(h->d_final);
+    delete h;
+}
+
+int64_t hag_seq_cells(const hag_seq_t *h) { return h ? (int64_t)(h->jobs.size() / 3) : 0; }
+int64_t hag_seq_ranks(const hag_seq_t *h) { return h ? (int64_t)h->rank_ptr.size() - 1 : 0; }
+int64_t hag_seq_merges(const hag_seq_t *h) { return h ? h->n_merges : 0; }
+
+int hag_seq_upload(hag_seq_t *h) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (h->d_final) return HAG_OK;
+    HIP_TRY(hipGetDevice(&h->device));
+    HIP_TRY(hipMalloc(&h->d_jobs, std::max<size_t>(h->jobs.size(), 1) * sizeof(int32_t)));
+    HIP_TRY(hipMalloc(&h->d_final, std::max<size_t>(h->final_state.size(), 1) * sizeof(int32_t)));
+    if (!h->jobs.empty()) HIP_TRY(hipMemcpy(h->d_jobs, h->jobs.data(), h->jobs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    if (!h->final_state.empty())
+        HIP_TRY(hipMemcpy(h->d_final, h->final_state.data(), h->final_state.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    return HAG_OK;
+}
+
+static int64_t seq_kp(int64_t d, int64_t hidden) { return d + hidden <= 64 ? 64 : 128; }
+
+size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
+    if (!h || d <= 0 || hidden <= 0) return 0;
+    const size_t states = (size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float);
+    const size_t wp = (size_t)4 * hidden * seq_kp(d, hidden) * sizeof(float), bp = (size_t)4 * hidden * sizeof(float);
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    return up(wp) + up(bp) + 2 * up(states);
+}
+
+int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                         const float *b, float *a_out, void *workspace, void *stream) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
+    if (d <= 0 || d % 4 != 0 || hidden <= 0 || hidden % 8 != 0 || hidden > 64 || d + hidden > kSeqMaxK) {
+        set_error("d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+        return HAG_EINVAL;
+    }
+    if (h->n == 0) return HAG_OK;
+    if (!x || !w_ih || !w_hh || !b || !a_out || !workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
+    if (((uintptr_t)x | (uintptr_t)workspace | (uintptr_t)a_out) & 15) { set_error("x, a_out and workspace must be 16-byte aligned"); return HAG_EINVAL; }
+    hipStream_t s = (hipStream_t)stream;
+    const int kp = (int)seq_kp(d, hidden);
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    char *w = (char *)workspace;
+    float *wp = (float *)w; w += up((size_t)4 * hidden * kp * sizeof(float));
+    float *bp = (float *)w; w += up((size_t)4 * hidden * sizeof(float));
+    const size_t states = up((size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float));
+    float *hst = (float *)w; w += states;
+    float *cst = (float *)w;
+    {
+        const int64_t total = (int64_t)4 * hidden * kp;
+        hipLaunchKernelGGL(seq_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w_ih, w_hh, b, wp, bp, (int)d,
+                           (int)hidden, kp);
+        HIP_TRY(hipGetLastError());
+    }
+    const int64_t ranks = (int64_t)h->rank_ptr.size() - 1;
+    for (int64_t t = 0; t < ranks; ++t) {
+        SeqArgs a;
+        a.jobs = h->d_jobs + h->rank_ptr[t] * 3;
+        a.n_jobs = h->rank_ptr[t + 1] - h->rank_ptr[t];
+        a.x = x; a.wp = wp; a.bp = bp; a.h = hst; a.c = cst;
+        a.d = (int32_t)d; a.hidden = (int32_t)hidden; a.kp = kp;
+        if (a.n_jobs <= 0) continue;
+        const int64_t tiles = (a.n_jobs + kSeqJobs - 1) / kSeqJobs;
+        const dim3 grid((unsigned)std::min<int64_t>(tiles, 256 * 2)), block(256);
+        const bool two = hidden > 32;   // gate tiles per wavefront
+        if (kp == 64) {
+            if (two) hipLaunchKernelGGL((seq_lstm_kernel<32, 2>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((seq_lstm_kernel<32, 1>), grid, block, 0, s, a);
+        } else {
+            if (two) hipLaunchKernelGGL((seq_lstm_kernel<64, 2>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((seq_lstm_kernel<64, 1>), grid, block, 0, s, a);
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        const int64_t total = h->n * hidden;
+        hipLaunchKernelGGL(seq_output_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, h->d_final, hst, a_out, h->n,
+                           (int)hidden);
+        HIP_TRY(hipGetLastError());
+    }
+    return HAG_OK;
+}
+
+}  // extern "C"

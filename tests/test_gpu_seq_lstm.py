@@ -1,0 +1,116 @@
+"""GPU parity of the LSTM aggregator over ordered lists (hag_seq_create / hag_seq_lstm_forward) with
+the fp64 oracle (oracle/lstm.py): naive lists and prefix HAGs of several capacities, widths that take
+every kernel variant, empty lists, repeated nodes, a ragged last tile of jobs.
+
+Tolerance: the kernel computes every cell in fp32 (fp32 matrix-core products, fp32 exp/tanh); one cell's
+pre-activations carry a rounding error of at most about (d + H) * 2^-24 * sum|terms| (a few 1e-6 here), the
+gate functions do not amplify it (slopes <= 1) and the state passes it on through the forget gate (< 1), so
+over the chains here (<= 40 cells) the outputs, which lie in (-1, 1), stay within 1e-5 of the oracle (observed: 1e-6)."""
+import numpy as np
+import pytest
+
+from oracle import lstm, sequential
+from paper_1906_03707_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+ATOL = 1e-5
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1906_03707_amd import binding
+    binding.lib()
+    return binding
+
+
+def params(d, hidden, seed, scale=0.4):
+    rng = np.random.default_rng(seed)
+    return (rng.normal(0, scale, (4 * hidden, d)), rng.normal(0, scale, (4 * hidden, hidden)), rng.normal(0, scale, 4 * hidden))
+
+
+def route_graph(n, deg, seed):
+    """Ordered lists with common prefixes, empty lists and repeated nodes."""
+    rng = np.random.default_rng(seed)
+    routes = [rng.permutation(n)[:deg] for _ in range(5)]
+    rowptr, col = [0], []
+    for v in range(n):
+        k = int(rng.integers(0, deg + 1))
+        col += list(routes[int(rng.integers(0, 5))][:k]) + list(rng.integers(0, n, int(rng.integers(0, 4))))
+        rowptr.append(len(col))
+    return np.asarray(rowptr, dtype=np.int64), np.asarray(col, dtype=np.int32)
+
+
+def first_neighbours(rowptr, col, k):
+    """Every list cut to its first k entries (ascending ids: hubs first, so prefixes are shared)."""
+    n = rowptr.size - 1
+    keep = [col[rowptr[v]:min(rowptr[v + 1], rowptr[v] + k)] for v in range(n)]
+    return np.concatenate([[0], np.cumsum([len(x) for x in keep])]).astype(np.int64), np.concatenate(keep).astype(np.int32)
+
+
+def check(B, rowptr, col, d, hidden, seed, capacities):
+    n = rowptr.size - 1
+    w_ih, w_hh, b = params(d, hidden, seed)
+    x = np.random.default_rng(seed + 1).normal(size=(n, d))
+    want, cells_naive = lstm.naive_aggregate(rowptr, col, x, w_ih, w_hh, b)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    xd, wid, whd, bd = dev(x), dev(w_ih), dev(w_hh), dev(b)
+    # the oracle sees the same fp32-rounded inputs
+    want, _ = lstm.naive_aggregate(rowptr, col, xd.cpu().numpy().astype(np.float64), wid.cpu().numpy().astype(np.float64),
+                                   whd.cpu().numpy().astype(np.float64), bd.cpu().numpy().astype(np.float64))
+    worst = 0.0
+    for cap in capacities:
+        h = B.SeqHag(rowptr, col, cap).upload()
+        merges, lists = sequential.search(rowptr, col, cap)
+        if cap == 0:
+            assert h.cells == cells_naive and h.merges == 0
+        else:
+            _, cells = lstm.hag_aggregate(n, merges, lists, x, w_ih, w_hh, b)
+            assert h.merges == len(merges)
+            assert h.cells == cells
+        for rep in range(2):            # the second call reuses the state rows of the first
+            got = h.lstm_forward(xd, wid, whd, bd).cpu().numpy().astype(np.float64)
+            err = np.abs(got - want).max() if got.size else 0.0
+            worst = max(worst, err)
+            assert err <= ATOL, f"cap {cap} d {d} H {hidden}: max |gpu - oracle| = {err}"
+            empty = np.diff(rowptr) == 0
+            assert not got[empty].any()
+    return worst
+
+
+@pytest.mark.parametrize("d,hidden", [(8, 8), (16, 32), (4, 16), (64, 64), (24, 40), (96, 32)])
+def test_route_graph_all_kernel_variants(B, d, hidden):
+    rowptr, col = route_graph(150, 9, seed=d + hidden)
+    check(B, rowptr, col, d, hidden, seed=5, capacities=(0, 7, col.size))
+
+
+def test_power_law_graph_first_neighbours(B):
+    # a Holme-Kim graph, every list cut to its 16 smallest ids: thousands of jobs per rank (several tiles per
+    # workgroup, ragged last tile), deep prefix sharing
+    rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=77)
+    rowptr, col = first_neighbours(rowptr, col, 16)
+    n = rowptr.size - 1
+    worst = check(B, rowptr, col, 32, 32, seed=9, capacities=(0, n // 4, col.size))
+    h0, h1 = B.SeqHag(rowptr, col, 0), B.SeqHag(rowptr, col, col.size)
+    print(f"cells naive {h0.cells} prefix HAG {h1.cells} ({h0.cells / h1.cells:.2f}x fewer), ranks {h0.ranks}/{h1.ranks}, max error {worst:.2e}")
+    assert h1.cells < h0.cells
+
+
+def test_rejections(B):
+    rowptr, col = route_graph(20, 4, seed=3)
+    h = B.SeqHag(rowptr, col, 3)
+    x = torch.zeros((20, 8), device="cuda")
+    w_ih, w_hh, b = torch.zeros((32, 8), device="cuda"), torch.zeros((32, 8), device="cuda"), torch.zeros(32, device="cuda")
+    with pytest.raises(B.HagError):       # before upload
+        h.lstm_forward(x, w_ih, w_hh, b)
+    h.upload()
+    h.lstm_forward(x, w_ih, w_hh, b)
+    with pytest.raises(ValueError):       # wrong shape
+        h.lstm_forward(x[:10].contiguous(), w_ih, w_hh, b)
+    with pytest.raises(B.HagError):       # hidden not a multiple of 8
+        h.lstm_forward(x, torch.zeros((16, 8), device="cuda"), torch.zeros((16, 4), device="cuda"), torch.zeros(16, device="cuda"))
+    with pytest.raises(B.HagError):       # hidden above the kernel's limit
+        h.lstm_forward(x, torch.zeros((512, 8), device="cuda"), torch.zeros((512, 128), device="cuda"), torch.zeros(512, device="cuda"))
