@@ -34,7 +34,7 @@ struct hag_seq {
 
 namespace hag {
 
-constexpr int kSeqJobs = 32;      // jobs per tile
+constexpr int kSeqJobs = 64;      // jobs per tile
 constexpr int kSeqMaxK = 128;     // D + H at most
 
 struct SeqArgs {
@@ -75,113 +75,102 @@ __device__ __forceinline__ float seq_tanh(float z) {
 
 typedef float seq_acc_t __attribute__((ext_vector_type(16)));
 
-// One rank of jobs.  KSTEPS = KP / 2 matrix-core steps per tile; TPW gate tiles (of 8 hidden units)
-// per wavefront, 4 wavefronts per workgroup: hidden <= 32 * TPW.
-template <int KSTEPS, int TPW>
-__global__ __launch_bounds__(256, 2) void seq_lstm_kernel(SeqArgs A) {
+// One rank of jobs.  A workgroup of 8 wavefronts takes tiles of 64 jobs; KSTEPS = KP / 2 matrix-core steps
+// per 32 x 32 product.  WIDE (hidden > 32, up to 8 gate tiles of 8 hidden units): wavefront w holds gate
+// tile w and multiplies it with both halves of the job tile; otherwise (up to 4 gate tiles) wavefront w
+// holds gate tile w % 4 and takes the half w / 4 of the job tile.  Either way a wavefront keeps one gate
+// tile of Wp in registers, so four wavefronts fit a SIMD and the staging and element-wise phases of
+// one hide behind the products of the others.
+template <int KSTEPS, bool WIDE>
+__global__ __launch_bounds__(512, 4) void seq_lstm_kernel(SeqArgs A) {
     constexpr int KP = 2 * KSTEPS, ZS = KP + 2;            // row stride of the staged inputs: even, and 2 banks apart per job
+    constexpr int HS = (WIDE ? 64 : 32) + 1, JG = WIDE ? 2 : 1;
     __shared__ float z[kSeqJobs * ZS];
-    __shared__ float hs[kSeqJobs * (32 * TPW + 1)];   // new h of the tile, [job][unit]
-    __shared__ float cs[kSeqJobs * (32 * TPW + 1)];
-    constexpr int HS = 32 * TPW + 1;
+    __shared__ float hs[kSeqJobs * HS];                    // new h of the tile, [job][unit]
+    __shared__ float cs[kSeqJobs * HS];                    // previous, then new cell state
+    __shared__ __align__(16) float sb[4 * 64];             // packed bias (read from LDS per tile: held in registers it would cost a wavefront per SIMD)
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int hidden = A.hidden, d = A.d, n_tiles = hidden / 8;
-    // this wavefront's slice of the packed weights, in the operand layout of the matrix instruction:
+    const int tile = WIDE ? wave : (wave & 3), group0 = WIDE ? 0 : (wave >> 2);
+    // this wavefront's gate tile of the packed weights, in the operand layout of the matrix instruction:
     // lane l supplies row (l % 32) of the tile and column 2 * step + l / 32
-    float wreg[TPW][KSTEPS];
+    float wreg[KSTEPS];
 #pragma unroll
-    for (int t = 0; t < TPW; ++t) {
-        const int tile = wave * TPW + t;
-#pragma unroll
-        for (int s = 0; s < KSTEPS; ++s)
-            wreg[t][s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
-    }
+    for (int s = 0; s < KSTEPS; ++s)
+        wreg[s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
+    if ((int)threadIdx.x < 4 * hidden) sb[threadIdx.x] = A.bp[threadIdx.x];
     const int64_t n_job_tiles = (A.n_jobs + kSeqJobs - 1) / kSeqJobs;
-    // Staging is done by 8 threads per job, 16 bytes at a time, and runs one tile ahead: the rows of the
-    // next tile are requested before the matrix products of this one and written to LDS after its results
-    // have left, so their latency hides behind the products.  (A job's own state row may be its input and
-    // its output; no other job of the same launch reads or writes it, so reading ahead is safe.)
-    constexpr int ZV = KP / 32, CV = TPW;                  // 16-byte vectors per thread: inputs, previous cell state
+    // Staging is done by 8 threads per job, 16 bytes at a time.  Its latency hides behind the products of the
+    // other wavefronts on the SIMD (reading a tile ahead into registers instead was measured: the registers
+    // it holds cost a wavefront per SIMD, which costs more).
+    constexpr int ZV = KP / 32, CV = WIDE ? 2 : 1;         // 16-byte vectors per thread: inputs, previous cell state
     const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;
-    int in_row = -1, prev = -1, out = -1;
-    float4 zr[ZV], cr[CV];
-    auto fetch = [&](int64_t jt) {
+    for (int64_t jt = blockIdx.x; jt < n_job_tiles; jt += gridDim.x) {
         const int64_t job = jt * kSeqJobs + sj;
-        in_row = prev = out = -1;
-        if (jt < n_job_tiles && job < A.n_jobs) {
-            in_row = A.jobs[job * 3]; prev = A.jobs[job * 3 + 1]; out = A.jobs[job * 3 + 2];
-        }
+        int in_row = -1, prev = -1, out = -1;
+        if (job < A.n_jobs) { in_row = A.jobs[job * 3]; prev = A.jobs[job * 3 + 1]; out = A.jobs[job * 3 + 2]; }
+        {
+            float4 zr[ZV];
 #pragma unroll
-        for (int i = 0; i < ZV; ++i) {
-            const int k = part * 4 + 32 * i;
-            zr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (in_row >= 0) {
-                if (k < d) zr[i] = *reinterpret_cast<const float4 *>(A.x + (size_t)in_row * d + k);
-                else if (k < d + hidden && prev >= 0) zr[i] = *reinterpret_cast<const float4 *>(A.h + (size_t)prev * hidden + (k - d));
+            for (int i = 0; i < ZV; ++i) {
+                const int k = part * 4 + 32 * i;
+                zr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (in_row >= 0) {
+                    if (k < d) zr[i] = *reinterpret_cast<const float4 *>(A.x + (size_t)in_row * d + k);
+                    else if (k < d + hidden && prev >= 0) zr[i] = *reinterpret_cast<const float4 *>(A.h + (size_t)prev * hidden + (k - d));
+                }
+            }
+            // rows of z are only 8-byte aligned: two 8-byte stores per vector
+#pragma unroll
+            for (int i = 0; i < ZV; ++i) {
+                const int k = part * 4 + 32 * i;
+                *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(zr[i].x, zr[i].y);
+                *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(zr[i].z, zr[i].w);
             }
         }
 #pragma unroll
         for (int i = 0; i < CV; ++i) {
             const int u = part * 4 + 32 * i;
-            cr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (in_row >= 0 && prev >= 0 && u < hidden) cr[i] = *reinterpret_cast<const float4 *>(A.c + (size_t)prev * hidden + u);
-        }
-    };
-    fetch(blockIdx.x);
-    for (int64_t jt = blockIdx.x; jt < n_job_tiles; jt += gridDim.x) {
-        // rows of z are only 8-byte aligned: two 8-byte stores per vector
-#pragma unroll
-        for (int i = 0; i < ZV; ++i) {
-            const int k = part * 4 + 32 * i;
-            *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(zr[i].x, zr[i].y);
-            *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(zr[i].z, zr[i].w);
-        }
-#pragma unroll
-        for (int i = 0; i < CV; ++i) {
-            const int u = part * 4 + 32 * i;
-            if (u < hidden) { cs[sj * HS + u] = cr[i].x; cs[sj * HS + u + 1] = cr[i].y; cs[sj * HS + u + 2] = cr[i].z; cs[sj * HS + u + 3] = cr[i].w; }
+            if (u < hidden) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (in_row >= 0 && prev >= 0) v = *reinterpret_cast<const float4 *>(A.c + (size_t)prev * hidden + u);
+                cs[sj * HS + u] = v.x; cs[sj * HS + u + 1] = v.y; cs[sj * HS + u + 2] = v.z; cs[sj * HS + u + 3] = v.w;
+            }
         }
         const int out_now = in_row >= 0 ? out : -1;
         __syncthreads();
-        fetch(jt + gridDim.x);
-        seq_acc_t acc[TPW];
+        // the products start from the bias: register 4 m + gate of a lane belongs to hidden unit 2 m + lane / 32 of the tile
+        seq_acc_t acc[JG];
 #pragma unroll
-        for (int t = 0; t < TPW; ++t)
+        for (int m = 0; m < 4; ++m) {
+            const float4 bias = tile < n_tiles ? *reinterpret_cast<const float4 *>(&sb[(tile * 8 + 2 * m + (lane >> 5)) * 4])
+                                               : make_float4(0.f, 0.f, 0.f, 0.f);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[t][r] = 0.f;
-        // the operand of the step after next is read from LDS before the products of this step are issued
-        const float *zl = &z[(lane & 31) * ZS + (lane >> 5)];
-        float b0 = zl[0], b1 = zl[2];
-#pragma unroll
-        for (int s = 0; s < KSTEPS; s += 2) {
-            const float n0 = s + 2 < KSTEPS ? zl[2 * s + 4] : 0.f, n1 = s + 2 < KSTEPS ? zl[2 * s + 6] : 0.f;
-            __builtin_amdgcn_sched_barrier(0);          // keep the read above the products below
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[t][s], b0, acc[t], 0, 0, 0);
-#pragma unroll
-            for (int t = 0; t < TPW; ++t) acc[t] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[t][s + 1], b1, acc[t], 0, 0, 0);
-            b0 = n0; b1 = n1;
+            for (int g = 0; g < JG; ++g) { acc[g][4 * m] = bias.x; acc[g][4 * m + 1] = bias.y; acc[g][4 * m + 2] = bias.z; acc[g][4 * m + 3] = bias.w; }
         }
-        // element-wise part: lane l holds, for job l % 32, gate rows 8 * (r / 4) + 4 * (l / 32) + r % 4 of each
-        // tile, i.e. the four gates (r % 4) of hidden units 2 * (r / 4) + l / 32 of the tile
-        {
-            const int j = lane & 31;
+        const float *zl = &z[(group0 * 32 + (lane & 31)) * ZS + (lane >> 5)];
 #pragma unroll
-            for (int t = 0; t < TPW; ++t) {
-                const int tile = wave * TPW + t;
-                if (tile < n_tiles) {
+        for (int s = 0; s < KSTEPS; ++s) {
 #pragma unroll
-                    for (int m = 0; m < 4; ++m) {
-                        const int unit = tile * 8 + 2 * m + (lane >> 5);
-                        const float gi = acc[t][4 * m + 0] + A.bp[unit * 4 + 0];
-                        const float gf = acc[t][4 * m + 1] + A.bp[unit * 4 + 1];
-                        const float gg = acc[t][4 * m + 2] + A.bp[unit * 4 + 2];
-                        const float go = acc[t][4 * m + 3] + A.bp[unit * 4 + 3];
-                        const float c_prev = cs[j * HS + unit];   // staged above; this lane is the only one to touch the element
-                        const float c_new = seq_sigmoid(gf) * c_prev + seq_sigmoid(gi) * seq_tanh(gg);
-                        cs[j * HS + unit] = c_new;
-                        hs[j * HS + unit] = seq_sigmoid(go) * seq_tanh(c_new);
-                    }
+            for (int g = 0; g < JG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[s], zl[g * 32 * ZS + 2 * s], acc[g], 0, 0, 0);
+        }
+        // element-wise part: lane l holds, for job l % 32 of its half, gate rows 8 * (r / 4) + 4 * (l / 32) + r % 4 of the
+        // gate tile, i.e. the four gates (r % 4) of hidden units 2 * (r / 4) + l / 32 of the tile
+        if (tile < n_tiles) {
+#pragma unroll
+            for (int g = 0; g < JG; ++g) {
+                const int j = (group0 + g) * 32 + (lane & 31);
+#pragma unroll
+                for (int m = 0; m < 4; ++m) {
+                    const int unit = tile * 8 + 2 * m + (lane >> 5);
+                    const float gi = acc[g][4 * m + 0];
+                    const float gf = acc[g][4 * m + 1];
+                    const float gg = acc[g][4 * m + 2];
+                    const float go = acc[g][4 * m + 3];
+                    const float c_prev = cs[j * HS + unit];   // staged above; this lane is the only one to touch the element
+                    const float c_new = seq_sigmoid(gf) * c_prev + seq_sigmoid(gi) * seq_tanh(gg);
+                    cs[j * HS + unit] = c_new;
+                    hs[j * HS + unit] = seq_sigmoid(go) * seq_tanh(c_new);
                 }
             }
         }
@@ -363,14 +352,14 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
         a.d = (int32_t)d; a.hidden = (int32_t)hidden; a.kp = kp;
         if (a.n_jobs <= 0) continue;
         const int64_t tiles = (a.n_jobs + kSeqJobs - 1) / kSeqJobs;
-        const dim3 grid((unsigned)std::min<int64_t>(tiles, 256 * 2)), block(256);
-        const bool two = hidden > 32;   // gate tiles per wavefront
+        const dim3 grid((unsigned)std::min<int64_t>(tiles, 256 * 2)), block(512);
+        const bool wide = hidden > 32;   // more than four gate tiles
         if (kp == 64) {
-            if (two) hipLaunchKernelGGL((seq_lstm_kernel<32, 2>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((seq_lstm_kernel<32, 1>), grid, block, 0, s, a);
+            if (wide) hipLaunchKernelGGL((seq_lstm_kernel<32, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((seq_lstm_kernel<32, false>), grid, block, 0, s, a);
         } else {
-            if (two) hipLaunchKernelGGL((seq_lstm_kernel<64, 2>), grid, block, 0, s, a);
-            else hipLaunchKernelGGL((seq_lstm_kernel<64, 1>), grid, block, 0, s, a);
+            if (wide) hipLaunchKernelGGL((seq_lstm_kernel<64, true>), grid, block, 0, s, a);
+            else hipLaunchKernelGGL((seq_lstm_kernel<64, false>), grid, block, 0, s, a);
         }
         HIP_TRY(hipGetLastError());
     }

@@ -139,3 +139,30 @@ def test_invalid_input_is_rejected():
         B.hag_seq_search(np.array([0, 2, 1], dtype=np.int64), np.array([0, 1], dtype=np.int32), 1)
     with pytest.raises(B.HagError):
         B.hag_seq_search(np.array([0, 1], dtype=np.int64), np.array([5], dtype=np.int32), 1)
+
+
+def test_lstm_plan_counts_match_the_oracle():
+    # hag_seq_create (host part of the device path): cell evaluations, aggregation nodes and the length of the
+    # longest chain of evaluations, against the oracle's execution of the same prefix HAG
+    from oracle import lstm
+    rng = np.random.default_rng(5)
+    n = 80
+    routes = [rng.permutation(n)[:8] for _ in range(4)]
+    rowptr, col = [0], []
+    for v in range(n):
+        col += list(routes[int(rng.integers(0, 4))][:int(rng.integers(0, 9))]) + list(rng.integers(0, n, int(rng.integers(0, 3))))
+        rowptr.append(len(col))
+    rowptr, col = np.asarray(rowptr, dtype=np.int64), np.asarray(col, dtype=np.int32)
+    x = rng.normal(size=(n, 3))
+    w_ih, w_hh, b = rng.normal(size=(8, 3)), rng.normal(size=(8, 2)), rng.normal(size=8)
+    longest = int(np.diff(rowptr).max())
+    for cap in (0, 3, col.size):
+        plan = B.SeqHag(rowptr, col, cap)
+        merges, lists = S.search(rowptr, col, cap)
+        if cap == 0:
+            assert (plan.cells, plan.merges) == (col.size, 0)
+        else:
+            _, cells = lstm.hag_aggregate(n, merges, lists, x, w_ih, w_hh, b)
+            assert (plan.cells, plan.merges) == (cells, len(merges))
+        # sharing never lengthens a chain: the state after k elements is still k evaluations deep
+        assert plan.ranks == longest
