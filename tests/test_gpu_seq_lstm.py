@@ -114,3 +114,31 @@ def test_rejections(B):
         h.lstm_forward(x, torch.zeros((16, 8), device="cuda"), torch.zeros((16, 4), device="cuda"), torch.zeros(16, device="cuda"))
     with pytest.raises(B.HagError):       # hidden above the kernel's limit
         h.lstm_forward(x, torch.zeros((512, 8), device="cuda"), torch.zeros((512, 128), device="cuda"), torch.zeros(512, device="cuda"))
+
+
+def test_replay_from_a_hip_graph(B):
+    # the pass allocates nothing and records no memset: captured once, replayed with eager work in between, every
+    # replay against the eager result (new inputs each time)
+    rowptr, col = route_graph(400, 9, seed=21)
+    d = hidden = 32
+    w_ih, w_hh, b = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda() for a in params(d, hidden, 13))
+    h = B.SeqHag(rowptr, col, col.size).upload()
+    x = torch.randn((400, d), device="cuda")
+    out = torch.empty((400, hidden), device="cuda")
+    ws = torch.empty(h.workspace_bytes(d, hidden), dtype=torch.uint8, device="cuda")
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        h.lstm_forward(x, w_ih, w_hh, b, out=out, workspace=ws)
+    torch.cuda.current_stream().wait_stream(side)
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        h.lstm_forward(x, w_ih, w_hh, b, out=out, workspace=ws)
+    for rep in range(3):
+        x.copy_(torch.randn((400, d), device="cuda"))
+        want = h.lstm_forward(x, w_ih, w_hh, b).clone()      # eager, its own workspace
+        torch.cuda.synchronize()
+        out.zero_()
+        g.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, want), f"replay {rep}"
