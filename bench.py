@@ -652,6 +652,8 @@ def main():
     if cfg == 3 and not args.no_others and args.capacity < 0 and not args.d and op == "sum":
         out["other_workloads"] = {f"config{c}:{synth.CONFIGS[c]['name']}":
                                   short_workload(torch, binding, synth, workloads, c, 100, 10) for c in (1, 2, 4)}
+        # the sequential Aggregate (LSTM over ordered lists): plain lists against prefix HAGs
+        out["seq_lstm"] = seq_lstm_bench(torch, binding, synth, 4, 16, 64, 64, 20, 3)
     print(json.dumps(out), flush=True)
 
 
