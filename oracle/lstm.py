@@ -84,3 +84,42 @@ def hag_aggregate(n, merges, lists, x, w_ih, w_hh, b):
             cells += 1
         out[v] = h
     return out, cells
+
+
+def naive_aggregate_backward(rowptr, col, x, w_ih, w_hh, b, g_a):
+    """Gradients of L = sum_v <g_a[v], a_v> with respect to x, w_ih, w_hh and b, by backpropagation
+    through time over every list (the chain rule applied to the definition above, list by list).
+    Returns (g_x [n, D], g_w_ih, g_w_hh, g_b)."""
+    n = rowptr.size - 1
+    hidden = w_hh.shape[1]
+    x = np.asarray(x, dtype=np.float64)
+    g_x = np.zeros_like(x)
+    g_w_ih, g_w_hh, g_b = np.zeros_like(w_ih), np.zeros_like(w_hh), np.zeros_like(b)
+    for v in range(n):
+        ids = [int(u) for u in col[rowptr[v]:rowptr[v + 1]]]
+        if not ids:
+            continue
+        # forward, keeping what the backward pass needs
+        h, c = np.zeros(hidden), np.zeros(hidden)
+        tape = []
+        for u in ids:
+            gates = w_ih @ x[u] + w_hh @ h + b
+            i, f, g, o = (gates[k * hidden:(k + 1) * hidden] for k in range(4))
+            i, f, g, o = sigmoid(i), sigmoid(f), np.tanh(g), sigmoid(o)
+            c_new = f * c + i * g
+            tape.append((u, h, c, i, f, g, o, c_new))
+            h, c = o * np.tanh(c_new), c_new
+        d_h, d_c = np.asarray(g_a[v], dtype=np.float64).copy(), np.zeros(hidden)
+        for u, h_prev, c_prev, i, f, g, o, c_new in reversed(tape):
+            t = np.tanh(c_new)
+            d_o = d_h * t
+            d_c = d_c + d_h * o * (1.0 - t * t)
+            d_gates = np.concatenate([d_c * g * i * (1.0 - i), d_c * c_prev * f * (1.0 - f), d_c * i * (1.0 - g * g),
+                                      d_o * o * (1.0 - o)])
+            g_w_ih += np.outer(d_gates, x[u])
+            g_w_hh += np.outer(d_gates, h_prev)
+            g_b += d_gates
+            g_x[u] += w_ih.T @ d_gates
+            d_h = w_hh.T @ d_gates
+            d_c = d_c * f
+    return g_x, g_w_ih, g_w_hh, g_b

@@ -109,3 +109,45 @@ def test_a_planted_mistake_in_the_hag_is_seen():
     bad = [(m[1], m[0], m[2]) if i == 0 else m for i, m in enumerate(merges)]
     got, _ = lstm.hag_aggregate(n, bad, lists, x, w_ih, w_hh, b)
     assert np.abs(got - naive).max() > 1e-6
+
+
+def test_backward_against_autograd_of_a_library_lstm_and_finite_differences():
+    torch = pytest.importorskip("torch")
+    d, hidden, n = 4, 3, 7
+    w_ih, w_hh, b = params(d, hidden, 31)
+    rng = np.random.default_rng(32)
+    x = rng.normal(size=(n, d))
+    g_a = rng.normal(size=(n, hidden))
+    rowptr = np.array([0, 3, 3, 5, 9, 10, 12, 12], dtype=np.int64)
+    col = np.array([2, 0, 1, 4, 4, 6, 5, 0, 2, 3, 1, 1], dtype=np.int32)       # repeated nodes, empty lists
+    g_x, g_wi, g_wh, g_b = lstm.naive_aggregate_backward(rowptr, col, x, w_ih, w_hh, b, g_a)
+    # the library's LSTM run list by list, differentiated by the library
+    xt = torch.from_numpy(x).requires_grad_(True)
+    net = torch.nn.LSTM(d, hidden, batch_first=True).double()
+    with torch.no_grad():
+        net.weight_ih_l0.copy_(torch.from_numpy(w_ih)); net.weight_hh_l0.copy_(torch.from_numpy(w_hh))
+        net.bias_ih_l0.copy_(torch.from_numpy(b)); net.bias_hh_l0.zero_()
+    loss = 0.0
+    for v in range(n):
+        ids = col[rowptr[v]:rowptr[v + 1]]
+        if ids.size:
+            _, (h, _) = net(xt[torch.from_numpy(ids.astype(np.int64))][None])
+            loss = loss + (h[0, 0] * torch.from_numpy(g_a[v])).sum()
+    loss.backward()
+    np.testing.assert_allclose(g_x, xt.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g_wi, net.weight_ih_l0.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g_wh, net.weight_hh_l0.grad.numpy(), rtol=1e-10, atol=1e-12)
+    np.testing.assert_allclose(g_b, net.bias_ih_l0.grad.numpy(), rtol=1e-10, atol=1e-12)
+    # and a finite difference of the oracle's own forward pass in one direction of every argument
+    def loss_of(x_, wi_, wh_, b_):
+        a, _ = lstm.naive_aggregate(rowptr, col, x_, wi_, wh_, b_)
+        return float((a * g_a).sum())
+    eps = 1e-6
+    for arg, grad in ((0, g_x), (1, g_wi), (2, g_wh), (3, g_b)):
+        args = [x, w_ih, w_hh, b]
+        direction = rng.normal(size=args[arg].shape)
+        plus, minus = list(args), list(args)
+        plus[arg] = args[arg] + eps * direction
+        minus[arg] = args[arg] - eps * direction
+        fd = (loss_of(*plus) - loss_of(*minus)) / (2 * eps)
+        assert abs(fd - float((grad * direction).sum())) <= 1e-6 * max(1.0, abs(fd))
