@@ -353,11 +353,11 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         else:
             (ms, _), (ms_base, _) = time_interleaved(torch, fn, base, steps, warmup)
         tf = p.cells * flops_per_cell / (ms * 1e-3) / 1e12
-        res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.ranks, "ms_per_pass": ms,
+        res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.launches, "longest_chain": p.ranks, "ms_per_pass": ms,
                               "lists_ms_per_pass": ms_base, "speedup_vs_lists": ms_base / ms,
                               "cells_fewer": plans["lists"].cells / max(p.cells, 1), "tflops": tf,
                               "frac_of_fp32_matrix_peak": tf / FP32_MFMA_PEAK_TFLOPS, "frac_of_measured_ceiling": tf / mfma_ceiling}
-        log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.ranks} launches, "
+        log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.launches} launches, "
             f"{ms:.3f} ms per pass ({ms_base / ms:.2f}x the plain lists' speed), {tf:.1f} TFLOP/s = "
             f"{100 * tf / FP32_MFMA_PEAK_TFLOPS:.1f}% of the fp32 matrix-core peak")
     return res

@@ -164,18 +164,20 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * Equation 2's ordered cover, or the one-element prefix a list or a merge starts from) is evaluated once,
  * then every node continues from the state of its list's head; capacity = 0 plans the plain lists with
  * nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
- * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: dependent launches of one pass (the longest
- * chain of evaluations); hag_seq_merges: aggregation nodes.  hag_seq_upload copies the plan to the current
- * device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
+ * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: the longest chain of dependent evaluations;
+ * hag_seq_launches: cell-kernel launches of one pass (one per depth of the SHARED prefixes, plus one that
+ * walks every node's private remainder with the running state held on chip); hag_seq_merges: aggregation
+ * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
  * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
  * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights and one (h, c) state row per
- * shared prefix and per node).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
+ * shared prefix).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
  * `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload, HAG_EINVAL otherwise. */
 typedef struct hag_seq hag_seq_t;
 int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out);
 void hag_seq_free(hag_seq_t *h);
 int64_t hag_seq_cells(const hag_seq_t *h);
 int64_t hag_seq_ranks(const hag_seq_t *h);
+int64_t hag_seq_launches(const hag_seq_t *h);
 int64_t hag_seq_merges(const hag_seq_t *h);
 int hag_seq_upload(hag_seq_t *h);
 size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);

@@ -30,7 +30,7 @@ EXPORTS = [
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
     "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_probe_mfma_f32", "hag_set_option", "hag_check", "hag_seq_search",
-    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
+    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
     "hag_seq_lstm_forward",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
@@ -92,7 +92,7 @@ def lib():
         L.hag_seq_create.argtypes = [i64, vp, vp, i64, ctypes.POINTER(vp)]
         L.hag_seq_free.argtypes = [vp]
         L.hag_seq_free.restype = None
-        for name in ("hag_seq_cells", "hag_seq_ranks", "hag_seq_merges"):
+        for name in ("hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_merges"):
             getattr(L, name).argtypes = [vp]
             getattr(L, name).restype = i64
         L.hag_seq_upload.argtypes = [vp]
@@ -390,6 +390,10 @@ class SeqHag:
     @property
     def ranks(self) -> int:
         return int(lib().hag_seq_ranks(self._h))
+
+    @property
+    def launches(self) -> int:
+        return int(lib().hag_seq_launches(self._h))
 
     @property
     def merges(self) -> int:

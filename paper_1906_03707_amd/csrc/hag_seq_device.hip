@@ -27,8 +27,12 @@ struct hag_seq {
     int64_t n = 0, e = 0, n_merges = 0, n_states = 0;
     std::vector<int32_t> jobs;        // 3 per job: input row, previous state (-1: none), written state
     std::vector<int64_t> rank_ptr;    // jobs of rank t: [rank_ptr[t], rank_ptr[t+1])
-    std::vector<int32_t> final_state; // per node: state row holding a_v, -1 for an empty list
-    int32_t *d_jobs = nullptr, *d_final = nullptr;
+    std::vector<int32_t> final_state; // per node: state row holding a_v, -1 for an empty list, -2: written by its chain
+    // the private part of every node's walk (what follows the shared state of its list's head): 4 per chain,
+    // (state it starts from or -1, first entry in `chain_col`, entries, node), longest first
+    std::vector<int32_t> chains, chain_col;
+    int64_t chain_cells = 0, longest = 0;
+    int32_t *d_jobs = nullptr, *d_final = nullptr, *d_chains = nullptr, *d_chain_col = nullptr;
     int device = -1;
 };
 
@@ -187,12 +191,161 @@ __global__ __launch_bounds__(512, 4) void seq_lstm_kernel(SeqArgs A) {
     }
 }
 
+struct SeqChainArgs {
+    const int32_t *chains;   // 4 per chain, longest first
+    int64_t n_chains;
+    const int32_t *col;      // the chains' input rows
+    const float *x, *wp, *bp;
+    const float *h, *c;      // states of the shared prefixes (read only here)
+    float *a_out;            // [n, H]
+    int32_t d, hidden;
+};
+
+// The private part of every node's walk, 64 nodes per workgroup tile, ALL its steps in one launch: the
+// running states never leave the compute unit (h in the staged operand rows, c beside them in LDS), so
+// a cell costs one input row of global traffic instead of reading and writing both state rows as well.
+// Chains are sorted by length, so the chains of a tile end within a step or two of each other; a chain
+// that has ended keeps its state while the others finish.  Same tiling of the products as above.
+// Hides a value's origin from the optimiser, so that what is derived from it is computed where it is used
+// instead of being held in a register across the products.
+__device__ __forceinline__ int seq_opaque(int v) { asm volatile("" : "+v"(v)); return v; }
+
+template <int KSTEPS, bool WIDE>
+__global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
+    constexpr int KP = 2 * KSTEPS, ZS = KP + 2;
+    constexpr int HS = (WIDE ? 64 : 32) + 1, JG = WIDE ? 2 : 1;
+    __shared__ float z[kSeqJobs * ZS];
+    __shared__ float hs[kSeqJobs * HS];
+    __shared__ float cs[kSeqJobs * HS];
+    __shared__ __align__(16) float sb[4 * 64];
+    __shared__ int32_t sdesc[kSeqJobs * 4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int hidden = A.hidden, d = A.d, n_tiles = hidden / 8;
+    const int tile = WIDE ? wave : (wave & 3), group0 = WIDE ? 0 : (wave >> 2);
+    float wreg[KSTEPS];
+#pragma unroll
+    for (int s = 0; s < KSTEPS; ++s)
+        wreg[s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
+    if ((int)threadIdx.x < 4 * hidden) sb[threadIdx.x] = A.bp[threadIdx.x];
+    constexpr int ZV = KP / 32;
+    const int64_t n_chain_tiles = (A.n_chains + kSeqJobs - 1) / kSeqJobs;
+    for (int64_t ct = blockIdx.x; ct < n_chain_tiles; ct += gridDim.x) {
+        if (threadIdx.x < kSeqJobs * 4) {
+            const int64_t ch = ct * kSeqJobs + threadIdx.x / 4;
+            sdesc[threadIdx.x] = ch < A.n_chains ? A.chains[ch * 4 + threadIdx.x % 4] : ((threadIdx.x & 3) == 2 ? 0 : -1);
+        }
+        __syncthreads();
+        // (thread indices are derived again in every phase, and the descriptor is re-read from LDS where it is needed rather than held in registers, which are short)
+        const int steps = sdesc[2];                        // the tile's first chain is its longest
+        // the state the chain starts from, the first input row, zero padding
+        {
+            const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+            const int start = sdesc[sj * 4], beg = sdesc[sj * 4 + 1], len = sdesc[sj * 4 + 2];
+            const int row0 = len > 0 ? A.col[beg] : -1;
+#pragma unroll 1                                           // (one vector in flight: this runs once per tile, and registers are short)
+            for (int i = 0; i < ZV; ++i) {
+                const int k = part * 4 + 32 * i;
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < d) { if (row0 >= 0) v = *reinterpret_cast<const float4 *>(A.x + (size_t)row0 * d + k); }
+                else if (k < d + hidden && start >= 0) v = *reinterpret_cast<const float4 *>(A.h + (size_t)start * hidden + (k - d));
+                *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(v.x, v.y);
+                *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(v.z, v.w);
+            }
+            for (int u = part * 4; u < hidden; u += 32) {
+                float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (start >= 0) v = *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
+                cs[sj * HS + u] = v.x; cs[sj * HS + u + 1] = v.y; cs[sj * HS + u + 2] = v.z; cs[sj * HS + u + 3] = v.w;
+            }
+        }
+        __syncthreads();
+        for (int t = 0; t < steps; ++t) {
+            // the next step's input row is requested before this step's products and lands in LDS after them
+            // (its first 64 columns, that is: holding more across the products would spill registers)
+            constexpr int ZE = ZV < 2 ? ZV : 2;
+            float4 xr[ZE];
+            const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+            const int len = sdesc[sj * 4 + 2];
+            const int row1 = t + 1 < len ? A.col[sdesc[sj * 4 + 1] + t + 1] : -1;
+#pragma unroll
+            for (int i = 0; i < ZE; ++i) {
+                const int k = part * 4 + 32 * i;
+                xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
+                if (k < d && row1 >= 0) xr[i] = *reinterpret_cast<const float4 *>(A.x + (size_t)row1 * d + k);
+            }
+            seq_acc_t acc[JG];
+#pragma unroll
+            for (int m = 0; m < 4; ++m) {
+                const float4 bias = tile < n_tiles ? *reinterpret_cast<const float4 *>(&sb[(tile * 8 + 2 * m + (lane >> 5)) * 4])
+                                                   : make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+                for (int g = 0; g < JG; ++g) { acc[g][4 * m] = bias.x; acc[g][4 * m + 1] = bias.y; acc[g][4 * m + 2] = bias.z; acc[g][4 * m + 3] = bias.w; }
+            }
+            const float *zl = &z[(group0 * 32 + (lane & 31)) * ZS + (lane >> 5)];
+#pragma unroll
+            for (int s = 0; s < KSTEPS; ++s) {
+#pragma unroll
+                for (int g = 0; g < JG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[s], zl[g * 32 * ZS + 2 * s], acc[g], 0, 0, 0);
+            }
+            if (tile < n_tiles) {
+#pragma unroll
+                for (int g = 0; g < JG; ++g) {
+                    const int j = (group0 + g) * 32 + (lane & 31);
+                    if (t < sdesc[j * 4 + 2]) {
+#pragma unroll
+                        for (int m = 0; m < 4; ++m) {
+                            const int unit = tile * 8 + 2 * m + (lane >> 5);
+                            const float c_new = seq_sigmoid(acc[g][4 * m + 1]) * cs[j * HS + unit] +
+                                                seq_sigmoid(acc[g][4 * m + 0]) * seq_tanh(acc[g][4 * m + 2]);
+                            cs[j * HS + unit] = c_new;
+                            hs[j * HS + unit] = seq_sigmoid(acc[g][4 * m + 3]) * seq_tanh(c_new);
+                        }
+                    }
+                }
+            }
+            __syncthreads();                               // every product has read z, every new h is in hs
+            {
+                const int tid2 = seq_opaque(threadIdx.x), sj2 = tid2 >> 3, part2 = tid2 & 7;
+                if (t < sdesc[sj2 * 4 + 2]) {
+                    for (int u = part2 * 4; u < hidden; u += 32) {
+                        const float *ph = &hs[sj2 * HS + u];
+                        *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u]) = make_float2(ph[0], ph[1]);
+                        *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u + 2]) = make_float2(ph[2], ph[3]);
+                    }
+                }
+                if (row1 >= 0) {
+#pragma unroll
+                    for (int i = 0; i < ZV; ++i) {
+                        const int k = part2 * 4 + 32 * i;
+                        if (k < d) {
+                            const float4 v = i < ZE ? xr[i < ZE ? i : 0] : *reinterpret_cast<const float4 *>(A.x + (size_t)row1 * d + k);
+                            *reinterpret_cast<float2 *>(&z[sj2 * ZS + k]) = make_float2(v.x, v.y);
+                            *reinterpret_cast<float2 *>(&z[sj2 * ZS + k + 2]) = make_float2(v.z, v.w);
+                        }
+                    }
+                }
+            }
+            __syncthreads();
+        }
+        // a_v = the last h of the chain
+        const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+        const int node = sdesc[sj * 4 + 3];
+        if (node >= 0) {
+            for (int u = part * 4; u < hidden; u += 32) {
+                const float *ph = &z[sj * ZS + d + u];
+                *reinterpret_cast<float4 *>(A.a_out + (size_t)node * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
+            }
+        }
+        __syncthreads();
+    }
+}
+
 __global__ __launch_bounds__(256) void seq_output_kernel(const int32_t *__restrict__ final_state, const float *__restrict__ h,
                                                         float *__restrict__ out, int64_t n, int hidden) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= n * hidden) return;
     const int64_t v = i / hidden;
     const int s = final_state[v];
+    if (s == -2) return;                                   // written by the node's chain
     out[i] = s >= 0 ? h[(size_t)s * hidden + (i % hidden)] : 0.f;
 }
 
@@ -232,9 +385,9 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
             for (int64_t v = 0; v < n; ++v)
                 if (hrowptr[v + 1] > hrowptr[v] && hcol[hrowptr[v]] < n) need_first(hcol[hrowptr[v]]);
         }
-        const int32_t agg0 = n_first, run0 = (int32_t)(n_first + a);
-        h->n_states = (int64_t)run0 + n;
-        std::vector<int32_t> rank_of_state((size_t)h->n_states, 0);
+        const int32_t agg0 = n_first;
+        h->n_states = (int64_t)n_first + a;
+        std::vector<int32_t> rank_of_state((size_t)std::max<int64_t>(h->n_states, 1), 0);
         struct J { int32_t x, prev, out, rank; };
         std::vector<J> js;
         js.reserve((size_t)(e + n_first));
@@ -248,20 +401,24 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
             js.push_back(J{right[i], prev, out_s, r});
         }
         h->final_state.assign(n, -1);
+        struct C { int32_t start, beg, len, node; };
+        std::vector<C> cs;
         for (int64_t v = 0; v < n; ++v) {
             const int64_t b0 = hrowptr[v], b1 = hrowptr[v + 1];
             if (b1 == b0) continue;
-            const int32_t mine = run0 + (int32_t)v;
-            int32_t cur, r;
+            int32_t cur = -1, depth = 0;
             int64_t i = b0;
-            if (share) { cur = state_of(hcol[b0]); r = rank_of_state[cur]; i = b0 + 1; }
-            else { cur = -1; r = -1; }
-            for (; i < b1; ++i) {
-                js.push_back(J{hcol[i], cur, mine, ++r});
-                cur = mine;
-            }
-            h->final_state[v] = cur;
+            if (share) { cur = state_of(hcol[b0]); depth = rank_of_state[cur] + 1; i = b0 + 1; }
+            if (i == b1) { h->final_state[v] = cur; h->longest = std::max<int64_t>(h->longest, depth); continue; }
+            cs.push_back(C{cur, (int32_t)i, (int32_t)(b1 - i), (int32_t)v});
+            h->final_state[v] = -2;
+            h->chain_cells += b1 - i;
+            h->longest = std::max<int64_t>(h->longest, depth + (b1 - i));
         }
+        std::stable_sort(cs.begin(), cs.end(), [](const C &p, const C &q) { return p.len > q.len; });
+        h->chains.reserve(cs.size() * 4);
+        for (const C &c : cs) { h->chains.push_back(c.start); h->chains.push_back(c.beg); h->chains.push_back(c.len); h->chains.push_back(c.node); }
+        h->chain_col.assign(hcol.begin(), hcol.begin() + (size_t)hrowptr[n]);
         int32_t ranks = 0;
         for (const J &j : js) ranks = std::max(ranks, j.rank + 1);
         h->rank_ptr.assign((size_t)ranks + 1, 0);
@@ -288,11 +445,14 @@ void hag_seq_free(hag_seq_t *h) {
     if (!h) return;
     if (h->d_jobs) (void)hipFree(h->d_jobs);
     if (h->d_final) (void)hipFree(h->d_final);
+    if (h->d_chains) (void)hipFree(h->d_chains);
+    if (h->d_chain_col) (void)hipFree(h->d_chain_col);
     delete h;
 }
 
-int64_t hag_seq_cells(const hag_seq_t *h) { return h ? (int64_t)(h->jobs.size() / 3) : 0; }
-int64_t hag_seq_ranks(const hag_seq_t *h) { return h ? (int64_t)h->rank_ptr.size() - 1 : 0; }
+int64_t hag_seq_cells(const hag_seq_t *h) { return h ? (int64_t)(h->jobs.size() / 3) + h->chain_cells : 0; }
+int64_t hag_seq_ranks(const hag_seq_t *h) { return h ? h->longest : 0; }
+int64_t hag_seq_launches(const hag_seq_t *h) { return h ? (int64_t)h->rank_ptr.size() - 1 + (h->chains.empty() ? 0 : 1) : 0; }
 int64_t hag_seq_merges(const hag_seq_t *h) { return h ? h->n_merges : 0; }
 
 int hag_seq_upload(hag_seq_t *h) {
@@ -304,6 +464,11 @@ int hag_seq_upload(hag_seq_t *h) {
     if (!h->jobs.empty()) HIP_TRY(hipMemcpy(h->d_jobs, h->jobs.data(), h->jobs.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     if (!h->final_state.empty())
         HIP_TRY(hipMemcpy(h->d_final, h->final_state.data(), h->final_state.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    HIP_TRY(hipMalloc(&h->d_chains, std::max<size_t>(h->chains.size(), 1) * sizeof(int32_t)));
+    HIP_TRY(hipMalloc(&h->d_chain_col, std::max<size_t>(h->chain_col.size(), 1) * sizeof(int32_t)));
+    if (!h->chains.empty()) HIP_TRY(hipMemcpy(h->d_chains, h->chains.data(), h->chains.size() * sizeof(int32_t), hipMemcpyHostToDevice));
+    if (!h->chain_col.empty())
+        HIP_TRY(hipMemcpy(h->d_chain_col, h->chain_col.data(), h->chain_col.size() * sizeof(int32_t), hipMemcpyHostToDevice));
     return HAG_OK;
 }
 
@@ -360,6 +525,23 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
         } else {
             if (wide) hipLaunchKernelGGL((seq_lstm_kernel<64, true>), grid, block, 0, s, a);
             else hipLaunchKernelGGL((seq_lstm_kernel<64, false>), grid, block, 0, s, a);
+        }
+        HIP_TRY(hipGetLastError());
+    }
+    if (!h->chains.empty()) {
+        SeqChainArgs c;
+        c.chains = h->d_chains; c.n_chains = (int64_t)(h->chains.size() / 4); c.col = h->d_chain_col;
+        c.x = x; c.wp = wp; c.bp = bp; c.h = hst; c.c = cst; c.a_out = a_out;
+        c.d = (int32_t)d; c.hidden = (int32_t)hidden;
+        const int64_t tiles = (c.n_chains + kSeqJobs - 1) / kSeqJobs;
+        const dim3 grid((unsigned)std::min<int64_t>(tiles, 256 * 2)), block(512);
+        const bool wide = hidden > 32;
+        if (kp == 64) {
+            if (wide) hipLaunchKernelGGL((seq_chain_kernel<32, true>), grid, block, 0, s, c);
+            else hipLaunchKernelGGL((seq_chain_kernel<32, false>), grid, block, 0, s, c);
+        } else {
+            if (wide) hipLaunchKernelGGL((seq_chain_kernel<64, true>), grid, block, 0, s, c);
+            else hipLaunchKernelGGL((seq_chain_kernel<64, false>), grid, block, 0, s, c);
         }
         HIP_TRY(hipGetLastError());
     }

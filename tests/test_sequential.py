@@ -166,3 +166,8 @@ def test_lstm_plan_counts_match_the_oracle():
             assert (plan.cells, plan.merges) == (cells, len(merges))
         # sharing never lengthens a chain: the state after k elements is still k evaluations deep
         assert plan.ranks == longest
+        # one launch per depth of the shared prefixes, one more for the private remainders
+        private = any(len(l) > (1 if cap else 0) for l in lists)
+        assert plan.launches >= int(private) and plan.launches <= longest + 1
+        if cap == 0:
+            assert plan.launches == 1
