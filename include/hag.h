@@ -160,13 +160,12 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * (a_v = 0 for an empty list), cell = the standard LSTM step: gates = w_ih x + w_hh h + b split into
  * input, forget, cell and output gate, c' = sigmoid(f) c + sigmoid(i) tanh(g), h' = sigmoid(o) tanh(c').
  * hag_seq_create (host): capacity > 0 runs hag_seq_search with that capacity and plans the evaluation of
- * the resulting prefix HAG in the order of Algorithm 2 -- every shared prefix (an aggregation node of
- * Equation 2's ordered cover, or the one-element prefix a list or a merge starts from) is evaluated once,
- * then every node continues from the state of its list's head; capacity = 0 plans the plain lists with
+ * the resulting prefix HAG respecting the order of Algorithm 2 -- every shared prefix (an aggregation node
+ * of Equation 2's ordered cover, or the one-element prefix a list or a merge starts from) is evaluated once,
+ * before whatever continues from it, and every node continues from the state of its list's head; capacity = 0 plans the plain lists with
  * nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
  * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: the longest chain of dependent evaluations;
- * hag_seq_launches: cell-kernel launches of one pass (one per depth of the SHARED prefixes, plus one that
- * walks every node's private remainder with the running state held on chip); hag_seq_merges: aggregation
+ * hag_seq_launches: cell-kernel launches of one pass (the levels of hag_seq_get_plan); hag_seq_merges: aggregation
  * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
  * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
  * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights and one (h, c) state row per
@@ -179,6 +178,16 @@ int64_t hag_seq_cells(const hag_seq_t *h);
 int64_t hag_seq_ranks(const hag_seq_t *h);
 int64_t hag_seq_launches(const hag_seq_t *h);
 int64_t hag_seq_merges(const hag_seq_t *h);
+/* The plan as the device executes it (host arrays owned by the handle, valid until hag_seq_free; any out
+ * pointer may be NULL): the shared prefixes and the nodes' remainders cut into PATHS -- a path carries its
+ * running (h, c) from step to step on chip -- grouped into levels, one launch each, a path starting from a
+ * state that a lower level wrote.  paths [4 * n_paths]: (state row it starts from or -1 for the zero
+ * state, first step, steps, node whose a_v is its last h or -1), level by level, longest first;
+ * level_ptr [n_levels + 1] in paths; step_x / step_out [hag_seq_cells]: per step the input row and the
+ * state row the step's (h, c) is written to or -1; final_state [n]: the state row holding a_v, -1 for an
+ * empty list, -2 where a path writes a_v itself. */
+int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
+                     const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr, const int32_t **final_state);
 int hag_seq_upload(hag_seq_t *h);
 size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
 int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,

@@ -30,7 +30,7 @@ EXPORTS = [
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
     "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_probe_mfma_f32", "hag_set_option", "hag_check", "hag_seq_search",
-    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
+    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_get_plan", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
     "hag_seq_lstm_forward",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
@@ -96,6 +96,7 @@ def lib():
             getattr(L, name).argtypes = [vp]
             getattr(L, name).restype = i64
         L.hag_seq_upload.argtypes = [vp]
+        L.hag_seq_get_plan.argtypes = [vp] + [vp] * 8
         L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
         L.hag_seq_workspace_bytes.restype = ctypes.c_size_t
         L.hag_seq_lstm_forward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
@@ -398,6 +399,18 @@ class SeqHag:
     @property
     def merges(self) -> int:
         return int(lib().hag_seq_merges(self._h))
+
+    def plan(self):
+        """(n_states, paths [n_paths, 4], step_x, step_out, level_ptr, final_state) as copies (hag_seq_get_plan)."""
+        i64, p32, p64 = ctypes.c_int64, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
+        ns, npaths, nl = i64(), i64(), i64()
+        paths, sx, so, fs, lp = p32(), p32(), p32(), p32(), p64()
+        _check(lib().hag_seq_get_plan(self._h, ctypes.byref(ns), ctypes.byref(npaths), ctypes.byref(paths), ctypes.byref(sx),
+                                      ctypes.byref(so), ctypes.byref(nl), ctypes.byref(lp), ctypes.byref(fs)))
+        take = lambda ptr, count, dt: (np.ctypeslib.as_array(ptr, shape=(count,)).astype(dt, copy=True) if count else np.zeros(0, dt))
+        cells = self.cells
+        return (ns.value, take(paths, 4 * npaths.value, np.int32).reshape(-1, 4), take(sx, cells, np.int32), take(so, cells, np.int32),
+                take(lp, nl.value + 1, np.int64), take(fs, self.n, np.int32))
 
     def upload(self):
         _check(lib().hag_seq_upload(self._h))

@@ -6,6 +6,7 @@ import os
 import numpy as np
 import pytest
 
+from oracle import lstm
 from oracle import sequential as S
 from paper_1906_03707_amd import binding as B
 
@@ -144,7 +145,6 @@ def test_invalid_input_is_rejected():
 def test_lstm_plan_counts_match_the_oracle():
     # hag_seq_create (host part of the device path): cell evaluations, aggregation nodes and the length of the
     # longest chain of evaluations, against the oracle's execution of the same prefix HAG
-    from oracle import lstm
     rng = np.random.default_rng(5)
     n = 80
     routes = [rng.permutation(n)[:8] for _ in range(4)]
@@ -171,3 +171,67 @@ def test_lstm_plan_counts_match_the_oracle():
         assert plan.launches >= int(private) and plan.launches <= longest + 1
         if cap == 0:
             assert plan.launches == 1
+
+
+def replay_plan(plan, n, x, w_ih, w_hh, b):
+    """The plan of hag_seq_create executed step by step with the oracle's cell, one level after the other, checking
+    on the way what the device relies on: a path starts only from a state that a LOWER level has written, every
+    state row is written at most once, paths of a level are sorted by length."""
+    n_states, paths, step_x, step_out, level_ptr, final_state = plan.plan()
+    hidden = w_hh.shape[1]
+    h_rows, c_rows = np.full((max(n_states, 1), hidden), np.nan), np.full((max(n_states, 1), hidden), np.nan)
+    written_at = np.full(max(n_states, 1), -1)
+    out = np.zeros((n, hidden))
+    by_path = np.zeros(n, dtype=bool)
+    assert level_ptr[0] == 0 and level_ptr[-1] == len(paths)
+    for level in range(len(level_ptr) - 1):
+        lens = paths[level_ptr[level]:level_ptr[level + 1], 2]
+        assert (np.diff(lens) <= 0).all() and (lens >= 1).all()
+        for start, beg, length, node in paths[level_ptr[level]:level_ptr[level + 1]]:
+            if start >= 0:
+                assert 0 <= written_at[start] < level
+                h, c = h_rows[start], c_rows[start]
+            else:
+                h, c = np.zeros(hidden), np.zeros(hidden)
+            for t in range(beg, beg + length):
+                assert 0 <= step_x[t] < n
+                h, c = lstm.cell(x[step_x[t]], h, c, w_ih, w_hh, b)
+                if step_out[t] >= 0:
+                    assert written_at[step_out[t]] < 0
+                    written_at[step_out[t]] = level
+                    h_rows[step_out[t]], c_rows[step_out[t]] = h, c
+            if node >= 0:
+                assert final_state[node] == -2 and not by_path[node]
+                by_path[node] = True
+                out[node] = h
+    for v in range(n):
+        if final_state[v] >= 0:
+            assert written_at[final_state[v]] >= 0
+            out[v] = h_rows[final_state[v]]
+        else:
+            assert (final_state[v] == -2) == by_path[v]
+    return out, int(paths[:, 2].sum()), int((step_out >= 0).sum())
+
+
+@pytest.mark.parametrize("seed", [5, 6, 7])
+def test_lstm_plan_replayed_on_the_host_equals_the_naive_walk(seed):
+    rng = np.random.default_rng(seed)
+    n = 90
+    routes = [rng.permutation(n)[:9] for _ in range(5)]
+    rowptr, col = [0], []
+    for v in range(n):
+        col += list(routes[int(rng.integers(0, 5))][:int(rng.integers(0, 10))]) + list(rng.integers(0, n, int(rng.integers(0, 4))))
+        rowptr.append(len(col))
+    rowptr, col = np.asarray(rowptr, dtype=np.int64), np.asarray(col, dtype=np.int32)
+    x = rng.normal(size=(n, 3))
+    w_ih, w_hh, b = rng.normal(0, 0.5, (8, 3)), rng.normal(0, 0.5, (8, 2)), rng.normal(0, 0.5, 8)
+    want, _ = lstm.naive_aggregate(rowptr, col, x, w_ih, w_hh, b)
+    for cap in (0, 4, col.size):
+        plan = B.SeqHag(rowptr, col, cap)
+        got, cells, kept = replay_plan(plan, n, x, w_ih, w_hh, b)
+        assert np.array_equal(got, want)                  # the same cells in the same order along every list
+        assert cells == plan.cells
+        if cap == 0:
+            assert kept == 0 and plan.launches == (1 if col.size else 0)
+        else:
+            assert kept < plan.cells                      # most states never leave the path that computes them
