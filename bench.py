@@ -353,7 +353,7 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         else:
             (ms, _), (ms_base, _) = time_interleaved(torch, fn, base, steps, warmup)
         tf = p.cells * flops_per_cell / (ms * 1e-3) / 1e12
-        res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.launches, "longest_chain": p.ranks, "ms_per_pass": ms,
+        res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.launches, "levels": int(p.plan()[4].size - 1), "longest_chain": p.ranks, "ms_per_pass": ms,
                               "lists_ms_per_pass": ms_base, "speedup_vs_lists": ms_base / ms,
                               "cells_fewer": plans["lists"].cells / max(p.cells, 1), "tflops": tf,
                               "frac_of_fp32_matrix_peak": tf / FP32_MFMA_PEAK_TFLOPS, "frac_of_measured_ceiling": tf / mfma_ceiling}

@@ -168,8 +168,8 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * hag_seq_launches: cell-kernel launches of one pass (the levels of hag_seq_get_plan); hag_seq_merges: aggregation
  * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
  * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
- * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights and one (h, c) state row per
- * shared prefix).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
+ * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights, one (h, c) state row and one flag
+ * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
  * `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload, HAG_EINVAL otherwise. */
 typedef struct hag_seq hag_seq_t;
 int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out);
@@ -189,6 +189,16 @@ int64_t hag_seq_merges(const hag_seq_t *h);
 int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
                      const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr, const int32_t **final_state);
 int hag_seq_upload(hag_seq_t *h);
+/* With more than one level, hag_seq_lstm_forward runs all of them in ONE launch when every workgroup of it
+ * can be resident at once: a tile of paths waits (polling a per-state flag, at most HAG_OPT_SPIN_LIMIT times,
+ * default 2^21, about half a microsecond apart) until the states it starts from are written, by tiles that come
+ * before it and never wait for it.  hag_seq_set_option (host state only; later calls): HAG_OPT_SEQ_ONE_LAUNCH
+ * (default 1, or the environment's HAG_SEQ_ONE_LAUNCH when the handle was built; 0 = one launch per level, no
+ * waits), HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE (tests only: no flag is ever set, so every wait
+ * gives up).  hag_seq_check synchronises `stream` and returns HAG_OK, or HAG_ETIMEOUT if a wait on this handle
+ * gave up since the last check (its output is not valid; the state is cleared). */
+int hag_seq_set_option(hag_seq_t *h, int32_t option, int64_t value);
+int hag_seq_check(const hag_seq_t *h, void *stream);
 size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
 int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,
                          const float *w_hh, const float *b, float *a_out, void *workspace, void *stream);
@@ -265,7 +275,7 @@ int hag_backward(const hag_t *h, hag_op_t op, hag_dtype_t dtype, int64_t d,
  * hag_check synchronises `stream` and returns HAG_OK, or HAG_ETIMEOUT if a one-launch pass on this handle
  * gave up waiting since the last check (and clears that state). */
 enum { HAG_OPT_ONE_LAUNCH_MAX_ITEMS = 1, HAG_OPT_SPIN_LIMIT = 2, HAG_OPT_TEST_WAIT_UNREACHABLE = 3,
-       HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 4, HAG_OPT_PARTITION_SHIFT = 5 };
+       HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 4, HAG_OPT_PARTITION_SHIFT = 5, HAG_OPT_SEQ_ONE_LAUNCH = 6 };
 int hag_set_option(hag_t *h, int32_t option, int64_t value);
 int hag_check(const hag_t *h, void *stream);
 

@@ -20,6 +20,7 @@ HAG_SUM, HAG_MEAN, HAG_MAX, HAG_GCN = 0, 1, 2, 3
 HAG_F32, HAG_I32 = 0, 1
 HAG_OK, HAG_EINVAL, HAG_ENOMEM, HAG_EHIP, HAG_ESTATE, HAG_ETIMEOUT = 0, -1, -2, -3, -4, -5
 HAG_OPT_ONE_LAUNCH_MAX_ITEMS, HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE, HAG_OPT_DETERMINISTIC_MAX_BACKWARD = 1, 2, 3, 4
+HAG_OPT_SEQ_ONE_LAUNCH = 6
 HAG_OPT_PARTITION_SHIFT = 5
 HAG_SEARCH_CANONICAL, HAG_SEARCH_DEDUP, HAG_SEARCH_DEVICE = 1, 2, 4
 HAG_PHASE_LEVELS, HAG_PHASE_GATHER, HAG_PHASE_FOLD, HAG_PHASE_ALL = 1, 2, 4, 7
@@ -30,7 +31,7 @@ EXPORTS = [
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
     "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_probe_mfma_f32", "hag_set_option", "hag_check", "hag_seq_search",
-    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_get_plan", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
+    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_get_plan", "hag_seq_set_option", "hag_seq_check", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
     "hag_seq_lstm_forward",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
@@ -97,6 +98,8 @@ def lib():
             getattr(L, name).restype = i64
         L.hag_seq_upload.argtypes = [vp]
         L.hag_seq_get_plan.argtypes = [vp] + [vp] * 8
+        L.hag_seq_set_option.argtypes = [vp, i32, i64]
+        L.hag_seq_check.argtypes = [vp, vp]
         L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
         L.hag_seq_workspace_bytes.restype = ctypes.c_size_t
         L.hag_seq_lstm_forward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
@@ -415,6 +418,14 @@ class SeqHag:
     def upload(self):
         _check(lib().hag_seq_upload(self._h))
         return self
+
+    def set_option(self, option, value):
+        _check(lib().hag_seq_set_option(self._h, int(option), int(value)))
+        return self
+
+    def check(self):
+        """Synchronise the current stream; raises HagError(HAG_ETIMEOUT) if a wait of a one-launch pass gave up."""
+        _check(lib().hag_seq_check(self._h, _stream_ptr()))
 
     def workspace_bytes(self, d, hidden) -> int:
         return int(lib().hag_seq_workspace_bytes(self._h, int(d), int(hidden)))

@@ -19,6 +19,7 @@
 
 #include <algorithm>
 #include <cstdint>
+#include <cstdlib>
 #include <cstring>
 #include <new>
 #include <vector>
@@ -33,8 +34,14 @@ struct hag_seq {
     // step's (h, c) is written to (-1: not needed outside the path)
     std::vector<int32_t> paths, step_x, step_out;
     std::vector<int64_t> level_ptr;   // paths of level l: [level_ptr[l], level_ptr[l+1])
+    std::vector<int64_t> tile_ptr;    // tiles of 64 paths of level l: [tile_ptr[l], tile_ptr[l+1]) (a tile never mixes levels)
     int64_t longest = 0;
-    int32_t *d_final = nullptr, *d_paths = nullptr, *d_step_x = nullptr, *d_step_out = nullptr;
+    bool one_launch = true;           // HAG_SEQ_ONE_LAUNCH (default 1): all levels in one launch, paths waiting for the states they start from
+    int32_t spin_limit = 1 << 21;     // HAG_SPIN_LIMIT: polls (about half a microsecond apart) after which such a wait gives up
+    bool wait_unreachable = false;    // tests only: flags are never set, so every wait gives up
+    int32_t *d_final = nullptr, *d_paths = nullptr, *d_step_x = nullptr, *d_step_out = nullptr;   // d_paths: padded to whole tiles per level
+    int64_t resident[4] = {0, 0, 0, 0};   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
+    int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
     int device = -1;
 };
 
@@ -47,9 +54,12 @@ constexpr int kSeqMaxK = 128;     // D + H at most
 // cell, output gate).
 __global__ __launch_bounds__(256) void seq_pack_kernel(const float *__restrict__ w_ih, const float *__restrict__ w_hh,
                                                       const float *__restrict__ b, float *__restrict__ wp,
-                                                      float *__restrict__ bp, int d, int hidden, int kp) {
+                                                      float *__restrict__ bp, int d, int hidden, int kp,
+                                                      int32_t *__restrict__ flags, int64_t n_flags) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t total = (int64_t)4 * hidden * kp;
+    // the "state is written" flags of this pass start at zero
+    for (int64_t f = i; f < n_flags; f += (int64_t)gridDim.x * 256) flags[f] = 0;
     if (i >= total) return;
     const int r = (int)(i / kp), k = (int)(i % kp);
     const int unit = r >> 2, gate = r & 3, src_row = gate * hidden + unit;
@@ -72,8 +82,12 @@ __device__ __forceinline__ float seq_tanh(float z) {
 typedef float seq_acc_t __attribute__((ext_vector_type(16)));
 
 struct SeqChainArgs {
-    const int32_t *chains;   // this level's paths, 4 per path, longest first
-    int64_t n_chains;
+    const int32_t *chains;   // paths, 4 per path, in tiles of 64 (padded with empty paths), longest first within a level
+    int64_t n_path_tiles;
+    int32_t *flags;          // per state row: set once the row is written (NULL: every start state was written by an earlier launch)
+    int32_t *gave_up;        // set by a wait that gives up
+    int32_t spin_limit;      // polls of a flag before giving up
+    int32_t publish;         // 0 in a test of the time-out: no flag is ever set
     const int32_t *step_x;   // per step: input row
     const int32_t *step_out; // per step: state row to write, or -1
     const float *x, *wp, *bp;
@@ -114,13 +128,35 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
         wreg[s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
     if ((int)threadIdx.x < 4 * hidden) sb[threadIdx.x] = A.bp[threadIdx.x];
     constexpr int ZV = KP / 32;
-    const int64_t n_chain_tiles = (A.n_chains + kSeqJobs - 1) / kSeqJobs;
-    for (int64_t ct = blockIdx.x; ct < n_chain_tiles; ct += gridDim.x) {
-        if (threadIdx.x < kSeqJobs * 4) {
-            const int64_t ch = ct * kSeqJobs + threadIdx.x / 4;
-            sdesc[threadIdx.x] = ch < A.n_chains ? A.chains[ch * 4 + threadIdx.x % 4] : ((threadIdx.x & 3) == 2 ? 0 : -1);
+    for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
+        {
+            const int tid0 = seq_opaque(threadIdx.x);
+            if (tid0 < kSeqJobs * 4) sdesc[tid0] = A.chains[ct * (kSeqJobs * 4) + tid0];
         }
         __syncthreads();
+        if (A.flags) {
+            // All levels in one launch: wait until the states this tile's paths start from are written.  They
+            // belong to tiles with a smaller index, which this or another resident workgroup finishes without
+            // waiting for this one, so the wait ends; it is bounded all the same, and a time-out is recorded.
+            const int tid0 = seq_opaque(threadIdx.x);
+            if (tid0 < kSeqJobs) {
+                const int start = sdesc[tid0 * 4];
+                if (start >= 0) {
+                    bool ready = false;
+                    for (int spin = 0; spin < A.spin_limit; ++spin) {
+                        if (__hip_atomic_load(A.flags + start, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) { ready = true; break; }
+                        // once any wait of the pass has given up its output is void: the others do not sit theirs out
+                        if (__hip_atomic_load(A.gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+                    if (!ready) __hip_atomic_store(A.gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+            __syncthreads();
+            // the awaited rows are read with device-scope loads, which do not look into a private cache, so no
+            // cache is invalidated here; the fence keeps those loads behind the polls
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+        }
         // (thread indices are derived again in every phase, and the descriptor is re-read from LDS where it is needed rather than held in registers, which are short)
         const int steps = sdesc[2];                        // the tile's first path is its longest
         // the state the path starts from, the first input row, zero padding
@@ -133,13 +169,14 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 const int k = part * 4 + 32 * i;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (k < d) { if (row0 >= 0) v = *reinterpret_cast<const float4 *>(A.x + (size_t)row0 * d + k); }
-                else if (k < d + hidden && start >= 0) v = *reinterpret_cast<const float4 *>(A.h + (size_t)start * hidden + (k - d));
+                else if (k < d + hidden && start >= 0)
+                    v = A.flags ? ld4_coherent(A.h + (size_t)start * hidden + (k - d)) : *reinterpret_cast<const float4 *>(A.h + (size_t)start * hidden + (k - d));
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(v.x, v.y);
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(v.z, v.w);
             }
             for (int u = part * 4; u < hidden; u += 32) {
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (start >= 0) v = *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
+                if (start >= 0) v = A.flags ? ld4_coherent(A.c + (size_t)start * hidden + u) : *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
                 cs[sj * HS + u] = v.x; cs[sj * HS + u + 1] = v.y; cs[sj * HS + u + 2] = v.z; cs[sj * HS + u + 3] = v.w;
             }
         }
@@ -152,7 +189,6 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
             const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
             const int len = sdesc[sj * 4 + 2], at = sdesc[sj * 4 + 1] + t;
             const int row1 = t + 1 < len ? A.step_x[at + 1] : -1;
-            const int keep = t < len ? A.step_out[at] : -1;
 #pragma unroll
             for (int i = 0; i < ZE; ++i) {
                 const int k = part * 4 + 32 * i;
@@ -190,17 +226,26 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 }
             }
             __syncthreads();                               // every product has read z, every new h is in hs
+            int keep = -1;
             {
                 const int tid2 = seq_opaque(threadIdx.x), sj2 = tid2 >> 3, part2 = tid2 & 7;
                 if (t < sdesc[sj2 * 4 + 2]) {
+                    keep = A.step_out[sdesc[sj2 * 4 + 1] + t];
                     for (int u = part2 * 4; u < hidden; u += 32) {
                         const float *ph = &hs[sj2 * HS + u];
                         *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u]) = make_float2(ph[0], ph[1]);
                         *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u + 2]) = make_float2(ph[2], ph[3]);
                         if (keep >= 0) {                   // a state that another path starts from, or some a_v
                             const float *pc = &cs[sj2 * HS + u];
-                            *reinterpret_cast<float4 *>(A.h + (size_t)keep * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
-                            *reinterpret_cast<float4 *>(A.c + (size_t)keep * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
+                            if (A.flags) {
+                                // read by another workgroup of this launch, possibly on another XCD: device-scope stores,
+                                // written through to the level all XCDs share
+                                st4_coherent(A.h + (size_t)keep * hidden + u, make_float4(ph[0], ph[1], ph[2], ph[3]));
+                                st4_coherent(A.c + (size_t)keep * hidden + u, make_float4(pc[0], pc[1], pc[2], pc[3]));
+                            } else {
+                                *reinterpret_cast<float4 *>(A.h + (size_t)keep * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
+                                *reinterpret_cast<float4 *>(A.c + (size_t)keep * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
+                            }
                         }
                     }
                 }
@@ -216,7 +261,11 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                     }
                 }
             }
+            // a state's flag is set once all eight threads of its path have seen their stores complete (the barrier
+            // itself does not wait for stores to global memory)
+            if (A.flags && keep >= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
+            if (A.flags && A.publish && keep >= 0 && (threadIdx.x & 7) == 0) __hip_atomic_store(A.flags + keep, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // a_v = the last h of the path, where the path ends a node's list
         const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
@@ -267,6 +316,8 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
         if (n + a + e + n >= (int64_t)INT32_MAX) { set_error("too many states for 32-bit ids"); return HAG_EINVAL; }
         auto *h = new hag_seq();
         h->n = n; h->e = e; h->n_merges = a;
+        if (const char *v = getenv("HAG_SEQ_ONE_LAUNCH")) h->one_launch = atoi(v) != 0;
+        if (const char *v = getenv("HAG_SPIN_LIMIT")) h->spin_limit = (int32_t)std::min<long long>(std::max<long long>(atoll(v), 1), INT32_MAX);
         const bool share = capacity > 0;
         // shared states: the one-element prefixes in use, then the aggregation nodes (a state's predecessor
         // has a smaller index)
@@ -356,6 +407,9 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
             h->paths.push_back(p.start); h->paths.push_back(beg); h->paths.push_back(p.len); h->paths.push_back(p.node);
         }
         for (int32_t l = 0; l < levels; ++l) h->level_ptr[(size_t)l + 1] += h->level_ptr[l];
+        h->tile_ptr.assign((size_t)levels + 1, 0);
+        for (int32_t l = 0; l < levels; ++l)
+            h->tile_ptr[(size_t)l + 1] = h->tile_ptr[l] + (h->level_ptr[(size_t)l + 1] - h->level_ptr[l] + kSeqJobs - 1) / kSeqJobs;
         *out = h;
         return HAG_OK;
     } catch (const std::bad_alloc &) {
@@ -373,12 +427,17 @@ void hag_seq_free(hag_seq_t *h) {
     if (h->d_paths) (void)hipFree(h->d_paths);
     if (h->d_step_x) (void)hipFree(h->d_step_x);
     if (h->d_step_out) (void)hipFree(h->d_step_out);
+    if (h->d_gave_up) (void)hipFree(h->d_gave_up);
     delete h;
 }
 
 int64_t hag_seq_cells(const hag_seq_t *h) { return h ? (int64_t)h->step_x.size() : 0; }
 int64_t hag_seq_ranks(const hag_seq_t *h) { return h ? h->longest : 0; }
-int64_t hag_seq_launches(const hag_seq_t *h) { return h ? (int64_t)h->level_ptr.size() - 1 : 0; }
+int64_t hag_seq_launches(const hag_seq_t *h) {
+    if (!h) return 0;
+    const int64_t levels = (int64_t)h->level_ptr.size() - 1;
+    return h->one_launch ? std::min<int64_t>(levels, 1) : levels;
+}
 int64_t hag_seq_merges(const hag_seq_t *h) { return h ? h->n_merges : 0; }
 
 int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
@@ -404,11 +463,58 @@ int hag_seq_upload(hag_seq_t *h) {
         if (e == hipSuccess && !src.empty()) e = hipMemcpy(*dst, src.data(), src.size() * sizeof(int32_t), hipMemcpyHostToDevice);
         return e;
     };
-    HIP_TRY(put(&h->d_paths, h->paths));
+    {
+        // every level padded to whole tiles with empty paths (no start state, no steps, no node)
+        std::vector<int32_t> padded;
+        padded.reserve((size_t)h->tile_ptr.back() * kSeqJobs * 4);
+        for (size_t l = 0; l + 1 < h->level_ptr.size(); ++l) {
+            padded.insert(padded.end(), h->paths.begin() + h->level_ptr[l] * 4, h->paths.begin() + h->level_ptr[l + 1] * 4);
+            while ((int64_t)padded.size() < h->tile_ptr[l + 1] * kSeqJobs * 4) { padded.push_back(-1); padded.push_back(0); padded.push_back(0); padded.push_back(-1); }
+        }
+        HIP_TRY(put(&h->d_paths, padded));
+    }
     HIP_TRY(put(&h->d_step_x, h->step_x));
     HIP_TRY(put(&h->d_step_out, h->step_out));
+    HIP_TRY(put(&h->d_gave_up, std::vector<int32_t>(1, 0)));
+    {
+        // workgroups of each kernel variant that the device holds at once (at most the two per compute unit the
+        // kernel is tuned for): the grid of a one-launch pass
+        const void *variants[4] = {(const void *)seq_chain_kernel<32, false>, (const void *)seq_chain_kernel<32, true>,
+                                   (const void *)seq_chain_kernel<64, false>, (const void *)seq_chain_kernel<64, true>};
+        int cus = 0;
+        HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
+        for (int k = 0; k < 4; ++k) {
+            int per_cu = 0;
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, variants[k], 512, 0));
+            h->resident[k] = (int64_t)std::min(per_cu, 2) * cus;
+        }
+    }
     HIP_TRY(put(&h->d_final, h->final_state));
     return HAG_OK;
+}
+
+int hag_seq_set_option(hag_seq_t *h, int32_t option, int64_t value) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    switch (option) {
+        case HAG_OPT_SEQ_ONE_LAUNCH: h->one_launch = value != 0; return HAG_OK;
+        case HAG_OPT_SPIN_LIMIT: h->spin_limit = (int32_t)std::min<int64_t>(std::max<int64_t>(value, 1), INT32_MAX); return HAG_OK;
+        case HAG_OPT_TEST_WAIT_UNREACHABLE: h->wait_unreachable = value != 0; return HAG_OK;
+        default: set_error("unknown option"); return HAG_EINVAL;
+    }
+}
+
+int hag_seq_check(const hag_seq_t *h, void *stream) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
+    hipStream_t s = (hipStream_t)stream;
+    int32_t word = 0;
+    HIP_TRY(hipMemcpyAsync(&word, h->d_gave_up, sizeof(word), hipMemcpyDeviceToHost, s));
+    HIP_TRY(hipStreamSynchronize(s));
+    if (!word) return HAG_OK;
+    HIP_TRY(hipMemsetAsync(h->d_gave_up, 0, sizeof(word), s));
+    HIP_TRY(hipStreamSynchronize(s));
+    set_error("a pass of the LSTM aggregator gave up waiting for a state: its output is not valid");
+    return HAG_ETIMEOUT;
 }
 
 static int64_t seq_kp(int64_t d, int64_t hidden) { return d + hidden <= 64 ? 64 : 128; }
@@ -418,7 +524,8 @@ size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
     const size_t states = (size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float);
     const size_t wp = (size_t)4 * hidden * seq_kp(d, hidden) * sizeof(float), bp = (size_t)4 * hidden * sizeof(float);
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
-    return up(wp) + up(bp) + 2 * up(states);
+    const size_t flags = (size_t)std::max<int64_t>(h->n_states, 1) * sizeof(int32_t);
+    return up(wp) + up(bp) + 2 * up(states) + up(flags);
 }
 
 int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
@@ -440,25 +547,34 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
     float *bp = (float *)w; w += up((size_t)4 * hidden * sizeof(float));
     const size_t states = up((size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float));
     float *hst = (float *)w; w += states;
-    float *cst = (float *)w;
+    float *cst = (float *)w; w += states;
+    int32_t *flags = (int32_t *)w;                          // [n_states]
     {
         const int64_t total = (int64_t)4 * hidden * kp;
         hipLaunchKernelGGL(seq_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w_ih, w_hh, b, wp, bp, (int)d,
-                           (int)hidden, kp);
+                           (int)hidden, kp, flags, h->n_states);
         HIP_TRY(hipGetLastError());
     }
-    const int64_t levels = (int64_t)h->level_ptr.size() - 1;
-    for (int64_t l = 0; l < levels; ++l) {
+    const int64_t levels = (int64_t)h->tile_ptr.size() - 1;
+    const bool wide = hidden > 32;   // more than four gate tiles
+    // All levels in ONE launch when every workgroup of it can be resident at once (then a workgroup that waits
+    // for a state never keeps the one that writes it off the machine); one launch per level otherwise.
+    const int64_t resident = h->resident[(kp == 64 ? 0 : 2) + (wide ? 1 : 0)];
+    const bool fused = levels > 1 && h->one_launch && resident > 0;
+    for (int64_t l = 0; l < (fused ? 1 : levels); ++l) {
         SeqChainArgs c;
-        c.chains = h->d_paths + h->level_ptr[l] * 4;
-        c.n_chains = h->level_ptr[l + 1] - h->level_ptr[l];
+        const int64_t t0 = fused ? 0 : h->tile_ptr[l], t1 = fused ? h->tile_ptr[levels] : h->tile_ptr[l + 1];
+        c.chains = h->d_paths + t0 * kSeqJobs * 4;
+        c.n_path_tiles = t1 - t0;
+        c.flags = fused ? flags : nullptr;
+        c.spin_limit = h->spin_limit;
+        c.publish = h->wait_unreachable ? 0 : 1;
+        c.gave_up = h->d_gave_up;
         c.step_x = h->d_step_x; c.step_out = h->d_step_out;
         c.x = x; c.wp = wp; c.bp = bp; c.h = hst; c.c = cst; c.a_out = a_out;
         c.d = (int32_t)d; c.hidden = (int32_t)hidden;
-        if (c.n_chains <= 0) continue;
-        const int64_t tiles = (c.n_chains + kSeqJobs - 1) / kSeqJobs;
-        const dim3 grid((unsigned)std::min<int64_t>(tiles, 256 * 2)), block(512);
-        const bool wide = hidden > 32;   // more than four gate tiles
+        if (c.n_path_tiles <= 0) continue;
+        const dim3 grid((unsigned)std::min<int64_t>(c.n_path_tiles, fused ? resident : 256 * 2)), block(512);
         if (kp == 64) {
             if (wide) hipLaunchKernelGGL((seq_chain_kernel<32, true>), grid, block, 0, s, c);
             else hipLaunchKernelGGL((seq_chain_kernel<32, false>), grid, block, 0, s, c);

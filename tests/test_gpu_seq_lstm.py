@@ -71,13 +71,20 @@ def check(B, rowptr, col, d, hidden, seed, capacities):
             _, cells = lstm.hag_aggregate(n, merges, lists, x, w_ih, w_hh, b)
             assert h.merges == len(merges)
             assert h.cells == cells
-        for rep in range(2):            # the second call reuses the state rows of the first
-            got = h.lstm_forward(xd, wid, whd, bd).cpu().numpy().astype(np.float64)
-            err = np.abs(got - want).max() if got.size else 0.0
-            worst = max(worst, err)
-            assert err <= ATOL, f"cap {cap} d {d} H {hidden}: max |gpu - oracle| = {err}"
-            empty = np.diff(rowptr) == 0
-            assert not got[empty].any()
+        per_mode = []
+        for one_launch in (1, 0):       # all levels in one launch (paths wait for their start states) / one launch per level
+            h.set_option(B.HAG_OPT_SEQ_ONE_LAUNCH, one_launch)
+            for rep in range(2):        # the second call reuses the state rows and flags of the first
+                got_t = h.lstm_forward(xd, wid, whd, bd)
+                h.check()
+                got = got_t.cpu().numpy().astype(np.float64)
+                err = np.abs(got - want).max() if got.size else 0.0
+                worst = max(worst, err)
+                assert err <= ATOL, f"cap {cap} d {d} H {hidden} one_launch {one_launch}: max |gpu - oracle| = {err}"
+                empty = np.diff(rowptr) == 0
+                assert not got[empty].any()
+            per_mode.append(got)
+        assert np.array_equal(per_mode[0], per_mode[1])      # the same arithmetic either way
     return worst
 
 
@@ -114,6 +121,27 @@ def test_rejections(B):
         h.lstm_forward(x, torch.zeros((16, 8), device="cuda"), torch.zeros((16, 4), device="cuda"), torch.zeros(16, device="cuda"))
     with pytest.raises(B.HagError):       # hidden above the kernel's limit
         h.lstm_forward(x, torch.zeros((512, 8), device="cuda"), torch.zeros((512, 128), device="cuda"), torch.zeros(512, device="cuda"))
+
+
+def test_bounded_wait_gives_up_and_reports(B):
+    # forced from the host: no "state is written" flag is ever set and the spin limit is tiny, so every wait of the
+    # one-launch pass ends by giving up; the kernel still runs to its end and hag_seq_check reports it
+    rowptr, col = route_graph(300, 9, seed=31)
+    d = hidden = 16
+    w_ih, w_hh, b = (torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda() for a in params(d, hidden, 3))
+    h = B.SeqHag(rowptr, col, col.size).upload()
+    assert h.plan()[4].size - 1 > 1                          # more than one level: there are waits
+    x = torch.randn((300, d), device="cuda")
+    want = h.lstm_forward(x, w_ih, w_hh, b).clone()
+    h.check()
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 1).set_option(B.HAG_OPT_SPIN_LIMIT, 4)
+    h.lstm_forward(x, w_ih, w_hh, b)
+    with pytest.raises(B.HagError) as ei:
+        h.check()
+    assert ei.value.code == B.HAG_ETIMEOUT
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 0).set_option(B.HAG_OPT_SPIN_LIMIT, 1 << 21)
+    assert torch.equal(h.lstm_forward(x, w_ih, w_hh, b), want)           # the next pass is sound again
+    h.check()
 
 
 def test_replay_from_a_hip_graph(B):
