@@ -320,13 +320,10 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
     import numpy as np
     rowptr, col, _ = synth.graph_for_config(cfg)
     n = rowptr.size - 1
-    take = np.minimum(np.diff(rowptr), first_k)
-    rp = np.concatenate([[0], np.cumsum(take)]).astype(np.int64)
-    cl = col[np.repeat(rowptr[:-1], take) + (np.arange(rp[-1]) - np.repeat(rp[:-1], take))].astype(np.int32)
-    rng = np.random.default_rng(synth.SEED_BASE + 100 * cfg + 7)
+    from paper_1906_03707_amd import workloads
+    rp, cl = workloads.first_neighbour_lists(rowptr, col, first_k)
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
-    x = dev(rng.normal(size=(n, d)))
-    w_ih, w_hh, b = dev(rng.normal(0, 0.3, (4 * hidden, d))), dev(rng.normal(0, 0.3, (4 * hidden, hidden))), dev(rng.normal(0, 0.3, 4 * hidden))
+    x, w_ih, w_hh, b = (dev(a) for a in workloads.lstm_inputs(cfg, n, d, hidden))
     out = torch.empty((n, hidden), dtype=torch.float32, device="cuda")
     plans = {"lists": binding.SeqHag(rp, cl, 0).upload(), "hag_quarter": binding.SeqHag(rp, cl, n // 4).upload(),
              "hag_unlimited": binding.SeqHag(rp, cl, int(cl.size)).upload()}

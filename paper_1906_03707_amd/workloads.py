@@ -63,6 +63,22 @@ def build_hag(cfg: int, rowptr, col, graph_ptr=None, capacity=None, log=None, de
     return h
 
 
+def first_neighbour_lists(rowptr, col, first_k: int):
+    """Ordered lists for a sequential Aggregate (Section 3.1): every node's list is its first `first_k` neighbours
+    in the CSR's (ascending id) order.  Returns (rowptr int64, col int32)."""
+    take = np.minimum(np.diff(rowptr), first_k)
+    rp = np.concatenate([[0], np.cumsum(take)]).astype(np.int64)
+    cl = col[np.repeat(rowptr[:-1], take) + (np.arange(rp[-1]) - np.repeat(rp[:-1], take))].astype(np.int32)
+    return rp, cl
+
+
+def lstm_inputs(cfg: int, n: int, d: int, hidden: int):
+    """Seeded features and LSTM parameters of the LSTM-aggregator workload (fp64 arrays; callers round to fp32)."""
+    rng = np.random.default_rng(synth.SEED_BASE + 100 * cfg + 7)
+    return (rng.normal(size=(n, d)), rng.normal(0, 0.3, (4 * hidden, d)), rng.normal(0, 0.3, (4 * hidden, hidden)),
+            rng.normal(0, 0.3, 4 * hidden))
+
+
 def make_cache(cfg: int, capacity=None, device=False):
     rowptr, col, _ = synth.graph_for_config(cfg)
     n = rowptr.size - 1

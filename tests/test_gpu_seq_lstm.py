@@ -106,6 +106,36 @@ def test_power_law_graph_first_neighbours(B):
     assert h1.cells < h0.cells
 
 
+@pytest.mark.timeout(600)
+def test_bench_workload_sampled_nodes(B):
+    # the workload bench.py --seq-lstm times, at its full size and in its launch configuration (config 4's graphs,
+    # first 16 neighbours, d = H = 64; plain lists, capacity |V|/4, unlimited): the oracle walks the lists of sampled
+    # nodes one by one
+    from paper_1906_03707_amd import workloads
+    cfg, d, hidden = 4, 64, 64
+    rowptr, col, _ = synth.graph_for_config(cfg)
+    n = rowptr.size - 1
+    rp, cl = workloads.first_neighbour_lists(rowptr, col, 16)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    xd, wid, whd, bd = (dev(a) for a in workloads.lstm_inputs(cfg, n, d, hidden))
+    x64, wi64, wh64, b64 = (t.cpu().numpy().astype(np.float64) for t in (xd, wid, whd, bd))
+    sample = np.unique(np.concatenate([np.random.default_rng(5).integers(0, n, 400), [0, n - 1]]))
+    s_rp = np.concatenate([[0], np.cumsum(rp[sample + 1] - rp[sample])]).astype(np.int64)
+    s_cl = np.concatenate([cl[rp[v]:rp[v + 1]] for v in sample]).astype(np.int32)
+    want, _ = lstm.naive_aggregate(s_rp, s_cl, x64, wi64, wh64, b64)
+    results = []
+    for cap in (0, n // 4, int(cl.size)):
+        h = B.SeqHag(rp, cl, cap).upload()
+        got = h.lstm_forward(xd, wid, whd, bd)
+        h.check()
+        err = np.abs(got[torch.from_numpy(sample).cuda()].cpu().numpy().astype(np.float64) - want).max()
+        print(f"capacity {cap}: {h.cells} cells, {h.plan()[4].size - 1} levels, max |gpu - oracle| on {sample.size} nodes = {err:.2e}", flush=True)
+        assert err <= ATOL
+        results.append(got)
+    # the three plans evaluate the same cells in the same order along every list
+    assert torch.equal(results[0], results[1]) and torch.equal(results[0], results[2])
+
+
 def test_rejections(B):
     rowptr, col = route_graph(20, 4, seed=3)
     h = B.SeqHag(rowptr, col, 3)
