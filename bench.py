@@ -313,7 +313,7 @@ def sweep_config5(torch, synth, workloads, steps, warmup):
 FP32_MFMA_PEAK_TFLOPS = 157.3
 
 
-def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup):
+def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup, only=None):
     """LSTM aggregator over ordered neighbour lists (Section 3.1's sequential Aggregate): every node's list is its
     first `first_k` neighbours in ascending id order; the plain lists against prefix HAGs of capacity |V|/4 and
     unlimited.  One step = one forward pass (all cell evaluations of the plan)."""
@@ -325,8 +325,10 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
     dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
     x, w_ih, w_hh, b = (dev(a) for a in workloads.lstm_inputs(cfg, n, d, hidden))
     out = torch.empty((n, hidden), dtype=torch.float32, device="cuda")
-    plans = {"lists": binding.SeqHag(rp, cl, 0).upload(), "hag_quarter": binding.SeqHag(rp, cl, n // 4).upload(),
-             "hag_unlimited": binding.SeqHag(rp, cl, int(cl.size)).upload()}
+    capacities = {"lists": 0, "hag_quarter": n // 4, "hag_unlimited": int(cl.size)}
+    # `only` (one plan's name): that plan alone, nothing interleaved -- for counter runs, where every launch of the kernel
+    # should be the same work
+    plans = {name: binding.SeqHag(rp, cl, cap).upload() for name, cap in capacities.items() if only in (None, name)}
     # what the matrix cores deliver on this machine for the instruction the kernel uses
     sink = torch.empty(256 * 8 * 256, dtype=torch.float32, device="cuda")
     binding.probe_mfma_f32(2000, 256 * 8, sink)
@@ -341,18 +343,18 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
     res = {"workload": f"config{cfg}:{synth.CONFIGS[cfg]['name']}, first {first_k} neighbours in id order", "nodes": n,
            "list_entries": int(cl.size), "d": d, "hidden": hidden, "flops_per_cell": flops_per_cell,
            "measured_fp32_matrix_TFLOPs": mfma_ceiling, "plans": {}}
-    base = lambda: plans["lists"].lstm_forward(x, w_ih, w_hh, b, out=out)
+    base = (lambda: plans["lists"].lstm_forward(x, w_ih, w_hh, b, out=out)) if "lists" in plans else None
     for name, p in plans.items():
         fn = (lambda p=p: p.lstm_forward(x, w_ih, w_hh, b, out=out))
-        if name == "lists":
+        if name == "lists" or base is None:
             ms, _ = time_steps(torch, fn, steps, warmup)
-            ms_base = ms
+            ms_base = ms if name == "lists" else float("nan")
         else:
             (ms, _), (ms_base, _) = time_interleaved(torch, fn, base, steps, warmup)
         tf = p.cells * flops_per_cell / (ms * 1e-3) / 1e12
         res["plans"][name] = {"cells": p.cells, "aggregation_nodes": p.merges, "launches": p.launches, "levels": int(p.plan()[4].size - 1), "longest_chain": p.ranks, "ms_per_pass": ms,
                               "lists_ms_per_pass": ms_base, "speedup_vs_lists": ms_base / ms,
-                              "cells_fewer": plans["lists"].cells / max(p.cells, 1), "tflops": tf,
+                              "cells_fewer": int(cl.size) / max(p.cells, 1), "tflops": tf,
                               "frac_of_fp32_matrix_peak": tf / FP32_MFMA_PEAK_TFLOPS, "frac_of_measured_ceiling": tf / mfma_ceiling}
         log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.launches} launches, "
             f"{ms:.3f} ms per pass ({ms_base / ms:.2f}x the plain lists' speed), {tf:.1f} TFLOP/s = "
@@ -416,6 +418,8 @@ def main():
     ap.add_argument("--seq-lstm", action="store_true",
                     help="time the LSTM aggregator over ordered lists (first 16 neighbours of --config 4 or 2, d = hidden = --d or 64): "
                          "plain lists against prefix HAGs")
+    ap.add_argument("--seq-plan", choices=["lists", "hag_quarter", "hag_unlimited"], default=None,
+                    help="with --seq-lstm: time this plan alone (every launch of the kernel is then the same work: for counter runs)")
     ap.add_argument("--one-launch", action="store_true",
                     help="run the HAG passes with the one-launch schedule (all stages and the gather over V in a single "
                          "kernel launch; off by default because it measures slower)")
@@ -439,9 +443,10 @@ def main():
     if args.seq_lstm:
         c = cfg if cfg in (1, 2, 4) else 4
         width = args.d if args.d else 64
-        res = seq_lstm_bench(torch, binding, synth, c, 16, width, width, max(args.steps // 2, 5), 3)
+        res = seq_lstm_bench(torch, binding, synth, c, 16, width, width, max(args.steps // 2, 5), 3, only=args.seq_plan)
+        main_plan = res["plans"][args.seq_plan or "hag_quarter"]
         print(json.dumps({"metric": "LSTM aggregator over ordered lists, forward: cell evaluations/s", "unit": "cells/s",
-                          "value": res["plans"]["hag_quarter"]["cells"] / (res["plans"]["hag_quarter"]["ms_per_pass"] * 1e-3),
+                          "value": main_plan["cells"] / (main_plan["ms_per_pass"] * 1e-3),
                           "n_gpus": 1, "dtype": "f32", "data": "synthetic", "config": res}), flush=True)
         return
     if cfg == 5:

@@ -383,9 +383,12 @@ class SeqHag:
         self._ws = {}
 
     def __del__(self):
-        if getattr(self, "_h", None):
-            lib().hag_seq_free(self._h)
-            self._h = None
+        try:                                # at interpreter shutdown the module's globals may be gone already
+            if getattr(self, "_h", None):
+                lib().hag_seq_free(self._h)
+                self._h = None
+        except Exception:
+            pass
 
     @property
     def cells(self) -> int:

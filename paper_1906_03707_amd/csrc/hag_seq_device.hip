@@ -96,6 +96,21 @@ struct SeqChainArgs {
     int32_t d, hidden;
 };
 
+// State rows that another workgroup of the same launch reads, possibly on another XCD: device-scope accesses,
+// which are written through to, and read from, the level all XCDs share instead of a private cache; eight bytes
+// at a time (the widest access that has a device-scope form).
+__device__ __forceinline__ float4 seq_ld4_device(const float *p) {
+    const unsigned long long a = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const unsigned long long b = __hip_atomic_load(reinterpret_cast<const unsigned long long *>(p) + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return make_float4(__uint_as_float((unsigned)a), __uint_as_float((unsigned)(a >> 32)), __uint_as_float((unsigned)b), __uint_as_float((unsigned)(b >> 32)));
+}
+__device__ __forceinline__ void seq_st4_device(float *p, float4 v) {
+    const unsigned long long a = (unsigned long long)__float_as_uint(v.x) | ((unsigned long long)__float_as_uint(v.y) << 32);
+    const unsigned long long b = (unsigned long long)__float_as_uint(v.z) | ((unsigned long long)__float_as_uint(v.w) << 32);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p), a, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    __hip_atomic_store(reinterpret_cast<unsigned long long *>(p) + 1, b, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+}
+
 // Hides a value's origin from the optimiser, so that what is derived from it is computed where it is used
 // instead of being held in a register across the products.
 __device__ __forceinline__ int seq_opaque(int v) { asm volatile("" : "+v"(v)); return v; }
@@ -170,13 +185,13 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (k < d) { if (row0 >= 0) v = *reinterpret_cast<const float4 *>(A.x + (size_t)row0 * d + k); }
                 else if (k < d + hidden && start >= 0)
-                    v = A.flags ? ld4_coherent(A.h + (size_t)start * hidden + (k - d)) : *reinterpret_cast<const float4 *>(A.h + (size_t)start * hidden + (k - d));
+                    v = A.flags ? seq_ld4_device(A.h + (size_t)start * hidden + (k - d)) : *reinterpret_cast<const float4 *>(A.h + (size_t)start * hidden + (k - d));
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(v.x, v.y);
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(v.z, v.w);
             }
             for (int u = part * 4; u < hidden; u += 32) {
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-                if (start >= 0) v = A.flags ? ld4_coherent(A.c + (size_t)start * hidden + u) : *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
+                if (start >= 0) v = A.flags ? seq_ld4_device(A.c + (size_t)start * hidden + u) : *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
                 cs[sj * HS + u] = v.x; cs[sj * HS + u + 1] = v.y; cs[sj * HS + u + 2] = v.z; cs[sj * HS + u + 3] = v.w;
             }
         }
@@ -238,10 +253,8 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                         if (keep >= 0) {                   // a state that another path starts from, or some a_v
                             const float *pc = &cs[sj2 * HS + u];
                             if (A.flags) {
-                                // read by another workgroup of this launch, possibly on another XCD: device-scope stores,
-                                // written through to the level all XCDs share
-                                st4_coherent(A.h + (size_t)keep * hidden + u, make_float4(ph[0], ph[1], ph[2], ph[3]));
-                                st4_coherent(A.c + (size_t)keep * hidden + u, make_float4(pc[0], pc[1], pc[2], pc[3]));
+                                seq_st4_device(A.h + (size_t)keep * hidden + u, make_float4(ph[0], ph[1], ph[2], ph[3]));
+                                seq_st4_device(A.c + (size_t)keep * hidden + u, make_float4(pc[0], pc[1], pc[2], pc[3]));
                             } else {
                                 *reinterpret_cast<float4 *>(A.h + (size_t)keep * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
                                 *reinterpret_cast<float4 *>(A.c + (size_t)keep * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
