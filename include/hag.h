@@ -169,7 +169,9 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
  * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
  * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights, one (h, c) state row and one flag
- * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 64, d + H <= 128.  Enqueues on
+ * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 128, d + H <= 256 (H <= 64 with
+ * d + H <= 128 keeps the packed weights in registers; beyond that every wavefront streams its part of them from the
+ * L2 cache once per step).  Enqueues on
  * `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload, HAG_EINVAL otherwise. */
 typedef struct hag_seq hag_seq_t;
 int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out);

@@ -40,7 +40,7 @@ struct hag_seq {
     int32_t spin_limit = 1 << 21;     // HAG_SPIN_LIMIT: polls (about half a microsecond apart) after which such a wait gives up
     bool wait_unreachable = false;    // tests only: flags are never set, so every wait gives up
     int32_t *d_final = nullptr, *d_paths = nullptr, *d_step_x = nullptr, *d_step_out = nullptr;   // d_paths: padded to whole tiles per level
-    int64_t resident[4] = {0, 0, 0, 0};   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
+    int64_t resident[6] = {0, 0, 0, 0, 0, 0};   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
     int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
     int device = -1;
 };
@@ -48,26 +48,34 @@ struct hag_seq {
 namespace hag {
 
 constexpr int kSeqJobs = 64;      // paths per tile
-constexpr int kSeqMaxK = 128;     // D + H at most
+constexpr int kSeqMaxK = 256;     // D + H at most (128 for the variants that hold Wp in registers)
 
 // Wp / bp from the usual layout: w_ih [4H, D], w_hh [4H, H], b [4H], gate-major rows (input, forget,
 // cell, output gate).
 __global__ __launch_bounds__(256) void seq_pack_kernel(const float *__restrict__ w_ih, const float *__restrict__ w_hh,
                                                       const float *__restrict__ b, float *__restrict__ wp,
-                                                      float *__restrict__ bp, int d, int hidden, int kp,
+                                                      float *__restrict__ bp, int d, int hidden, int kp, int operand_order,
                                                       int32_t *__restrict__ flags, int64_t n_flags) {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     const int64_t total = (int64_t)4 * hidden * kp;
     // the "state is written" flags of this pass start at zero
     for (int64_t f = i; f < n_flags; f += (int64_t)gridDim.x * 256) flags[f] = 0;
     if (i >= total) return;
-    const int r = (int)(i / kp), k = (int)(i % kp);
+    int r = (int)(i / kp), k = (int)(i % kp);
+    if (operand_order) {
+        // the kernel that streams Wp reads it in the order its matrix instructions consume it:
+        // [gate tile][4 k-steps][lane][step in the group], lane l supplying row l % 32 and column 2 * step + l / 32
+        const int per_tile = 32 * kp, tile = (int)(i / per_tile), rest = (int)(i % per_tile);
+        const int q = rest / 256, lane = (rest % 256) / 4, step = 4 * q + (rest & 3);
+        r = tile * 32 + (lane & 31);
+        k = 2 * step + (lane >> 5);
+    }
     const int unit = r >> 2, gate = r & 3, src_row = gate * hidden + unit;
     float v = 0.f;
     if (k < d) v = w_ih[(size_t)src_row * d + k];
     else if (k < d + hidden) v = w_hh[(size_t)src_row * hidden + (k - d)];
     wp[i] = v;
-    if (k == 0) bp[r] = b[src_row];
+    if (k == 0) bp[r] = b[src_row];                        // (every row has exactly one element with k == 0 in either order)
 }
 
 // Gate functions on the hardware's exp2 and reciprocal: absolute error of a few 1e-7 on outputs in (0, 1) and
@@ -125,24 +133,34 @@ __device__ __forceinline__ int seq_opaque(int v) { asm volatile("" : "+v"(v)); r
 // holds gate tile w % 4 and takes the half w / 4 of the path tile.  Either way a wavefront keeps one gate
 // tile of Wp in registers (64 of the 128 it may use at four wavefronts per SIMD, 32 more for the
 // accumulators), so the staging and element-wise phases of one workgroup hide behind the products of the other.
-template <int KSTEPS, bool WIDE>
-__global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
+//
+// BIG (hidden up to 128, D + H up to 256): 16 wavefronts, wavefront w takes gate tile w and both halves of the
+// path tile; Wp no longer fits the registers of a compute unit, so every wavefront streams its gate tile,
+// stored in the order the matrix instructions consume it, from the L2 cache once per step (16-byte loads, one
+// group of four k-steps ahead): 4H (D + H) * 4 bytes per 64 cells, against 2 * 4H (D + H) * 64 flops.
+template <int KSTEPS, bool WIDE, bool BIG>
+__global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChainArgs A) {
+    static_assert(!BIG || WIDE, "the streamed variant uses the wide tiling");
     constexpr int KP = 2 * KSTEPS, ZS = KP + 2;
-    constexpr int HS = (WIDE ? 64 : 32) + 1, JG = WIDE ? 2 : 1;
+    constexpr int HMAX = BIG ? 128 : (WIDE ? 64 : 32);
+    constexpr int HS = HMAX + 1, JG = WIDE ? 2 : 1;
+    constexpr int TPP = BIG ? 16 : 8;                      // threads per path in the staging phases
     __shared__ float z[kSeqJobs * ZS];
     __shared__ float hs[kSeqJobs * HS];
     __shared__ float cs[kSeqJobs * HS];
-    __shared__ __align__(16) float sb[4 * 64];
+    __shared__ __align__(16) float sb[4 * (BIG ? 128 : 64)];
     __shared__ int32_t sdesc[kSeqJobs * 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int hidden = A.hidden, d = A.d, n_tiles = hidden / 8;
     const int tile = WIDE ? wave : (wave & 3), group0 = WIDE ? 0 : (wave >> 2);
-    float wreg[KSTEPS];
+    float wreg[BIG ? 1 : KSTEPS];
+    if constexpr (!BIG) {
 #pragma unroll
-    for (int s = 0; s < KSTEPS; ++s)
-        wreg[s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
+        for (int s = 0; s < KSTEPS; ++s)
+            wreg[s] = tile < n_tiles ? A.wp[(size_t)(tile * 32 + (lane & 31)) * KP + 2 * s + (lane >> 5)] : 0.f;
+    }
     if ((int)threadIdx.x < 4 * hidden) sb[threadIdx.x] = A.bp[threadIdx.x];
-    constexpr int ZV = KP / 32;
+    constexpr int ZV = KP / (4 * TPP);
     for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
         {
             const int tid0 = seq_opaque(threadIdx.x);
@@ -176,12 +194,12 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
         const int steps = sdesc[2];                        // the tile's first path is its longest
         // the state the path starts from, the first input row, zero padding
         {
-            const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+            const int tid = seq_opaque(threadIdx.x), sj = tid / TPP, part = tid % TPP;
             const int start = sdesc[sj * 4], beg = sdesc[sj * 4 + 1], len = sdesc[sj * 4 + 2];
             const int row0 = len > 0 ? A.step_x[beg] : -1;
 #pragma unroll 1                                           // (one vector in flight: this runs once per tile, and registers are short)
             for (int i = 0; i < ZV; ++i) {
-                const int k = part * 4 + 32 * i;
+                const int k = part * 4 + 4 * TPP * i;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (k < d) { if (row0 >= 0) v = *reinterpret_cast<const float4 *>(A.x + (size_t)row0 * d + k); }
                 else if (k < d + hidden && start >= 0)
@@ -189,7 +207,7 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k]) = make_float2(v.x, v.y);
                 *reinterpret_cast<float2 *>(&z[sj * ZS + k + 2]) = make_float2(v.z, v.w);
             }
-            for (int u = part * 4; u < hidden; u += 32) {
+            for (int u = part * 4; u < hidden; u += 4 * TPP) {
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (start >= 0) v = A.flags ? seq_ld4_device(A.c + (size_t)start * hidden + u) : *reinterpret_cast<const float4 *>(A.c + (size_t)start * hidden + u);
                 cs[sj * HS + u] = v.x; cs[sj * HS + u + 1] = v.y; cs[sj * HS + u + 2] = v.z; cs[sj * HS + u + 3] = v.w;
@@ -201,12 +219,12 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
             // (its first 64 columns, that is: holding more across the products would spill registers)
             constexpr int ZE = ZV < 2 ? ZV : 2;
             float4 xr[ZE];
-            const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+            const int tid = seq_opaque(threadIdx.x), sj = tid / TPP, part = tid % TPP;
             const int len = sdesc[sj * 4 + 2], at = sdesc[sj * 4 + 1] + t;
             const int row1 = t + 1 < len ? A.step_x[at + 1] : -1;
 #pragma unroll
             for (int i = 0; i < ZE; ++i) {
-                const int k = part * 4 + 32 * i;
+                const int k = part * 4 + 4 * TPP * i;
                 xr[i] = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (k < d && row1 >= 0) xr[i] = *reinterpret_cast<const float4 *>(A.x + (size_t)row1 * d + k);
             }
@@ -219,10 +237,27 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 for (int g = 0; g < JG; ++g) { acc[g][4 * m] = bias.x; acc[g][4 * m + 1] = bias.y; acc[g][4 * m + 2] = bias.z; acc[g][4 * m + 3] = bias.w; }
             }
             const float *zl = &z[(group0 * 32 + (lane & 31)) * ZS + (lane >> 5)];
+            if constexpr (!BIG) {
 #pragma unroll
-            for (int s = 0; s < KSTEPS; ++s) {
+                for (int s = 0; s < KSTEPS; ++s) {
 #pragma unroll
-                for (int g = 0; g < JG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[s], zl[g * 32 * ZS + 2 * s], acc[g], 0, 0, 0);
+                    for (int g = 0; g < JG; ++g) acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(wreg[s], zl[g * 32 * ZS + 2 * s], acc[g], 0, 0, 0);
+                }
+            } else if (tile < n_tiles) {                   // (a wavefront without a gate tile has nothing to stream)
+                const float4 *wq = reinterpret_cast<const float4 *>(A.wp) + (size_t)tile * (KSTEPS / 4) * 64 + lane;
+                float4 wa = wq[0];
+#pragma unroll 4
+                for (int q = 0; q < KSTEPS / 4; ++q) {
+                    const float4 wn = wq[(q + 1 < KSTEPS / 4 ? q + 1 : q) * 64];
+                    const float w4[4] = {wa.x, wa.y, wa.z, wa.w};
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+#pragma unroll
+                        for (int g = 0; g < JG; ++g)
+                            acc[g] = __builtin_amdgcn_mfma_f32_32x32x2f32(w4[r], zl[g * 32 * ZS + 2 * (4 * q + r)], acc[g], 0, 0, 0);
+                    }
+                    wa = wn;
+                }
             }
             if (tile < n_tiles) {
 #pragma unroll
@@ -243,10 +278,10 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
             __syncthreads();                               // every product has read z, every new h is in hs
             int keep = -1;
             {
-                const int tid2 = seq_opaque(threadIdx.x), sj2 = tid2 >> 3, part2 = tid2 & 7;
+                const int tid2 = seq_opaque(threadIdx.x), sj2 = tid2 / TPP, part2 = tid2 % TPP;
                 if (t < sdesc[sj2 * 4 + 2]) {
                     keep = A.step_out[sdesc[sj2 * 4 + 1] + t];
-                    for (int u = part2 * 4; u < hidden; u += 32) {
+                    for (int u = part2 * 4; u < hidden; u += 4 * TPP) {
                         const float *ph = &hs[sj2 * HS + u];
                         *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u]) = make_float2(ph[0], ph[1]);
                         *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u + 2]) = make_float2(ph[2], ph[3]);
@@ -265,7 +300,7 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
                 if (row1 >= 0) {
 #pragma unroll
                     for (int i = 0; i < ZV; ++i) {
-                        const int k = part2 * 4 + 32 * i;
+                        const int k = part2 * 4 + 4 * TPP * i;
                         if (k < d) {
                             const float4 v = i < ZE ? xr[i < ZE ? i : 0] : *reinterpret_cast<const float4 *>(A.x + (size_t)row1 * d + k);
                             *reinterpret_cast<float2 *>(&z[sj2 * ZS + k]) = make_float2(v.x, v.y);
@@ -278,13 +313,13 @@ __global__ __launch_bounds__(512, 4) void seq_chain_kernel(SeqChainArgs A) {
             // itself does not wait for stores to global memory)
             if (A.flags && keep >= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
             __syncthreads();
-            if (A.flags && A.publish && keep >= 0 && (threadIdx.x & 7) == 0) __hip_atomic_store(A.flags + keep, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if (A.flags && A.publish && keep >= 0 && threadIdx.x % TPP == 0) __hip_atomic_store(A.flags + keep, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
         // a_v = the last h of the path, where the path ends a node's list
-        const int tid = seq_opaque(threadIdx.x), sj = tid >> 3, part = tid & 7;
+        const int tid = seq_opaque(threadIdx.x), sj = tid / TPP, part = tid % TPP;
         const int node = sdesc[sj * 4 + 3];
         if (node >= 0) {
-            for (int u = part * 4; u < hidden; u += 32) {
+            for (int u = part * 4; u < hidden; u += 4 * TPP) {
                 const float *ph = &z[sj * ZS + d + u];
                 *reinterpret_cast<float4 *>(A.a_out + (size_t)node * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
             }
@@ -453,6 +488,18 @@ int64_t hag_seq_launches(const hag_seq_t *h) {
 }
 int64_t hag_seq_merges(const hag_seq_t *h) { return h ? h->n_merges : 0; }
 
+// Padded D + H, which also names the kernel variant: 64 and 128 hold Wp in registers (hidden <= 64), 192 and 256 stream it.
+static int64_t seq_kp(int64_t d, int64_t hidden) {
+    if (hidden <= 64 && d + hidden <= 128) return d + hidden <= 64 ? 64 : 128;
+    return d + hidden <= 192 ? 192 : 256;
+}
+// Index into hag_seq::resident / the variant table below.
+static int seq_variant(int64_t kp, int64_t hidden) { return kp > 128 ? (kp == 192 ? 4 : 5) : (kp == 64 ? 0 : 2) + (hidden > 32 ? 1 : 0); }
+typedef void (*seq_kernel_t)(SeqChainArgs);
+static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false>, seq_chain_kernel<32, true, false>,
+                                             seq_chain_kernel<64, false, false>, seq_chain_kernel<64, true, false>,
+                                             seq_chain_kernel<96, true, true>,   seq_chain_kernel<128, true, true>};
+
 int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
                      const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr, const int32_t **final_state) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
@@ -492,13 +539,11 @@ int hag_seq_upload(hag_seq_t *h) {
     {
         // workgroups of each kernel variant that the device holds at once (at most the two per compute unit the
         // kernel is tuned for): the grid of a one-launch pass
-        const void *variants[4] = {(const void *)seq_chain_kernel<32, false>, (const void *)seq_chain_kernel<32, true>,
-                                   (const void *)seq_chain_kernel<64, false>, (const void *)seq_chain_kernel<64, true>};
         int cus = 0;
         HIP_TRY(hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, h->device));
-        for (int k = 0; k < 4; ++k) {
+        for (int k = 0; k < 6; ++k) {
             int per_cu = 0;
-            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, variants[k], 512, 0));
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqVariants[k], k >= 4 ? 1024 : 512, 0));
             h->resident[k] = (int64_t)std::min(per_cu, 2) * cus;
         }
     }
@@ -530,8 +575,6 @@ int hag_seq_check(const hag_seq_t *h, void *stream) {
     return HAG_ETIMEOUT;
 }
 
-static int64_t seq_kp(int64_t d, int64_t hidden) { return d + hidden <= 64 ? 64 : 128; }
-
 size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
     if (!h || d <= 0 || hidden <= 0) return 0;
     const size_t states = (size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float);
@@ -545,8 +588,8 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
                          const float *b, float *a_out, void *workspace, void *stream) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
     if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
-    if (d <= 0 || d % 4 != 0 || hidden <= 0 || hidden % 8 != 0 || hidden > 64 || d + hidden > kSeqMaxK) {
-        set_error("d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+    if (d <= 0 || d % 4 != 0 || hidden <= 0 || hidden % 8 != 0 || hidden > 128 || d + hidden > kSeqMaxK) {
+        set_error("d must be a multiple of 4, hidden a multiple of 8 up to 128, d + hidden at most 256");
         return HAG_EINVAL;
     }
     if (h->n == 0) return HAG_OK;
@@ -565,14 +608,13 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
     {
         const int64_t total = (int64_t)4 * hidden * kp;
         hipLaunchKernelGGL(seq_pack_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, w_ih, w_hh, b, wp, bp, (int)d,
-                           (int)hidden, kp, flags, h->n_states);
+                           (int)hidden, kp, kp > 128 ? 1 : 0, flags, h->n_states);
         HIP_TRY(hipGetLastError());
     }
     const int64_t levels = (int64_t)h->tile_ptr.size() - 1;
-    const bool wide = hidden > 32;   // more than four gate tiles
-    // All levels in ONE launch when every workgroup of it can be resident at once (then a workgroup that waits
-    // for a state never keeps the one that writes it off the machine); one launch per level otherwise.
-    const int64_t resident = h->resident[(kp == 64 ? 0 : 2) + (wide ? 1 : 0)];
+    const int variant = seq_variant(kp, hidden);
+    const bool big = variant >= 4;
+    const int64_t resident = h->resident[variant];
     const bool fused = levels > 1 && h->one_launch && resident > 0;
     for (int64_t l = 0; l < (fused ? 1 : levels); ++l) {
         SeqChainArgs c;
@@ -587,14 +629,8 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
         c.x = x; c.wp = wp; c.bp = bp; c.h = hst; c.c = cst; c.a_out = a_out;
         c.d = (int32_t)d; c.hidden = (int32_t)hidden;
         if (c.n_path_tiles <= 0) continue;
-        const dim3 grid((unsigned)std::min<int64_t>(c.n_path_tiles, fused ? resident : 256 * 2)), block(512);
-        if (kp == 64) {
-            if (wide) hipLaunchKernelGGL((seq_chain_kernel<32, true>), grid, block, 0, s, c);
-            else hipLaunchKernelGGL((seq_chain_kernel<32, false>), grid, block, 0, s, c);
-        } else {
-            if (wide) hipLaunchKernelGGL((seq_chain_kernel<64, true>), grid, block, 0, s, c);
-            else hipLaunchKernelGGL((seq_chain_kernel<64, false>), grid, block, 0, s, c);
-        }
+        const dim3 grid((unsigned)std::min<int64_t>(c.n_path_tiles, fused ? resident : (big ? 256 : 512))), block(big ? 1024 : 512);
+        hipLaunchKernelGGL(kSeqVariants[variant], grid, block, 0, s, c);
         HIP_TRY(hipGetLastError());
     }
     {
