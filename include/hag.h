@@ -182,17 +182,20 @@ int64_t hag_seq_launches(const hag_seq_t *h);
 int64_t hag_seq_merges(const hag_seq_t *h);
 /* The plan as the device executes it (host arrays owned by the handle, valid until hag_seq_free; any out
  * pointer may be NULL): the shared prefixes and the nodes' remainders cut into PATHS -- a path carries its
- * running (h, c) from step to step on chip -- grouped into levels, one launch each, a path starting from a
- * state that a lower level wrote.  paths [4 * n_paths]: (state row it starts from or -1 for the zero
- * state, first step, steps, node whose a_v is its last h or -1), level by level, longest first;
- * level_ptr [n_levels + 1] in paths; step_x / step_out [hag_seq_cells]: per step the input row and the
- * state row the step's (h, c) is written to or -1; final_state [n]: the state row holding a_v, -1 for an
- * empty list, -2 where a path writes a_v itself. */
-int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
-                     const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr, const int32_t **final_state);
+ * running (h, c) from step to step on chip -- in groups such that a path starts only from a state that a path
+ * of an EARLIER group writes.  order 0: groups are levels (level 0 starts from the zero state, level l + 1
+ * from states that level l writes), the order of one launch per level; order 1: groups are the depths of the
+ * start states (evaluations behind them), the order of the one-launch pass.  paths [4 * n_paths]: (state row
+ * it starts from or -1 for the zero state, first step, steps, node whose a_v is its last h or -1), group by
+ * group, longest first; level_ptr [n_levels + 1]: the groups, in paths; step_x / step_out [hag_seq_cells]
+ * (the same for both orders): per step the input row and the state row the step's (h, c) is written to or
+ * -1; final_state [n]: the state row holding a_v, -1 for an empty list, -2 where a path writes a_v itself. */
+int hag_seq_get_plan(const hag_seq_t *h, int32_t order, int64_t *n_states, int64_t *n_paths, const int32_t **paths,
+                     const int32_t **step_x, const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr,
+                     const int32_t **final_state);
 int hag_seq_upload(hag_seq_t *h);
 /* With more than one level, hag_seq_lstm_forward runs all of them in ONE launch when every workgroup of it
- * can be resident at once: a tile of paths waits (polling a per-state flag, at most HAG_OPT_SPIN_LIMIT times,
+ * can be resident at once (paths in order 1 of hag_seq_get_plan): a tile of paths waits (polling a per-state flag, at most HAG_OPT_SPIN_LIMIT times,
  * default 2^21, about half a microsecond apart) until the states it starts from are written, by tiles that come
  * before it and never wait for it.  hag_seq_set_option (host state only; later calls): HAG_OPT_SEQ_ONE_LAUNCH
  * (default 1, or the environment's HAG_SEQ_ONE_LAUNCH when the handle was built; 0 = one launch per level, no

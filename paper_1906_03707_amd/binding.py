@@ -97,7 +97,7 @@ def lib():
             getattr(L, name).argtypes = [vp]
             getattr(L, name).restype = i64
         L.hag_seq_upload.argtypes = [vp]
-        L.hag_seq_get_plan.argtypes = [vp] + [vp] * 8
+        L.hag_seq_get_plan.argtypes = [vp, i32] + [vp] * 8
         L.hag_seq_set_option.argtypes = [vp, i32, i64]
         L.hag_seq_check.argtypes = [vp, vp]
         L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
@@ -406,12 +406,13 @@ class SeqHag:
     def merges(self) -> int:
         return int(lib().hag_seq_merges(self._h))
 
-    def plan(self):
-        """(n_states, paths [n_paths, 4], step_x, step_out, level_ptr, final_state) as copies (hag_seq_get_plan)."""
+    def plan(self, order=0):
+        """(n_states, paths [n_paths, 4], step_x, step_out, level_ptr, final_state) as copies (hag_seq_get_plan);
+        order 0: paths grouped by level, 1: by the depth of their start state (the one-launch pass)."""
         i64, p32, p64 = ctypes.c_int64, ctypes.POINTER(ctypes.c_int32), ctypes.POINTER(ctypes.c_int64)
         ns, npaths, nl = i64(), i64(), i64()
         paths, sx, so, fs, lp = p32(), p32(), p32(), p32(), p64()
-        _check(lib().hag_seq_get_plan(self._h, ctypes.byref(ns), ctypes.byref(npaths), ctypes.byref(paths), ctypes.byref(sx),
+        _check(lib().hag_seq_get_plan(self._h, int(order), ctypes.byref(ns), ctypes.byref(npaths), ctypes.byref(paths), ctypes.byref(sx),
                                       ctypes.byref(so), ctypes.byref(nl), ctypes.byref(lp), ctypes.byref(fs)))
         take = lambda ptr, count, dt: (np.ctypeslib.as_array(ptr, shape=(count,)).astype(dt, copy=True) if count else np.zeros(0, dt))
         cells = self.cells

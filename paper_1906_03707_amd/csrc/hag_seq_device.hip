@@ -35,11 +35,18 @@ struct hag_seq {
     std::vector<int32_t> paths, step_x, step_out;
     std::vector<int64_t> level_ptr;   // paths of level l: [level_ptr[l], level_ptr[l+1])
     std::vector<int64_t> tile_ptr;    // tiles of 64 paths of level l: [tile_ptr[l], tile_ptr[l+1]) (a tile never mixes levels)
+    // The same paths in the order of the one-launch pass: grouped by the DEPTH of the state they start from (the
+    // number of evaluations behind it; 0 for the zero state), longest first within a group.  A path that writes a
+    // state starts from a shallower one, so here too a path depends only on earlier groups; and the order follows
+    // the time at which start states become available, which keeps tiles from waiting.
+    std::vector<int32_t> paths_by_depth;
+    std::vector<int64_t> depth_ptr, depth_tile_ptr;
     int64_t longest = 0;
     bool one_launch = true;           // HAG_SEQ_ONE_LAUNCH (default 1): all levels in one launch, paths waiting for the states they start from
     int32_t spin_limit = 1 << 21;     // HAG_SPIN_LIMIT: polls (about half a microsecond apart) after which such a wait gives up
     bool wait_unreachable = false;    // tests only: flags are never set, so every wait gives up
     int32_t *d_final = nullptr, *d_paths = nullptr, *d_step_x = nullptr, *d_step_out = nullptr;   // d_paths: padded to whole tiles per level
+    int32_t *d_paths_by_depth = nullptr;                    // likewise per depth group
     int64_t resident[6] = {0, 0, 0, 0, 0, 0};   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
     int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
     int device = -1;
@@ -458,6 +465,31 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
         h->tile_ptr.assign((size_t)levels + 1, 0);
         for (int32_t l = 0; l < levels; ++l)
             h->tile_ptr[(size_t)l + 1] = h->tile_ptr[l] + (h->level_ptr[(size_t)l + 1] - h->level_ptr[l] + kSeqJobs - 1) / kSeqJobs;
+        {
+            const int64_t np = (int64_t)(h->paths.size() / 4);
+            std::vector<int32_t> key((size_t)np), order((size_t)np);
+            int32_t groups = 0;
+            for (int64_t i = 0; i < np; ++i) {
+                const int32_t start = h->paths[i * 4];
+                key[i] = start < 0 ? 0 : depth[start];
+                order[i] = (int32_t)i;
+                groups = std::max(groups, key[i] + 1);
+            }
+            std::stable_sort(order.begin(), order.end(), [&](int32_t p, int32_t q) {
+                return key[p] != key[q] ? key[p] < key[q] : h->paths[(size_t)p * 4 + 2] > h->paths[(size_t)q * 4 + 2];
+            });
+            h->depth_ptr.assign((size_t)groups + 1, 0);
+            h->paths_by_depth.reserve(h->paths.size());
+            for (int32_t i : order) {
+                ++h->depth_ptr[(size_t)key[i] + 1];
+                h->paths_by_depth.insert(h->paths_by_depth.end(), h->paths.begin() + (size_t)i * 4, h->paths.begin() + (size_t)i * 4 + 4);
+            }
+            h->depth_tile_ptr.assign((size_t)groups + 1, 0);
+            for (int32_t g = 0; g < groups; ++g) {
+                h->depth_tile_ptr[(size_t)g + 1] = h->depth_tile_ptr[g] + (h->depth_ptr[(size_t)g + 1] + kSeqJobs - 1) / kSeqJobs;
+                h->depth_ptr[(size_t)g + 1] += h->depth_ptr[g];
+            }
+        }
         *out = h;
         return HAG_OK;
     } catch (const std::bad_alloc &) {
@@ -473,6 +505,7 @@ void hag_seq_free(hag_seq_t *h) {
     if (!h) return;
     if (h->d_final) (void)hipFree(h->d_final);
     if (h->d_paths) (void)hipFree(h->d_paths);
+    if (h->d_paths_by_depth) (void)hipFree(h->d_paths_by_depth);
     if (h->d_step_x) (void)hipFree(h->d_step_x);
     if (h->d_step_out) (void)hipFree(h->d_step_out);
     if (h->d_gave_up) (void)hipFree(h->d_gave_up);
@@ -500,16 +533,18 @@ static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false>,
                                              seq_chain_kernel<64, false, false>, seq_chain_kernel<64, true, false>,
                                              seq_chain_kernel<96, true, true>,   seq_chain_kernel<128, true, true>};
 
-int hag_seq_get_plan(const hag_seq_t *h, int64_t *n_states, int64_t *n_paths, const int32_t **paths, const int32_t **step_x,
-                     const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr, const int32_t **final_state) {
+int hag_seq_get_plan(const hag_seq_t *h, int32_t order, int64_t *n_states, int64_t *n_paths, const int32_t **paths,
+                     const int32_t **step_x, const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr,
+                     const int32_t **final_state) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (order != 0 && order != 1) { set_error("order must be 0 (levels) or 1 (depth of the start state)"); return HAG_EINVAL; }
     if (n_states) *n_states = h->n_states;
     if (n_paths) *n_paths = (int64_t)(h->paths.size() / 4);
-    if (paths) *paths = h->paths.data();
+    if (paths) *paths = order ? h->paths_by_depth.data() : h->paths.data();
     if (step_x) *step_x = h->step_x.data();
     if (step_out) *step_out = h->step_out.data();
-    if (n_levels) *n_levels = (int64_t)h->level_ptr.size() - 1;
-    if (level_ptr) *level_ptr = h->level_ptr.data();
+    if (n_levels) *n_levels = (int64_t)(order ? h->depth_ptr.size() : h->level_ptr.size()) - 1;
+    if (level_ptr) *level_ptr = order ? h->depth_ptr.data() : h->level_ptr.data();
     if (final_state) *final_state = h->final_state.data();
     return HAG_OK;
 }
@@ -524,14 +559,18 @@ int hag_seq_upload(hag_seq_t *h) {
         return e;
     };
     {
-        // every level padded to whole tiles with empty paths (no start state, no steps, no node)
-        std::vector<int32_t> padded;
-        padded.reserve((size_t)h->tile_ptr.back() * kSeqJobs * 4);
-        for (size_t l = 0; l + 1 < h->level_ptr.size(); ++l) {
-            padded.insert(padded.end(), h->paths.begin() + h->level_ptr[l] * 4, h->paths.begin() + h->level_ptr[l + 1] * 4);
-            while ((int64_t)padded.size() < h->tile_ptr[l + 1] * kSeqJobs * 4) { padded.push_back(-1); padded.push_back(0); padded.push_back(0); padded.push_back(-1); }
-        }
-        HIP_TRY(put(&h->d_paths, padded));
+        // every group padded to whole tiles with empty paths (no start state, no steps, no node)
+        auto padded = [](const std::vector<int32_t> &paths, const std::vector<int64_t> &ptr, const std::vector<int64_t> &tiles) {
+            std::vector<int32_t> out;
+            out.reserve((size_t)tiles.back() * kSeqJobs * 4);
+            for (size_t l = 0; l + 1 < ptr.size(); ++l) {
+                out.insert(out.end(), paths.begin() + ptr[l] * 4, paths.begin() + ptr[l + 1] * 4);
+                while ((int64_t)out.size() < tiles[l + 1] * kSeqJobs * 4) { out.push_back(-1); out.push_back(0); out.push_back(0); out.push_back(-1); }
+            }
+            return out;
+        };
+        HIP_TRY(put(&h->d_paths, padded(h->paths, h->level_ptr, h->tile_ptr)));
+        HIP_TRY(put(&h->d_paths_by_depth, padded(h->paths_by_depth, h->depth_ptr, h->depth_tile_ptr)));
     }
     HIP_TRY(put(&h->d_step_x, h->step_x));
     HIP_TRY(put(&h->d_step_out, h->step_out));
@@ -618,8 +657,8 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
     const bool fused = levels > 1 && h->one_launch && resident > 0;
     for (int64_t l = 0; l < (fused ? 1 : levels); ++l) {
         SeqChainArgs c;
-        const int64_t t0 = fused ? 0 : h->tile_ptr[l], t1 = fused ? h->tile_ptr[levels] : h->tile_ptr[l + 1];
-        c.chains = h->d_paths + t0 * kSeqJobs * 4;
+        const int64_t t0 = fused ? 0 : h->tile_ptr[l], t1 = fused ? h->depth_tile_ptr.back() : h->tile_ptr[l + 1];
+        c.chains = fused ? h->d_paths_by_depth : h->d_paths + t0 * kSeqJobs * 4;
         c.n_path_tiles = t1 - t0;
         c.flags = fused ? flags : nullptr;
         c.spin_limit = h->spin_limit;

@@ -173,11 +173,12 @@ def test_lstm_plan_counts_match_the_oracle():
             assert plan.launches == 1
 
 
-def replay_plan(plan, n, x, w_ih, w_hh, b):
+def replay_plan(plan, n, x, w_ih, w_hh, b, order=0):
     """The plan of hag_seq_create executed step by step with the oracle's cell, one level after the other, checking
-    on the way what the device relies on: a path starts only from a state that a LOWER level has written, every
+    on the way what the device relies on: a path starts only from a state that an EARLIER group (order 0: level,
+    order 1: depth of the start state) has written, every
     state row is written at most once, paths of a level are sorted by length."""
-    n_states, paths, step_x, step_out, level_ptr, final_state = plan.plan()
+    n_states, paths, step_x, step_out, level_ptr, final_state = plan.plan(order)
     hidden = w_hh.shape[1]
     h_rows, c_rows = np.full((max(n_states, 1), hidden), np.nan), np.full((max(n_states, 1), hidden), np.nan)
     written_at = np.full(max(n_states, 1), -1)
@@ -230,6 +231,9 @@ def test_lstm_plan_replayed_on_the_host_equals_the_naive_walk(seed):
         plan = B.SeqHag(rowptr, col, cap)
         got, cells, kept = replay_plan(plan, n, x, w_ih, w_hh, b)
         assert np.array_equal(got, want)                  # the same cells in the same order along every list
+        got1, cells1, kept1 = replay_plan(plan, n, x, w_ih, w_hh, b, order=1)      # the order of the one-launch pass
+        assert np.array_equal(got1, want) and (cells1, kept1) == (cells, kept)
+        assert sorted(map(tuple, plan.plan(0)[1])) == sorted(map(tuple, plan.plan(1)[1]))   # the same paths, regrouped
         assert cells == plan.cells
         if cap == 0:
             assert kept == 0 and plan.launches == (1 if col.size else 0)
