@@ -201,7 +201,11 @@ int hag_seq_upload(hag_seq_t *h);
  * (default 1, or the environment's HAG_SEQ_ONE_LAUNCH when the handle was built; 0 = one launch per level, no
  * waits), HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE (tests only: no flag is ever set, so every wait
  * gives up).  hag_seq_check synchronises `stream` and returns HAG_OK, or HAG_ETIMEOUT if a wait on this handle
- * gave up since the last check (its output is not valid; the state is cleared). */
+ * gave up since the last check (its output is not valid; the state is cleared).
+ * The one-launch pass fills the device with workgroups that may wait for one another, which is safe because all of
+ * them are resident; two such passes running at the same time on one device (two streams, two processes) can each
+ * hold the places the other's remaining workgroups need, and then both time out.  Callers that overlap passes on
+ * one device set HAG_OPT_SEQ_ONE_LAUNCH to 0. */
 int hag_seq_set_option(hag_seq_t *h, int32_t option, int64_t value);
 int hag_seq_check(const hag_seq_t *h, void *stream);
 size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);

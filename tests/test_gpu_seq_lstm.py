@@ -140,6 +140,41 @@ def test_bench_workload_sampled_nodes(B, width):
     assert torch.equal(results[0], results[1]) and torch.equal(results[0], results[2])
 
 
+def test_degenerate_shapes(B):
+    # no nodes; nodes without any list; one-entry lists only (every a_v is a shared one-element prefix); one list much
+    # longer than a tile is wide, next to short ones (a tile whose paths end far apart); a list that repeats one node
+    d, hidden = 8, 16
+    w_ih, w_hh, b = params(d, hidden, 2)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    wid, whd, bd = dev(w_ih), dev(w_hh), dev(b)
+    h = B.SeqHag(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4).upload()
+    assert h.cells == 0 and h.launches == 0
+    assert h.lstm_forward(torch.zeros((0, d), device="cuda"), wid, whd, bd).shape == (0, hidden)
+    rng = np.random.default_rng(3)
+    cases = {
+        "all empty": (np.zeros(6, dtype=np.int64), np.zeros(0, dtype=np.int32)),
+        "one entry each": (np.arange(0, 41, dtype=np.int64), rng.integers(0, 5, 40).astype(np.int32)),
+        "one long list": (np.concatenate([[0], np.cumsum([300] + [2] * 99)]).astype(np.int64),
+                          np.concatenate([rng.integers(0, 100, 300), np.tile([7, 9], 99)]).astype(np.int32)),
+        "one node repeated": (np.array([0, 50, 75, 75], dtype=np.int64), np.full(75, 2, dtype=np.int32)),
+    }
+    for name, (rowptr, col) in cases.items():
+        n = rowptr.size - 1
+        x = np.random.default_rng(4).normal(size=(n, d))
+        xd = dev(x)
+        want, _ = lstm.naive_aggregate(rowptr, col, xd.cpu().numpy().astype(np.float64), wid.cpu().numpy().astype(np.float64),
+                                       whd.cpu().numpy().astype(np.float64), bd.cpu().numpy().astype(np.float64))
+        for cap in (0, max(n // 4, 1), max(int(col.size), 1)):
+            h = B.SeqHag(rowptr, col, cap).upload()
+            for one_launch in (1, 0):
+                h.set_option(B.HAG_OPT_SEQ_ONE_LAUNCH, one_launch)
+                got = h.lstm_forward(xd, wid, whd, bd)
+                h.check()
+                err = np.abs(got.cpu().numpy().astype(np.float64) - want).max() if n else 0.0
+                # 300 steps: the forget gate keeps the accumulated rounding error bounded, the tolerance of the short chains holds
+                assert err <= ATOL, f"{name}, capacity {cap}, one_launch {one_launch}: {err}"
+
+
 def test_rejections(B):
     rowptr, col = route_graph(20, 4, seed=3)
     h = B.SeqHag(rowptr, col, 3)

@@ -239,3 +239,29 @@ def test_lstm_plan_replayed_on_the_host_equals_the_naive_walk(seed):
             assert kept == 0 and plan.launches == (1 if col.size else 0)
         else:
             assert kept < plan.cells                      # most states never leave the path that computes them
+
+
+def test_lstm_plan_of_degenerate_inputs():
+    # no nodes, no lists, one-entry lists, one list far longer than the rest, one node repeated: the plan replayed on the host
+    rng = np.random.default_rng(3)
+    cases = {
+        "all empty": (np.zeros(6, dtype=np.int64), np.zeros(0, dtype=np.int32)),
+        "one entry each": (np.arange(0, 41, dtype=np.int64), rng.integers(0, 5, 40).astype(np.int32)),
+        "one long list": (np.concatenate([[0], np.cumsum([300] + [2] * 99)]).astype(np.int64),
+                          np.concatenate([rng.integers(0, 100, 300), np.tile([7, 9], 99)]).astype(np.int32)),
+        "one node repeated": (np.array([0, 50, 75, 75], dtype=np.int64), np.full(75, 2, dtype=np.int32)),
+    }
+    w_ih, w_hh, b = rng.normal(0, 0.4, (8, 3)), rng.normal(0, 0.4, (8, 2)), rng.normal(0, 0.4, 8)
+    for name, (rowptr, col) in cases.items():
+        n = rowptr.size - 1
+        x = rng.normal(size=(n, 3))
+        want, cells_naive = lstm.naive_aggregate(rowptr, col, x, w_ih, w_hh, b)
+        for cap in (0, max(n // 4, 1), max(int(col.size), 1)):
+            plan = B.SeqHag(rowptr, col, cap)
+            assert plan.cells <= cells_naive and plan.ranks == (int(np.diff(rowptr).max()) if col.size else 0)
+            for order in (0, 1):
+                got, cells, _ = replay_plan(plan, n, x, w_ih, w_hh, b, order)
+                assert np.array_equal(got, want), (name, cap, order)
+                assert cells == plan.cells
+    empty = B.SeqHag(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4)
+    assert (empty.cells, empty.launches, empty.ranks) == (0, 0, 0)
