@@ -153,7 +153,6 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
     constexpr int HS = HMAX + 1, JG = WIDE ? 2 : 1;
     constexpr int TPP = BIG ? 16 : 8;                      // threads per path in the staging phases
     __shared__ float z[kSeqJobs * ZS];
-    __shared__ float hs[kSeqJobs * HS];
     __shared__ float cs[kSeqJobs * HS];
     __shared__ __align__(16) float sb[4 * (BIG ? 128 : 64)];
     __shared__ int32_t sdesc[kSeqJobs * 4];
@@ -253,7 +252,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
             } else if (tile < n_tiles) {                   // (a wavefront without a gate tile has nothing to stream)
                 const float4 *wq = reinterpret_cast<const float4 *>(A.wp) + (size_t)tile * (KSTEPS / 4) * 64 + lane;
                 float4 wa = wq[0];
-#pragma unroll 4
+#pragma unroll 16
                 for (int q = 0; q < KSTEPS / 4; ++q) {
                     const float4 wn = wq[(q + 1 < KSTEPS / 4 ? q + 1 : q) * 64];
                     const float w4[4] = {wa.x, wa.y, wa.z, wa.w};
@@ -266,6 +265,16 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
                     wa = wn;
                 }
             }
+            __syncthreads();                               // every product has read z
+            // the state row this step writes, if any: asked for now, used after the next barrier
+            int keep = -1;
+            {
+                const int tid1 = seq_opaque(threadIdx.x), sj1 = tid1 / TPP;
+                if (t < sdesc[sj1 * 4 + 2]) keep = A.step_out[sdesc[sj1 * 4 + 1] + t];
+            }
+            // element-wise part: lane l holds, for path l % 32 of its half, gate rows 8 * (r / 4) + 4 * (l / 32) + r % 4 of the
+            // gate tile, i.e. the four gates (r % 4) of hidden units 2 * (r / 4) + l / 32 of the tile; the new h goes straight
+            // into the operand rows of the next step
             if (tile < n_tiles) {
 #pragma unroll
                 for (int g = 0; g < JG; ++g) {
@@ -277,33 +286,13 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
                             const float c_new = seq_sigmoid(acc[g][4 * m + 1]) * cs[j * HS + unit] +
                                                 seq_sigmoid(acc[g][4 * m + 0]) * seq_tanh(acc[g][4 * m + 2]);
                             cs[j * HS + unit] = c_new;
-                            hs[j * HS + unit] = seq_sigmoid(acc[g][4 * m + 3]) * seq_tanh(c_new);
+                            z[j * ZS + d + unit] = seq_sigmoid(acc[g][4 * m + 3]) * seq_tanh(c_new);
                         }
                     }
                 }
             }
-            __syncthreads();                               // every product has read z, every new h is in hs
-            int keep = -1;
             {
                 const int tid2 = seq_opaque(threadIdx.x), sj2 = tid2 / TPP, part2 = tid2 % TPP;
-                if (t < sdesc[sj2 * 4 + 2]) {
-                    keep = A.step_out[sdesc[sj2 * 4 + 1] + t];
-                    for (int u = part2 * 4; u < hidden; u += 4 * TPP) {
-                        const float *ph = &hs[sj2 * HS + u];
-                        *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u]) = make_float2(ph[0], ph[1]);
-                        *reinterpret_cast<float2 *>(&z[sj2 * ZS + d + u + 2]) = make_float2(ph[2], ph[3]);
-                        if (keep >= 0) {                   // a state that another path starts from, or some a_v
-                            const float *pc = &cs[sj2 * HS + u];
-                            if (A.flags) {
-                                seq_st4_device(A.h + (size_t)keep * hidden + u, make_float4(ph[0], ph[1], ph[2], ph[3]));
-                                seq_st4_device(A.c + (size_t)keep * hidden + u, make_float4(pc[0], pc[1], pc[2], pc[3]));
-                            } else {
-                                *reinterpret_cast<float4 *>(A.h + (size_t)keep * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
-                                *reinterpret_cast<float4 *>(A.c + (size_t)keep * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
-                            }
-                        }
-                    }
-                }
                 if (row1 >= 0) {
 #pragma unroll
                     for (int i = 0; i < ZV; ++i) {
@@ -316,11 +305,26 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
                     }
                 }
             }
-            // a state's flag is set once all eight threads of its path have seen their stores complete (the barrier
-            // itself does not wait for stores to global memory)
-            if (A.flags && keep >= 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-            __syncthreads();
-            if (A.flags && A.publish && keep >= 0 && threadIdx.x % TPP == 0) __hip_atomic_store(A.flags + keep, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            __syncthreads();                               // the operand rows and cell states of the next step are complete
+            if (keep >= 0) {                               // a state that another path starts from, or some a_v
+                const int tid3 = seq_opaque(threadIdx.x), sj3 = tid3 / TPP, part3 = tid3 % TPP;
+                for (int u = part3 * 4; u < hidden; u += 4 * TPP) {
+                    const float *ph = &z[sj3 * ZS + d + u], *pc = &cs[sj3 * HS + u];
+                    if (A.flags) {
+                        seq_st4_device(A.h + (size_t)keep * hidden + u, make_float4(ph[0], ph[1], ph[2], ph[3]));
+                        seq_st4_device(A.c + (size_t)keep * hidden + u, make_float4(pc[0], pc[1], pc[2], pc[3]));
+                    } else {
+                        *reinterpret_cast<float4 *>(A.h + (size_t)keep * hidden + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
+                        *reinterpret_cast<float4 *>(A.c + (size_t)keep * hidden + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
+                    }
+                }
+                if (A.flags) {
+                    // the threads of a path are adjacent lanes of one wavefront: once the wavefront has seen its stores complete,
+                    // the whole row is out, and one of them sets the state's flag
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (A.publish && part3 == 0) __hip_atomic_store(A.flags + keep, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
         }
         // a_v = the last h of the path, where the path ends a node's list
         const int tid = seq_opaque(threadIdx.x), sj = tid / TPP, part = tid % TPP;
