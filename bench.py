@@ -447,7 +447,11 @@ def main():
         main_plan = res["plans"][args.seq_plan or "hag_quarter"]
         print(json.dumps({"metric": "LSTM aggregator over ordered lists, forward: cell evaluations/s", "unit": "cells/s",
                           "value": main_plan["cells"] / (main_plan["ms_per_pass"] * 1e-3),
-                          "n_gpus": 1, "dtype": "f32", "data": "synthetic", "config": res}), flush=True)
+                          "n_gpus": 1, "dtype": "f32", "data": "synthetic", "higher_is_better": True, "vs_baseline": None,
+                          # the pass is one launch of the cell kernel: its flops over the pass's time (pack and output kernels included)
+                          "roofline": {"bound": "mfma", "achieved": main_plan["tflops"], "peak": FP32_MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+                                       "frac": main_plan["tflops"] / FP32_MFMA_PEAK_TFLOPS, "traffic": None},
+                          "config": res}), flush=True)
         return
     if cfg == 5:
         sweep_config5(torch, synth, workloads, max(min(args.steps, 10), 3), 2)
