@@ -252,7 +252,8 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
             } else if (tile < n_tiles) {                   // (a wavefront without a gate tile has nothing to stream)
                 const float4 *wq = reinterpret_cast<const float4 *>(A.wp) + (size_t)tile * (KSTEPS / 4) * 64 + lane;
                 float4 wa = wq[0];
-#pragma unroll 16
+                constexpr int UNR = KSTEPS == 96 ? 12 : 16;   // a divisor of the trip count: how far the loads run ahead within the registers there are
+#pragma unroll UNR
                 for (int q = 0; q < KSTEPS / 4; ++q) {
                     const float4 wn = wq[(q + 1 < KSTEPS / 4 ? q + 1 : q) * 64];
                     const float w4[4] = {wa.x, wa.y, wa.z, wa.w};
