@@ -359,6 +359,24 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.launches} launches, "
             f"{ms:.3f} ms per pass ({ms_base / ms:.2f}x the plain lists' speed), {tf:.1f} TFLOP/s = "
             f"{100 * tf / FP32_MFMA_PEAK_TFLOPS:.1f}% of the fp32 matrix-core peak")
+    # inference latency of a 2-layer GraphSAGE with LSTM aggregators around the same passes (Section 5.3 reports inference
+    # latency next to training time); dense Update in torch, `hidden` wide throughout, 16 classes
+    from paper_1906_03707_amd import layers
+    gen = torch.Generator(device="cuda").manual_seed(3)
+    dims = [d, hidden, 16]
+    cells = [(torch.randn(4 * hidden, dims[i], device="cuda", generator=gen) * 0.3, torch.randn(4 * hidden, hidden, device="cuda", generator=gen) * 0.3,
+              torch.randn(4 * hidden, device="cuda", generator=gen) * 0.3) for i in range(2)]
+    comb = [torch.randn(hidden + dims[i], dims[i + 1], device="cuda", generator=gen) / (hidden + dims[i]) ** 0.5 for i in range(2)]
+    infer = {name: (lambda p=p: layers.sage_lstm2_logits(p, x, cells, comb)) for name, p in plans.items()}
+    for name, fn in infer.items():
+        if name == "lists" or "lists" not in infer:
+            ms, _ = time_steps(torch, fn, steps, warmup)
+            ms_base = ms if name == "lists" else float("nan")
+        else:
+            (ms, _), (ms_base, _) = time_interleaved(torch, fn, infer["lists"], steps, warmup)
+        res["plans"][name]["sage_lstm2_inference_ms"] = ms
+        res["plans"][name]["sage_lstm2_inference_speedup_vs_lists"] = ms_base / ms
+        log(f"[bench] 2-layer GraphSAGE-LSTM inference, {name}: {ms:.3f} ms ({ms_base / ms:.2f}x the plain lists' speed)")
     return res
 
 

@@ -118,3 +118,22 @@ def sage_pool2(rowptr, col, x, pool, comb, labels):
     g_o1, g_p1, g_c1 = sage_pool_layer_backward(c2, g)
     g_x, g_p0, g_c0 = sage_pool_layer_backward(c1, g_o1)
     return dict(loss=loss, logits=o2, g_pool=[g_p0, g_p1], g_comb=[g_c0, g_c1], g_x=g_x)
+
+
+def sage_lstm_layer(rowptr, col, h, w_ih, w_hh, b, w2, relu_out=True):
+    """One GraphSAGE layer with an LSTM aggregator over the ORDERED lists N(v) (the sequential Aggregate of
+    Section 3.1; Update as in Table 1's pooling row): a_v = the last hidden state of the LSTM run over
+    (h_u : u in N(v)) from the zero state, h'_v = relu(W2 [a_v, h_v])."""
+    from . import lstm
+    h, w2 = np.asarray(h, dtype=np.float64), np.asarray(w2, dtype=np.float64)
+    a, _ = lstm.naive_aggregate(rowptr, col, h, np.asarray(w_ih, dtype=np.float64), np.asarray(w_hh, dtype=np.float64),
+                                np.asarray(b, dtype=np.float64))
+    pre = np.concatenate([a, h], axis=1) @ w2
+    return np.maximum(pre, 0.0) if relu_out else pre
+
+
+def sage_lstm2_logits(rowptr, col, x, cells, comb):
+    """Logits of a 2-layer GraphSAGE with LSTM aggregators (inference): cells[i] = (w_ih, w_hh, b) of layer i,
+    comb[i] = W2 of layer i [hidden_i + d_i, d_{i+1}]; the second layer has no ReLU."""
+    h1 = sage_lstm_layer(rowptr, col, x, *cells[0], comb[0], relu_out=True)
+    return sage_lstm_layer(rowptr, col, h1, *cells[1], comb[1], relu_out=False)

@@ -68,3 +68,18 @@ def sage_pool2_loss(h, x, pool, comb, labels, naive=False, record=None):
         if i == 0:
             hcur = torch.relu(hcur)
     return torch.nn.functional.cross_entropy(hcur, labels)
+
+
+def sage_lstm2_logits(seq, x, cells, comb):
+    """Logits of a 2-layer GraphSAGE with LSTM aggregators over ordered neighbour lists (inference only: the
+    library's LSTM aggregator has no backward pass).  seq: binding.SeqHag (a prefix HAG or the plain lists);
+    cells[i] = (w_ih, w_hh, b) of layer i; comb[i] = W2 of layer i, [hidden_i + d_i, d_{i+1}].
+    a_v = LSTM over (h_u : u in N(v)), h'_v = relu(W2 [a_v, h_v]); the second layer has no ReLU."""
+    with torch.no_grad():
+        h = x
+        for i in range(2):
+            a = seq.lstm_forward(h.contiguous(), *cells[i])
+            h = torch.cat([a, h], dim=1) @ comb[i]
+            if i == 0:
+                h = torch.relu(h)
+        return h

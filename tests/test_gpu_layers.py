@@ -105,3 +105,30 @@ def test_two_layer_graphsage_pool_forward_and_backward(B, naive):
         for i in range(2):
             assert rel(pd[i].grad.cpu().numpy(), ref["g_pool"][i]) <= 1e-4, (name, i)
             assert rel(cd[i].grad.cpu().numpy(), ref["g_comb"][i]) <= 1e-4, (name, i)
+
+
+@pytest.mark.parametrize("capacity", ["lists", "quarter", "unlimited"])
+def test_two_layer_graphsage_lstm_inference(B, capacity):
+    # 2-layer GraphSAGE with LSTM aggregators over ordered lists (first 12 neighbours of a power-law graph), inference:
+    # the aggregation of each layer is the library's LSTM aggregator over the plain lists or a prefix HAG, the dense
+    # Update is torch.  Against the fp64 layer oracle, norm-wise (fp32 GEMMs and ReLU around the aggregator).
+    from paper_1906_03707_amd import layers, workloads
+    rowptr, col = synth.holme_kim(1500, 8, 0.5, seed=93)
+    rp, cl = workloads.first_neighbour_lists(rowptr, col, 12)
+    n, d, hidden, classes = rp.size - 1, 24, 32, 8
+    rng = np.random.default_rng(94)
+    dims = [d, hidden, classes]
+    cells = [(rng.normal(0, 0.3, (4 * hidden, dims[i])), rng.normal(0, 0.3, (4 * hidden, hidden)), rng.normal(0, 0.3, 4 * hidden))
+             for i in range(2)]
+    comb = [rng.normal(0, 1.0 / np.sqrt(hidden + dims[i]), (hidden + dims[i], dims[i + 1])) for i in range(2)]
+    x = rng.normal(size=(n, d))
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    r64 = lambda a: dev(a).cpu().numpy().astype(np.float64)          # the oracle sees the fp32-rounded values
+    want = OL.sage_lstm2_logits(rp, cl, r64(x), [tuple(r64(a) for a in c) for c in cells], [r64(w) for w in comb])
+    cap = {"lists": 0, "quarter": n // 4, "unlimited": int(cl.size)}[capacity]
+    seq = B.SeqHag(rp, cl, cap).upload()
+    got = layers.sage_lstm2_logits(seq, dev(x), [tuple(dev(a) for a in c) for c in cells], [dev(w) for w in comb])
+    seq.check()
+    err = rel(got.cpu().numpy(), want)
+    print(f"{capacity}: {seq.cells} cells, relative error of the logits {err:.2e}")
+    assert err <= 1e-5

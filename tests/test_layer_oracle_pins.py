@@ -96,3 +96,31 @@ def test_layer_gradients_match_finite_differences():
                                    finite_difference(lambda: L.sage_pool2(rowptr, col, x, pool, comb, labels)["loss"], pool[i]), atol=1e-7)
         np.testing.assert_allclose(r["g_comb"][i],
                                    finite_difference(lambda: L.sage_pool2(rowptr, col, x, pool, comb, labels)["loss"], comb[i]), atol=1e-7)
+
+
+def test_sage_lstm_layer_against_library_modules():
+    # the layer composed from a library LSTM (run list by list), concatenation and a library linear map, in fp64
+    torch = __import__("pytest").importorskip("torch")
+    rng = np.random.default_rng(17)
+    n, d, hidden, out = 9, 4, 3, 5
+    rowptr = np.array([0, 3, 3, 5, 9, 10, 12, 12, 14, 15], dtype=np.int64)
+    col = np.array([2, 0, 1, 4, 4, 6, 5, 0, 2, 3, 1, 1, 8, 7, 0], dtype=np.int32)
+    h = rng.normal(size=(n, d))
+    w_ih, w_hh, b = rng.normal(0, 0.5, (4 * hidden, d)), rng.normal(0, 0.5, (4 * hidden, hidden)), rng.normal(0, 0.5, 4 * hidden)
+    w2 = rng.normal(0, 0.5, (hidden + d, out))
+    got = L.sage_lstm_layer(rowptr, col, h, w_ih, w_hh, b, w2, relu_out=True)
+    net = torch.nn.LSTM(d, hidden, batch_first=True).double()
+    lin = torch.nn.Linear(hidden + d, out, bias=False).double()
+    with torch.no_grad():
+        net.weight_ih_l0.copy_(torch.from_numpy(w_ih)); net.weight_hh_l0.copy_(torch.from_numpy(w_hh))
+        net.bias_ih_l0.copy_(torch.from_numpy(b)); net.bias_hh_l0.zero_()
+        lin.weight.copy_(torch.from_numpy(w2.T))
+        ht = torch.from_numpy(h)
+        a = torch.zeros((n, hidden), dtype=torch.float64)
+        for v in range(n):
+            ids = col[rowptr[v]:rowptr[v + 1]].astype(np.int64)
+            if ids.size:
+                a[v] = net(ht[torch.from_numpy(ids)][None])[1][0][0, 0]
+        want = torch.relu(lin(torch.cat([a, ht], dim=1))).numpy()
+    np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
+    assert (got[[1, 6]] == np.maximum(np.concatenate([np.zeros((2, hidden)), h[[1, 6]]], axis=1) @ w2, 0)).all()   # empty lists: a_v = 0
