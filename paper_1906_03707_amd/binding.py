@@ -31,7 +31,7 @@ EXPORTS = [
     "hag_get_merges", "hag_get_forward", "hag_upload", "hag_workspace_bytes", "hag_forward",
     "hag_backward", "hag_forward_phases", "hag_backward_phases", "hag_naive_forward", "hag_naive_backward",
     "hag_algorithmic_bytes", "hag_last_error", "hag_forward_static_scratch", "hag_probe_rows", "hag_probe_copy", "hag_probe_mfma_f32", "hag_set_option", "hag_check", "hag_seq_search",
-    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_get_plan", "hag_seq_set_option", "hag_seq_check", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
+    "hag_seq_create", "hag_seq_free", "hag_seq_cells", "hag_seq_ranks", "hag_seq_launches", "hag_seq_get_plan", "hag_seq_set_option", "hag_seq_check", "hag_seq_train_workspace_bytes", "hag_seq_lstm_forward_train", "hag_seq_lstm_backward", "hag_seq_merges", "hag_seq_upload", "hag_seq_workspace_bytes",
     "hag_seq_lstm_forward",
 ]
 HAG_STATIC_SCRATCH_BYTES = 64 << 20
@@ -100,6 +100,10 @@ def lib():
         L.hag_seq_get_plan.argtypes = [vp, i32] + [vp] * 8
         L.hag_seq_set_option.argtypes = [vp, i32, i64]
         L.hag_seq_check.argtypes = [vp, vp]
+        L.hag_seq_train_workspace_bytes.argtypes = [vp, i64, i64]
+        L.hag_seq_train_workspace_bytes.restype = ctypes.c_size_t
+        L.hag_seq_lstm_forward_train.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
+        L.hag_seq_lstm_backward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
         L.hag_seq_workspace_bytes.restype = ctypes.c_size_t
         L.hag_seq_lstm_forward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
@@ -426,6 +430,45 @@ class SeqHag:
     def set_option(self, option, value):
         _check(lib().hag_seq_set_option(self._h, int(option), int(value)))
         return self
+
+    def train_workspace_bytes(self, d, hidden) -> int:
+        return int(lib().hag_seq_train_workspace_bytes(self._h, int(d), int(hidden)))
+
+    def lstm_forward_train(self, x, w_ih, w_hh, b, workspace=None):
+        """As lstm_forward, keeping what lstm_backward needs; returns (a [n, H], workspace)."""
+        import torch
+        hidden, d = int(w_hh.shape[1]), int(x.shape[1])
+        for name, t, shape in (("x", x, (self.n, d)), ("w_ih", w_ih, (4 * hidden, d)), ("w_hh", w_hh, (4 * hidden, hidden)),
+                               ("b", b, (4 * hidden,))):
+            if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"{name} must be a contiguous float32 device tensor of shape {shape}")
+        need = self.train_workspace_bytes(d, hidden)
+        if need == 0:
+            raise ValueError("training needs hidden <= 64 and d + hidden <= 128 (d a multiple of 4, hidden of 8)")
+        if workspace is None:
+            workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
+        elif workspace.numel() * workspace.element_size() < need or workspace.device != x.device:
+            raise ValueError("workspace too small or on another device")
+        out = torch.empty((self.n, hidden), dtype=torch.float32, device=x.device)
+        _check(lib().hag_seq_lstm_forward_train(self._h, d, hidden, _dev_ptr(x), _dev_ptr(w_ih), _dev_ptr(w_hh), _dev_ptr(b),
+                                                _dev_ptr(out), _dev_ptr(workspace), _stream_ptr()))
+        return out, workspace
+
+    def lstm_backward(self, x, g_a, hidden, workspace):
+        """Gradients (g_x, g_w_ih, g_w_hh, g_b) of a loss with gradient g_a [n, H] at a_out, after lstm_forward_train with
+        the same x and workspace."""
+        import torch
+        d = int(x.shape[1])
+        for name, t, shape in (("x", x, (self.n, d)), ("g_a", g_a, (self.n, hidden))):
+            if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
+                raise ValueError(f"{name} must be a contiguous float32 device tensor of shape {shape}")
+        if workspace.numel() * workspace.element_size() < self.train_workspace_bytes(d, hidden) or workspace.device != x.device:
+            raise ValueError("workspace too small or on another device")
+        new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
+        g_x, g_w_ih, g_w_hh, g_b = new(self.n, d), new(4 * hidden, d), new(4 * hidden, hidden), new(4 * hidden)
+        _check(lib().hag_seq_lstm_backward(self._h, d, hidden, _dev_ptr(x), _dev_ptr(g_a), _dev_ptr(g_x), _dev_ptr(g_w_ih),
+                                           _dev_ptr(g_w_hh), _dev_ptr(g_b), _dev_ptr(workspace), _stream_ptr()))
+        return g_x, g_w_ih, g_w_hh, g_b
 
     def check(self):
         """Synchronise the current stream; raises HagError(HAG_ETIMEOUT) if a wait of a one-launch pass gave up."""

@@ -47,7 +47,12 @@ struct hag_seq {
     bool wait_unreachable = false;    // tests only: flags are never set, so every wait gives up
     int32_t *d_final = nullptr, *d_paths = nullptr, *d_step_x = nullptr, *d_step_out = nullptr;   // d_paths: padded to whole tiles per level
     int32_t *d_paths_by_depth = nullptr;                    // likewise per depth group
-    int64_t resident[6] = {0, 0, 0, 0, 0, 0};   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
+    // for the backward pass: per step where its h_{t-1} lives (>= 0: that step's tape row, -1: the zero state,
+    // <= -2: state row -(value) - 2), and the steps grouped by the input row they read (for the gradient of x)
+    std::vector<int32_t> step_prev, xt_ptr, xt_idx;
+    int32_t *d_step_prev = nullptr, *d_xt_ptr = nullptr, *d_xt_idx = nullptr;
+    int64_t resident[6] = {0, 0, 0, 0, 0, 0};
+    int64_t resident_tape[4] = {0, 0, 0, 0};   // likewise for the variants that write the tape   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
     int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
     int device = -1;
 };
@@ -108,6 +113,7 @@ struct SeqChainArgs {
     const float *x, *wp, *bp;
     float *h, *c;            // [n_states, H]: read where a path starts (written by a lower level), written where a step says so
     float *a_out;            // [n, H]
+    float *tape_g, *tape_c, *tape_h;   // training: per step the activated gates [H][4], the new c [H] and the new h [H] (NULL: inference)
     int32_t d, hidden;
 };
 
@@ -145,8 +151,8 @@ __device__ __forceinline__ int seq_opaque(int v) { asm volatile("" : "+v"(v)); r
 // path tile; Wp no longer fits the registers of a compute unit, so every wavefront streams its gate tile,
 // stored in the order the matrix instructions consume it, from the L2 cache once per step (16-byte loads, one
 // group of four k-steps ahead): 4H (D + H) * 4 bytes per 64 cells, against 2 * 4H (D + H) * 64 flops.
-template <int KSTEPS, bool WIDE, bool BIG>
-__global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChainArgs A) {
+template <int KSTEPS, bool WIDE, bool BIG, bool TAPE>
+__global__ __launch_bounds__(BIG ? 1024 : 512, TAPE ? 2 : 4) void seq_chain_kernel(SeqChainArgs A) {
     static_assert(!BIG || WIDE, "the streamed variant uses the wide tiling");
     constexpr int KP = 2 * KSTEPS, ZS = KP + 2;
     constexpr int HMAX = BIG ? 128 : (WIDE ? 64 : 32);
@@ -287,6 +293,18 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, 4) void seq_chain_kernel(SeqChain
                             const float c_new = seq_sigmoid(acc[g][4 * m + 1]) * cs[j * HS + unit] +
                                                 seq_sigmoid(acc[g][4 * m + 0]) * seq_tanh(acc[g][4 * m + 2]);
                             cs[j * HS + unit] = c_new;
+                            if constexpr (TAPE) {
+                                // what the backward pass needs of this cell, indexed by the step
+                                const float gi = seq_sigmoid(acc[g][4 * m + 0]), gf = seq_sigmoid(acc[g][4 * m + 1]);
+                                const float gg = seq_tanh(acc[g][4 * m + 2]), go = seq_sigmoid(acc[g][4 * m + 3]);
+                                const float h_new = go * seq_tanh(c_new);
+                                const size_t cell = (size_t)(sdesc[j * 4 + 1] + t) * hidden + unit;
+                                *reinterpret_cast<float4 *>(A.tape_g + cell * 4) = make_float4(gi, gf, gg, go);
+                                A.tape_c[cell] = c_new;
+                                A.tape_h[cell] = h_new;
+                                z[j * ZS + d + unit] = h_new;
+                                continue;
+                            }
                             z[j * ZS + d + unit] = seq_sigmoid(acc[g][4 * m + 3]) * seq_tanh(c_new);
                         }
                     }
@@ -348,6 +366,281 @@ __global__ __launch_bounds__(256) void seq_output_kernel(const int32_t *__restri
     const int s = final_state[v];
     if (s == -2) return;                                   // written by the node's path
     out[i] = s >= 0 ? h[(size_t)s * hidden + (i % hidden)] : 0.f;
+}
+
+
+// ---------------------------------------------------------------------------------------------------------
+// Backward pass (backpropagation through time along the same paths, last step first).  For the cell of a step,
+// with the gradients dh, dc of its outputs:  t = tanh(c'),  d_o = dh t,  dc += dh o (1 - t^2),
+//   d(pre-activations) = (dc g i(1-i),  dc c f(1-f),  dc i (1-g^2),  d_o o(1-o)),   dc_prev = dc f,
+//   (dx, dh_prev) = Wp^T d(pre-activations),   dWp += d(pre-activations) (x, h_prev)^T,   db += d(pre-activations).
+// A state that other paths start from (or that is some a_v) collects their gradients in its row of gh / gc; levels
+// run last to first, so a path finds those rows complete when it reaches the step that wrote the state.
+
+struct SeqRevArgs {
+    const int32_t *paths;    // this level's paths in tiles of 64
+    int64_t n_path_tiles;
+    const int32_t *step_out;
+    const float *wqt;        // Wp^T in the order the matrix instructions consume it
+    float *tape_g;           // in: the activated gates of every step; out: the gradients of its pre-activations
+    const float *tape_c;     // c' of every step
+    const float *c_state;    // c rows of the kept states
+    const float *g_a;        // [n, H]
+    float *gh, *gc;          // [n_states, H]
+    float *dx;               // [cells, d]: every step's gradient of its input row
+    int32_t d, hidden, kp;
+};
+
+constexpr int kSeqRevStride = 4 * 64 + 2;   // row stride of the staged pre-activation gradients (hidden <= 64)
+
+__global__ __launch_bounds__(256) void seq_fill_kernel(float *p, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
+}
+
+// Wp^T for the backward product: [kp / 32 row tiles][4H / 8 groups of four k-steps][64 lanes][4]; lane l supplies row
+// (tile * 32 + l % 32) of Wp^T, i.e. column of Wp, and Wp's row 2 * step + l / 32.
+__global__ __launch_bounds__(256) void seq_pack_transposed_kernel(const float *__restrict__ wp, float *__restrict__ wqt, int hidden, int kp) {
+    const int64_t total = (int64_t)kp * 4 * hidden;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int per_tile = 32 * 4 * hidden, tile = (int)(i / per_tile), rest = (int)(i % per_tile);
+        const int q = rest / 256, lane = (rest % 256) / 4, step = 4 * q + (rest & 3);
+        wqt[i] = wp[(size_t)(2 * step + (lane >> 5)) * kp + tile * 32 + (lane & 31)];
+    }
+}
+
+// a_v that is a shared state's h (the node's whole list is a shared prefix): its gradient goes to the state's row
+__global__ __launch_bounds__(256) void seq_final_grad_kernel(const int32_t *__restrict__ final_state, const float *__restrict__ g_a,
+                                                            float *gh, int64_t n, int hidden) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n * hidden; i += (int64_t)gridDim.x * 256) {
+        const int st = final_state[i / hidden];
+        if (st >= 0) __hip_atomic_fetch_add(gh + (size_t)st * hidden + (i % hidden), g_a[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+}
+
+__global__ __launch_bounds__(512, 2) void seq_reverse_kernel(SeqRevArgs A) {
+    constexpr int ZG = kSeqRevStride, HS = 65;
+    __shared__ __align__(16) float zg[kSeqJobs * ZG];      // per path: the pre-activation gradients of the current step, then the product's dx
+    __shared__ float dh[kSeqJobs * HS], dc[kSeqJobs * HS];
+    __shared__ int32_t sdesc[kSeqJobs * 4];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int hidden = A.hidden, d = A.d, n_rt = A.kp / 32;          // 2 or 4 row tiles of the product
+    const int rt = wave % n_rt, grp = wave / n_rt;                   // this wavefront's row tile and half of the paths
+    const bool multiplies = grp < 2;
+    const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;         // element-wise phases: 8 threads per path
+    for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
+        if (threadIdx.x < kSeqJobs * 4) sdesc[threadIdx.x] = A.paths[ct * (kSeqJobs * 4) + threadIdx.x];
+        __syncthreads();
+        const int steps = sdesc[2];
+        const int start = sdesc[sj * 4], beg = sdesc[sj * 4 + 1], len = sdesc[sj * 4 + 2], node = sdesc[sj * 4 + 3];
+        for (int u = part * 4; u < hidden; u += 32) {
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (node >= 0) v = *reinterpret_cast<const float4 *>(A.g_a + (size_t)node * hidden + u);
+            dh[sj * HS + u] = v.x; dh[sj * HS + u + 1] = v.y; dh[sj * HS + u + 2] = v.z; dh[sj * HS + u + 3] = v.w;
+            dc[sj * HS + u] = 0.f; dc[sj * HS + u + 1] = 0.f; dc[sj * HS + u + 2] = 0.f; dc[sj * HS + u + 3] = 0.f;
+        }
+        __syncthreads();
+        for (int t = steps - 1; t >= 0; --t) {
+            if (t < len) {
+                const size_t cell = (size_t)beg + t;
+                const int keep = A.step_out[cell];
+                for (int u = part * 4; u < hidden; u += 32) {
+                    float dhv[4], dcv[4], cn[4], cp[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) { dhv[e] = dh[sj * HS + u + e]; dcv[e] = dc[sj * HS + u + e]; }
+                    if (keep >= 0) {                       // what the other users of this state sent back
+                        const float4 a = *reinterpret_cast<const float4 *>(A.gh + (size_t)keep * hidden + u);
+                        const float4 b = *reinterpret_cast<const float4 *>(A.gc + (size_t)keep * hidden + u);
+                        dhv[0] += a.x; dhv[1] += a.y; dhv[2] += a.z; dhv[3] += a.w;
+                        dcv[0] += b.x; dcv[1] += b.y; dcv[2] += b.z; dcv[3] += b.w;
+                    }
+                    {
+                        const float4 a = *reinterpret_cast<const float4 *>(A.tape_c + cell * hidden + u);
+                        cn[0] = a.x; cn[1] = a.y; cn[2] = a.z; cn[3] = a.w;
+                        float4 b = make_float4(0.f, 0.f, 0.f, 0.f);
+                        if (t > 0) b = *reinterpret_cast<const float4 *>(A.tape_c + (cell - 1) * hidden + u);
+                        else if (start >= 0) b = *reinterpret_cast<const float4 *>(A.c_state + (size_t)start * hidden + u);
+                        cp[0] = b.x; cp[1] = b.y; cp[2] = b.z; cp[3] = b.w;
+                    }
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        float4 *pg = reinterpret_cast<float4 *>(A.tape_g + (cell * hidden + u + e) * 4);
+                        const float4 g4 = *pg;             // i, f, g, o
+                        const float tc = seq_tanh(cn[e]);
+                        const float d_o = dhv[e] * tc;
+                        const float dcc = dcv[e] + dhv[e] * g4.w * (1.f - tc * tc);
+                        const float4 dg = make_float4(dcc * g4.z * g4.x * (1.f - g4.x), dcc * cp[e] * g4.y * (1.f - g4.y),
+                                                      dcc * g4.x * (1.f - g4.z * g4.z), d_o * g4.w * (1.f - g4.w));
+                        *pg = dg;                          // kept for the weight gradients
+                        *reinterpret_cast<float2 *>(&zg[sj * ZG + (u + e) * 4]) = make_float2(dg.x, dg.y);
+                        *reinterpret_cast<float2 *>(&zg[sj * ZG + (u + e) * 4 + 2]) = make_float2(dg.z, dg.w);
+                        dc[sj * HS + u + e] = dcc * g4.y;
+                    }
+                }
+            }
+            __syncthreads();
+            // (dx, dh_prev)^T [kp, paths] = Wp^T [kp, 4H] . dG^T [4H, paths]
+            seq_acc_t acc;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
+            if (multiplies) {
+                const float4 *wq = reinterpret_cast<const float4 *>(A.wqt) + (size_t)rt * (hidden / 2) * 64 + lane;
+                const float *zl = &zg[(grp * 32 + (lane & 31)) * ZG + (lane >> 5)];
+                float4 wa = wq[0];
+                for (int q = 0; q < hidden / 2; ++q) {
+                    const float4 wn = wq[(q + 1 < hidden / 2 ? q + 1 : q) * 64];
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.x, zl[2 * (4 * q + 0)], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.y, zl[2 * (4 * q + 1)], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.z, zl[2 * (4 * q + 2)], acc, 0, 0, 0);
+                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.w, zl[2 * (4 * q + 3)], acc, 0, 0, 0);
+                    wa = wn;
+                }
+            }
+            __syncthreads();                               // every product has read the staged gradients
+            if (multiplies) {
+                const int j = grp * 32 + (lane & 31);
+                if (t < sdesc[j * 4 + 2]) {
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int row = rt * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                        if (row < d) zg[j * ZG + row] = acc[r];
+                        else if (row < d + hidden) dh[j * HS + row - d] = acc[r];
+                    }
+                }
+            }
+            __syncthreads();
+            if (t < len) {                                 // the step's dx row; read back by this path's own lanes only
+                const size_t cell = (size_t)beg + t;
+                for (int k = part * 4; k < d; k += 32) {
+                    const float *pz = &zg[sj * ZG + k];
+                    *reinterpret_cast<float4 *>(A.dx + cell * d + k) = make_float4(pz[0], pz[1], pz[2], pz[3]);
+                }
+            }
+        }
+        // what is left is the gradient of the state the path started from
+        if (start >= 0 && len > 0) {
+            for (int u = part * 4; u < hidden; u += 32) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    __hip_atomic_fetch_add(A.gh + (size_t)start * hidden + u + e, dh[sj * HS + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __hip_atomic_fetch_add(A.gc + (size_t)start * hidden + u + e, dc[sj * HS + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                }
+            }
+        }
+        __syncthreads();
+    }
+}
+
+// g_x[u] = the sum of the dx rows of the steps that read x[u]; one thread per (u, four columns)
+__global__ __launch_bounds__(256) void seq_input_grad_kernel(const int32_t *__restrict__ xt_ptr, const int32_t *__restrict__ xt_idx,
+                                                            const float *__restrict__ dx, float *__restrict__ g_x, int64_t n, int d) {
+    const int q = d / 4;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n * q; i += (int64_t)gridDim.x * 256) {
+        const int64_t u = i / q;
+        const int k = (int)(i % q) * 4;
+        float4 sum = make_float4(0.f, 0.f, 0.f, 0.f);
+        for (int32_t e = xt_ptr[u]; e < xt_ptr[u + 1]; ++e) {
+            const float4 v = *reinterpret_cast<const float4 *>(dx + (size_t)xt_idx[e] * d + k);
+            sum.x += v.x; sum.y += v.y; sum.z += v.z; sum.w += v.w;
+        }
+        *reinterpret_cast<float4 *>(g_x + (size_t)u * d + k) = sum;
+    }
+}
+
+// dWp [4H, kp] += sum over steps of dG[step] (x[in], h_prev)^T and dbp += sum of dG[step]: a register-tiled product, thread
+// (ty, tx) of 16 x 16 owning rows 16 ty .. 16 ty + 15 and columns 8 tx .. 8 tx + 7, fed from LDS eight steps at a time.
+struct SeqWgradArgs {
+    const float *dg, *x, *tape_h, *h_state;
+    const int32_t *step_x, *step_prev;
+    int64_t cells;
+    int32_t d, hidden, kp;
+    float *dwp, *dbp;
+};
+constexpr int kSeqWgradCells = 8;
+
+__global__ __launch_bounds__(256) void seq_weight_grad_kernel(SeqWgradArgs A) {
+    constexpr int CK = kSeqWgradCells;
+    __shared__ __align__(16) float sdg[CK][256];
+    __shared__ __align__(16) float sz[CK][128];
+    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    const int rows = 4 * A.hidden, d = A.d, hidden = A.hidden, kp = A.kp;
+    float acc[16][8], accb[16];
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        accb[i] = 0.f;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
+    }
+    const int64_t chunks = (A.cells + CK - 1) / CK;
+    for (int64_t ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
+        const int64_t c0 = ch * CK;
+        // stage CK rows of dG (4H floats each) and of (x[in], h_prev) (kp floats each, zero padded)
+        for (int i = threadIdx.x; i < CK * 64; i += 256) {
+            const int c = i / 64, k = (i % 64) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + c < A.cells && k < rows) v = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + k);
+            *reinterpret_cast<float4 *>(&sdg[c][k]) = v;
+        }
+        for (int i = threadIdx.x; i < CK * 32; i += 256) {
+            const int c = i / 32, k = (i % 32) * 4;
+            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (c0 + c < A.cells) {
+                if (k < d) v = *reinterpret_cast<const float4 *>(A.x + (size_t)A.step_x[c0 + c] * d + k);
+                else if (k < d + hidden) {
+                    const int pv = A.step_prev[c0 + c];
+                    if (pv >= 0) v = *reinterpret_cast<const float4 *>(A.tape_h + (size_t)pv * hidden + (k - d));
+                    else if (pv <= -2) v = *reinterpret_cast<const float4 *>(A.h_state + (size_t)(-pv - 2) * hidden + (k - d));
+                }
+            }
+            *reinterpret_cast<float4 *>(&sz[c][k]) = v;
+        }
+        __syncthreads();
+#pragma unroll
+        for (int c = 0; c < CK; ++c) {
+            float a[16], b[8];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float4 v = *reinterpret_cast<const float4 *>(&sdg[c][ty * 16 + 4 * i]);
+                a[4 * i] = v.x; a[4 * i + 1] = v.y; a[4 * i + 2] = v.z; a[4 * i + 3] = v.w;
+            }
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const float4 v = *reinterpret_cast<const float4 *>(&sz[c][tx * 8 + 4 * j]);
+                b[4 * j] = v.x; b[4 * j + 1] = v.y; b[4 * j + 2] = v.z; b[4 * j + 3] = v.w;
+            }
+#pragma unroll
+            for (int i = 0; i < 16; ++i) {
+                accb[i] += a[i];
+#pragma unroll
+                for (int j = 0; j < 8; ++j) acc[i][j] += a[i] * b[j];
+            }
+        }
+        __syncthreads();
+    }
+#pragma unroll
+    for (int i = 0; i < 16; ++i) {
+        const int r = ty * 16 + i;
+        if (r >= rows) continue;
+        if (tx == 0) __hip_atomic_fetch_add(A.dbp + r, accb[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+            const int k = tx * 8 + j;
+            if (k < kp) __hip_atomic_fetch_add(A.dwp + (size_t)r * kp + k, acc[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+    }
+}
+
+// packed gradients back to the usual layout: rows (unit, gate) -> gate-major rows, columns split into input and hidden part
+__global__ __launch_bounds__(256) void seq_unpack_grad_kernel(const float *__restrict__ dwp, const float *__restrict__ dbp,
+                                                             float *__restrict__ g_w_ih, float *__restrict__ g_w_hh,
+                                                             float *__restrict__ g_b, int d, int hidden, int kp) {
+    const int64_t total = (int64_t)4 * hidden * kp;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
+        const int r = (int)(i / kp), k = (int)(i % kp);
+        const int unit = r >> 2, gate = r & 3, row = gate * hidden + unit;
+        if (k < d) g_w_ih[(size_t)row * d + k] = dwp[i];
+        else if (k < d + hidden) g_w_hh[(size_t)row * hidden + (k - d)] = dwp[i];
+        if (k == 0) g_b[row] = dbp[r];
+    }
 }
 
 }  // namespace hag
@@ -495,6 +788,20 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
                 h->depth_ptr[(size_t)g + 1] += h->depth_ptr[g];
             }
         }
+        {
+            const int64_t cells = (int64_t)h->step_x.size(), np = (int64_t)(h->paths.size() / 4);
+            h->step_prev.assign((size_t)cells, -1);
+            for (int64_t i = 0; i < np; ++i) {
+                const int32_t start = h->paths[i * 4], beg = h->paths[i * 4 + 1], len = h->paths[i * 4 + 2];
+                for (int32_t t = 0; t < len; ++t) h->step_prev[(size_t)beg + t] = t > 0 ? beg + t - 1 : (start >= 0 ? -start - 2 : -1);
+            }
+            h->xt_ptr.assign((size_t)n + 1, 0);
+            for (int64_t a2 = 0; a2 < cells; ++a2) ++h->xt_ptr[(size_t)h->step_x[a2] + 1];
+            for (int64_t u = 0; u < n; ++u) h->xt_ptr[(size_t)u + 1] += h->xt_ptr[u];
+            h->xt_idx.resize((size_t)cells);
+            std::vector<int32_t> at(h->xt_ptr.begin(), h->xt_ptr.end() - 1);
+            for (int64_t a2 = 0; a2 < cells; ++a2) h->xt_idx[(size_t)at[h->step_x[a2]]++] = (int32_t)a2;
+        }
         *out = h;
         return HAG_OK;
     } catch (const std::bad_alloc &) {
@@ -511,6 +818,9 @@ void hag_seq_free(hag_seq_t *h) {
     if (h->d_final) (void)hipFree(h->d_final);
     if (h->d_paths) (void)hipFree(h->d_paths);
     if (h->d_paths_by_depth) (void)hipFree(h->d_paths_by_depth);
+    if (h->d_step_prev) (void)hipFree(h->d_step_prev);
+    if (h->d_xt_ptr) (void)hipFree(h->d_xt_ptr);
+    if (h->d_xt_idx) (void)hipFree(h->d_xt_idx);
     if (h->d_step_x) (void)hipFree(h->d_step_x);
     if (h->d_step_out) (void)hipFree(h->d_step_out);
     if (h->d_gave_up) (void)hipFree(h->d_gave_up);
@@ -534,9 +844,12 @@ static int64_t seq_kp(int64_t d, int64_t hidden) {
 // Index into hag_seq::resident / the variant table below.
 static int seq_variant(int64_t kp, int64_t hidden) { return kp > 128 ? (kp == 192 ? 4 : 5) : (kp == 64 ? 0 : 2) + (hidden > 32 ? 1 : 0); }
 typedef void (*seq_kernel_t)(SeqChainArgs);
-static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false>, seq_chain_kernel<32, true, false>,
-                                             seq_chain_kernel<64, false, false>, seq_chain_kernel<64, true, false>,
-                                             seq_chain_kernel<96, true, true>,   seq_chain_kernel<128, true, true>};
+static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false, false>, seq_chain_kernel<32, true, false, false>,
+                                             seq_chain_kernel<64, false, false, false>, seq_chain_kernel<64, true, false, false>,
+                                             seq_chain_kernel<96, true, true, false>,   seq_chain_kernel<128, true, true, false>};
+// the same with the tape written (training; the variants that hold Wp in registers only)
+static const seq_kernel_t kSeqTapeVariants[4] = {seq_chain_kernel<32, false, false, true>, seq_chain_kernel<32, true, false, true>,
+                                                 seq_chain_kernel<64, false, false, true>, seq_chain_kernel<64, true, false, true>};
 
 int hag_seq_get_plan(const hag_seq_t *h, int32_t order, int64_t *n_states, int64_t *n_paths, const int32_t **paths,
                      const int32_t **step_x, const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr,
@@ -579,6 +892,9 @@ int hag_seq_upload(hag_seq_t *h) {
     }
     HIP_TRY(put(&h->d_step_x, h->step_x));
     HIP_TRY(put(&h->d_step_out, h->step_out));
+    HIP_TRY(put(&h->d_step_prev, h->step_prev));
+    HIP_TRY(put(&h->d_xt_ptr, h->xt_ptr));
+    HIP_TRY(put(&h->d_xt_idx, h->xt_idx));
     HIP_TRY(put(&h->d_gave_up, std::vector<int32_t>(1, 0)));
     {
         // workgroups of each kernel variant that the device holds at once (at most the two per compute unit the
@@ -589,6 +905,10 @@ int hag_seq_upload(hag_seq_t *h) {
             int per_cu = 0;
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqVariants[k], k >= 4 ? 1024 : 512, 0));
             h->resident[k] = (int64_t)std::min(per_cu, 2) * cus;
+            if (k < 4) {
+                HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqTapeVariants[k], 512, 0));
+                h->resident_tape[k] = (int64_t)std::min(per_cu, 2) * cus;
+            }
         }
     }
     HIP_TRY(put(&h->d_final, h->final_state));
@@ -628,8 +948,8 @@ size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
     return up(wp) + up(bp) + 2 * up(states) + up(flags);
 }
 
-int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
-                         const float *b, float *a_out, void *workspace, void *stream) {
+static int seq_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                       const float *b, float *a_out, void *workspace, void *stream, float *tape_g, float *tape_c, float *tape_h) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
     if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
     if (d <= 0 || d % 4 != 0 || hidden <= 0 || hidden % 8 != 0 || hidden > 128 || d + hidden > kSeqMaxK) {
@@ -658,7 +978,7 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
     const int64_t levels = (int64_t)h->tile_ptr.size() - 1;
     const int variant = seq_variant(kp, hidden);
     const bool big = variant >= 4;
-    const int64_t resident = h->resident[variant];
+    const int64_t resident = tape_g ? h->resident_tape[variant] : h->resident[variant];
     const bool fused = levels > 1 && h->one_launch && resident > 0;
     for (int64_t l = 0; l < (fused ? 1 : levels); ++l) {
         SeqChainArgs c;
@@ -671,16 +991,139 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
         c.gave_up = h->d_gave_up;
         c.step_x = h->d_step_x; c.step_out = h->d_step_out;
         c.x = x; c.wp = wp; c.bp = bp; c.h = hst; c.c = cst; c.a_out = a_out;
+        c.tape_g = tape_g; c.tape_c = tape_c; c.tape_h = tape_h;
         c.d = (int32_t)d; c.hidden = (int32_t)hidden;
         if (c.n_path_tiles <= 0) continue;
         const dim3 grid((unsigned)std::min<int64_t>(c.n_path_tiles, fused ? resident : (big ? 256 : 512))), block(big ? 1024 : 512);
-        hipLaunchKernelGGL(kSeqVariants[variant], grid, block, 0, s, c);
+        hipLaunchKernelGGL(tape_g ? kSeqTapeVariants[variant] : kSeqVariants[variant], grid, block, 0, s, c);
         HIP_TRY(hipGetLastError());
     }
     {
         const int64_t total = h->n * hidden;
         hipLaunchKernelGGL(seq_output_kernel, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, s, h->d_final, hst, a_out, h->n,
                            (int)hidden);
+        HIP_TRY(hipGetLastError());
+    }
+    return HAG_OK;
+}
+
+int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                         const float *b, float *a_out, void *workspace, void *stream) {
+    return seq_forward(h, d, hidden, x, w_ih, w_hh, b, a_out, workspace, stream, nullptr, nullptr, nullptr);
+}
+
+// Layout of the training workspace: the forward workspace, then the tape and the backward pass's own buffers.
+struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, wqt, dwp, dbp, total; };
+static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hidden) {
+    auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
+    const size_t cells = std::max<size_t>(h->step_x.size(), 1), states = (size_t)std::max<int64_t>(h->n_states, 1);
+    const size_t kp = (size_t)seq_kp(d, hidden), H = (size_t)hidden, f = sizeof(float);
+    SeqTrainLayout L;
+    size_t at = up(hag_seq_workspace_bytes(h, d, hidden));
+    L.fwd = 0;
+    L.tape_g = at; at += up(cells * 4 * H * f);
+    L.tape_c = at; at += up(cells * H * f);
+    L.tape_h = at; at += up(cells * H * f);
+    L.dx = at; at += up(cells * (size_t)d * f);
+    L.gh = at; at += up(states * H * f);
+    L.gc = at; at += up(states * H * f);
+    L.wqt = at; at += up(kp * 4 * H * f);
+    L.dwp = at; at += up(4 * H * kp * f);
+    L.dbp = at; at += up(4 * H * f);
+    L.total = at;
+    return L;
+}
+static bool seq_backward_supported(int64_t d, int64_t hidden) {
+    return d > 0 && d % 4 == 0 && hidden > 0 && hidden % 8 == 0 && hidden <= 64 && d + hidden <= 128;
+}
+
+size_t hag_seq_train_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
+    if (!h || !seq_backward_supported(d, hidden)) return 0;
+    return seq_train_layout(h, d, hidden).total;
+}
+
+int hag_seq_lstm_forward_train(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                               const float *b, float *a_out, void *workspace, void *stream) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (!seq_backward_supported(d, hidden)) {
+        set_error("training: d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+        return HAG_EINVAL;
+    }
+    if (!workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
+    const SeqTrainLayout L = seq_train_layout(h, d, hidden);
+    char *w = (char *)workspace;
+    return seq_forward(h, d, hidden, x, w_ih, w_hh, b, a_out, workspace, stream, (float *)(w + L.tape_g), (float *)(w + L.tape_c),
+                       (float *)(w + L.tape_h));
+}
+
+int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *g_a, float *g_x, float *g_w_ih,
+                          float *g_w_hh, float *g_b, void *workspace, void *stream) {
+    if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
+    if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
+    if (!seq_backward_supported(d, hidden)) {
+        set_error("training: d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+        return HAG_EINVAL;
+    }
+    if (h->n == 0) return HAG_OK;
+    if (!x || !g_a || !g_x || !g_w_ih || !g_w_hh || !g_b || !workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
+    if (((uintptr_t)x | (uintptr_t)workspace | (uintptr_t)g_a | (uintptr_t)g_x) & 15) { set_error("x, g_a, g_x and workspace must be 16-byte aligned"); return HAG_EINVAL; }
+    hipStream_t s = (hipStream_t)stream;
+    const int kp = (int)seq_kp(d, hidden);
+    const SeqTrainLayout L = seq_train_layout(h, d, hidden);
+    auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
+    char *w = (char *)workspace;
+    // the forward workspace as seq_forward laid it out: packed weights, packed bias, h rows, c rows
+    const float *wp = (const float *)w;
+    const size_t states = up((size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float));
+    const float *hst = (const float *)(w + up((size_t)4 * hidden * kp * sizeof(float)) + up((size_t)4 * hidden * sizeof(float)));
+    const float *cst = (const float *)((const char *)hst + states);
+    float *tape_g = (float *)(w + L.tape_g), *tape_c = (float *)(w + L.tape_c), *tape_h = (float *)(w + L.tape_h);
+    float *dx = (float *)(w + L.dx), *gh = (float *)(w + L.gh), *gc = (float *)(w + L.gc), *wqt = (float *)(w + L.wqt);
+    float *dwp = (float *)(w + L.dwp), *dbp = (float *)(w + L.dbp);
+    const int64_t cells = (int64_t)h->step_x.size();
+    auto blocks = [](int64_t total) { return dim3((unsigned)std::min<int64_t>((total + 255) / 256, 65535 * 16)); };
+    // gradient rows of the kept states and the packed weight gradients start at zero (gh .. dbp are adjacent)
+    {
+        const int64_t total = (int64_t)((L.total - L.gh) / sizeof(float));
+        hipLaunchKernelGGL(seq_fill_kernel, blocks(total), dim3(256), 0, s, gh, total);
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        const int64_t total = (int64_t)kp * 4 * hidden;
+        hipLaunchKernelGGL(seq_pack_transposed_kernel, blocks(total), dim3(256), 0, s, wp, wqt, (int)hidden, kp);
+        HIP_TRY(hipGetLastError());
+        const int64_t nh = h->n * hidden;
+        hipLaunchKernelGGL(seq_final_grad_kernel, blocks(nh), dim3(256), 0, s, h->d_final, g_a, gh, h->n, (int)hidden);
+        HIP_TRY(hipGetLastError());
+    }
+    const int64_t levels = (int64_t)h->tile_ptr.size() - 1;
+    for (int64_t l = levels - 1; l >= 0; --l) {
+        SeqRevArgs r;
+        r.paths = h->d_paths + h->tile_ptr[l] * kSeqJobs * 4;
+        r.n_path_tiles = h->tile_ptr[l + 1] - h->tile_ptr[l];
+        r.step_out = h->d_step_out;
+        r.wqt = wqt; r.tape_g = tape_g; r.tape_c = tape_c; r.c_state = cst; r.g_a = g_a; r.gh = gh; r.gc = gc; r.dx = dx;
+        r.d = (int32_t)d; r.hidden = (int32_t)hidden; r.kp = kp;
+        if (r.n_path_tiles <= 0) continue;
+        hipLaunchKernelGGL(seq_reverse_kernel, dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 256)), dim3(512), 0, s, r);
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        const int64_t total = h->n * (d / 4);
+        hipLaunchKernelGGL(seq_input_grad_kernel, blocks(total), dim3(256), 0, s, h->d_xt_ptr, h->d_xt_idx, dx, g_x, h->n, (int)d);
+        HIP_TRY(hipGetLastError());
+    }
+    if (cells > 0) {
+        SeqWgradArgs g;
+        g.dg = tape_g; g.x = x; g.tape_h = tape_h; g.h_state = hst; g.step_x = h->d_step_x; g.step_prev = h->d_step_prev;
+        g.cells = cells; g.d = (int32_t)d; g.hidden = (int32_t)hidden; g.kp = kp; g.dwp = dwp; g.dbp = dbp;
+        const int64_t chunks = (cells + kSeqWgradCells - 1) / kSeqWgradCells;
+        hipLaunchKernelGGL(seq_weight_grad_kernel, dim3((unsigned)std::min<int64_t>(chunks, 1024)), dim3(256), 0, s, g);
+        HIP_TRY(hipGetLastError());
+    }
+    {
+        const int64_t total = (int64_t)4 * hidden * kp;
+        hipLaunchKernelGGL(seq_unpack_grad_kernel, blocks(total), dim3(256), 0, s, dwp, dbp, g_w_ih, g_w_hh, g_b, (int)d, (int)hidden, kp);
         HIP_TRY(hipGetLastError());
     }
     return HAG_OK;

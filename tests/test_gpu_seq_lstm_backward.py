@@ -1,0 +1,114 @@
+"""GPU parity of the LSTM aggregator's backward pass (hag_seq_lstm_forward_train / hag_seq_lstm_backward) with the fp64
+oracle's backpropagation through time over every list (oracle/lstm.py::naive_aggregate_backward): the gradients over a
+prefix HAG equal those over the plain lists (equal outputs for all inputs, Theorem 2), so one oracle serves every plan.
+
+Tolerance: every gradient entry is a sum of products of fp32 quantities along chains of <= 40 cells and, for the weights,
+over all cells; compared norm-wise per tensor (relative 2e-5) and element-wise against the tensor's largest entry."""
+import numpy as np
+import pytest
+
+from oracle import lstm
+from paper_1906_03707_amd import synth
+
+torch = pytest.importorskip("torch")
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def B():
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    from paper_1906_03707_amd import binding
+    binding.lib()
+    return binding
+
+
+def route_graph(n, deg, seed):
+    rng = np.random.default_rng(seed)
+    routes = [rng.permutation(n)[:deg] for _ in range(5)]
+    rowptr, col = [0], []
+    for v in range(n):
+        k = int(rng.integers(0, deg + 1))
+        col += list(routes[int(rng.integers(0, 5))][:k]) + list(rng.integers(0, n, int(rng.integers(0, 4))))
+        rowptr.append(len(col))
+    return np.asarray(rowptr, dtype=np.int64), np.asarray(col, dtype=np.int32)
+
+
+def check(B, rowptr, col, d, hidden, seed, capacities, only_nodes=None):
+    n = rowptr.size - 1
+    rng = np.random.default_rng(seed)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    xd, wid, whd, bd = dev(rng.normal(size=(n, d))), dev(rng.normal(0, 0.4, (4 * hidden, d))), dev(rng.normal(0, 0.4, (4 * hidden, hidden))), \
+        dev(rng.normal(0, 0.4, 4 * hidden))
+    g_a = rng.normal(size=(n, hidden))
+    f64 = lambda t: t.cpu().numpy().astype(np.float64)
+    if only_nodes is None:
+        o_rowptr, o_col, rows = rowptr, col, np.arange(n)
+    else:
+        # the loss depends on a_v of these nodes only: the oracle then needs their lists alone, and still yields the
+        # complete gradients (everything else contributes zero)
+        rows = np.asarray(only_nodes)
+        mask = np.zeros(n, dtype=bool)
+        mask[rows] = True
+        g_a[~mask] = 0.0
+        o_rowptr = np.concatenate([[0], np.cumsum(rowptr[rows + 1] - rowptr[rows])]).astype(np.int64)
+        o_col = np.concatenate([col[rowptr[v]:rowptr[v + 1]] for v in rows]).astype(np.int32)
+    gad = dev(g_a)
+    want_a, _ = lstm.naive_aggregate(o_rowptr, o_col, f64(xd), f64(wid), f64(whd), f64(bd))
+    want = lstm.naive_aggregate_backward(o_rowptr, o_col, f64(xd), f64(wid), f64(whd), f64(bd), f64(gad)[rows])
+    for cap in capacities:
+        h = B.SeqHag(rowptr, col, cap).upload()
+        for one_launch in (1, 0):
+            h.set_option(B.HAG_OPT_SEQ_ONE_LAUNCH, one_launch)
+            a, ws = h.lstm_forward_train(xd, wid, whd, bd)
+            h.check()
+            assert np.abs(f64(a)[rows] - want_a).max() <= 1e-5
+            got = h.lstm_backward(xd, gad, hidden, ws)
+            torch.cuda.synchronize()
+            for name, g, w in zip(("g_x", "g_w_ih", "g_w_hh", "g_b"), got, want):
+                g = f64(g)
+                scale = max(np.abs(w).max(), 1e-30)
+                rel = np.linalg.norm(g - w) / max(np.linalg.norm(w), 1e-30)
+                worst = np.abs(g - w).max() / scale
+                assert rel <= 2e-5 and worst <= 2e-5, f"cap {cap} d {d} H {hidden} one_launch {one_launch} {name}: rel {rel:.2e} worst {worst:.2e}"
+
+
+@pytest.mark.parametrize("d,hidden", [(8, 8), (16, 32), (64, 64), (24, 40), (96, 32)])
+def test_route_graph(B, d, hidden):
+    rowptr, col = route_graph(150, 9, seed=d + hidden)
+    check(B, rowptr, col, d, hidden, seed=5, capacities=(0, 7, col.size))
+
+
+def test_power_law_graph_first_neighbours(B):
+    # thousands of paths per level (several tiles per workgroup, ragged last tile), deep prefix sharing
+    from paper_1906_03707_amd import workloads
+    rowptr, col = synth.holme_kim(3000, 8, 0.5, seed=77)
+    rowptr, col = workloads.first_neighbour_lists(rowptr, col, 16)
+    check(B, rowptr, col, 32, 32, seed=9, capacities=(0, (rowptr.size - 1) // 4, col.size))
+
+
+@pytest.mark.timeout(600)
+def test_bench_workload_loss_on_sampled_nodes(B):
+    # the workload bench.py --seq-lstm times, at its full size (config 4's graphs, first 16 neighbours, d = H = 64; plain
+    # lists, capacity |V|/4, unlimited), with a loss that depends on 300 sampled nodes
+    from paper_1906_03707_amd import workloads
+    rowptr, col, _ = synth.graph_for_config(4)
+    rp, cl = workloads.first_neighbour_lists(rowptr, col, 16)
+    n = rp.size - 1
+    sample = np.unique(np.concatenate([np.random.default_rng(6).integers(0, n, 300), [0, n - 1]]))
+    check(B, rp, cl, 64, 64, seed=11, capacities=(0, n // 4, int(cl.size)), only_nodes=sample)
+
+
+def test_rejections(B):
+    rowptr, col = route_graph(20, 4, seed=3)
+    h = B.SeqHag(rowptr, col, 3).upload()
+    z = lambda *shape: torch.zeros(shape, device="cuda")
+    with pytest.raises(ValueError):       # hidden above what the backward pass supports
+        h.lstm_forward_train(z(20, 8), z(512, 8), z(512, 128), z(512))
+    a, ws = h.lstm_forward_train(z(20, 8), z(32, 8), z(32, 8), z(32))
+    with pytest.raises(ValueError):       # workspace of the wrong size
+        h.lstm_backward(z(20, 8), z(20, 8), 8, ws[:16])
+    with pytest.raises(ValueError):       # gradient of the wrong shape
+        h.lstm_backward(z(20, 8), z(20, 16), 8, ws)
+    g = h.lstm_backward(z(20, 8), z(20, 8), 8, ws)
+    assert all(not t.any() for t in g)    # zero gradient in, zero gradients out
