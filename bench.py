@@ -359,6 +359,31 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         log(f"[bench] LSTM aggregator, {name}: {p.cells} cells ({res['plans'][name]['cells_fewer']:.2f}x fewer), {p.launches} launches, "
             f"{ms:.3f} ms per pass ({ms_base / ms:.2f}x the plain lists' speed), {tf:.1f} TFLOP/s = "
             f"{100 * tf / FP32_MFMA_PEAK_TFLOPS:.1f}% of the fp32 matrix-core peak")
+    # training: forward keeping the tape + backward (gradients of x and of the LSTM's parameters), where the sizes allow
+    if plans and next(iter(plans.values())).train_workspace_bytes(d, hidden) > 0:
+        g_a = torch.from_numpy(np.random.default_rng(synth.SEED_BASE + 100 * cfg + 8).normal(size=(n, hidden)).astype(np.float32)).cuda()
+        ws = torch.empty(max(p.train_workspace_bytes(d, hidden) for p in plans.values()), dtype=torch.uint8, device="cuda")
+        def train_step(p):
+            p.lstm_forward_train(x, w_ih, w_hh, b, workspace=ws)
+            p.lstm_backward(x, g_a, hidden, ws)
+        def bwd_only(p):
+            p.lstm_backward(x, g_a, hidden, ws)
+        for name, p in plans.items():
+            ms, _ = time_steps(torch, lambda p=p: train_step(p), steps, warmup)
+            p.lstm_forward_train(x, w_ih, w_hh, b, workspace=ws)
+            ms_f, _ = time_steps(torch, lambda p=p: p.lstm_forward_train(x, w_ih, w_hh, b, workspace=ws), steps, warmup)
+            res["plans"][name]["train_step_ms"] = ms
+            res["plans"][name]["forward_train_ms"] = ms_f
+            res["plans"][name]["train_workspace_GB"] = p.train_workspace_bytes(d, hidden) / 1e9
+        base_ms = res["plans"]["lists"]["train_step_ms"] if "lists" in plans else float("nan")
+        for name in plans:
+            r = res["plans"][name]
+            r["train_step_speedup_vs_lists"] = base_ms / r["train_step_ms"]
+            r["train_step_tflops"] = 3 * r["cells"] * flops_per_cell / (r["train_step_ms"] * 1e-3) / 1e12
+            log(f"[bench] LSTM aggregator training step (forward + backward), {name}: {r['train_step_ms']:.3f} ms "
+                f"(forward {r['forward_train_ms']:.3f}; {r['train_step_speedup_vs_lists']:.2f}x the plain lists' speed; "
+                f"{r['train_step_tflops']:.1f} TFLOP/s over 3x the forward flops; workspace {r['train_workspace_GB']:.1f} GB)")
+        del ws
     # inference latency of a 2-layer GraphSAGE with LSTM aggregators around the same passes (Section 5.3 reports inference
     # latency next to training time); dense Update in torch, `hidden` wide throughout, 16 classes
     from paper_1906_03707_amd import layers

@@ -546,41 +546,44 @@ __global__ __launch_bounds__(256) void seq_input_grad_kernel(const int32_t *__re
     }
 }
 
-// dWp [4H, kp] += sum over steps of dG[step] (x[in], h_prev)^T and dbp += sum of dG[step]: a register-tiled product, thread
-// (ty, tx) of 16 x 16 owning rows 16 ty .. 16 ty + 15 and columns 8 tx .. 8 tx + 7, fed from LDS eight steps at a time.
+// dWp [4H, kp] = sum over steps of dG[step] (x[in], h_prev)^T and dbp = sum of dG[step], on the matrix cores: the sum over
+// steps is the contraction.  A workgroup of 8 wavefronts stages 32 steps at a time in LDS (their dG rows and their
+// gathered (x[in], h_prev) rows), wavefront w accumulates row tile w of dWp (32 rows of dG) against all column tiles
+// (kp / 32, 16 registers each); every workgroup ends with its own partial sums, which a second kernel adds up in a
+// fixed order (so the weight gradients do not depend on timing) and writes in the layout of w_ih, w_hh and b.
 struct SeqWgradArgs {
     const float *dg, *x, *tape_h, *h_state;
     const int32_t *step_x, *step_prev;
     int64_t cells;
     int32_t d, hidden, kp;
-    float *dwp, *dbp;
+    float *partial;          // [gridDim.x][4H * kp + 4H]
 };
-constexpr int kSeqWgradCells = 8;
+constexpr int kSeqWgradCells = 32;
+constexpr int kSeqWgradGroups = 768;        // workgroups at most (three per compute unit)
 
-__global__ __launch_bounds__(256) void seq_weight_grad_kernel(SeqWgradArgs A) {
+__global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A) {
     constexpr int CK = kSeqWgradCells;
     __shared__ __align__(16) float sdg[CK][256];
     __shared__ __align__(16) float sz[CK][128];
-    const int ty = threadIdx.x >> 4, tx = threadIdx.x & 15;
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rows = 4 * A.hidden, d = A.d, hidden = A.hidden, kp = A.kp;
-    float acc[16][8], accb[16];
+    const int n_rt = rows / 32, n_ct = kp / 32;
+    seq_acc_t acc[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        accb[i] = 0.f;
+    for (int c = 0; c < 4; ++c)
 #pragma unroll
-        for (int j = 0; j < 8; ++j) acc[i][j] = 0.f;
-    }
+        for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
+    float accb = 0.f;                                      // thread i < 4H: the sum of dG[.][i]
     const int64_t chunks = (A.cells + CK - 1) / CK;
     for (int64_t ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
         const int64_t c0 = ch * CK;
-        // stage CK rows of dG (4H floats each) and of (x[in], h_prev) (kp floats each, zero padded)
-        for (int i = threadIdx.x; i < CK * 64; i += 256) {
+        for (int i = threadIdx.x; i < CK * 64; i += 512) {
             const int c = i / 64, k = (i % 64) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (c0 + c < A.cells && k < rows) v = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + k);
             *reinterpret_cast<float4 *>(&sdg[c][k]) = v;
         }
-        for (int i = threadIdx.x; i < CK * 32; i += 256) {
+        for (int i = threadIdx.x; i < CK * 32; i += 512) {
             const int c = i / 32, k = (i % 32) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (c0 + c < A.cells) {
@@ -594,52 +597,55 @@ __global__ __launch_bounds__(256) void seq_weight_grad_kernel(SeqWgradArgs A) {
             *reinterpret_cast<float4 *>(&sz[c][k]) = v;
         }
         __syncthreads();
+        if (wave < n_rt) {
 #pragma unroll
-        for (int c = 0; c < CK; ++c) {
-            float a[16], b[8];
+            for (int st = 0; st < CK / 2; ++st) {
+                const int c = 2 * st + (lane >> 5);
+                const float a = sdg[c][wave * 32 + (lane & 31)];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 v = *reinterpret_cast<const float4 *>(&sdg[c][ty * 16 + 4 * i]);
-                a[4 * i] = v.x; a[4 * i + 1] = v.y; a[4 * i + 2] = v.z; a[4 * i + 3] = v.w;
+                for (int ct = 0; ct < 4; ++ct)
+                    if (ct < n_ct) acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, sz[c][ct * 32 + (lane & 31)], acc[ct], 0, 0, 0);
             }
+        }
+        if ((int)threadIdx.x < rows) {
 #pragma unroll
-            for (int j = 0; j < 2; ++j) {
-                const float4 v = *reinterpret_cast<const float4 *>(&sz[c][tx * 8 + 4 * j]);
-                b[4 * j] = v.x; b[4 * j + 1] = v.y; b[4 * j + 2] = v.z; b[4 * j + 3] = v.w;
-            }
-#pragma unroll
-            for (int i = 0; i < 16; ++i) {
-                accb[i] += a[i];
-#pragma unroll
-                for (int j = 0; j < 8; ++j) acc[i][j] += a[i] * b[j];
-            }
+            for (int c = 0; c < CK; ++c) accb += sdg[c][threadIdx.x];
         }
         __syncthreads();
     }
+    float *out = A.partial + (size_t)blockIdx.x * ((size_t)rows * kp + rows);
+    if (wave < n_rt) {
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-        const int r = ty * 16 + i;
-        if (r >= rows) continue;
-        if (tx == 0) __hip_atomic_fetch_add(A.dbp + r, accb[i], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        for (int ct = 0; ct < 4; ++ct) {
+            if (ct >= n_ct) continue;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) {
-            const int k = tx * 8 + j;
-            if (k < kp) __hip_atomic_fetch_add(A.dwp + (size_t)r * kp + k, acc[i][j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            for (int r = 0; r < 16; ++r) {
+                const int row = wave * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                out[(size_t)row * kp + ct * 32 + (lane & 31)] = acc[ct][r];
+            }
         }
     }
+    if ((int)threadIdx.x < rows) out[(size_t)rows * kp + threadIdx.x] = accb;
 }
 
-// packed gradients back to the usual layout: rows (unit, gate) -> gate-major rows, columns split into input and hidden part
-__global__ __launch_bounds__(256) void seq_unpack_grad_kernel(const float *__restrict__ dwp, const float *__restrict__ dbp,
-                                                             float *__restrict__ g_w_ih, float *__restrict__ g_w_hh,
-                                                             float *__restrict__ g_b, int d, int hidden, int kp) {
-    const int64_t total = (int64_t)4 * hidden * kp;
-    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
-        const int r = (int)(i / kp), k = (int)(i % kp);
-        const int unit = r >> 2, gate = r & 3, row = gate * hidden + unit;
-        if (k < d) g_w_ih[(size_t)row * d + k] = dwp[i];
-        else if (k < d + hidden) g_w_hh[(size_t)row * hidden + (k - d)] = dwp[i];
-        if (k == 0) g_b[row] = dbp[r];
+// adds the workgroups' partial sums in index order and writes the usual layout: rows (unit, gate) -> gate-major rows,
+// columns split into the input and the hidden part
+__global__ __launch_bounds__(256) void seq_weight_grad_reduce_kernel(const float *__restrict__ partial, int groups, float *__restrict__ g_w_ih,
+                                                                    float *__restrict__ g_w_hh, float *__restrict__ g_b, int d, int hidden,
+                                                                    int kp) {
+    const int64_t per = (int64_t)4 * hidden * kp + 4 * hidden;
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < per; i += (int64_t)gridDim.x * 256) {
+        float sum = 0.f;
+        for (int g = 0; g < groups; ++g) sum += partial[(size_t)g * per + i];
+        if (i < (int64_t)4 * hidden * kp) {
+            const int r = (int)(i / kp), k = (int)(i % kp);
+            const int row = (r & 3) * hidden + (r >> 2);
+            if (k < d) g_w_ih[(size_t)row * d + k] = sum;
+            else if (k < d + hidden) g_w_hh[(size_t)row * hidden + (k - d)] = sum;
+        } else {
+            const int r = (int)(i - (int64_t)4 * hidden * kp);
+            g_b[(r & 3) * hidden + (r >> 2)] = sum;
+        }
     }
 }
 
@@ -1013,7 +1019,7 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
 }
 
 // Layout of the training workspace: the forward workspace, then the tape and the backward pass's own buffers.
-struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, wqt, dwp, dbp, total; };
+struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, wqt, partial, total; };
 static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hidden) {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t cells = std::max<size_t>(h->step_x.size(), 1), states = (size_t)std::max<int64_t>(h->n_states, 1);
@@ -1028,8 +1034,7 @@ static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hi
     L.gh = at; at += up(states * H * f);
     L.gc = at; at += up(states * H * f);
     L.wqt = at; at += up(kp * 4 * H * f);
-    L.dwp = at; at += up(4 * H * kp * f);
-    L.dbp = at; at += up(4 * H * f);
+    L.partial = at; at += up((size_t)kSeqWgradGroups * (4 * H * kp + 4 * H) * f);
     L.total = at;
     return L;
 }
@@ -1079,12 +1084,12 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
     const float *cst = (const float *)((const char *)hst + states);
     float *tape_g = (float *)(w + L.tape_g), *tape_c = (float *)(w + L.tape_c), *tape_h = (float *)(w + L.tape_h);
     float *dx = (float *)(w + L.dx), *gh = (float *)(w + L.gh), *gc = (float *)(w + L.gc), *wqt = (float *)(w + L.wqt);
-    float *dwp = (float *)(w + L.dwp), *dbp = (float *)(w + L.dbp);
+    float *partial = (float *)(w + L.partial);
     const int64_t cells = (int64_t)h->step_x.size();
     auto blocks = [](int64_t total) { return dim3((unsigned)std::min<int64_t>((total + 255) / 256, 65535 * 16)); };
-    // gradient rows of the kept states and the packed weight gradients start at zero (gh .. dbp are adjacent)
+    // gradient rows of the kept states start at zero (gh and gc are adjacent)
     {
-        const int64_t total = (int64_t)((L.total - L.gh) / sizeof(float));
+        const int64_t total = (int64_t)((L.wqt - L.gh) / sizeof(float));
         hipLaunchKernelGGL(seq_fill_kernel, blocks(total), dim3(256), 0, s, gh, total);
         HIP_TRY(hipGetLastError());
     }
@@ -1113,17 +1118,17 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
         hipLaunchKernelGGL(seq_input_grad_kernel, blocks(total), dim3(256), 0, s, h->d_xt_ptr, h->d_xt_idx, dx, g_x, h->n, (int)d);
         HIP_TRY(hipGetLastError());
     }
-    if (cells > 0) {
+    {
         SeqWgradArgs g;
         g.dg = tape_g; g.x = x; g.tape_h = tape_h; g.h_state = hst; g.step_x = h->d_step_x; g.step_prev = h->d_step_prev;
-        g.cells = cells; g.d = (int32_t)d; g.hidden = (int32_t)hidden; g.kp = kp; g.dwp = dwp; g.dbp = dbp;
+        g.cells = cells; g.d = (int32_t)d; g.hidden = (int32_t)hidden; g.kp = kp; g.partial = partial;
         const int64_t chunks = (cells + kSeqWgradCells - 1) / kSeqWgradCells;
-        hipLaunchKernelGGL(seq_weight_grad_kernel, dim3((unsigned)std::min<int64_t>(chunks, 1024)), dim3(256), 0, s, g);
+        const int groups = (int)std::max<int64_t>(std::min<int64_t>(chunks, kSeqWgradGroups), 1);
+        hipLaunchKernelGGL(seq_weight_grad_kernel, dim3((unsigned)groups), dim3(512), 0, s, g);
         HIP_TRY(hipGetLastError());
-    }
-    {
-        const int64_t total = (int64_t)4 * hidden * kp;
-        hipLaunchKernelGGL(seq_unpack_grad_kernel, blocks(total), dim3(256), 0, s, dwp, dbp, g_w_ih, g_w_hh, g_b, (int)d, (int)hidden, kp);
+        const int64_t per = (int64_t)4 * hidden * kp + 4 * hidden;
+        hipLaunchKernelGGL(seq_weight_grad_reduce_kernel, blocks(per), dim3(256), 0, s, partial, groups, g_w_ih, g_w_hh, g_b, (int)d,
+                           (int)hidden, kp);
         HIP_TRY(hipGetLastError());
     }
     return HAG_OK;
