@@ -417,41 +417,61 @@ __global__ __launch_bounds__(256) void seq_final_grad_kernel(const int32_t *__re
     }
 }
 
-__global__ __launch_bounds__(512, 2) void seq_reverse_kernel(SeqRevArgs A) {
-    constexpr int ZG = kSeqRevStride, HS = 65;
-    __shared__ __align__(16) float zg[kSeqJobs * ZG];      // per path: the pre-activation gradients of the current step, then the product's dx
-    __shared__ float dh[kSeqJobs * HS], dc[kSeqJobs * HS];
+__global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
+    constexpr int ZG = kSeqRevStride;
+    // per path: the pre-activation gradients of the current step (the product's operand), then the product's result
+    // (dx, dh_prev); the running dh and dc themselves stay in the registers of the path's eight threads
+    __shared__ __align__(16) float zg[kSeqJobs * ZG];
     __shared__ int32_t sdesc[kSeqJobs * 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int hidden = A.hidden, d = A.d, n_rt = A.kp / 32;          // 2 or 4 row tiles of the product
     const int rt = wave % n_rt, grp = wave / n_rt;                   // this wavefront's row tile and half of the paths
     const bool multiplies = grp < 2;
-    const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;         // element-wise phases: 8 threads per path
+    const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;         // element-wise phases: 8 threads per path, all in one wavefront
     for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
         if (threadIdx.x < kSeqJobs * 4) sdesc[threadIdx.x] = A.paths[ct * (kSeqJobs * 4) + threadIdx.x];
         __syncthreads();
         const int steps = sdesc[2];
         const int start = sdesc[sj * 4], beg = sdesc[sj * 4 + 1], len = sdesc[sj * 4 + 2], node = sdesc[sj * 4 + 3];
-        for (int u = part * 4; u < hidden; u += 32) {
+        float dhv[2][4], dcv[2][4];                        // units part * 4 + 32 * it + e
+#pragma unroll
+        for (int it = 0; it < 2; ++it) {
+            const int u = part * 4 + 32 * it;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (node >= 0) v = *reinterpret_cast<const float4 *>(A.g_a + (size_t)node * hidden + u);
-            dh[sj * HS + u] = v.x; dh[sj * HS + u + 1] = v.y; dh[sj * HS + u + 2] = v.z; dh[sj * HS + u + 3] = v.w;
-            dc[sj * HS + u] = 0.f; dc[sj * HS + u + 1] = 0.f; dc[sj * HS + u + 2] = 0.f; dc[sj * HS + u + 3] = 0.f;
+            if (node >= 0 && u < hidden) v = *reinterpret_cast<const float4 *>(A.g_a + (size_t)node * hidden + u);
+            dhv[it][0] = v.x; dhv[it][1] = v.y; dhv[it][2] = v.z; dhv[it][3] = v.w;
+            dcv[it][0] = dcv[it][1] = dcv[it][2] = dcv[it][3] = 0.f;
         }
-        __syncthreads();
         for (int t = steps - 1; t >= 0; --t) {
             if (t < len) {
                 const size_t cell = (size_t)beg + t;
-                const int keep = A.step_out[cell];
-                for (int u = part * 4; u < hidden; u += 32) {
-                    float dhv[4], dcv[4], cn[4], cp[4];
+                if (t + 1 < len) {
+                    // the product of the step before left (dx, dh_prev) of this path in its row: dx goes out, dh_prev is this
+                    // step's dh.  Only this path's own lanes touch the row between the barriers, and they read it before
+                    // they overwrite it below (one wavefront, program order).
+                    for (int k = part * 4; k < d; k += 32) {
+                        const float *pz = &zg[sj * ZG + k];
+                        *reinterpret_cast<float4 *>(A.dx + (cell + 1) * d + k) = make_float4(pz[0], pz[1], pz[2], pz[3]);
+                    }
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) { dhv[e] = dh[sj * HS + u + e]; dcv[e] = dc[sj * HS + u + e]; }
+                    for (int it = 0; it < 2; ++it) {
+                        const int u = part * 4 + 32 * it;
+                        if (u >= hidden) continue;
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) dhv[it][e] = zg[sj * ZG + d + u + e];
+                    }
+                }
+                const int keep = A.step_out[cell];
+#pragma unroll
+                for (int it = 0; it < 2; ++it) {
+                    const int u = part * 4 + 32 * it;
+                    if (u >= hidden) continue;
+                    float cn[4], cp[4];
                     if (keep >= 0) {                       // what the other users of this state sent back
                         const float4 a = *reinterpret_cast<const float4 *>(A.gh + (size_t)keep * hidden + u);
                         const float4 b = *reinterpret_cast<const float4 *>(A.gc + (size_t)keep * hidden + u);
-                        dhv[0] += a.x; dhv[1] += a.y; dhv[2] += a.z; dhv[3] += a.w;
-                        dcv[0] += b.x; dcv[1] += b.y; dcv[2] += b.z; dcv[3] += b.w;
+                        dhv[it][0] += a.x; dhv[it][1] += a.y; dhv[it][2] += a.z; dhv[it][3] += a.w;
+                        dcv[it][0] += b.x; dcv[it][1] += b.y; dcv[it][2] += b.z; dcv[it][3] += b.w;
                     }
                     {
                         const float4 a = *reinterpret_cast<const float4 *>(A.tape_c + cell * hidden + u);
@@ -466,14 +486,14 @@ __global__ __launch_bounds__(512, 2) void seq_reverse_kernel(SeqRevArgs A) {
                         float4 *pg = reinterpret_cast<float4 *>(A.tape_g + (cell * hidden + u + e) * 4);
                         const float4 g4 = *pg;             // i, f, g, o
                         const float tc = seq_tanh(cn[e]);
-                        const float d_o = dhv[e] * tc;
-                        const float dcc = dcv[e] + dhv[e] * g4.w * (1.f - tc * tc);
+                        const float d_o = dhv[it][e] * tc;
+                        const float dcc = dcv[it][e] + dhv[it][e] * g4.w * (1.f - tc * tc);
                         const float4 dg = make_float4(dcc * g4.z * g4.x * (1.f - g4.x), dcc * cp[e] * g4.y * (1.f - g4.y),
                                                       dcc * g4.x * (1.f - g4.z * g4.z), d_o * g4.w * (1.f - g4.w));
                         *pg = dg;                          // kept for the weight gradients
                         *reinterpret_cast<float2 *>(&zg[sj * ZG + (u + e) * 4]) = make_float2(dg.x, dg.y);
                         *reinterpret_cast<float2 *>(&zg[sj * ZG + (u + e) * 4 + 2]) = make_float2(dg.z, dg.w);
-                        dc[sj * HS + u + e] = dcc * g4.y;
+                        dcv[it][e] = dcc * g4.y;
                     }
                 }
             }
@@ -502,27 +522,28 @@ __global__ __launch_bounds__(512, 2) void seq_reverse_kernel(SeqRevArgs A) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int row = rt * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                        if (row < d) zg[j * ZG + row] = acc[r];
-                        else if (row < d + hidden) dh[j * HS + row - d] = acc[r];
+                        if (row < d + hidden) zg[j * ZG + row] = acc[r];
                     }
                 }
             }
             __syncthreads();
-            if (t < len) {                                 // the step's dx row; read back by this path's own lanes only
-                const size_t cell = (size_t)beg + t;
-                for (int k = part * 4; k < d; k += 32) {
-                    const float *pz = &zg[sj * ZG + k];
-                    *reinterpret_cast<float4 *>(A.dx + cell * d + k) = make_float4(pz[0], pz[1], pz[2], pz[3]);
-                }
-            }
         }
-        // what is left is the gradient of the state the path started from
-        if (start >= 0 && len > 0) {
-            for (int u = part * 4; u < hidden; u += 32) {
+        // the first step's dx, and what is left: the gradient of the state the path started from
+        if (len > 0) {
+            for (int k = part * 4; k < d; k += 32) {
+                const float *pz = &zg[sj * ZG + k];
+                *reinterpret_cast<float4 *>(A.dx + (size_t)beg * d + k) = make_float4(pz[0], pz[1], pz[2], pz[3]);
+            }
+            if (start >= 0) {
 #pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    __hip_atomic_fetch_add(A.gh + (size_t)start * hidden + u + e, dh[sj * HS + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                    __hip_atomic_fetch_add(A.gc + (size_t)start * hidden + u + e, dc[sj * HS + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                for (int it = 0; it < 2; ++it) {
+                    const int u = part * 4 + 32 * it;
+                    if (u >= hidden) continue;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        __hip_atomic_fetch_add(A.gh + (size_t)start * hidden + u + e, zg[sj * ZG + d + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                        __hip_atomic_fetch_add(A.gc + (size_t)start * hidden + u + e, dcv[it][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    }
                 }
             }
         }
@@ -1110,7 +1131,7 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
         r.wqt = wqt; r.tape_g = tape_g; r.tape_c = tape_c; r.c_state = cst; r.g_a = g_a; r.gh = gh; r.gc = gc; r.dx = dx;
         r.d = (int32_t)d; r.hidden = (int32_t)hidden; r.kp = kp;
         if (r.n_path_tiles <= 0) continue;
-        hipLaunchKernelGGL(seq_reverse_kernel, dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 256)), dim3(512), 0, s, r);
+        hipLaunchKernelGGL(seq_reverse_kernel, dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
         HIP_TRY(hipGetLastError());
     }
     {
