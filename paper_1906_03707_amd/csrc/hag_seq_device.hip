@@ -596,18 +596,21 @@ __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A)
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
     float accb = 0.f;                                      // thread i < 4H: the sum of dG[.][i]
     const int64_t chunks = (A.cells + CK - 1) / CK;
-    for (int64_t ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
+    // the next 32 steps' rows are requested into registers before the products of the current ones (4 + 2 vectors a thread)
+    float4 rg[4], rz[2];
+    auto request = [&](int64_t ch) {
         const int64_t c0 = ch * CK;
-        for (int i = threadIdx.x; i < CK * 64; i += 512) {
-            const int c = i / 64, k = (i % 64) * 4;
-            float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c0 + c < A.cells && k < rows) v = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + k);
-            *reinterpret_cast<float4 *>(&sdg[c][k]) = v;
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int i = threadIdx.x + 512 * v4, c = i / 64, k = (i % 64) * 4;
+            rg[v4] = make_float4(0.f, 0.f, 0.f, 0.f);
+            if (ch < chunks && c0 + c < A.cells && k < rows) rg[v4] = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + k);
         }
-        for (int i = threadIdx.x; i < CK * 32; i += 512) {
-            const int c = i / 32, k = (i % 32) * 4;
+#pragma unroll
+        for (int v4 = 0; v4 < 2; ++v4) {
+            const int i = threadIdx.x + 512 * v4, c = i / 32, k = (i % 32) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (c0 + c < A.cells) {
+            if (ch < chunks && c0 + c < A.cells) {
                 if (k < d) v = *reinterpret_cast<const float4 *>(A.x + (size_t)A.step_x[c0 + c] * d + k);
                 else if (k < d + hidden) {
                     const int pv = A.step_prev[c0 + c];
@@ -615,9 +618,23 @@ __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A)
                     else if (pv <= -2) v = *reinterpret_cast<const float4 *>(A.h_state + (size_t)(-pv - 2) * hidden + (k - d));
                 }
             }
-            *reinterpret_cast<float4 *>(&sz[c][k]) = v;
+            rz[v4] = v;
+        }
+    };
+    request(blockIdx.x);
+    for (int64_t ch = blockIdx.x; ch < chunks; ch += gridDim.x) {
+#pragma unroll
+        for (int v4 = 0; v4 < 4; ++v4) {
+            const int i = threadIdx.x + 512 * v4;
+            *reinterpret_cast<float4 *>(&sdg[i / 64][(i % 64) * 4]) = rg[v4];
+        }
+#pragma unroll
+        for (int v4 = 0; v4 < 2; ++v4) {
+            const int i = threadIdx.x + 512 * v4;
+            *reinterpret_cast<float4 *>(&sz[i / 32][(i % 32) * 4]) = rz[v4];
         }
         __syncthreads();
+        request(ch + gridDim.x);
         if (wave < n_rt) {
 #pragma unroll
             for (int st = 0; st < CK / 2; ++st) {
