@@ -166,7 +166,7 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
  * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: the longest chain of dependent evaluations;
  * hag_seq_launches: cell-kernel launches of one pass (the levels of hag_seq_get_plan); hag_seq_merges: aggregation
- * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32, forward only): x [n, d], w_ih [4H, d],
+ * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32; inference, the training pair is further down): x [n, d], w_ih [4H, d],
  * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
  * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights, one (h, c) state row and one flag
  * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 128, d + H <= 256 (H <= 64 with

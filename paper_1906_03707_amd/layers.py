@@ -71,8 +71,8 @@ def sage_pool2_loss(h, x, pool, comb, labels, naive=False, record=None):
 
 
 def sage_lstm2_logits(seq, x, cells, comb):
-    """Logits of a 2-layer GraphSAGE with LSTM aggregators over ordered neighbour lists (inference only: the
-    library's LSTM aggregator has no backward pass).  seq: binding.SeqHag (a prefix HAG or the plain lists);
+    """Logits of a 2-layer GraphSAGE with LSTM aggregators over ordered neighbour lists (inference; training would wrap
+    SeqHag.lstm_forward_train / lstm_backward the way `aggregation` wraps the set aggregates).  seq: binding.SeqHag (a prefix HAG or the plain lists);
     cells[i] = (w_ih, w_hh, b) of layer i; comb[i] = W2 of layer i, [hidden_i + d_i, d_{i+1}].
     a_v = LSTM over (h_u : u in N(v)), h'_v = relu(W2 [a_v, h_v]); the second layer has no ReLU."""
     with torch.no_grad():
