@@ -402,6 +402,22 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         res["plans"][name]["sage_lstm2_inference_ms"] = ms
         res["plans"][name]["sage_lstm2_inference_speedup_vs_lists"] = ms_base / ms
         log(f"[bench] 2-layer GraphSAGE-LSTM inference, {name}: {ms:.3f} ms ({ms_base / ms:.2f}x the plain lists' speed)")
+    # and its training epoch (forward + backward through both layers; Section 5.3's other figure), where the sizes allow
+    if plans and next(iter(plans.values())).train_workspace_bytes(d, hidden) > 0:
+        labels = torch.randint(0, 16, (n,), device="cuda", generator=gen)
+        params = [t.requires_grad_() for c in cells for t in c] + [w.requires_grad_() for w in comb]
+        def epoch(p):
+            for t in params:
+                t.grad = None
+            layers.sage_lstm2_loss(p, x, cells, comb, labels).backward()
+        base_ms = None
+        for name, p in plans.items():
+            ms, _ = time_steps(torch, lambda p=p: epoch(p), max(steps // 2, 3), 2)
+            base_ms = ms if name == "lists" else base_ms
+            res["plans"][name]["sage_lstm2_epoch_ms"] = ms
+            res["plans"][name]["sage_lstm2_epoch_speedup_vs_lists"] = (base_ms / ms) if base_ms else float("nan")
+            log(f"[bench] 2-layer GraphSAGE-LSTM training epoch, {name}: {ms:.3f} ms"
+                + (f" ({base_ms / ms:.2f}x the plain lists' speed)" if base_ms else ""))
     return res
 
 

@@ -137,3 +137,30 @@ def sage_lstm2_logits(rowptr, col, x, cells, comb):
     comb[i] = W2 of layer i [hidden_i + d_i, d_{i+1}]; the second layer has no ReLU."""
     h1 = sage_lstm_layer(rowptr, col, x, *cells[0], comb[0], relu_out=True)
     return sage_lstm_layer(rowptr, col, h1, *cells[1], comb[1], relu_out=False)
+
+
+def sage_lstm2(rowptr, col, x, cells, comb, labels):
+    """Loss and gradients of the 2-layer GraphSAGE with LSTM aggregators above under a SoftMax cross-entropy loss (the
+    chain rule through sage_lstm_layer, the aggregator's part being lstm.naive_aggregate_backward).
+    Returns loss, logits, g_cells [(g_w_ih, g_w_hh, g_b)] and g_comb per layer, and g_x."""
+    from . import lstm
+    x = np.asarray(x, dtype=np.float64)
+    cells = [tuple(np.asarray(a, dtype=np.float64) for a in c) for c in cells]
+    comb = [np.asarray(w, dtype=np.float64) for w in comb]
+    hs, cats, pres = [x], [], []
+    for i in range(2):
+        a, _ = lstm.naive_aggregate(rowptr, col, hs[i], *cells[i])
+        cats.append(np.concatenate([a, hs[i]], axis=1))
+        pres.append(cats[i] @ comb[i])
+        hs.append(np.maximum(pres[i], 0.0) if i == 0 else pres[i])
+    loss, g = softmax_xent(hs[2], labels)
+    g_cells, g_comb = [None, None], [None, None]
+    for i in (1, 0):
+        g_pre = g * (pres[i] > 0) if i == 0 else g
+        g_comb[i] = cats[i].T @ g_pre
+        g_cat = g_pre @ comb[i].T
+        hidden = cells[i][1].shape[1]
+        g_x, g_wi, g_wh, g_b = lstm.naive_aggregate_backward(rowptr, col, hs[i], *cells[i], g_cat[:, :hidden])
+        g_cells[i] = (g_wi, g_wh, g_b)
+        g = g_cat[:, hidden:] + g_x
+    return dict(loss=loss, logits=hs[2], g_cells=g_cells, g_comb=g_comb, g_x=g)

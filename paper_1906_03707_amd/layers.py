@@ -83,3 +83,37 @@ def sage_lstm2_logits(seq, x, cells, comb):
             if i == 0:
                 h = torch.relu(h)
         return h
+
+
+def lstm_aggregation(seq):
+    """torch.autograd.Function around SeqHag.lstm_forward_train / lstm_backward: a = f(x, w_ih, w_hh, b)."""
+    class Agg(torch.autograd.Function):
+        @staticmethod
+        def forward(ctx, x, w_ih, w_hh, b):
+            x = x.contiguous()
+            a, ws = seq.lstm_forward_train(x, w_ih.contiguous(), w_hh.contiguous(), b.contiguous())
+            ctx.save_for_backward(x)
+            ctx.ws, ctx.hidden = ws, int(w_hh.shape[1])
+            return a
+
+        @staticmethod
+        def backward(ctx, g):
+            (x,) = ctx.saved_tensors
+            out = seq.lstm_backward(x, g.contiguous(), ctx.hidden, ctx.ws)
+            ctx.ws = None
+            return out
+
+    return Agg.apply
+
+
+def sage_lstm2_loss(seq, x, cells, comb, labels):
+    """SoftMax cross-entropy of the 2-layer GraphSAGE with LSTM aggregators of sage_lstm2_logits, differentiable:
+    the aggregator's forward and backward passes are the library's, the dense parts torch."""
+    agg = lstm_aggregation(seq)
+    h = x
+    for i in range(2):
+        a = agg(h, *cells[i])
+        h = torch.cat([a, h], dim=1) @ comb[i]
+        if i == 0:
+            h = torch.relu(h)
+    return torch.nn.functional.cross_entropy(h, labels)

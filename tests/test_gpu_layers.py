@@ -132,3 +132,36 @@ def test_two_layer_graphsage_lstm_inference(B, capacity):
     err = rel(got.cpu().numpy(), want)
     print(f"{capacity}: {seq.cells} cells, relative error of the logits {err:.2e}")
     assert err <= 1e-5
+
+
+@pytest.mark.parametrize("capacity", ["lists", "unlimited"])
+def test_two_layer_graphsage_lstm_training(B, capacity):
+    # the same model trained: loss and every gradient (both LSTM cells, both dense maps) against the fp64 layer oracle,
+    # norm-wise; the aggregator's forward and backward passes are the library's over the plain lists or a prefix HAG
+    from paper_1906_03707_amd import layers, workloads
+    rowptr, col = synth.holme_kim(600, 6, 0.5, seed=97)
+    rp, cl = workloads.first_neighbour_lists(rowptr, col, 10)
+    n, d, hidden, classes = rp.size - 1, 16, 24, 6
+    rng = np.random.default_rng(98)
+    dims = [d, hidden, classes]
+    cells = [(rng.normal(0, 0.3, (4 * hidden, dims[i])), rng.normal(0, 0.3, (4 * hidden, hidden)), rng.normal(0, 0.3, 4 * hidden))
+             for i in range(2)]
+    comb = [rng.normal(0, 1.0 / np.sqrt(hidden + dims[i]), (hidden + dims[i], dims[i + 1])) for i in range(2)]
+    x = rng.normal(size=(n, d))
+    labels = rng.integers(0, classes, n)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    r64 = lambda a: dev(a).cpu().numpy().astype(np.float64)
+    ref = OL.sage_lstm2(rp, cl, r64(x), [tuple(r64(a) for a in c) for c in cells], [r64(w) for w in comb], labels)
+    seq = B.SeqHag(rp, cl, {"lists": 0, "unlimited": int(cl.size)}[capacity]).upload()
+    xd = dev(x).requires_grad_()
+    cd = [tuple(dev(a).requires_grad_() for a in c) for c in cells]
+    wd = [dev(w).requires_grad_() for w in comb]
+    loss = layers.sage_lstm2_loss(seq, xd, cd, wd, torch.from_numpy(labels).cuda())
+    loss.backward()
+    seq.check()
+    assert abs(loss.item() - ref["loss"]) <= 1e-5 * abs(ref["loss"])
+    assert rel(xd.grad.cpu().numpy(), ref["g_x"]) <= 1e-4
+    for i in range(2):
+        assert rel(wd[i].grad.cpu().numpy(), ref["g_comb"][i]) <= 1e-4, i
+        for k in range(3):
+            assert rel(cd[i][k].grad.cpu().numpy(), ref["g_cells"][i][k]) <= 1e-4, (i, k)

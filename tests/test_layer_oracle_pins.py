@@ -124,3 +124,45 @@ def test_sage_lstm_layer_against_library_modules():
         want = torch.relu(lin(torch.cat([a, ht], dim=1))).numpy()
     np.testing.assert_allclose(got, want, rtol=1e-12, atol=1e-13)
     assert (got[[1, 6]] == np.maximum(np.concatenate([np.zeros((2, hidden)), h[[1, 6]]], axis=1) @ w2, 0)).all()   # empty lists: a_v = 0
+
+
+def test_sage_lstm2_gradients_against_library_autograd():
+    # the 2-layer model built from library modules (LSTM run list by list, Linear, ReLU, cross entropy), differentiated
+    # by the library, in fp64
+    torch = __import__("pytest").importorskip("torch")
+    rng = np.random.default_rng(23)
+    n, d, hidden, classes = 8, 3, 4, 3
+    rowptr = np.array([0, 3, 3, 5, 9, 10, 12, 12, 14], dtype=np.int64)
+    col = np.array([2, 0, 1, 4, 4, 6, 5, 0, 2, 3, 1, 1, 7, 0], dtype=np.int32)
+    dims = [d, 5, classes]
+    cells = [(rng.normal(0, 0.5, (4 * hidden, dims[i])), rng.normal(0, 0.5, (4 * hidden, hidden)), rng.normal(0, 0.5, 4 * hidden)) for i in range(2)]
+    comb = [rng.normal(0, 0.5, (hidden + dims[i], dims[i + 1])) for i in range(2)]
+    x = rng.normal(size=(n, d))
+    labels = rng.integers(0, classes, n)
+    got = L.sage_lstm2(rowptr, col, x, cells, comb, labels)
+    t = lambda a: torch.from_numpy(np.asarray(a)).clone().requires_grad_()
+    xt, ct, wt = t(x), [tuple(t(a) for a in c) for c in cells], [t(w) for w in comb]
+    h = xt
+    for i in range(2):
+        rows = []
+        for v in range(n):
+            ids = col[rowptr[v]:rowptr[v + 1]].astype(np.int64)
+            if ids.size == 0:
+                rows.append(torch.zeros(hidden, dtype=torch.float64))
+                continue
+            hv, cv = torch.zeros(hidden, dtype=torch.float64), torch.zeros(hidden, dtype=torch.float64)
+            for u in ids:
+                hv, cv = torch._VF.lstm_cell(h[u][None], (hv[None], cv[None]), ct[i][0], ct[i][1], ct[i][2], None)
+                hv, cv = hv[0], cv[0]
+            rows.append(hv)
+        h = torch.cat([torch.stack(rows), h], dim=1) @ wt[i]
+        if i == 0:
+            h = torch.relu(h)
+    loss = torch.nn.functional.cross_entropy(h, torch.from_numpy(labels))
+    loss.backward()
+    assert abs(loss.item() - got["loss"]) <= 1e-12
+    np.testing.assert_allclose(got["g_x"], xt.grad.numpy(), rtol=1e-9, atol=1e-12)
+    for i in range(2):
+        np.testing.assert_allclose(got["g_comb"][i], wt[i].grad.numpy(), rtol=1e-9, atol=1e-12)
+        for k in range(3):
+            np.testing.assert_allclose(got["g_cells"][i][k], ct[i][k].grad.numpy(), rtol=1e-9, atol=1e-12)
