@@ -365,9 +365,7 @@ def seq_lstm_bench(torch, binding, synth, cfg, first_k, d, hidden, steps, warmup
         ws = torch.empty(max(p.train_workspace_bytes(d, hidden) for p in plans.values()), dtype=torch.uint8, device="cuda")
         def train_step(p):
             p.lstm_forward_train(x, w_ih, w_hh, b, workspace=ws)
-            p.lstm_backward(x, g_a, hidden, ws)
-        def bwd_only(p):
-            p.lstm_backward(x, g_a, hidden, ws)
+            p.lstm_backward(x, w_ih, w_hh, g_a, ws)
         for name, p in plans.items():
             ms, _ = time_steps(torch, lambda p=p: train_step(p), steps, warmup)
             p.lstm_forward_train(x, w_ih, w_hh, b, workspace=ws)

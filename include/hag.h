@@ -212,22 +212,22 @@ size_t hag_seq_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
 int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,
                          const float *w_hh, const float *b, float *a_out, void *workspace, void *stream);
 
-/* Training with the LSTM aggregator (hidden <= 64, d + hidden <= 128; other sizes: HAG_EINVAL).
+/* Training with the LSTM aggregator (the sizes of hag_seq_lstm_forward).
  * hag_seq_lstm_forward_train is hag_seq_lstm_forward that also keeps, in `workspace`
  * (hag_seq_train_workspace_bytes(h, d, hidden) bytes, 16-byte aligned), what the backward pass needs of every cell: the
  * activated gates, c and h (24 H bytes per cell evaluation), besides the states of the shared prefixes.
- * hag_seq_lstm_backward, called after it with the same handle, sizes, x and workspace (nothing else may have used the
- * workspace in between), backpropagates through time along the plan's paths, last step first: given g_a [n, H], the gradient
- * of a loss with respect to a_out, it writes the gradients g_x [n, d], g_w_ih [4H, d], g_w_hh [4H, H], g_b [4H]
+ * hag_seq_lstm_backward, called after it with the same handle, sizes, x, w_ih, w_hh and workspace (nothing else may have
+ * used the workspace in between), backpropagates through time along the plan's paths, last step first: given g_a [n, H], the
+ * gradient of a loss with respect to a_out, it writes the gradients g_x [n, d], g_w_ih [4H, d], g_w_hh [4H, H], g_b [4H]
  * (the layouts of x, w_ih, w_hh, b).  A shared prefix is differentiated once, with the gradients of everything that
- * continues from it added up first (fp32 atomics: the last bits depend on the order).  Device pointers, fp32; enqueues on
- * `stream` and returns; allocates nothing.  The packed weights of the forward pass are reused: w_ih, w_hh, b must be
- * unchanged since hag_seq_lstm_forward_train. */
+ * continues from it added up first (fp32 atomics: the last bits of g_x and of the weight gradients depend on the order in
+ * which those arrive).  Device pointers, fp32; enqueues on `stream` and returns; allocates nothing. */
 size_t hag_seq_train_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
 int hag_seq_lstm_forward_train(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,
                                const float *w_hh, const float *b, float *a_out, void *workspace, void *stream);
-int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *g_a, float *g_x,
-                          float *g_w_ih, float *g_w_hh, float *g_b, void *workspace, void *stream);
+int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                          const float *g_a, float *g_x, float *g_w_ih, float *g_w_hh, float *g_b, void *workspace,
+                          void *stream);
 
 void hag_free(hag_t *h);
 

@@ -103,7 +103,7 @@ def lib():
         L.hag_seq_train_workspace_bytes.argtypes = [vp, i64, i64]
         L.hag_seq_train_workspace_bytes.restype = ctypes.c_size_t
         L.hag_seq_lstm_forward_train.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
-        L.hag_seq_lstm_backward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.hag_seq_lstm_backward.argtypes = [vp, i64, i64] + [vp] * 10
         L.hag_seq_workspace_bytes.argtypes = [vp, i64, i64]
         L.hag_seq_workspace_bytes.restype = ctypes.c_size_t
         L.hag_seq_lstm_forward.argtypes = [vp, i64, i64, vp, vp, vp, vp, vp, vp, vp]
@@ -444,7 +444,7 @@ class SeqHag:
                 raise ValueError(f"{name} must be a contiguous float32 device tensor of shape {shape}")
         need = self.train_workspace_bytes(d, hidden)
         if need == 0:
-            raise ValueError("training needs hidden <= 64 and d + hidden <= 128 (d a multiple of 4, hidden of 8)")
+            raise ValueError("d must be a multiple of 4, hidden a multiple of 8 up to 128, d + hidden at most 256")
         if workspace is None:
             workspace = torch.empty(need, dtype=torch.uint8, device=x.device)
         elif workspace.numel() * workspace.element_size() < need or workspace.device != x.device:
@@ -454,20 +454,22 @@ class SeqHag:
                                                 _dev_ptr(out), _dev_ptr(workspace), _stream_ptr()))
         return out, workspace
 
-    def lstm_backward(self, x, g_a, hidden, workspace):
+    def lstm_backward(self, x, w_ih, w_hh, g_a, workspace):
         """Gradients (g_x, g_w_ih, g_w_hh, g_b) of a loss with gradient g_a [n, H] at a_out, after lstm_forward_train with
-        the same x and workspace."""
+        the same x, w_ih, w_hh and workspace."""
         import torch
-        d = int(x.shape[1])
-        for name, t, shape in (("x", x, (self.n, d)), ("g_a", g_a, (self.n, hidden))):
+        hidden, d = int(w_hh.shape[1]), int(x.shape[1])
+        for name, t, shape in (("x", x, (self.n, d)), ("w_ih", w_ih, (4 * hidden, d)), ("w_hh", w_hh, (4 * hidden, hidden)),
+                               ("g_a", g_a, (self.n, hidden))):
             if tuple(t.shape) != shape or t.dtype != torch.float32 or not t.is_cuda or not t.is_contiguous():
                 raise ValueError(f"{name} must be a contiguous float32 device tensor of shape {shape}")
-        if workspace.numel() * workspace.element_size() < self.train_workspace_bytes(d, hidden) or workspace.device != x.device:
+        need = self.train_workspace_bytes(d, hidden)
+        if need == 0 or workspace.numel() * workspace.element_size() < need or workspace.device != x.device:
             raise ValueError("workspace too small or on another device")
         new = lambda *shape: torch.empty(shape, dtype=torch.float32, device=x.device)
         g_x, g_w_ih, g_w_hh, g_b = new(self.n, d), new(4 * hidden, d), new(4 * hidden, hidden), new(4 * hidden)
-        _check(lib().hag_seq_lstm_backward(self._h, d, hidden, _dev_ptr(x), _dev_ptr(g_a), _dev_ptr(g_x), _dev_ptr(g_w_ih),
-                                           _dev_ptr(g_w_hh), _dev_ptr(g_b), _dev_ptr(workspace), _stream_ptr()))
+        _check(lib().hag_seq_lstm_backward(self._h, d, hidden, _dev_ptr(x), _dev_ptr(w_ih), _dev_ptr(w_hh), _dev_ptr(g_a), _dev_ptr(g_x),
+                                           _dev_ptr(g_w_ih), _dev_ptr(g_w_hh), _dev_ptr(g_b), _dev_ptr(workspace), _stream_ptr()))
         return g_x, g_w_ih, g_w_hh, g_b
 
     def check(self):

@@ -52,7 +52,7 @@ struct hag_seq {
     std::vector<int32_t> step_prev, xt_ptr, xt_idx;
     int32_t *d_step_prev = nullptr, *d_xt_ptr = nullptr, *d_xt_idx = nullptr;
     int64_t resident[6] = {0, 0, 0, 0, 0, 0};
-    int64_t resident_tape[4] = {0, 0, 0, 0};   // likewise for the variants that write the tape   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
+    int64_t resident_tape[6] = {0, 0, 0, 0, 0, 0};   // likewise for the variants that write the tape   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
     int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
     int device = -1;
 };
@@ -152,7 +152,7 @@ __device__ __forceinline__ int seq_opaque(int v) { asm volatile("" : "+v"(v)); r
 // stored in the order the matrix instructions consume it, from the L2 cache once per step (16-byte loads, one
 // group of four k-steps ahead): 4H (D + H) * 4 bytes per 64 cells, against 2 * 4H (D + H) * 64 flops.
 template <int KSTEPS, bool WIDE, bool BIG, bool TAPE>
-__global__ __launch_bounds__(BIG ? 1024 : 512, TAPE ? 2 : 4) void seq_chain_kernel(SeqChainArgs A) {
+__global__ __launch_bounds__(BIG ? 1024 : 512, (TAPE && !BIG) ? 2 : 4) void seq_chain_kernel(SeqChainArgs A) {
     static_assert(!BIG || WIDE, "the streamed variant uses the wide tiling");
     constexpr int KP = 2 * KSTEPS, ZS = KP + 2;
     constexpr int HMAX = BIG ? 128 : (WIDE ? 64 : 32);
@@ -391,20 +391,26 @@ struct SeqRevArgs {
     int32_t d, hidden, kp;
 };
 
-constexpr int kSeqRevStride = 4 * 64 + 2;   // row stride of the staged pre-activation gradients (hidden <= 64)
 
 __global__ __launch_bounds__(256) void seq_fill_kernel(float *p, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
 }
 
-// Wp^T for the backward product: [kp / 32 row tiles][4H / 8 groups of four k-steps][64 lanes][4]; lane l supplies row
-// (tile * 32 + l % 32) of Wp^T, i.e. column of Wp, and Wp's row 2 * step + l / 32.
-__global__ __launch_bounds__(256) void seq_pack_transposed_kernel(const float *__restrict__ wp, float *__restrict__ wqt, int hidden, int kp) {
+// Wp^T for the backward product, from the usual layout: [kp / 32 row tiles][4H / 8 groups of four k-steps][64 lanes][4];
+// lane l supplies row (tile * 32 + l % 32) of Wp^T, i.e. column z of Wp = (w_ih | w_hh | 0), and Wp's row 2 * step + l / 32,
+// rows of Wp being ordered (unit, gate).
+__global__ __launch_bounds__(256) void seq_pack_transposed_kernel(const float *__restrict__ w_ih, const float *__restrict__ w_hh,
+                                                                 float *__restrict__ wqt, int d, int hidden, int kp) {
     const int64_t total = (int64_t)kp * 4 * hidden;
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < total; i += (int64_t)gridDim.x * 256) {
         const int per_tile = 32 * 4 * hidden, tile = (int)(i / per_tile), rest = (int)(i % per_tile);
         const int q = rest / 256, lane = (rest % 256) / 4, step = 4 * q + (rest & 3);
-        wqt[i] = wp[(size_t)(2 * step + (lane >> 5)) * kp + tile * 32 + (lane & 31)];
+        const int r = 2 * step + (lane >> 5), z = tile * 32 + (lane & 31);
+        const int row = (r & 3) * hidden + (r >> 2);
+        float v = 0.f;
+        if (z < d) v = w_ih[(size_t)row * d + z];
+        else if (z < d + hidden) v = w_hh[(size_t)row * hidden + (z - d)];
+        wqt[i] = v;
     }
 }
 
@@ -417,25 +423,26 @@ __global__ __launch_bounds__(256) void seq_final_grad_kernel(const int32_t *__re
     }
 }
 
-__global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
-    constexpr int ZG = kSeqRevStride;
+// WIDE_H: hidden above 64 (up to 128): rows of 4 * 128 + 2 staged gradients, one workgroup per compute unit.
+template <bool WIDE_H, int NPI>
+__global__ __launch_bounds__(512, WIDE_H ? 2 : 4) void seq_reverse_kernel(SeqRevArgs A) {
+    constexpr int ZG = 4 * (WIDE_H ? 128 : 64) + 2, IT = WIDE_H ? 4 : 2;
     // per path: the pre-activation gradients of the current step (the product's operand), then the product's result
     // (dx, dh_prev); the running dh and dc themselves stay in the registers of the path's eight threads
     __shared__ __align__(16) float zg[kSeqJobs * ZG];
     __shared__ int32_t sdesc[kSeqJobs * 4];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int hidden = A.hidden, d = A.d, n_rt = A.kp / 32;          // 2 or 4 row tiles of the product
-    const int rt = wave % n_rt, grp = wave / n_rt;                   // this wavefront's row tile and half of the paths
-    const bool multiplies = grp < 2;
+    // the product has n_rt row tiles x 2 halves of the paths; wavefront w takes pairs w and, with more than 8 (NPI = 2), w + 8
     const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;         // element-wise phases: 8 threads per path, all in one wavefront
     for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
         if (threadIdx.x < kSeqJobs * 4) sdesc[threadIdx.x] = A.paths[ct * (kSeqJobs * 4) + threadIdx.x];
         __syncthreads();
         const int steps = sdesc[2];
         const int start = sdesc[sj * 4], beg = sdesc[sj * 4 + 1], len = sdesc[sj * 4 + 2], node = sdesc[sj * 4 + 3];
-        float dhv[2][4], dcv[2][4];                        // units part * 4 + 32 * it + e
+        float dhv[IT][4], dcv[IT][4];                        // units part * 4 + 32 * it + e
 #pragma unroll
-        for (int it = 0; it < 2; ++it) {
+        for (int it = 0; it < IT; ++it) {
             const int u = part * 4 + 32 * it;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (node >= 0 && u < hidden) v = *reinterpret_cast<const float4 *>(A.g_a + (size_t)node * hidden + u);
@@ -454,7 +461,7 @@ __global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
                         *reinterpret_cast<float4 *>(A.dx + (cell + 1) * d + k) = make_float4(pz[0], pz[1], pz[2], pz[3]);
                     }
 #pragma unroll
-                    for (int it = 0; it < 2; ++it) {
+                    for (int it = 0; it < IT; ++it) {
                         const int u = part * 4 + 32 * it;
                         if (u >= hidden) continue;
 #pragma unroll
@@ -463,7 +470,7 @@ __global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
                 }
                 const int keep = A.step_out[cell];
 #pragma unroll
-                for (int it = 0; it < 2; ++it) {
+                for (int it = 0; it < IT; ++it) {
                     const int u = part * 4 + 32 * it;
                     if (u >= hidden) continue;
                     float cn[4], cp[4];
@@ -499,30 +506,38 @@ __global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
             }
             __syncthreads();
             // (dx, dh_prev)^T [kp, paths] = Wp^T [kp, 4H] . dG^T [4H, paths]
-            seq_acc_t acc;
+            seq_acc_t acc[NPI];
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[r] = 0.f;
-            if (multiplies) {
+            for (int pi = 0; pi < NPI; ++pi) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) acc[pi][r] = 0.f;
+                const int pair = wave + 8 * pi;
+                if (pair >= 2 * n_rt) continue;
+                const int rt = pair % n_rt, grp = pair / n_rt;
                 const float4 *wq = reinterpret_cast<const float4 *>(A.wqt) + (size_t)rt * (hidden / 2) * 64 + lane;
                 const float *zl = &zg[(grp * 32 + (lane & 31)) * ZG + (lane >> 5)];
                 float4 wa = wq[0];
                 for (int q = 0; q < hidden / 2; ++q) {
                     const float4 wn = wq[(q + 1 < hidden / 2 ? q + 1 : q) * 64];
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.x, zl[2 * (4 * q + 0)], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.y, zl[2 * (4 * q + 1)], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.z, zl[2 * (4 * q + 2)], acc, 0, 0, 0);
-                    acc = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.w, zl[2 * (4 * q + 3)], acc, 0, 0, 0);
+                    acc[pi] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.x, zl[2 * (4 * q + 0)], acc[pi], 0, 0, 0);
+                    acc[pi] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.y, zl[2 * (4 * q + 1)], acc[pi], 0, 0, 0);
+                    acc[pi] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.z, zl[2 * (4 * q + 2)], acc[pi], 0, 0, 0);
+                    acc[pi] = __builtin_amdgcn_mfma_f32_32x32x2f32(wa.w, zl[2 * (4 * q + 3)], acc[pi], 0, 0, 0);
                     wa = wn;
                 }
             }
             __syncthreads();                               // every product has read the staged gradients
-            if (multiplies) {
+#pragma unroll
+            for (int pi = 0; pi < NPI; ++pi) {
+                const int pair = wave + 8 * pi;
+                if (pair >= 2 * n_rt) continue;
+                const int rt = pair % n_rt, grp = pair / n_rt;
                 const int j = grp * 32 + (lane & 31);
                 if (t < sdesc[j * 4 + 2]) {
 #pragma unroll
                     for (int r = 0; r < 16; ++r) {
                         const int row = rt * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
-                        if (row < d + hidden) zg[j * ZG + row] = acc[r];
+                        if (row < d + hidden) zg[j * ZG + row] = acc[pi][r];
                     }
                 }
             }
@@ -536,7 +551,7 @@ __global__ __launch_bounds__(512, 4) void seq_reverse_kernel(SeqRevArgs A) {
             }
             if (start >= 0) {
 #pragma unroll
-                for (int it = 0; it < 2; ++it) {
+                for (int it = 0; it < IT; ++it) {
                     const int u = part * 4 + 32 * it;
                     if (u >= hidden) continue;
 #pragma unroll
@@ -580,35 +595,38 @@ struct SeqWgradArgs {
     float *partial;          // [gridDim.x][4H * kp + 4H]
 };
 constexpr int kSeqWgradCells = 32;
-constexpr int kSeqWgradGroups = 768;        // workgroups at most (three per compute unit)
+constexpr int kSeqWgradGroups = 768;        // workgroups along x at most (three per compute unit)
+constexpr int64_t kSeqWgradPartialFloats = 64 << 20;   // and no more partial sums than this many floats
 
+// NCT: column tiles of 32 (kp / 32 rounded up to 4 or 8).  blockIdx.y selects a slab of 256 rows of dWp (hidden > 64 has two).
+template <int NCT, bool SLABS>
 __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A) {
-    constexpr int CK = kSeqWgradCells;
+    constexpr int CK = kSeqWgradCells, ZW = NCT * 32, RZ = NCT / 2;
     __shared__ __align__(16) float sdg[CK][256];
-    __shared__ __align__(16) float sz[CK][128];
+    __shared__ __align__(16) float sz[CK][ZW];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int rows = 4 * A.hidden, d = A.d, hidden = A.hidden, kp = A.kp;
-    const int n_rt = rows / 32, n_ct = kp / 32;
-    seq_acc_t acc[4];
+    const int row0 = SLABS ? blockIdx.y * 256 : 0, n_rt = (rows - row0 < 256 ? rows - row0 : 256) / 32, n_ct = kp / 32;
+    seq_acc_t acc[NCT];
 #pragma unroll
-    for (int c = 0; c < 4; ++c)
+    for (int c = 0; c < NCT; ++c)
 #pragma unroll
         for (int r = 0; r < 16; ++r) acc[c][r] = 0.f;
-    float accb = 0.f;                                      // thread i < 4H: the sum of dG[.][i]
+    float accb = 0.f;                                      // thread i < 256: the sum of dG[.][row0 + i]
     const int64_t chunks = (A.cells + CK - 1) / CK;
-    // the next 32 steps' rows are requested into registers before the products of the current ones (4 + 2 vectors a thread)
-    float4 rg[4], rz[2];
+    // the next 32 steps' rows are requested into registers before the products of the current ones
+    float4 rg[4], rz[RZ];
     auto request = [&](int64_t ch) {
         const int64_t c0 = ch * CK;
 #pragma unroll
         for (int v4 = 0; v4 < 4; ++v4) {
             const int i = threadIdx.x + 512 * v4, c = i / 64, k = (i % 64) * 4;
             rg[v4] = make_float4(0.f, 0.f, 0.f, 0.f);
-            if (ch < chunks && c0 + c < A.cells && k < rows) rg[v4] = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + k);
+            if (ch < chunks && c0 + c < A.cells && row0 + k < rows) rg[v4] = *reinterpret_cast<const float4 *>(A.dg + (size_t)(c0 + c) * rows + row0 + k);
         }
 #pragma unroll
-        for (int v4 = 0; v4 < 2; ++v4) {
-            const int i = threadIdx.x + 512 * v4, c = i / 32, k = (i % 32) * 4;
+        for (int v4 = 0; v4 < RZ; ++v4) {
+            const int i = threadIdx.x + 512 * v4, c = i / (ZW / 4), k = (i % (ZW / 4)) * 4;
             float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
             if (ch < chunks && c0 + c < A.cells) {
                 if (k < d) v = *reinterpret_cast<const float4 *>(A.x + (size_t)A.step_x[c0 + c] * d + k);
@@ -629,9 +647,9 @@ __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A)
             *reinterpret_cast<float4 *>(&sdg[i / 64][(i % 64) * 4]) = rg[v4];
         }
 #pragma unroll
-        for (int v4 = 0; v4 < 2; ++v4) {
+        for (int v4 = 0; v4 < RZ; ++v4) {
             const int i = threadIdx.x + 512 * v4;
-            *reinterpret_cast<float4 *>(&sz[i / 32][(i % 32) * 4]) = rz[v4];
+            *reinterpret_cast<float4 *>(&sz[i / (ZW / 4)][(i % (ZW / 4)) * 4]) = rz[v4];
         }
         __syncthreads();
         request(ch + gridDim.x);
@@ -641,11 +659,11 @@ __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A)
                 const int c = 2 * st + (lane >> 5);
                 const float a = sdg[c][wave * 32 + (lane & 31)];
 #pragma unroll
-                for (int ct = 0; ct < 4; ++ct)
+                for (int ct = 0; ct < NCT; ++ct)
                     if (ct < n_ct) acc[ct] = __builtin_amdgcn_mfma_f32_32x32x2f32(a, sz[c][ct * 32 + (lane & 31)], acc[ct], 0, 0, 0);
             }
         }
-        if ((int)threadIdx.x < rows) {
+        if ((int)threadIdx.x < 32 * n_rt) {
 #pragma unroll
             for (int c = 0; c < CK; ++c) accb += sdg[c][threadIdx.x];
         }
@@ -654,16 +672,16 @@ __global__ __launch_bounds__(512, 2) void seq_weight_grad_kernel(SeqWgradArgs A)
     float *out = A.partial + (size_t)blockIdx.x * ((size_t)rows * kp + rows);
     if (wave < n_rt) {
 #pragma unroll
-        for (int ct = 0; ct < 4; ++ct) {
+        for (int ct = 0; ct < NCT; ++ct) {
             if (ct >= n_ct) continue;
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int row = wave * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
+                const int row = row0 + wave * 32 + 8 * (r / 4) + 4 * (lane >> 5) + (r % 4);
                 out[(size_t)row * kp + ct * 32 + (lane & 31)] = acc[ct][r];
             }
         }
     }
-    if ((int)threadIdx.x < rows) out[(size_t)rows * kp + threadIdx.x] = accb;
+    if ((int)threadIdx.x < 32 * n_rt) out[(size_t)rows * kp + row0 + threadIdx.x] = accb;
 }
 
 // adds the workgroups' partial sums in index order and writes the usual layout: rows (unit, gate) -> gate-major rows,
@@ -891,9 +909,10 @@ typedef void (*seq_kernel_t)(SeqChainArgs);
 static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false, false>, seq_chain_kernel<32, true, false, false>,
                                              seq_chain_kernel<64, false, false, false>, seq_chain_kernel<64, true, false, false>,
                                              seq_chain_kernel<96, true, true, false>,   seq_chain_kernel<128, true, true, false>};
-// the same with the tape written (training; the variants that hold Wp in registers only)
-static const seq_kernel_t kSeqTapeVariants[4] = {seq_chain_kernel<32, false, false, true>, seq_chain_kernel<32, true, false, true>,
-                                                 seq_chain_kernel<64, false, false, true>, seq_chain_kernel<64, true, false, true>};
+// the same with the tape written (training)
+static const seq_kernel_t kSeqTapeVariants[6] = {seq_chain_kernel<32, false, false, true>, seq_chain_kernel<32, true, false, true>,
+                                                 seq_chain_kernel<64, false, false, true>, seq_chain_kernel<64, true, false, true>,
+                                                 seq_chain_kernel<96, true, true, true>,   seq_chain_kernel<128, true, true, true>};
 
 int hag_seq_get_plan(const hag_seq_t *h, int32_t order, int64_t *n_states, int64_t *n_paths, const int32_t **paths,
                      const int32_t **step_x, const int32_t **step_out, int64_t *n_levels, const int64_t **level_ptr,
@@ -949,10 +968,8 @@ int hag_seq_upload(hag_seq_t *h) {
             int per_cu = 0;
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqVariants[k], k >= 4 ? 1024 : 512, 0));
             h->resident[k] = (int64_t)std::min(per_cu, 2) * cus;
-            if (k < 4) {
-                HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqTapeVariants[k], 512, 0));
-                h->resident_tape[k] = (int64_t)std::min(per_cu, 2) * cus;
-            }
+            HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqTapeVariants[k], k >= 4 ? 1024 : 512, 0));
+            h->resident_tape[k] = (int64_t)std::min(per_cu, 2) * cus;
         }
     }
     HIP_TRY(put(&h->d_final, h->final_state));
@@ -1056,6 +1073,9 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
     return seq_forward(h, d, hidden, x, w_ih, w_hh, b, a_out, workspace, stream, nullptr, nullptr, nullptr);
 }
 
+// workgroups (along x) of the weight-gradient kernel at most: each leaves one set of partial sums
+static int64_t seq_wgrad_groups(size_t per) { return std::max<int64_t>(std::min<int64_t>(kSeqWgradGroups, kSeqWgradPartialFloats / (int64_t)per), 1); }
+
 // Layout of the training workspace: the forward workspace, then the tape and the backward pass's own buffers.
 struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, wqt, partial, total; };
 static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hidden) {
@@ -1072,12 +1092,12 @@ static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hi
     L.gh = at; at += up(states * H * f);
     L.gc = at; at += up(states * H * f);
     L.wqt = at; at += up(kp * 4 * H * f);
-    L.partial = at; at += up((size_t)kSeqWgradGroups * (4 * H * kp + 4 * H) * f);
+    L.partial = at; at += up((size_t)seq_wgrad_groups(4 * H * kp + 4 * H) * (4 * H * kp + 4 * H) * f);
     L.total = at;
     return L;
 }
 static bool seq_backward_supported(int64_t d, int64_t hidden) {
-    return d > 0 && d % 4 == 0 && hidden > 0 && hidden % 8 == 0 && hidden <= 64 && d + hidden <= 128;
+    return d > 0 && d % 4 == 0 && hidden > 0 && hidden % 8 == 0 && hidden <= 128 && d + hidden <= kSeqMaxK;
 }
 
 size_t hag_seq_train_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden) {
@@ -1089,7 +1109,7 @@ int hag_seq_lstm_forward_train(const hag_seq_t *h, int64_t d, int64_t hidden, co
                                const float *b, float *a_out, void *workspace, void *stream) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
     if (!seq_backward_supported(d, hidden)) {
-        set_error("training: d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+        set_error("d must be a multiple of 4, hidden a multiple of 8 up to 128, d + hidden at most 256");
         return HAG_EINVAL;
     }
     if (!workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
@@ -1099,16 +1119,16 @@ int hag_seq_lstm_forward_train(const hag_seq_t *h, int64_t d, int64_t hidden, co
                        (float *)(w + L.tape_h));
 }
 
-int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *g_a, float *g_x, float *g_w_ih,
-                          float *g_w_hh, float *g_b, void *workspace, void *stream) {
+int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih, const float *w_hh,
+                          const float *g_a, float *g_x, float *g_w_ih, float *g_w_hh, float *g_b, void *workspace, void *stream) {
     if (!h) { set_error("NULL handle"); return HAG_EINVAL; }
     if (!h->d_final) { set_error("hag_seq_upload has not been called on this handle"); return HAG_ESTATE; }
     if (!seq_backward_supported(d, hidden)) {
-        set_error("training: d must be a multiple of 4, hidden a multiple of 8 up to 64, d + hidden at most 128");
+        set_error("d must be a multiple of 4, hidden a multiple of 8 up to 128, d + hidden at most 256");
         return HAG_EINVAL;
     }
     if (h->n == 0) return HAG_OK;
-    if (!x || !g_a || !g_x || !g_w_ih || !g_w_hh || !g_b || !workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
+    if (!x || !w_ih || !w_hh || !g_a || !g_x || !g_w_ih || !g_w_hh || !g_b || !workspace) { set_error("NULL pointer"); return HAG_EINVAL; }
     if (((uintptr_t)x | (uintptr_t)workspace | (uintptr_t)g_a | (uintptr_t)g_x) & 15) { set_error("x, g_a, g_x and workspace must be 16-byte aligned"); return HAG_EINVAL; }
     hipStream_t s = (hipStream_t)stream;
     const int kp = (int)seq_kp(d, hidden);
@@ -1116,7 +1136,6 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
     auto up = [](size_t v) { return (v + 255) & ~(size_t)255; };
     char *w = (char *)workspace;
     // the forward workspace as seq_forward laid it out: packed weights, packed bias, h rows, c rows
-    const float *wp = (const float *)w;
     const size_t states = up((size_t)std::max<int64_t>(h->n_states, 1) * (size_t)hidden * sizeof(float));
     const float *hst = (const float *)(w + up((size_t)4 * hidden * kp * sizeof(float)) + up((size_t)4 * hidden * sizeof(float)));
     const float *cst = (const float *)((const char *)hst + states);
@@ -1133,7 +1152,7 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
     }
     {
         const int64_t total = (int64_t)kp * 4 * hidden;
-        hipLaunchKernelGGL(seq_pack_transposed_kernel, blocks(total), dim3(256), 0, s, wp, wqt, (int)hidden, kp);
+        hipLaunchKernelGGL(seq_pack_transposed_kernel, blocks(total), dim3(256), 0, s, w_ih, w_hh, wqt, (int)d, (int)hidden, kp);
         HIP_TRY(hipGetLastError());
         const int64_t nh = h->n * hidden;
         hipLaunchKernelGGL(seq_final_grad_kernel, blocks(nh), dim3(256), 0, s, h->d_final, g_a, gh, h->n, (int)hidden);
@@ -1148,7 +1167,9 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
         r.wqt = wqt; r.tape_g = tape_g; r.tape_c = tape_c; r.c_state = cst; r.g_a = g_a; r.gh = gh; r.gc = gc; r.dx = dx;
         r.d = (int32_t)d; r.hidden = (int32_t)hidden; r.kp = kp;
         if (r.n_path_tiles <= 0) continue;
-        hipLaunchKernelGGL(seq_reverse_kernel, dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
+        if (hidden > 64) hipLaunchKernelGGL((seq_reverse_kernel<true, 2>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 256)), dim3(512), 0, s, r);
+        else if (kp > 128) hipLaunchKernelGGL((seq_reverse_kernel<false, 2>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
+        else hipLaunchKernelGGL((seq_reverse_kernel<false, 1>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
         HIP_TRY(hipGetLastError());
     }
     {
@@ -1161,10 +1182,13 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
         g.dg = tape_g; g.x = x; g.tape_h = tape_h; g.h_state = hst; g.step_x = h->d_step_x; g.step_prev = h->d_step_prev;
         g.cells = cells; g.d = (int32_t)d; g.hidden = (int32_t)hidden; g.kp = kp; g.partial = partial;
         const int64_t chunks = (cells + kSeqWgradCells - 1) / kSeqWgradCells;
-        const int groups = (int)std::max<int64_t>(std::min<int64_t>(chunks, kSeqWgradGroups), 1);
-        hipLaunchKernelGGL(seq_weight_grad_kernel, dim3((unsigned)groups), dim3(512), 0, s, g);
-        HIP_TRY(hipGetLastError());
         const int64_t per = (int64_t)4 * hidden * kp + 4 * hidden;
+        const int groups = (int)std::max<int64_t>(std::min<int64_t>(chunks, seq_wgrad_groups((size_t)per)), 1);
+        const dim3 grid((unsigned)groups, (unsigned)((4 * hidden + 255) / 256));
+        if (hidden > 64) hipLaunchKernelGGL((seq_weight_grad_kernel<8, true>), grid, dim3(512), 0, s, g);
+        else if (kp > 128) hipLaunchKernelGGL((seq_weight_grad_kernel<8, false>), grid, dim3(512), 0, s, g);
+        else hipLaunchKernelGGL((seq_weight_grad_kernel<4, false>), grid, dim3(512), 0, s, g);
+        HIP_TRY(hipGetLastError());
         hipLaunchKernelGGL(seq_weight_grad_reduce_kernel, blocks(per), dim3(256), 0, s, partial, groups, g_w_ih, g_w_hh, g_b, (int)d,
                            (int)hidden, kp);
         HIP_TRY(hipGetLastError());

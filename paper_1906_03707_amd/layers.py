@@ -90,16 +90,16 @@ def lstm_aggregation(seq):
     class Agg(torch.autograd.Function):
         @staticmethod
         def forward(ctx, x, w_ih, w_hh, b):
-            x = x.contiguous()
-            a, ws = seq.lstm_forward_train(x, w_ih.contiguous(), w_hh.contiguous(), b.contiguous())
-            ctx.save_for_backward(x)
-            ctx.ws, ctx.hidden = ws, int(w_hh.shape[1])
+            x, w_ih, w_hh = x.contiguous(), w_ih.contiguous(), w_hh.contiguous()
+            a, ws = seq.lstm_forward_train(x, w_ih, w_hh, b.contiguous())
+            ctx.save_for_backward(x, w_ih, w_hh)
+            ctx.ws = ws
             return a
 
         @staticmethod
         def backward(ctx, g):
-            (x,) = ctx.saved_tensors
-            out = seq.lstm_backward(x, g.contiguous(), ctx.hidden, ctx.ws)
+            x, w_ih, w_hh = ctx.saved_tensors
+            out = seq.lstm_backward(x, w_ih, w_hh, g.contiguous(), ctx.ws)
             ctx.ws = None
             return out
 

@@ -63,7 +63,7 @@ def check(B, rowptr, col, d, hidden, seed, capacities, only_nodes=None):
             a, ws = h.lstm_forward_train(xd, wid, whd, bd)
             h.check()
             assert np.abs(f64(a)[rows] - want_a).max() <= 1e-5
-            got = h.lstm_backward(xd, gad, hidden, ws)
+            got = h.lstm_backward(xd, wid, whd, gad, ws)
             torch.cuda.synchronize()
             for name, g, w in zip(("g_x", "g_w_ih", "g_w_hh", "g_b"), got, want):
                 g = f64(g)
@@ -73,7 +73,9 @@ def check(B, rowptr, col, d, hidden, seed, capacities, only_nodes=None):
                 assert rel <= 2e-5 and worst <= 2e-5, f"cap {cap} d {d} H {hidden} one_launch {one_launch} {name}: rel {rel:.2e} worst {worst:.2e}"
 
 
-@pytest.mark.parametrize("d,hidden", [(8, 8), (16, 32), (64, 64), (24, 40), (96, 32)])
+@pytest.mark.parametrize("d,hidden", [(8, 8), (16, 32), (64, 64), (24, 40), (96, 32),
+                                      # the variants that stream the weights: hidden > 64 or d + hidden > 128
+                                      (64, 128), (128, 128), (32, 96), (128, 64), (120, 72)])
 def test_route_graph(B, d, hidden):
     rowptr, col = route_graph(150, 9, seed=d + hidden)
     check(B, rowptr, col, d, hidden, seed=5, capacities=(0, 7, col.size))
@@ -103,12 +105,12 @@ def test_rejections(B):
     rowptr, col = route_graph(20, 4, seed=3)
     h = B.SeqHag(rowptr, col, 3).upload()
     z = lambda *shape: torch.zeros(shape, device="cuda")
-    with pytest.raises(ValueError):       # hidden above what the backward pass supports
-        h.lstm_forward_train(z(20, 8), z(512, 8), z(512, 128), z(512))
+    with pytest.raises(ValueError):       # hidden above what the kernels support
+        h.lstm_forward_train(z(20, 8), z(544, 8), z(544, 136), z(544))
     a, ws = h.lstm_forward_train(z(20, 8), z(32, 8), z(32, 8), z(32))
     with pytest.raises(ValueError):       # workspace of the wrong size
-        h.lstm_backward(z(20, 8), z(20, 8), 8, ws[:16])
+        h.lstm_backward(z(20, 8), z(32, 8), z(32, 8), z(20, 8), ws[:16])
     with pytest.raises(ValueError):       # gradient of the wrong shape
-        h.lstm_backward(z(20, 8), z(20, 16), 8, ws)
-    g = h.lstm_backward(z(20, 8), z(20, 8), 8, ws)
+        h.lstm_backward(z(20, 8), z(32, 8), z(32, 8), z(20, 16), ws)
+    g = h.lstm_backward(z(20, 8), z(32, 8), z(32, 8), z(20, 8), ws)
     assert all(not t.any() for t in g)    # zero gradient in, zero gradients out
