@@ -162,17 +162,19 @@ int hag_seq_search(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
  * hag_seq_create (host): capacity > 0 runs hag_seq_search with that capacity and plans the evaluation of
  * the resulting prefix HAG respecting the order of Algorithm 2 -- every shared prefix (an aggregation node
  * of Equation 2's ordered cover, or the one-element prefix a list or a merge starts from) is evaluated once,
- * before whatever continues from it, and every node continues from the state of its list's head; capacity = 0 plans the plain lists with
- * nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
+ * before whatever continues from it, and every node continues from the state of its list's head; capacity = 0
+ * plans the plain lists with nothing shared (the baseline).  rowptr [n+1], col [rowptr[n]] as for hag_seq_search.
  * hag_seq_cells: cell evaluations of one pass; hag_seq_ranks: the longest chain of dependent evaluations;
- * hag_seq_launches: cell-kernel launches of one pass (the levels of hag_seq_get_plan); hag_seq_merges: aggregation
- * nodes.  hag_seq_upload copies the plan to the current device (once).  hag_seq_lstm_forward (device pointers, fp32; inference, the training pair is further down): x [n, d], w_ih [4H, d],
- * w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
+ * hag_seq_launches: cell-kernel launches of one forward pass under the handle's options (1 for the one-launch
+ * pass, else the levels of hag_seq_get_plan); hag_seq_merges: aggregation nodes.  hag_seq_upload copies the plan
+ * to the current device (once).
+ * hag_seq_lstm_forward (device pointers, fp32; inference, the training pair is further down): x [n, d],
+ * w_ih [4H, d], w_hh [4H, H], b [4H] with gate-major rows (input, forget, cell, output), a_out [n, H], workspace of
  * hag_seq_workspace_bytes(h, d, H) bytes (16-byte aligned; packed weights, one (h, c) state row and one flag
- * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 128, d + H <= 256 (H <= 64 with
- * d + H <= 128 keeps the packed weights in registers; beyond that every wavefront streams its part of them from the
- * L2 cache once per step).  Enqueues on
- * `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload, HAG_EINVAL otherwise. */
+ * per shared prefix).  d a multiple of 4, H a multiple of 8 up to 128, d + H <= 256 (H <= 64 with d + H <= 128
+ * keeps the packed weights in registers; beyond that every wavefront streams its part of them from the L2 cache
+ * once per step).  Enqueues on `stream` and returns; allocates nothing.  HAG_ESTATE before hag_seq_upload,
+ * HAG_EINVAL otherwise. */
 typedef struct hag_seq hag_seq_t;
 int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t capacity, hag_seq_t **out);
 void hag_seq_free(hag_seq_t *h);
@@ -195,8 +197,8 @@ int hag_seq_get_plan(const hag_seq_t *h, int32_t order, int64_t *n_states, int64
                      const int32_t **final_state);
 int hag_seq_upload(hag_seq_t *h);
 /* With more than one level, hag_seq_lstm_forward runs all of them in ONE launch when every workgroup of it
- * can be resident at once (paths in order 1 of hag_seq_get_plan): a tile of paths waits (polling a per-state flag, at most HAG_OPT_SPIN_LIMIT times,
- * default 2^21, about half a microsecond apart) until the states it starts from are written, by tiles that come
+ * can be resident at once (paths in order 1 of hag_seq_get_plan): a tile of paths waits (polling a per-state
+ * flag, at most HAG_OPT_SPIN_LIMIT times, default 2^21, about half a microsecond apart) until the states it starts from are written, by tiles that come
  * before it and never wait for it.  hag_seq_set_option (host state only; later calls): HAG_OPT_SEQ_ONE_LAUNCH
  * (default 1, or the environment's HAG_SEQ_ONE_LAUNCH when the handle was built; 0 = one launch per level, no
  * waits), HAG_OPT_SPIN_LIMIT, HAG_OPT_TEST_WAIT_UNREACHABLE (tests only: no flag is ever set, so every wait
