@@ -223,7 +223,9 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
  * gradient of a loss with respect to a_out, it writes the gradients g_x [n, d], g_w_ih [4H, d], g_w_hh [4H, H], g_b [4H]
  * (the layouts of x, w_ih, w_hh, b).  A shared prefix is differentiated once, with the gradients of everything that
  * continues from it added up first (fp32 atomics: the last bits of g_x and of the weight gradients depend on the order in
- * which those arrive).  Device pointers, fp32; enqueues on `stream` and returns; allocates nothing. */
+ * which those arrive).  Both calls follow HAG_OPT_SEQ_ONE_LAUNCH: by default the backward pass too is one launch in
+ * which a path waits, bounded, until everything that continues from a state has sent its gradients (hag_seq_check reports a
+ * wait that gave up).  Device pointers, fp32; enqueues on `stream` and returns; allocates nothing. */
 size_t hag_seq_train_workspace_bytes(const hag_seq_t *h, int64_t d, int64_t hidden);
 int hag_seq_lstm_forward_train(const hag_seq_t *h, int64_t d, int64_t hidden, const float *x, const float *w_ih,
                                const float *w_hh, const float *b, float *a_out, void *workspace, void *stream);

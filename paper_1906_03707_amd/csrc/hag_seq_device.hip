@@ -50,7 +50,9 @@ struct hag_seq {
     // for the backward pass: per step where its h_{t-1} lives (>= 0: that step's tape row, -1: the zero state,
     // <= -2: state row -(value) - 2), and the steps grouped by the input row they read (for the gradient of x)
     std::vector<int32_t> step_prev, xt_ptr, xt_idx;
-    int32_t *d_step_prev = nullptr, *d_xt_ptr = nullptr, *d_xt_idx = nullptr;
+    std::vector<int32_t> pending_init;   // per state: the paths that start from it
+    int32_t *d_step_prev = nullptr, *d_xt_ptr = nullptr, *d_xt_idx = nullptr, *d_pending_init = nullptr;
+    int64_t resident_reverse[3] = {0, 0, 0};   // reverse kernel variants <false,1>, <false,2>, <true,2>
     int64_t resident[6] = {0, 0, 0, 0, 0, 0};
     int64_t resident_tape[6] = {0, 0, 0, 0, 0, 0};   // likewise for the variants that write the tape   // per kernel variant: workgroups the device holds at once (set by hag_seq_upload)
     int32_t *d_gave_up = nullptr;     // set by a wait that gave up; read and cleared by hag_seq_check
@@ -388,9 +390,19 @@ struct SeqRevArgs {
     const float *g_a;        // [n, H]
     float *gh, *gc;          // [n_states, H]
     float *dx;               // [cells, d]: every step's gradient of its input row
+    // all levels in one launch (NULL: one launch per level): per kept state the number of paths that start from it and
+    // have not sent their gradients yet; tiles are taken last first
+    int32_t *pending;
+    int32_t *gave_up;
+    int32_t spin_limit, reversed;
+    int32_t publish;         // 0 in a test of the time-out: no path is ever counted off
     int32_t d, hidden, kp;
 };
 
+
+__global__ __launch_bounds__(256) void seq_copy_i32_kernel(const int32_t *__restrict__ src, int32_t *__restrict__ dst, int64_t n) {
+    for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) dst[i] = src[i];
+}
 
 __global__ __launch_bounds__(256) void seq_fill_kernel(float *p, int64_t n) {
     for (int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x; i < n; i += (int64_t)gridDim.x * 256) p[i] = 0.f;
@@ -435,7 +447,8 @@ __global__ __launch_bounds__(512, WIDE_H ? 2 : 4) void seq_reverse_kernel(SeqRev
     const int hidden = A.hidden, d = A.d, n_rt = A.kp / 32;          // 2 or 4 row tiles of the product
     // the product has n_rt row tiles x 2 halves of the paths; wavefront w takes pairs w and, with more than 8 (NPI = 2), w + 8
     const int sj = threadIdx.x >> 3, part = threadIdx.x & 7;         // element-wise phases: 8 threads per path, all in one wavefront
-    for (int64_t ct = blockIdx.x; ct < A.n_path_tiles; ct += gridDim.x) {
+    for (int64_t ci = blockIdx.x; ci < A.n_path_tiles; ci += gridDim.x) {
+        const int64_t ct = A.reversed ? A.n_path_tiles - 1 - ci : ci;
         if (threadIdx.x < kSeqJobs * 4) sdesc[threadIdx.x] = A.paths[ct * (kSeqJobs * 4) + threadIdx.x];
         __syncthreads();
         const int steps = sdesc[2];
@@ -469,14 +482,27 @@ __global__ __launch_bounds__(512, WIDE_H ? 2 : 4) void seq_reverse_kernel(SeqRev
                     }
                 }
                 const int keep = A.step_out[cell];
+                if (A.pending && keep >= 0) {
+                    // One launch for all levels: the paths that start from this state belong to tiles taken before this one,
+                    // which never wait for it, so the count reaches zero; the wait is bounded all the same.  Their sums are
+                    // then read with device-scope loads.
+                    bool ready = false;
+                    for (int spin = 0; spin < A.spin_limit; ++spin) {
+                        if (__hip_atomic_load(A.pending + keep, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) <= 0) { ready = true; break; }
+                        if (__hip_atomic_load(A.gave_up, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) != 0) break;
+                        __builtin_amdgcn_s_sleep(16);
+                    }
+                    if (!ready) __hip_atomic_store(A.gave_up, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup");
+                }
 #pragma unroll
                 for (int it = 0; it < IT; ++it) {
                     const int u = part * 4 + 32 * it;
                     if (u >= hidden) continue;
                     float cn[4], cp[4];
                     if (keep >= 0) {                       // what the other users of this state sent back
-                        const float4 a = *reinterpret_cast<const float4 *>(A.gh + (size_t)keep * hidden + u);
-                        const float4 b = *reinterpret_cast<const float4 *>(A.gc + (size_t)keep * hidden + u);
+                        const float4 a = A.pending ? seq_ld4_device(A.gh + (size_t)keep * hidden + u) : *reinterpret_cast<const float4 *>(A.gh + (size_t)keep * hidden + u);
+                        const float4 b = A.pending ? seq_ld4_device(A.gc + (size_t)keep * hidden + u) : *reinterpret_cast<const float4 *>(A.gc + (size_t)keep * hidden + u);
                         dhv[it][0] += a.x; dhv[it][1] += a.y; dhv[it][2] += a.z; dhv[it][3] += a.w;
                         dcv[it][0] += b.x; dcv[it][1] += b.y; dcv[it][2] += b.z; dcv[it][3] += b.w;
                     }
@@ -559,6 +585,12 @@ __global__ __launch_bounds__(512, WIDE_H ? 2 : 4) void seq_reverse_kernel(SeqRev
                         __hip_atomic_fetch_add(A.gh + (size_t)start * hidden + u + e, zg[sj * ZG + d + u + e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                         __hip_atomic_fetch_add(A.gc + (size_t)start * hidden + u + e, dcv[it][e], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                     }
+                }
+                if (A.pending) {
+                    // the eight threads of the path are lanes of one wavefront: once it has seen its atomics complete, one
+                    // of them counts the path off
+                    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                    if (part == 0 && A.publish) __hip_atomic_fetch_sub(A.pending + start, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
                 }
             }
         }
@@ -853,8 +885,10 @@ int hag_seq_create(int64_t n, const int64_t *rowptr, const int32_t *col, int64_t
         {
             const int64_t cells = (int64_t)h->step_x.size(), np = (int64_t)(h->paths.size() / 4);
             h->step_prev.assign((size_t)cells, -1);
+            h->pending_init.assign((size_t)std::max<int64_t>(h->n_states, 1), 0);
             for (int64_t i = 0; i < np; ++i) {
                 const int32_t start = h->paths[i * 4], beg = h->paths[i * 4 + 1], len = h->paths[i * 4 + 2];
+                if (start >= 0 && len > 0) ++h->pending_init[start];
                 for (int32_t t = 0; t < len; ++t) h->step_prev[(size_t)beg + t] = t > 0 ? beg + t - 1 : (start >= 0 ? -start - 2 : -1);
             }
             h->xt_ptr.assign((size_t)n + 1, 0);
@@ -883,6 +917,7 @@ void hag_seq_free(hag_seq_t *h) {
     if (h->d_step_prev) (void)hipFree(h->d_step_prev);
     if (h->d_xt_ptr) (void)hipFree(h->d_xt_ptr);
     if (h->d_xt_idx) (void)hipFree(h->d_xt_idx);
+    if (h->d_pending_init) (void)hipFree(h->d_pending_init);
     if (h->d_step_x) (void)hipFree(h->d_step_x);
     if (h->d_step_out) (void)hipFree(h->d_step_out);
     if (h->d_gave_up) (void)hipFree(h->d_gave_up);
@@ -909,6 +944,8 @@ typedef void (*seq_kernel_t)(SeqChainArgs);
 static const seq_kernel_t kSeqVariants[6] = {seq_chain_kernel<32, false, false, false>, seq_chain_kernel<32, true, false, false>,
                                              seq_chain_kernel<64, false, false, false>, seq_chain_kernel<64, true, false, false>,
                                              seq_chain_kernel<96, true, true, false>,   seq_chain_kernel<128, true, true, false>};
+typedef void (*seq_reverse_t)(SeqRevArgs);
+static const seq_reverse_t kSeqReverseVariants[3] = {seq_reverse_kernel<false, 1>, seq_reverse_kernel<false, 2>, seq_reverse_kernel<true, 2>};
 // the same with the tape written (training)
 static const seq_kernel_t kSeqTapeVariants[6] = {seq_chain_kernel<32, false, false, true>, seq_chain_kernel<32, true, false, true>,
                                                  seq_chain_kernel<64, false, false, true>, seq_chain_kernel<64, true, false, true>,
@@ -958,6 +995,7 @@ int hag_seq_upload(hag_seq_t *h) {
     HIP_TRY(put(&h->d_step_prev, h->step_prev));
     HIP_TRY(put(&h->d_xt_ptr, h->xt_ptr));
     HIP_TRY(put(&h->d_xt_idx, h->xt_idx));
+    HIP_TRY(put(&h->d_pending_init, h->pending_init));
     HIP_TRY(put(&h->d_gave_up, std::vector<int32_t>(1, 0)));
     {
         // workgroups of each kernel variant that the device holds at once (at most the two per compute unit the
@@ -970,6 +1008,10 @@ int hag_seq_upload(hag_seq_t *h) {
             h->resident[k] = (int64_t)std::min(per_cu, 2) * cus;
             HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqTapeVariants[k], k >= 4 ? 1024 : 512, 0));
             h->resident_tape[k] = (int64_t)std::min(per_cu, 2) * cus;
+            if (k < 3) {
+                HIP_TRY(hipOccupancyMaxActiveBlocksPerMultiprocessor(&per_cu, (const void *)kSeqReverseVariants[k], 512, 0));
+                h->resident_reverse[k] = (int64_t)std::min(per_cu, k == 2 ? 1 : 2) * cus;
+            }
         }
     }
     HIP_TRY(put(&h->d_final, h->final_state));
@@ -1077,7 +1119,7 @@ int hag_seq_lstm_forward(const hag_seq_t *h, int64_t d, int64_t hidden, const fl
 static int64_t seq_wgrad_groups(size_t per) { return std::max<int64_t>(std::min<int64_t>(kSeqWgradGroups, kSeqWgradPartialFloats / (int64_t)per), 1); }
 
 // Layout of the training workspace: the forward workspace, then the tape and the backward pass's own buffers.
-struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, wqt, partial, total; };
+struct SeqTrainLayout { size_t fwd, tape_g, tape_c, tape_h, dx, gh, gc, pending, wqt, partial, total; };
 static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hidden) {
     auto up = [](size_t x) { return (x + 255) & ~(size_t)255; };
     const size_t cells = std::max<size_t>(h->step_x.size(), 1), states = (size_t)std::max<int64_t>(h->n_states, 1);
@@ -1091,6 +1133,7 @@ static SeqTrainLayout seq_train_layout(const hag_seq_t *h, int64_t d, int64_t hi
     L.dx = at; at += up(cells * (size_t)d * f);
     L.gh = at; at += up(states * H * f);
     L.gc = at; at += up(states * H * f);
+    L.pending = at; at += up(states * sizeof(int32_t));
     L.wqt = at; at += up(kp * 4 * H * f);
     L.partial = at; at += up((size_t)seq_wgrad_groups(4 * H * kp + 4 * H) * (4 * H * kp + 4 * H) * f);
     L.total = at;
@@ -1146,7 +1189,7 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
     auto blocks = [](int64_t total) { return dim3((unsigned)std::min<int64_t>((total + 255) / 256, 65535 * 16)); };
     // gradient rows of the kept states start at zero (gh and gc are adjacent)
     {
-        const int64_t total = (int64_t)((L.wqt - L.gh) / sizeof(float));
+        const int64_t total = (int64_t)((L.pending - L.gh) / sizeof(float));
         hipLaunchKernelGGL(seq_fill_kernel, blocks(total), dim3(256), 0, s, gh, total);
         HIP_TRY(hipGetLastError());
     }
@@ -1159,17 +1202,30 @@ int hag_seq_lstm_backward(const hag_seq_t *h, int64_t d, int64_t hidden, const f
         HIP_TRY(hipGetLastError());
     }
     const int64_t levels = (int64_t)h->tile_ptr.size() - 1;
-    for (int64_t l = levels - 1; l >= 0; --l) {
+    const int rv = hidden > 64 ? 2 : (kp > 128 ? 1 : 0);
+    const int64_t resident = h->resident_reverse[rv];
+    const bool fused = levels > 1 && h->one_launch && resident > 0;
+    int32_t *pending = (int32_t *)(w + L.pending);
+    if (fused) {
+        hipLaunchKernelGGL(seq_copy_i32_kernel, blocks(h->n_states), dim3(256), 0, s, h->d_pending_init, pending, h->n_states);
+        HIP_TRY(hipGetLastError());
+    }
+    for (int64_t l = fused ? 0 : levels - 1; l >= 0; --l) {
         SeqRevArgs r;
-        r.paths = h->d_paths + h->tile_ptr[l] * kSeqJobs * 4;
-        r.n_path_tiles = h->tile_ptr[l + 1] - h->tile_ptr[l];
+        // one launch: the tiles of the depth order, last first (what starts deeper comes earlier); else level by level, last first
+        r.paths = fused ? h->d_paths_by_depth : h->d_paths + h->tile_ptr[l] * kSeqJobs * 4;
+        r.n_path_tiles = fused ? h->depth_tile_ptr.back() : h->tile_ptr[l + 1] - h->tile_ptr[l];
+        r.pending = fused ? pending : nullptr;
+        r.reversed = fused ? 1 : 0;
+        r.gave_up = h->d_gave_up;
+        r.spin_limit = h->spin_limit;
+        r.publish = h->wait_unreachable ? 0 : 1;
         r.step_out = h->d_step_out;
         r.wqt = wqt; r.tape_g = tape_g; r.tape_c = tape_c; r.c_state = cst; r.g_a = g_a; r.gh = gh; r.gc = gc; r.dx = dx;
         r.d = (int32_t)d; r.hidden = (int32_t)hidden; r.kp = kp;
         if (r.n_path_tiles <= 0) continue;
-        if (hidden > 64) hipLaunchKernelGGL((seq_reverse_kernel<true, 2>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 256)), dim3(512), 0, s, r);
-        else if (kp > 128) hipLaunchKernelGGL((seq_reverse_kernel<false, 2>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
-        else hipLaunchKernelGGL((seq_reverse_kernel<false, 1>), dim3((unsigned)std::min<int64_t>(r.n_path_tiles, 512)), dim3(512), 0, s, r);
+        const int64_t cap = fused ? resident : (rv == 2 ? 256 : 512);
+        hipLaunchKernelGGL(kSeqReverseVariants[rv], dim3((unsigned)std::min<int64_t>(r.n_path_tiles, cap)), dim3(512), 0, s, r);
         HIP_TRY(hipGetLastError());
     }
     {

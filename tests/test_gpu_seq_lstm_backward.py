@@ -101,6 +101,35 @@ def test_bench_workload_loss_on_sampled_nodes(B):
     check(B, rp, cl, 64, 64, seed=11, capacities=(0, n // 4, int(cl.size)), only_nodes=sample)
 
 
+def test_bounded_wait_of_the_backward_pass_gives_up_and_reports(B):
+    # forced from the host: no path is ever counted off and the spin limit is tiny, so every wait of the one-launch
+    # backward pass ends by giving up; the kernel still runs to its end and hag_seq_check reports it
+    rowptr, col = route_graph(300, 9, seed=31)
+    d = hidden = 16
+    rng = np.random.default_rng(3)
+    dev = lambda a: torch.from_numpy(np.ascontiguousarray(a, dtype=np.float32)).cuda()
+    wid, whd, bd = dev(rng.normal(0, 0.4, (4 * hidden, d))), dev(rng.normal(0, 0.4, (4 * hidden, hidden))), dev(rng.normal(0, 0.4, 4 * hidden))
+    x, g_a = torch.randn((300, d), device="cuda"), torch.randn((300, hidden), device="cuda")
+    h = B.SeqHag(rowptr, col, col.size).upload()
+    assert h.plan()[4].size - 1 > 1
+    a, ws = h.lstm_forward_train(x, wid, whd, bd)
+    want = [t.clone() for t in h.lstm_backward(x, wid, whd, g_a, ws)]
+    h.check()
+    a, ws = h.lstm_forward_train(x, wid, whd, bd)
+    h.check()
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 1).set_option(B.HAG_OPT_SPIN_LIMIT, 4)
+    h.lstm_backward(x, wid, whd, g_a, ws)
+    with pytest.raises(B.HagError) as ei:
+        h.check()
+    assert ei.value.code == B.HAG_ETIMEOUT
+    h.set_option(B.HAG_OPT_TEST_WAIT_UNREACHABLE, 0).set_option(B.HAG_OPT_SPIN_LIMIT, 1 << 21)
+    a, ws = h.lstm_forward_train(x, wid, whd, bd)
+    got = h.lstm_backward(x, wid, whd, g_a, ws)
+    h.check()
+    for g, w in zip(got, want):                             # the next pass is sound again (atomics: not bit-identical)
+        assert (g - w).abs().max().item() <= 1e-4 * max(w.abs().max().item(), 1e-30)
+
+
 def test_rejections(B):
     rowptr, col = route_graph(20, 4, seed=3)
     h = B.SeqHag(rowptr, col, 3).upload()
