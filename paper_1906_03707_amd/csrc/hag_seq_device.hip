@@ -302,9 +302,7 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, (TAPE && !BIG) ? 2 : 4) void seq_
                                 const float h_new = go * seq_tanh(c_new);
                                 const size_t cell = (size_t)(sdesc[j * 4 + 1] + t) * hidden + unit;
                                 *reinterpret_cast<float4 *>(A.tape_g + cell * 4) = make_float4(gi, gf, gg, go);
-                                A.tape_c[cell] = c_new;
-                                A.tape_h[cell] = h_new;
-                                z[j * ZS + d + unit] = h_new;
+                                z[j * ZS + d + unit] = h_new;              // (c and h go to the tape as whole rows, below)
                                 continue;
                             }
                             z[j * ZS + d + unit] = seq_sigmoid(acc[g][4 * m + 3]) * seq_tanh(c_new);
@@ -327,6 +325,18 @@ __global__ __launch_bounds__(BIG ? 1024 : 512, (TAPE && !BIG) ? 2 : 4) void seq_
                 }
             }
             __syncthreads();                               // the operand rows and cell states of the next step are complete
+            if constexpr (TAPE) {
+                // the step's c and h rows of the tape, from LDS: whole rows, a few lines per path instead of one request per element
+                const int tid4 = seq_opaque(threadIdx.x), sj4 = tid4 / TPP, part4 = tid4 % TPP;
+                if (t < sdesc[sj4 * 4 + 2]) {
+                    const size_t row = (size_t)(sdesc[sj4 * 4 + 1] + t) * hidden;
+                    for (int u = part4 * 4; u < hidden; u += 4 * TPP) {
+                        const float *ph = &z[sj4 * ZS + d + u], *pc = &cs[sj4 * HS + u];
+                        *reinterpret_cast<float4 *>(A.tape_h + row + u) = make_float4(ph[0], ph[1], ph[2], ph[3]);
+                        *reinterpret_cast<float4 *>(A.tape_c + row + u) = make_float4(pc[0], pc[1], pc[2], pc[3]);
+                    }
+                }
+            }
             if (keep >= 0) {                               // a state that another path starts from, or some a_v
                 const int tid3 = seq_opaque(threadIdx.x), sj3 = tid3 / TPP, part3 = tid3 % TPP;
                 for (int u = part3 * 4; u < hidden; u += 4 * TPP) {
