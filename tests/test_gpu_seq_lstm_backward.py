@@ -63,6 +63,7 @@ def check(B, rowptr, col, d, hidden, seed, capacities, only_nodes=None):
             a, ws = h.lstm_forward_train(xd, wid, whd, bd)
             h.check()
             assert np.abs(f64(a)[rows] - want_a).max() <= 1e-5
+            assert torch.equal(a, h.lstm_forward(xd, wid, whd, bd))      # keeping the tape changes nothing in the result
             got = h.lstm_backward(xd, wid, whd, gad, ws)
             torch.cuda.synchronize()
             for name, g, w in zip(("g_x", "g_w_ih", "g_w_hh", "g_b"), got, want):
