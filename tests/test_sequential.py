@@ -265,3 +265,16 @@ def test_lstm_plan_of_degenerate_inputs():
                 assert cells == plan.cells
     empty = B.SeqHag(np.zeros(1, dtype=np.int64), np.zeros(0, dtype=np.int32), 4)
     assert (empty.cells, empty.launches, empty.ranks) == (0, 0, 0)
+
+
+def test_lstm_workspace_sizes():
+    # host arithmetic only: the training workspace holds the forward one plus 24 H bytes per cell and more; unsupported
+    # sizes give 0
+    rng = np.random.default_rng(2)
+    rowptr = np.concatenate([[0], np.cumsum(rng.integers(0, 6, 50))]).astype(np.int64)
+    col = rng.integers(0, 50, rowptr[-1]).astype(np.int32)
+    plan = B.SeqHag(rowptr, col, 10)
+    for d, hidden in ((8, 8), (64, 64), (128, 128), (100, 24)):
+        fwd, train = plan.workspace_bytes(d, hidden), plan.train_workspace_bytes(d, hidden)
+        assert fwd > 0 and train >= fwd + plan.cells * 24 * hidden
+    assert plan.train_workspace_bytes(8, 136) == 0 and plan.train_workspace_bytes(200, 64) == 0 and plan.train_workspace_bytes(6, 8) == 0
